@@ -1,0 +1,121 @@
+"""Worked examples: the oracle against values derived by hand from the paper."""
+import glob
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2401_08156_amd import tracegen as tg
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+MiB = 1 << 20
+
+
+def load_fixture(path):
+    fx = {}
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        k, v = line.split(":", 1)
+        fx[k.strip()] = v.strip()
+    ops = []
+    for tok in fx["ops"].split():
+        if tok[0] == "A":
+            slot, mib = tok[1:].split(":")
+            ops.append(("A", int(slot), int(mib) * MiB))
+        else:
+            ops.append(("F", int(tok[1:])))
+    fx["events"] = tg.make_events(ops)
+    return fx
+
+
+FIXTURES = sorted(glob.glob(os.path.join(GOLDEN, "*.txt")))
+
+
+@pytest.mark.parametrize("path", FIXTURES, ids=[os.path.basename(p) for p in FIXTURES])
+def test_worked_example(path):
+    fx = load_fixture(path)
+    P = oracle.make_params(max_slots=16)
+    for pol, name in ((oracle.SPLIT, "split"), (oracle.VMS, "vms")):
+        if "codes_" + name not in fx:
+            continue
+        dec, st = oracle.replay(fx["events"], P, pol)
+        dec = dec[0]
+        assert (dec & np.uint64(15)).tolist() == [int(x) for x in fx["codes_" + name].split()]
+        if "ncand_" + name in fx:
+            got = ((dec >> np.uint64(8)) & np.uint64(0xFFFFFF)).tolist()
+            want = [int(x) for x in fx["ncand_" + name].split()]
+            alloc = [(int(d) & 15) in (1, 2, 3, 4) for d in dec]
+            assert [g for g, a in zip(got, alloc) if a] == [w for w, a in zip(want, alloc) if a]
+        if "sblock_" + name in fx:
+            is_alloc = (dec & np.uint64(15)) != 0
+            got = ((dec >> np.uint64(5)) & np.uint64(1)) * is_alloc
+            assert got.tolist() == [int(x) for x in fx["sblock_" + name].split()]
+        for key in ("peak_active", "peak_reserved"):
+            if key + "_" + name in fx:
+                assert st[key][0] == int(fx[key + "_" + name]) * MiB
+        if "frag_" + name in fx:
+            assert st["fragmentation"][0] == pytest.approx(float(fx["frag_" + name]), abs=1e-15)
+        assert st["status"][0] == 0
+
+
+def test_stitch_creates_no_physical_memory():
+    # Sec. 3.3.1: "For all sBlocks, they never create new physical chunks".
+    fx = load_fixture(os.path.join(GOLDEN, "stitch_4_2_6.txt"))
+    dec, st, series, hand = oracle.replay_verbose(fx["events"], oracle.make_params(16), oracle.VMS)
+    assert series[3, 1] == series[4, 1] == 6 * MiB        # reserved unchanged by the stitch
+    # the stitched block maps exactly the chunks of the two old blocks: 4 MiB = chunks 0-1, 2 MiB = chunk 2
+    runs = sorted((int(s), int(n)) for e, s, n in hand if e == 4)
+    assert runs == [(0, 2), (2, 1)]
+
+
+def test_oom_and_noop_free():
+    # Sec. 4.1 state S5: a failed Alloc is reported, nothing else changes.
+    ev = tg.make_events([("A", 0, 4 * MiB), ("A", 1, 8 * MiB), ("F", 1), ("A", 2, 2 * MiB), ("F", 0), ("A", 3, 6 * MiB)])
+    P = oracle.make_params(16, capacity_bytes=6 * MiB)
+    for pol in (oracle.SPLIT, oracle.VMS):
+        dec, st = oracle.replay(ev, P, pol)
+        codes = (dec[0] & np.uint64(15)).tolist()
+        # 4 fits; 8 does not (OOM); its free is a no-op; 2 fits; after freeing the 4, a 6 MiB request:
+        # stitching reuses 4 + 2 free? no: the 2 is live, so 4 cached + 2 new would exceed 6 -> OOM in both
+        assert codes[:5] == [4, 5, 6, 4, 0]
+        assert codes[5] == 5
+        assert st["first_oom_event"][0] == 1
+        assert st["peak_reserved"][0] == 6 * MiB
+
+
+def test_invalid_events_leave_state_unchanged():
+    ev = tg.make_events([("A", 0, 4 * MiB), ("A", 0, 2 * MiB), ("F", 3), ("A", 99, 2 * MiB), ("F", 0)])
+    ev = np.concatenate([ev, np.array([(1 << 32) | 0], dtype=np.uint64)])    # ALLOC of size 0
+    P = oracle.make_params(8)
+    for pol in (oracle.SPLIT, oracle.VMS):
+        dec, st = oracle.replay(ev, P, pol)
+        assert (dec[0] & np.uint64(15)).tolist() == [4, 15, 15, 15, 0, 15]
+        assert st["status"][0] == 1 and st["peak_reserved"][0] == 4 * MiB and st["final_active"][0] == 0
+
+
+def test_small_requests_use_the_splitting_pool():
+    # Sec. 3.1: requests below 2 MB keep the splitting method; larger ones use stitching.
+    ev = tg.make_events([("A", 0, 512 * 1024), ("A", 1, 1024 * 1024), ("A", 2, 2 * MiB), ("F", 0), ("F", 1)])
+    dec, st = oracle.replay(ev, oracle.make_params(8), oracle.VMS)
+    small = ((dec[0] >> np.uint64(4)) & np.uint64(1)).tolist()
+    assert small == [1, 1, 0, 1, 1]
+    # the second request is cut from the 1.5 MiB left of the first 2 MiB segment
+    assert (dec[0] & np.uint64(15)).tolist() == [4, 2, 4, 0, 0]
+    assert st["peak_reserved"][0] == 4 * MiB      # one 2 MiB segment for the small pool + one chunk
+    assert st["peak_active"][0] == 512 * 1024 + 1024 * 1024 + 2 * MiB
+
+
+def test_fragmentation_limit_hands_out_whole_block():
+    # Sec. 4.2.3: blocks below the limit are neither split nor stitched.
+    ev = tg.make_events([("A", 0, 6 * MiB), ("F", 0), ("A", 1, 4 * MiB), ("F", 1), ("A", 2, 4 * MiB), ("A", 3, 4 * MiB)])
+    P = oracle.make_params(8, frag_limit_bytes=8 * MiB)
+    dec, st = oracle.replay(ev, P, oracle.VMS)
+    codes = (dec[0] & np.uint64(15)).tolist()
+    cut = ((dec[0] >> np.uint64(6)) & np.uint64(1)).tolist()
+    # the 6 MiB block serves 4 MiB requests whole (state S2 without the cut); a second one must grow
+    assert codes == [4, 0, 2, 0, 2, 4] and cut[2] == 0 and cut[4] == 0
+    assert st["peak_active"][0] == 10 * MiB and st["peak_reserved"][0] == 10 * MiB
+    assert st["n_sblock_created"][0] == 0
