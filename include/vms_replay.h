@@ -1,0 +1,190 @@
+/*
+ * vms_replay: batched allocator trace replay on one AMD MI355X (gfx950).
+ *
+ * Thousands of independent alloc/free traces are replayed on the GPU, one
+ * wavefront per (trace, policy), under two allocator policies from the GMLake
+ * paper (arXiv 2401.08156):
+ *   VMS_POLICY_SPLIT  the splitting caching allocator: best fit, split, lazy
+ *                     free, merge with inactive neighbours (Sec. 2.2,
+ *                     "Caching Allocator");
+ *   VMS_POLICY_VMS    the virtual-memory-stitching allocator: pBlock / sBlock
+ *                     pools (Sec. 3.2), Alloc / Split / Stitch (Sec. 3.3.1),
+ *                     BestFit (Algorithm 1), Update / StitchFree (Sec. 3.3.2),
+ *                     the four allocation states S1-S5 (Sec. 4.1, Fig. 9), the
+ *                     fragmentation limit (Sec. 4.2.3) and the splitting path
+ *                     for requests below one chunk (Sec. 3.1).
+ * Per event it emits one decision word per policy; per trace it emits peak
+ * requested / active / reserved bytes and fragmentation = 1 - peak active /
+ * peak reserved (Sec. 5.1, "Metric").
+ *
+ * Plain C ABI: no C++ or framework types.  Pointers named d_* are DEVICE
+ * pointers owned by the caller; h_* and unprefixed pointers are HOST pointers.
+ * Every function returns VMS_OK (0) or a negative VMS_E* code and never
+ * throws or aborts.  Conditions inside a trace (out of memory, malformed
+ * events) are results, reported in the decision stream and the status word,
+ * not errors of the call.
+ *
+ * Event word (u64), the input format:
+ *   bits  0-30  request size in 512-byte units (ALLOC only, must be >= 1)
+ *   bit   31    kind: 0 = ALLOC, 1 = FREE
+ *   bits 32-63  slot: handle chosen by the trace; ALLOC binds an unbound slot,
+ *               FREE releases a bound one; slot < max_slots
+ *
+ * Decision word (u64), one per event and policy:
+ *   bits  0-3   code: 0 FREE, 1 EXACT (S1), 2 SPLIT (S2), 3 STITCH (S3),
+ *               4 GROW (S4, or a new segment of a splitting pool), 5 OOM (S5),
+ *               6 FREE_NOOP (free of a slot whose ALLOC hit OOM), 15 INVALID
+ *   bit   4     served by the small-request splitting pool of the VMS policy
+ *   bit   5     the block is a stitched block (sBlock)
+ *   bit   6     ALLOC: a block was cut (Split);  FREE in a splitting pool:
+ *               merged with the left neighbour
+ *   bit   7     ALLOC: StitchFree released at least one sBlock;  FREE in a
+ *               splitting pool: merged with the right neighbour
+ *   bits  8-31  number of candidate blocks taken from the pool (|CB| of
+ *               Algorithm 1; 1 for a hit in a splitting pool, 0 for pure growth)
+ *   bits 32-63  where: splitting pools: block address in 512-byte units in
+ *               that pool's address space; VMS pBlock: its first physical
+ *               chunk number; VMS sBlock: its creation number
+ *   OOM, FREE_NOOP and INVALID words carry the code only.
+ */
+#ifndef VMS_REPLAY_H
+#define VMS_REPLAY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VMS_OK          0
+#define VMS_EINVAL     (-1)   /* bad argument or inconsistent configuration            */
+#define VMS_ESTRUCT    (-2)   /* struct_size does not match this library               */
+#define VMS_ENOMEM     (-3)   /* host or device allocation failed                      */
+#define VMS_EWORKSPACE (-4)   /* workspace missing or misaligned                       */
+#define VMS_EHIP       (-5)   /* a HIP call failed; see vms_replay_last_hip_error      */
+#define VMS_ETOOBIG    (-6)   /* per-trace tables do not fit the 160 KB of LDS per CU  */
+#define VMS_ESTATE     (-7)   /* call out of order (stats before run, ...)             */
+
+#define VMS_POLICY_SPLIT 1u
+#define VMS_POLICY_VMS   2u
+
+/* status bits of vms_trace_stats.status */
+#define VMS_ST_INVALID_EVENT   1u   /* at least one INVALID decision (a result, not a failure) */
+#define VMS_ST_TABLE_OVERFLOW  2u   /* an engine table (below) was too small: replay of this
+                                       trace stopped early, its results are not valid       */
+
+typedef struct vms_config {
+    uint32_t struct_size;        /* sizeof(vms_config)                                      */
+    uint32_t n_traces;
+    uint32_t max_events;         /* row length of the event / decision arrays               */
+    uint32_t policy_mask;        /* VMS_POLICY_SPLIT | VMS_POLICY_VMS                        */
+    uint64_t chunk_bytes;        /* physical chunk, 2 MiB in the paper (Sec. 3.1); a power
+                                    of two >= 512; also the growth granularity of the
+                                    splitting pools                                          */
+    uint64_t small_limit_bytes;  /* VMS: requests below this use the splitting pool
+                                    (Sec. 3.1); <= chunk_bytes                               */
+    uint64_t frag_limit_bytes;   /* VMS: blocks below this are neither split nor stitched
+                                    (Sec. 4.2.3); a multiple of chunk_bytes; chunk_bytes
+                                    or 0 disables it                                         */
+    uint64_t capacity_bytes;     /* reserved-memory limit per trace (state S5); 0 selects
+                                    the engine maximum of 512 GiB                            */
+    uint32_t spool_threshold;    /* StitchFree releases least-recently-used inactive sBlocks
+                                    while more than this many are cached (Sec. 4.2.3)        */
+    uint32_t max_slots;          /* slots are 0 .. max_slots-1                               */
+    /* engine table sizes per trace; a trace that needs more gets VMS_ST_TABLE_OVERFLOW     */
+    uint32_t max_free_blocks;    /* inactive blocks of a splitting pool                      */
+    uint32_t max_pblocks;        /* pBlocks (active and inactive)                            */
+    uint32_t max_sblocks;        /* cached sBlocks; must exceed spool_threshold + 2          */
+    uint32_t max_runs;           /* chunk runs summed over all cached sBlocks                */
+    uint32_t max_chunks;         /* physical chunks of the VMS large path                    */
+    uint32_t reserved0;
+} vms_config;
+
+typedef struct vms_trace_stats {        /* one per (policy, trace) */
+    uint64_t peak_requested;     /* bytes: running maximum of live request sizes            */
+    uint64_t peak_active;        /* bytes held by live blocks (Sec. 5.1 "active memory")    */
+    uint64_t peak_reserved;      /* bytes obtained from the device (Sec. 5.1 "reserved")    */
+    uint64_t final_requested, final_active, final_reserved;
+    uint64_t digest;             /* d = 0xCBF29CE484222325; after every event, for x in
+                                    (decision, active/512, reserved/512):
+                                    d = (d ^ x) * 0x9E3779B97F4A7C15 mod 2^64               */
+    uint32_t n_code[8];          /* events per decision code 0..6; [7] counts INVALID       */
+    uint32_t n_split;            /* blocks cut (both kinds of pool)                          */
+    uint32_t n_merge;            /* neighbour merges in splitting pools                      */
+    uint32_t n_sblock_created, n_sblock_evicted;
+    uint32_t first_oom_event;    /* 0xFFFFFFFF if none                                       */
+    uint32_t status;             /* VMS_ST_* bits                                            */
+    uint32_t max_pblocks, max_sblocks, max_free_blocks, max_members;  /* high-water marks;
+                                    max_members = most blocks stitched into one sBlock       */
+    uint32_t max_runs;           /* high-water mark of chunk runs held by cached sBlocks     */
+    uint32_t overflow_event;     /* event at which a table overflowed, else 0xFFFFFFFF       */
+    double   fragmentation;      /* 1.0 - (double)peak_active / (double)peak_reserved;
+                                    0.0 when nothing was reserved                            */
+} vms_trace_stats;
+
+typedef struct vms_summary {            /* over all traces of one run (Sec. 5.1) */
+    uint64_t sum_peak_reserved[2];   /* [0] splitting, [1] VMS                               */
+    uint64_t sum_peak_active[2];
+    uint64_t n_flagged[2];           /* traces with a non-zero status                        */
+    double   max_fragmentation[2];
+    double   mean_fragmentation[2];
+    double   mem_reduction_ratio;    /* (sum reserved split - sum reserved VMS) / sum reserved
+                                        split; 0 unless both policies ran                    */
+} vms_summary;
+
+typedef struct vms_replay vms_replay;   /* opaque handle */
+
+/* Fill *cfg with the defaults (2 MiB chunks, limits disabled, threshold 512,
+ * table sizes for transformer-like traces) for the given shape.               */
+void vms_config_default(vms_config *cfg, uint32_t n_traces, uint32_t max_events, uint32_t max_slots);
+
+/* Validate cfg, choose the LDS layout and allocate the device statistics
+ * buffer (n_traces * 2 records) on the current HIP device.  *out is owned by
+ * the caller until vms_replay_destroy.                                         */
+int vms_replay_create(const vms_config *cfg, vms_replay **out);
+
+/* Bytes of device scratch memory vms_replay_run needs (may be 0); the caller
+ * allocates it, 256-byte aligned, and may reuse it between runs.              */
+size_t vms_replay_workspace_bytes(const vms_replay *h);
+
+/* LDS bytes per wavefront for each policy's kernel ([0] splitting, [1] VMS). */
+int vms_replay_lds_bytes(const vms_replay *h, uint32_t out[2]);
+
+/* Replay.  d_events[n_traces][max_events] holds the event words; d_n_events
+ * (nullable) the number of valid events per trace (default: max_events).
+ * d_dec_split / d_dec_vms (nullable each) receive the decision words in the
+ * same shape; entries past a trace's length are not written.  d_workspace as
+ * sized above.  Work is enqueued on hip_stream (a hipStream_t, NULL = default
+ * stream) and the call returns without waiting; buffers must stay alive until
+ * the stream has drained.  Runs on one handle must not overlap.               */
+int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_events,
+                   uint64_t *d_dec_split, uint64_t *d_dec_vms, void *d_workspace, void *hip_stream);
+
+/* Wait for the last run and copy statistics to the host: h_out[p * n_traces + t]
+ * with p = 0 splitting, 1 VMS; n must be 2 * n_traces.  Records of a policy
+ * that did not run are zero.                                                  */
+int vms_replay_stats(vms_replay *h, vms_trace_stats *h_out, size_t n);
+
+/* Wait for the last run and reduce the per-trace statistics on the device.   */
+int vms_replay_summary(vms_replay *h, vms_summary *h_out);
+
+/* Milliseconds the kernels of the last run took on their stream (HIP events
+ * recorded around them inside vms_replay_run); waits for the run.
+ * out_ms[0] splitting kernel, [1] VMS kernel, [2] whole run.                  */
+int vms_replay_last_kernel_ms(vms_replay *h, float out_ms[3]);
+
+void vms_replay_destroy(vms_replay *h);
+
+int vms_replay_last_hip_error(const vms_replay *h);   /* hipError_t of the last VMS_EHIP */
+const char *vms_strerror(int code);
+
+/* In-wavefront primitives self-test (reductions, scans, sorted insert): runs a
+ * small kernel on the current device and returns VMS_OK if every lane layout
+ * matches its definition.  Diagnostic; not part of a replay.                  */
+int vms_selftest(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

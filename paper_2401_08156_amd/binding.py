@@ -1,0 +1,191 @@
+"""ctypes binding of include/vms_replay.h: same names, argument marshalling only.
+
+Every step of the replay runs in the HIP kernels of libvmsreplay.so; PyTorch is
+used for device memory and the stream.  There is no CPU fallback: a missing or
+unloadable library raises.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+VMS_OK = 0
+VMS_POLICY_SPLIT, VMS_POLICY_VMS = 1, 2
+VMS_ST_INVALID_EVENT, VMS_ST_TABLE_OVERFLOW = 1, 2
+
+
+class vms_config(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("n_traces", ctypes.c_uint32),
+                ("max_events", ctypes.c_uint32), ("policy_mask", ctypes.c_uint32),
+                ("chunk_bytes", ctypes.c_uint64), ("small_limit_bytes", ctypes.c_uint64),
+                ("frag_limit_bytes", ctypes.c_uint64), ("capacity_bytes", ctypes.c_uint64),
+                ("spool_threshold", ctypes.c_uint32), ("max_slots", ctypes.c_uint32),
+                ("max_free_blocks", ctypes.c_uint32), ("max_pblocks", ctypes.c_uint32),
+                ("max_sblocks", ctypes.c_uint32), ("max_runs", ctypes.c_uint32),
+                ("max_chunks", ctypes.c_uint32), ("reserved0", ctypes.c_uint32)]
+
+
+class vms_summary(ctypes.Structure):
+    _fields_ = [("sum_peak_reserved", ctypes.c_uint64 * 2), ("sum_peak_active", ctypes.c_uint64 * 2),
+                ("n_flagged", ctypes.c_uint64 * 2), ("max_fragmentation", ctypes.c_double * 2),
+                ("mean_fragmentation", ctypes.c_double * 2), ("mem_reduction_ratio", ctypes.c_double)]
+
+
+# vms_trace_stats as a numpy record (same layout as the C struct)
+STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("peak_reserved", "<u8"),
+                        ("final_requested", "<u8"), ("final_active", "<u8"), ("final_reserved", "<u8"),
+                        ("digest", "<u8"), ("n_code", "<u4", (8,)),
+                        ("n_split", "<u4"), ("n_merge", "<u4"),
+                        ("n_sblock_created", "<u4"), ("n_sblock_evicted", "<u4"),
+                        ("first_oom_event", "<u4"), ("status", "<u4"),
+                        ("max_pblocks", "<u4"), ("max_sblocks", "<u4"),
+                        ("max_free_blocks", "<u4"), ("max_members", "<u4"),
+                        ("max_runs", "<u4"), ("overflow_event", "<u4"),
+                        ("fragmentation", "<f8")])
+
+EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
+           "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms",
+           "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
+           "vms_demo_run"]
+
+_lib = None
+
+
+def lib():
+    """Load libvmsreplay.so (built in-tree; built now only if it is missing)."""
+    global _lib
+    if _lib is None:
+        # PyTorch ships its own HIP runtime (same soname as the system one).  Import it first so
+        # that this library binds to the runtime torch already loaded: one runtime per process.
+        import torch  # noqa: F401
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        L = ctypes.CDLL(path)
+        vp, u32, u64, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_uint64, ctypes.c_size_t
+        L.vms_config_default.restype = None
+        L.vms_config_default.argtypes = [ctypes.POINTER(vms_config), u32, u32, u32]
+        L.vms_replay_create.restype = ctypes.c_int
+        L.vms_replay_create.argtypes = [ctypes.POINTER(vms_config), ctypes.POINTER(vp)]
+        L.vms_replay_workspace_bytes.restype = sz
+        L.vms_replay_workspace_bytes.argtypes = [vp]
+        L.vms_replay_lds_bytes.restype = ctypes.c_int
+        L.vms_replay_lds_bytes.argtypes = [vp, ctypes.POINTER(u32 * 2)]
+        L.vms_replay_run.restype = ctypes.c_int
+        L.vms_replay_run.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.vms_replay_stats.restype = ctypes.c_int
+        L.vms_replay_stats.argtypes = [vp, vp, sz]
+        L.vms_replay_summary.restype = ctypes.c_int
+        L.vms_replay_summary.argtypes = [vp, ctypes.POINTER(vms_summary)]
+        L.vms_replay_last_kernel_ms.restype = ctypes.c_int
+        L.vms_replay_last_kernel_ms.argtypes = [vp, ctypes.POINTER(ctypes.c_float * 3)]
+        L.vms_replay_destroy.restype = None
+        L.vms_replay_destroy.argtypes = [vp]
+        L.vms_replay_last_hip_error.restype = ctypes.c_int
+        L.vms_replay_last_hip_error.argtypes = [vp]
+        L.vms_strerror.restype = ctypes.c_char_p
+        L.vms_strerror.argtypes = [ctypes.c_int]
+        L.vms_selftest.restype = ctypes.c_int
+        L.vms_selftest.argtypes = []
+        _lib = L
+    return _lib
+
+
+class VmsError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__("%s: %s (%d)" % (what, lib().vms_strerror(code).decode(), code))
+        self.code = code
+
+
+def vms_config_default(n_traces, max_events, max_slots):
+    cfg = vms_config()
+    lib().vms_config_default(ctypes.byref(cfg), n_traces, max_events, max_slots)
+    return cfg
+
+
+def vms_strerror(code):
+    return lib().vms_strerror(code).decode()
+
+
+def vms_selftest():
+    return lib().vms_selftest()
+
+
+class Replay:
+    """One vms_replay handle.  Tensors are torch CUDA tensors; only their pointers cross the ABI."""
+
+    def __init__(self, cfg):
+        self.cfg = cfg
+        self._h = ctypes.c_void_p()
+        rc = lib().vms_replay_create(ctypes.byref(cfg), ctypes.byref(self._h))
+        if rc != VMS_OK:
+            self._h = None
+            raise VmsError(rc, "vms_replay_create")
+        self._ws = None
+
+    def workspace_bytes(self):
+        return int(lib().vms_replay_workspace_bytes(self._h))
+
+    def lds_bytes(self):
+        out = (ctypes.c_uint32 * 2)()
+        lib().vms_replay_lds_bytes(self._h, ctypes.byref(out))
+        return [int(out[0]), int(out[1])]
+
+    def run(self, d_events, d_n_events=None, d_dec_split=None, d_dec_vms=None, stream=None):
+        """Enqueue one replay of d_events (int64/uint64 CUDA tensor [n_traces, max_events])."""
+        import torch
+        assert d_events.is_cuda and d_events.is_contiguous() and d_events.element_size() == 8
+        assert tuple(d_events.shape) == (self.cfg.n_traces, self.cfg.max_events)
+        for d in (d_dec_split, d_dec_vms):
+            assert d is None or (d.is_cuda and d.is_contiguous() and d.shape == d_events.shape
+                                 and d.element_size() == 8)
+        if d_n_events is not None:
+            assert d_n_events.is_cuda and d_n_events.is_contiguous() and d_n_events.element_size() == 4
+            assert d_n_events.numel() == self.cfg.n_traces
+        need = self.workspace_bytes()
+        if need and (self._ws is None or self._ws.numel() < need + 256):
+            self._ws = torch.empty(need + 256, dtype=torch.uint8, device=d_events.device)
+        ws_ptr = 0
+        if need:
+            ws_ptr = (self._ws.data_ptr() + 255) & ~255
+        s = torch.cuda.current_stream(d_events.device) if stream is None else stream
+        ptr = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
+        rc = lib().vms_replay_run(self._h, ptr(d_events), ptr(d_n_events), ptr(d_dec_split), ptr(d_dec_vms),
+                                  ctypes.c_void_p(ws_ptr) if ws_ptr else None, ctypes.c_void_p(s.cuda_stream))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_replay_run (hip error %d)" % lib().vms_replay_last_hip_error(self._h))
+
+    def stats(self):
+        """Statistics of the last run: numpy record array [2, n_traces] ([0] splitting, [1] VMS)."""
+        out = np.zeros((2, self.cfg.n_traces), dtype=STATS_DTYPE)
+        rc = lib().vms_replay_stats(self._h, out.ctypes.data, out.size)
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_replay_stats")
+        return out
+
+    def summary(self):
+        out = vms_summary()
+        rc = lib().vms_replay_summary(self._h, ctypes.byref(out))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_replay_summary")
+        return out
+
+    def last_kernel_ms(self):
+        out = (ctypes.c_float * 3)()
+        rc = lib().vms_replay_last_kernel_ms(self._h, ctypes.byref(out))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_replay_last_kernel_ms")
+        return dict(split=float(out[0]), vms=float(out[1]), total=float(out[2]))
+
+    def close(self):
+        if self._h:
+            lib().vms_replay_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

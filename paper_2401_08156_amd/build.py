@@ -1,0 +1,40 @@
+"""Compile the HIP library for gfx950 in-tree (hipcc cross-compiles without a GPU)."""
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(_HERE, "csrc")
+LIB = os.path.join(_HERE, "libvmsreplay.so")
+SOURCES = ["vms_replay.hip", "vms_demo.hip"]
+HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h"]
+
+HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-Wall",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+
+def _stale():
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    deps = [os.path.join(CSRC, s) for s in SOURCES + HEADERS]
+    return any(os.path.exists(d) and os.path.getmtime(d) > t for d in deps)
+
+
+def build(force=False, save_temps_dir=None):
+    """Build libvmsreplay.so next to this file; returns its path."""
+    if not force and not _stale():
+        return LIB
+    srcs = [os.path.join(CSRC, s) for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
+    cmd = ["hipcc"] + HIPCC_FLAGS + ["-o", LIB] + srcs
+    cwd = CSRC
+    if save_temps_dir:
+        os.makedirs(save_temps_dir, exist_ok=True)
+        cmd.append("--save-temps")
+        cwd = save_temps_dir
+    r = subprocess.run(cmd, cwd=cwd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if r.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    if out.strip():
+        print(out)
+    return LIB

@@ -1,0 +1,73 @@
+// Self-test of the wavefront primitives: each is compared, on the device, with a
+// serial evaluation of its definition by lane 0.  Every access is to a fixed
+// 256-entry LDS array, so the test cannot touch memory it does not own.
+#pragma once
+#include "wave_ops.hpp"
+#include "../../include/vms_replay.h"
+
+__global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
+{
+    __shared__ u32 in[64], out[64];
+    __shared__ u64 arr[256];
+    const u32 lane = lane_id();
+    u32 bad = 0;
+    for (u32 round = 0; round < 8; round++) {
+        u32 v = (lane * 2654435761u + round * 40503u) ^ (lane << (round & 7));
+        v = round == 7 ? 5u : (v >> (round * 3));
+        in[lane] = v;
+        wave_sync();
+        // minimum
+        u32 m = wave_min_u32(v), ref = 0xFFFFFFFFu;
+        for (int i = 0; i < 64; i++) ref = min(ref, in[i]);
+        if (m != ref) bad |= 1;
+        // inclusive scan
+        u32 tot, s = wave_scan_add(v & 0xFFFF, &tot);
+        out[lane] = s;
+        wave_sync();
+        u32 run = 0;
+        for (int i = 0; i < 64; i++) {
+            run += in[i] & 0xFFFF;
+            if (out[i] != run) bad |= 2;
+        }
+        if (tot != run) bad |= 4;
+        // ballot / rank / lane reads
+        u64 b = ballot((v & 1) != 0);
+        u32 below = 0;
+        for (u32 i = 0; i < lane; i++) below += in[i] & 1;
+        if (rank_in(b) != below) bad |= 8;
+        if (from_lane(v, (round * 9) & 63) != in[(round * 9) & 63]) bad |= 16;
+        wave_sync();
+    }
+    // sorted-array helpers on a descending array of 150 keys
+    for (u32 i = lane; i < 150; i += 64) arr[i] = (u64)(1000 - 3 * i) << 32;
+    wave_sync();
+    if (count_gt(arr, 150, (u64)700 << 32) != 100) bad |= 32;     // 1000-3i > 700  <=>  i < 100
+    u32 c1, c2;
+    count_gt2(arr, 150, ((u64)700 << 32) | 0xFFFFFFFFu, ((u64)700 << 32) - 1, &c1, &c2);
+    if (c1 != 100 || c2 != 101) bad |= 32;
+    shift_up(arr, 70, 150);
+    st_one(arr, 70u, (u64)12345);
+    wave_sync();
+    for (u32 i = 0; i < 151; i++) {
+        u64 want = i < 70 ? (u64)(1000 - 3 * i) << 32 : (i == 70 ? (u64)12345 : (u64)(1000 - 3 * (i - 1)) << 32);
+        if (arr[i] != want) bad |= 64;
+    }
+    shift_down(arr, 70, 151);
+    for (u32 i = 0; i < 150; i++)
+        if (arr[i] != (u64)(1000 - 3 * i) << 32) bad |= 128;
+    u64 any = ballot(bad != 0);
+    if (lane == 0) *fail = any ? (bad | 0x80000000u) : 0;
+    if (any && bad) atomicOr(fail, bad);
+}
+
+static int selftest_run()
+{
+    u32 *d = nullptr, h = 0xFFFFFFFFu;
+    if (hipMalloc((void **)&d, sizeof(u32)) != hipSuccess) return VMS_EHIP;
+    hipLaunchKernelGGL(selftest_kernel, dim3(1), dim3(64), 0, 0, d);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(&h, d, sizeof h, hipMemcpyDeviceToHost);
+    (void)hipFree(d);
+    if (e != hipSuccess) return VMS_EHIP;
+    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFF));
+}

@@ -1,0 +1,158 @@
+// Wavefront-wide primitives for gfx950 (wave64).  Every workgroup of the replay
+// kernels is exactly one wavefront, so "the wave" and "the workgroup" coincide
+// and all of these must be called from wave-uniform control flow (EXEC full).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+#define DI __device__ __forceinline__
+
+DI u32 lane_id() { return threadIdx.x; }
+
+// Other lanes' LDS/global writes become visible to this lane's later reads.
+// LDS operations of one wavefront execute in order, so no hardware wait is
+// needed; the fence only stops the compiler from caching values across it.
+DI void wave_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+DI u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+DI u32 first_lane(u64 mask) { return (u32)__builtin_ctzll(mask); }
+DI u32 popc64(u64 m) { return (u32)__builtin_popcountll(m); }
+
+// number of set bits of mask below this lane
+DI u32 rank_in(u64 mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
+}
+
+DI u32 uni(u32 v) { return __builtin_amdgcn_readfirstlane(v); }
+DI u64 uni64(u64 v)
+{
+    u32 lo = __builtin_amdgcn_readfirstlane((u32)v);
+    u32 hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
+    return ((u64)hi << 32) | lo;
+}
+DI u32 from_lane(u32 v, u32 lane) { return __builtin_amdgcn_readlane(v, lane); }
+DI u64 from_lane64(u64 v, u32 lane)
+{
+    u32 lo = __builtin_amdgcn_readlane((u32)v, lane);
+    u32 hi = __builtin_amdgcn_readlane((u32)(v >> 32), lane);
+    return ((u64)hi << 32) | lo;
+}
+
+// DPP lane permutations (all rows / banks enabled, out-of-range source reads 0)
+template <int CTRL>
+DI u32 dpp_zero(u32 v)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+DI u32 dpp_perm(u32 v)
+{
+    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
+}
+
+enum {
+    DPP_QUAD_XOR1 = 0xB1,       // quad_perm [1,0,3,2]
+    DPP_QUAD_XOR2 = 0x4E,       // quad_perm [2,3,0,1]
+    DPP_ROW_HALF_MIRROR = 0x141,
+    DPP_ROW_MIRROR = 0x140,
+    DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118
+};
+
+// minimum over the 64 lanes, returned wave-uniform
+DI u32 wave_min_u32(u32 v)
+{
+    v = min(v, dpp_perm<DPP_QUAD_XOR1>(v));
+    v = min(v, dpp_perm<DPP_QUAD_XOR2>(v));
+    v = min(v, dpp_perm<DPP_ROW_HALF_MIRROR>(v));
+    v = min(v, dpp_perm<DPP_ROW_MIRROR>(v));          // every lane: minimum of its row of 16
+    u32 a = from_lane(v, 0), b = from_lane(v, 16), c = from_lane(v, 32), d = from_lane(v, 48);
+    return min(min(a, b), min(c, d));
+}
+
+// inclusive prefix sum over the 64 lanes; *total receives the wave sum (uniform)
+DI u32 wave_scan_add(u32 v, u32 *total)
+{
+    v += dpp_zero<DPP_ROW_SHR1>(v);
+    v += dpp_zero<DPP_ROW_SHR2>(v);
+    v += dpp_zero<DPP_ROW_SHR4>(v);
+    v += dpp_zero<DPP_ROW_SHR8>(v);                    // inclusive scan inside each row of 16
+    u32 t0 = from_lane(v, 15), t1 = from_lane(v, 31), t2 = from_lane(v, 47), t3 = from_lane(v, 63);
+    u32 row = lane_id() >> 4;
+    u32 add = row == 0 ? 0u : (row == 1 ? t0 : (row == 2 ? t0 + t1 : t0 + t1 + t2));
+    *total = t0 + t1 + t2 + t3;
+    return v + add;
+}
+
+// ---- arrays of one trace, shared by the 64 lanes ---------------------------
+
+// read one element at a wave-uniform index; result is wave-uniform
+DI u32 ld_uni(const u32 *a, u32 i) { return uni(a[i]); }
+DI u64 ld_uni(const u64 *a, u32 i) { return uni64(a[i]); }
+
+template <class T>
+DI void st_one(T *a, u32 i, T v)
+{
+    if (lane_id() == 0) a[i] = v;
+}
+
+// number of elements of a[0..n) that are greater than key
+DI u32 count_gt(const u64 *a, u32 n, u64 key)
+{
+    u32 c = 0;
+    for (u32 base = 0; base < n; base += 64) {
+        u32 i = base + lane_id();
+        bool p = i < n && a[i] > key;
+        c += popc64(ballot(p));
+    }
+    return c;
+}
+
+// same for two keys in one pass (k1 >= k2, hence c1 <= c2)
+DI void count_gt2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *c1, u32 *c2)
+{
+    u32 x = 0, y = 0;
+    for (u32 base = 0; base < n; base += 64) {
+        u32 i = base + lane_id();
+        u64 v = i < n ? a[i] : 0;
+        x += popc64(ballot(i < n && v > k1));
+        y += popc64(ballot(i < n && v > k2));
+    }
+    *c1 = x;
+    *c2 = y;
+}
+
+// a[pos..n) -> a[pos+1..n+1), highest tile first
+template <class T>
+DI void shift_up(T *a, u32 pos, u32 n)
+{
+    for (u32 hi = n; hi > pos;) {
+        u32 lo = hi - pos > 64 ? hi - 64 : pos;
+        u32 i = lo + lane_id();
+        bool v = i < hi;
+        T x = v ? a[i] : T(0);
+        if (v) a[i + 1] = x;
+        hi = lo;
+    }
+    wave_sync();
+}
+
+// a[pos+1..n) -> a[pos..n-1), lowest tile first
+template <class T>
+DI void shift_down(T *a, u32 pos, u32 n)
+{
+    for (u32 lo = pos + 1; lo < n; lo += 64) {
+        u32 i = lo + lane_id();
+        bool v = i < n;
+        T x = v ? a[i] : T(0);
+        if (v) a[i - 1] = x;
+    }
+    wave_sync();
+}

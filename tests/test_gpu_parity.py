@@ -1,0 +1,72 @@
+"""GPU parity: the HIP replay (through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import gpu_util
+import oracle
+from paper_2401_08156_amd import binding
+from paper_2401_08156_amd import tracegen as tg
+
+pytestmark = pytest.mark.gpu
+MiB = 1 << 20
+
+
+def test_wave_primitives_selftest():
+    assert binding.vms_selftest() == 0
+
+
+def test_config1_full():
+    ev, ms = tg.generate(1)
+    cfg = gpu_util.make_cfg(1, ev.shape[1], ms)
+    st = gpu_util.assert_parity(ev, cfg, label="config 1")
+    assert st["status"].max() == 0
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(frag_limit_bytes=8 * MiB), dict(spool_threshold=8),
+                                dict(capacity_bytes=512 * MiB), dict(small_limit_bytes=0)])
+def test_config1_variants_many_seeds(kw):
+    ev, ms = tg.generate(1, n_traces=96, n_events=1500, seed=11)
+    cfg = gpu_util.make_cfg(96, 1500, ms, **kw)
+    gpu_util.assert_parity(ev, cfg, label="config 1 %s" % kw)
+
+
+def test_worked_examples_on_gpu():
+    import glob
+    import os
+    from test_oracle_examples import load_fixture, GOLDEN
+    for path in sorted(glob.glob(os.path.join(GOLDEN, "*.txt"))):
+        fx = load_fixture(path)
+        ev = fx["events"][None, :]
+        gpu_util.assert_parity(ev, gpu_util.make_cfg(1, ev.shape[1], 16), label=os.path.basename(path))
+
+
+def test_ragged_and_empty_traces():
+    ev, ms = tg.generate(1, n_traces=70, n_events=333, seed=5)
+    n = (np.arange(70) * 37 % 334).astype(np.uint32)
+    n[0], n[1], n[2] = 0, 1, 333
+    cfg = gpu_util.make_cfg(70, 333, ms)
+    gpu_util.assert_parity(ev, cfg, n_events=n, label="ragged")
+
+
+def test_invalid_events_and_oom():
+    ev = tg.make_events([("A", 0, 4 * MiB), ("A", 0, 2 * MiB), ("F", 3), ("A", 99, 2 * MiB), ("F", 0),
+                         ("A", 1, 64 * MiB), ("F", 1), ("A", 2, 1024), ("F", 2)])
+    ev = np.concatenate([ev, np.array([(1 << 32) | 0], dtype=np.uint64)])[None, :]
+    cfg = gpu_util.make_cfg(1, ev.shape[1], 8, capacity_bytes=16 * MiB)
+    st = gpu_util.assert_parity(ev, cfg, label="invalid/oom")
+    assert st["status"][0, 0] == 1 and st["n_code"][1, 0, 5] == 1
+
+
+@pytest.mark.parametrize("cfg_id,nt,ne", [(2, 48, 4000), (4, 24, 6000)])
+def test_transformer_slices(cfg_id, nt, ne):
+    ev, ms = tg.generate(cfg_id, n_traces=nt, n_events=ne)
+    cfg = gpu_util.make_cfg(nt, ne, ms)
+    gpu_util.assert_parity(ev, cfg, label="config %d slice" % cfg_id)
+
+
+def test_table_overflow_is_reported_not_fatal():
+    ev, ms = tg.generate(1, n_traces=4, n_events=1000, seed=3)
+    cfg = gpu_util.make_cfg(4, 1000, ms, max_free_blocks=4, max_pblocks=8)
+    _, _, st = gpu_util.gpu_replay(ev, cfg)
+    assert (st["status"] & binding.VMS_ST_TABLE_OVERFLOW).all()
+    assert (st["overflow_event"] < 1000).all()
