@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark: allocator events replayed per second (splitting + stitching policies) on one MI355X.
+
+A step is one vms_replay_run over the whole workload: every trace replayed under both
+policies, events resident in HBM, decision words and statistics written to HBM.
+Prints one JSON line ("Measurement").
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# per-config engine table sizes (per trace); see DESIGN.md "Data layout"
+TABLES = {
+    1: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=4096, max_chunks=8192),
+    2: dict(max_free_blocks=256, max_pblocks=640, max_sblocks=640, max_runs=3072, max_chunks=4096),
+    4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=3072, max_chunks=24576),
+}
+WORKLOAD_NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "config4-lora",
+                  5: "config5-mixture"}
+HBM_PEAK_GBS = 8000.0
+BYTES_PER_EVENT_PER_KERNEL = 16       # 8 B event word read + 8 B decision word written
+
+
+def cpu_baseline(events, cfg_kw, max_slots, sample_traces):
+    """The oracle, as it stands, on a bounded sample of the same workload, all host cores."""
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    ev = events[:sample_traces]
+    P = oracle.make_params(max_slots, **cfg_kw)
+    t0 = time.perf_counter()
+    for pol in (oracle.SPLIT, oracle.VMS):
+        oracle.replay(ev, P, pol, want_decisions=True, threads=cores)
+    dt = time.perf_counter() - t0
+    return dict(value=ev.size / dt, unit="events/s", cores=min(cores, sample_traces), kind="oracle",
+                sample="%d of %d traces x %d events, both policies, decisions written" % (
+                    ev.shape[0], events.shape[0], ev.shape[1]))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="workload (default: config 2, the transformer step with recomputation)")
+    ap.add_argument("--traces", type=int, default=None)
+    ap.add_argument("--events", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=256)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (traces are independent; see DESIGN.md for how "
+              "it would shard); rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2401_08156_amd import binding
+    from paper_2401_08156_amd import tracegen as tg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = torch.device("cuda:0")
+
+    base = tg.CONFIGS[args.config]
+    n_traces = args.traces or base["n_traces"]
+    n_events = args.events or base["n_events"]
+    events, max_slots = tg.generate(args.config, n_traces=n_traces, n_events=n_events, threads=16)
+    cfg = binding.vms_config_default(n_traces, n_events, max_slots)
+    cfg.capacity_bytes = base["capacity_bytes"]
+    for k, v in TABLES.get(args.config, {}).items():
+        setattr(cfg, k, v)
+
+    d_events = torch.from_numpy(events.view(np.int64)).to(dev)
+    d_dec_split = torch.empty_like(d_events)
+    d_dec_vms = torch.empty_like(d_events)
+    rep = binding.Replay(cfg)
+    stream = torch.cuda.current_stream(dev)
+
+    for _ in range(args.warmup):
+        rep.run(d_events, None, d_dec_split, d_dec_vms, stream)
+    torch.cuda.synchronize()
+    kernel_ms = dict(split=0.0, vms=0.0, total=0.0)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        rep.run(d_events, None, d_dec_split, d_dec_vms, stream)
+        # HIP events recorded by the library on this stream around each kernel; reading them waits
+        # for the step, which is also what serialises steps on one handle
+        ms = rep.last_kernel_ms()
+        for k in kernel_ms:
+            kernel_ms[k] += ms[k]
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    for k in kernel_ms:
+        kernel_ms[k] /= max(args.steps, 1)
+
+    st = rep.stats()
+    summ = rep.summary()
+    flagged = int((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=1).sum())
+    if flagged:
+        print("bench.py: engine tables overflowed; the measurement is invalid", file=sys.stderr)
+        sys.exit(1)
+
+    total_events = n_traces * n_events
+    ms_per_step = dt / args.steps * 1e3
+    dom = "vms" if kernel_ms["vms"] >= kernel_ms["split"] else "split"
+    algo_bytes = BYTES_PER_EVENT_PER_KERNEL * total_events
+    achieved = algo_bytes / (kernel_ms[dom] * 1e-3) / 1e9
+    lds = rep.lds_bytes()
+    out = {
+        "metric": "allocator events replayed/sec (split + VMS) on 1 MI355X; bit-exact peaks vs oracle",
+        "value": total_events / (dt / args.steps),
+        "unit": "events/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": WORKLOAD_NAMES[args.config], "n_traces": n_traces, "n_events": n_events,
+                   "policies": "split+vms", "chunk_bytes": int(cfg.chunk_bytes),
+                   "spool_threshold": int(cfg.spool_threshold), "frag_limit_bytes": int(cfg.frag_limit_bytes),
+                   "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
+        "kernel_ms": kernel_ms,
+        "roofline": {"bound": "hbm", "kernel": "replay_kernel<%d> (%s policy)" % (1 if dom == "vms" else 0, dom),
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": None,
+                     "note": "latency/issue-bound serial state machine per trace; algorithmic bytes = 16 B per event "
+                             "(8 B event read + 8 B decision written) x events per launch"},
+        "table_high_water": {k: int(st[k].max()) for k in ("max_free_blocks", "max_pblocks", "max_sblocks", "max_runs",
+                                                            "max_members")},
+        "results": {"mean_fragmentation_split": summ.mean_fragmentation[0],
+                    "mean_fragmentation_vms": summ.mean_fragmentation[1],
+                    "mem_reduction_ratio": summ.mem_reduction_ratio},
+    }
+    if not args.no_cpu_baseline:
+        kw = dict(capacity_bytes=int(cfg.capacity_bytes), spool_threshold=int(cfg.spool_threshold),
+                  frag_limit_bytes=int(cfg.frag_limit_bytes), small_limit_bytes=int(cfg.small_limit_bytes),
+                  chunk_bytes=int(cfg.chunk_bytes))
+        out["cpu_baseline"] = cpu_baseline(events, kw, max_slots, min(args.cpu_sample, n_traces))
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -30,6 +30,7 @@ struct KParams {
     u32 off_slot_req, off_slot_a, off_slot_b, off_fl, off_pool, off_bmp, off_skey, off_smeta, off_sstamp,
         off_arena, off_cnt;
     u32 lds_bytes;
+    u32 run_len_bits;           // see VmsD::arena
     u64 ws_stride;              // workspace bytes per trace (sBlock run compaction buffer)
 };
 
@@ -136,6 +137,7 @@ DI SplitRes sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, 
         u64 rest = ((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1);
         st_one(sp.fl, sp.n, rest);
         sp.n++;
+        A.hw_free = max(A.hw_free, sp.n);
         wave_sync();
         r.flags &= 2;
         r.split = true;
@@ -199,6 +201,7 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         }
         st_one(sp.fl, sp.n, key);
         sp.n++;
+        A.hw_free = max(A.hw_free, sp.n);
     }
     wave_sync();
 }
@@ -213,18 +216,36 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //            of all its chunk runs are clear (Sec. 3.2: one active pBlock makes the sBlock active).
 //            Handing out / releasing any block is therefore only bit-range work.
 //   skey[]   sBlocks as key  size << 32 | ~creation_number, sorted descending (size descending,
-//            then older first), with smeta[] = arena offset << 32 | run count, sstamp[] = last use.
-//   arena[]  chunk runs (first_chunk << 32 | chunks) of all cached sBlocks, bump-allocated;
-//            compacted through a global-memory buffer when full.
+//            then older first), with smeta[] = arena offset << 16 | run count, sstamp[] = last use.
+//   arena[]  chunk runs of all cached sBlocks, bump-allocated, 32 bits each:
+//            first_chunk << len_bits | (chunks - 1); a longer run takes several entries.
+//            Compacted through a global-memory buffer when full.
 // ---------------------------------------------------------------------------
 struct VmsD {
     u64 *pool;
     u32 *bmp;
-    u64 *skey, *smeta;
-    u32 *sstamp;
-    u64 *arena, *bounce;
+    u64 *skey;
+    u32 *smeta, *sstamp;
+    u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_runs, next_sid, clock;
+    u32 len_bits;               // low bits of a run entry holding chunks - 1
 };
+
+DI u32 run_start(const VmsD &V, u32 run) { return run >> V.len_bits; }
+DI u32 run_end(const VmsD &V, u32 run) { return (run >> V.len_bits) + (run & ((1u << V.len_bits) - 1u)) + 1u; }
+DI u32 run_entries(const VmsD &V, u32 len) { return (len + (1u << V.len_bits) - 1u) >> V.len_bits; }
+
+// write the entries of one run (wave-uniform arguments) at arena[at..]; returns how many
+DI u32 arena_put(VmsD &V, u32 at, u32 start, u32 len)
+{
+    const u32 n = run_entries(V, len), q = lane_id(), maxlen = 1u << V.len_bits;
+    if (q < n) {
+        u32 l = min(maxlen, len - q * maxlen);
+        V.arena[at + q] = ((start + q * maxlen) << V.len_bits) | (l - 1u);
+    }
+    wave_sync();
+    return n;
+}
 
 DI bool bmp_test(const u32 *bmp, u32 c) { return (bmp[c >> 5] >> (c & 31)) & 1u; }
 
@@ -250,49 +271,74 @@ DI void bmp_fill(u32 *bmp, u32 start, u32 len, bool set)
     wave_sync();
 }
 
-// many runs, one lane per run (runs may share a word: atomics)
-DI void bmp_fill_runs(u32 *bmp, const u64 *runs, u32 cnt, bool set)
+// all runs of one sBlock, one lane per run (runs may share a word: atomics)
+DI void bmp_fill_runs(const VmsD &V, u32 off, u32 cnt, bool set)
 {
     for (u32 rb = 0; rb < cnt; rb += 64) {
         u32 r = rb + lane_id();
         if (r < cnt) {
-            u64 run = runs[r];
-            u32 start = (u32)(run >> 32), end = start + (u32)run;
+            u32 run = V.arena[off + r];
+            u32 start = run_start(V, run), end = run_end(V, run);
             for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
                 u32 m = word_mask(w, start, end);
-                if (set) atomicOr(&bmp[w], m);
-                else atomicAnd(&bmp[w], ~m);
+                if (set) atomicOr(&V.bmp[w], m);
+                else atomicAnd(&V.bmp[w], ~m);
             }
         }
     }
     wave_sync();
 }
 
-DI bool sblock_inactive(const VmsD &V, u32 s)
+// Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
+// sBlocks side by side): walks the runs and tests the bitmap words they cover.
+DI bool sblock_inactive_lane(const VmsD &V, u32 i)
 {
-    u64 meta = ld_uni(V.smeta, s);
-    const u64 *runs = V.arena + (u32)(meta >> 32);
-    u32 cnt = (u32)meta;
-    for (u32 rb = 0; rb < cnt; rb += 64) {
-        u32 r = rb + lane_id();
-        bool busy = false;
-        if (r < cnt) {
-            u64 run = runs[r];
-            u32 start = (u32)(run >> 32), end = start + (u32)run;
-            for (u32 w = start >> 5; w <= (end - 1) >> 5 && !busy; w++) busy = (V.bmp[w] & word_mask(w, start, end)) != 0;
-        }
-        if (ballot(busy)) return false;
+    u32 meta = V.smeta[i];
+    const u32 *runs = V.arena + (meta >> 16);
+    u32 cnt = meta & 0xFFFFu;
+    for (u32 r = 0; r < cnt; r++) {
+        u32 run = runs[r];
+        u32 start = run_start(V, run), end = run_end(V, run);
+        for (u32 w = start >> 5; w <= (end - 1) >> 5; w++)
+            if (V.bmp[w] & word_mask(w, start, end)) return false;
     }
     return true;
 }
 
-DI void pool_insert(VmsD &V, u32 size, u32 start)
+// First inactive sBlock among skey[slo, shi) (pool order), or NONE32.  Sixteen candidates are
+// tested side by side, four lanes per candidate, each lane taking every fourth chunk run.
+DI u32 first_inactive_sblock(const VmsD &V, u32 slo, u32 shi)
+{
+    const u32 lane = lane_id(), sub = lane & 3, grp = lane >> 2;
+    for (u32 base = slo; base < shi; base += 16) {
+        const u32 i = base + grp;
+        const bool valid = i < shi;
+        const u32 meta = valid ? V.smeta[i] : 0;
+        const u32 *runs = V.arena + (meta >> 16);
+        const u32 cnt = meta & 0xFFFFu;
+        bool busy = false;
+        for (u32 r = sub; r < cnt && !busy; r += 4) {
+            u32 run = runs[r];
+            u32 start = run_start(V, run), end = run_end(V, run);
+            for (u32 w = start >> 5; w <= (end - 1) >> 5 && !busy; w++) busy = (V.bmp[w] & word_mask(w, start, end)) != 0;
+        }
+        u64 b = ballot(busy);
+        b |= b >> 1;
+        b |= b >> 2;                                    // bit 4g: some lane of candidate g saw an active chunk
+        const u64 free16 = ballot(valid && sub == 0) & ~b;
+        if (free16) return base + (first_lane(free16) >> 2);
+    }
+    return NONE32;
+}
+
+DI void pool_insert(VmsD &V, u32 size, u32 start, Acct &A)
 {
     u64 key = ((u64)size << 32) | (u32)~start;
-    u32 pos = count_gt(V.pool, V.np, key);
+    u32 pos = rank_desc(V.pool, V.np, key);
     shift_up(V.pool, pos, V.np);
     st_one(V.pool, pos, key);
     V.np++;
+    A.hw_pblocks = max(A.hw_pblocks, V.np);
     wave_sync();
 }
 
@@ -303,25 +349,26 @@ DI void pool_remove(VmsD &V, u32 idx)
 }
 
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The runs are already in the arena.
-DI void spool_insert(VmsD &V, u32 size, u32 off, u32 cnt)
+DI void spool_insert(VmsD &V, u32 size, u32 off, u32 cnt, Acct &A)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
-    u32 pos = count_gt(V.skey, V.ns, key);
+    u32 pos = rank_desc(V.skey, V.ns, key);
     shift_up(V.skey, pos, V.ns);
     shift_up(V.smeta, pos, V.ns);
     shift_up(V.sstamp, pos, V.ns);
     st_one(V.skey, pos, key);
-    st_one(V.smeta, pos, ((u64)off << 32) | cnt);
+    st_one(V.smeta, pos, (off << 16) | cnt);
     st_one(V.sstamp, pos, ++V.clock);
     V.ns++;
     V.live_runs += cnt;
+    A.n_created++;
     wave_sync();
 }
 
 DI void spool_remove(VmsD &V, u32 idx)
 {
-    V.live_runs -= (u32)ld_uni(V.smeta, idx);
+    V.live_runs -= ld_uni(V.smeta, idx) & 0xFFFFu;
     shift_down(V.skey, idx, V.ns);
     shift_down(V.smeta, idx, V.ns);
     shift_down(V.sstamp, idx, V.ns);
@@ -334,10 +381,10 @@ DI void arena_compact(VmsD &V)
 {
     u32 top = 0;
     for (u32 s = 0; s < V.ns; s++) {
-        u64 meta = ld_uni(V.smeta, s);
-        u32 off = (u32)(meta >> 32), cnt = (u32)meta;
+        u32 meta = ld_uni(V.smeta, s);
+        u32 off = meta >> 16, cnt = meta & 0xFFFFu;
         for (u32 r = lane_id(); r < cnt; r += 64) V.bounce[top + r] = V.arena[off + r];
-        st_one(V.smeta, s, ((u64)top << 32) | cnt);
+        st_one(V.smeta, s, (top << 16) | cnt);
         top += cnt;
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");     // the copies below read other lanes' global writes
@@ -364,31 +411,27 @@ DI bool stitch_free(VmsD &V, const KParams &P, Acct &A)
     const u32 lane = lane_id();
     bool any = false;
     while (V.ns > P.spool_threshold) {
-        u32 prev = 0, victim = NONE32;
-        for (;;) {
-            u32 best = NONE32, besti = 0;       // oldest stamp above prev
-            for (u32 base = 0; base < V.ns; base += 64) {
-                u32 i = base + lane;
-                u32 s = i < V.ns ? V.sstamp[i] : NONE32;
-                if (s > prev && s < best) {
-                    best = s;
+        // every lane tests its own sBlocks; the oldest stamp among the inactive ones wins
+        u32 best = NONE32, besti = 0;
+        for (u32 base = 0; base < V.ns; base += 64) {
+            u32 i = base + lane;
+            if (i < V.ns) {
+                u32 st = V.sstamp[i];
+                if (st < best && sblock_inactive_lane(V, i)) {
+                    best = st;
                     besti = i;
                 }
             }
-            u32 m = wave_min_u32(best);
-            if (m == NONE32) break;
-            u32 idx = from_lane(besti, first_lane(ballot(best == m)));
-            if (sblock_inactive(V, idx)) {
-                victim = idx;
-                break;
-            }
-            prev = m;
         }
-        if (victim == NONE32) break;
+        u32 m = wave_min_u32(best);
+        if (m == NONE32) break;                 // everything cached is in use: the threshold stays exceeded
+        u32 victim = from_lane(besti, first_lane(ballot(best == m)));
         spool_remove(V, victim);
         A.n_evicted++;
         any = true;
     }
+    A.hw_sblocks = max(A.hw_sblocks, V.ns);     // high-water marks as seen between events
+    A.hw_runs = max(A.hw_runs, V.live_runs);
     return any;
 }
 
@@ -410,11 +453,11 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
     // ---- S1, stitched blocks: the run of equal sizes in skey[], oldest first
     {
         u32 slo, shi;
-        count_gt2(V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &slo, &shi);
-        for (u32 s = slo; s < shi; s++) {
-            if (!sblock_inactive(V, s)) continue;
-            u64 meta = ld_uni(V.smeta, s);
-            bmp_fill_runs(V.bmp, V.arena + (u32)(meta >> 32), (u32)meta, true);
+        rank_desc2(V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &slo, &shi);
+        const u32 s = first_inactive_sblock(V, slo, shi);
+        if (s != NONE32) {
+            u32 meta = ld_uni(V.smeta, s);
+            bmp_fill_runs(V, meta >> 16, meta & 0xFFFFu, true);
             st_one(V.sstamp, s, ++V.clock);
             wave_sync();
             R.kind = KIND_SBLOCK;
@@ -425,7 +468,7 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
     }
     // ---- S1, primitive blocks: pool[lo_p, hi_p) are the pBlocks of exactly bsize chunks
     u32 lo_p, hi_p;
-    count_gt2(V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &lo_p, &hi_p);
+    rank_desc2(V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &lo_p, &hi_p);
     for (u32 base = lo_p; base < hi_p; base += 64) {
         u32 i = base + lane;
         u64 key = i < hi_p ? V.pool[i] : 0;
@@ -438,6 +481,9 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
             return R;
         }
     }
+
+    // worst-case arena entries of the runs created below, beyond one per candidate
+    const u32 slack = 2u * ((P.cap_chunks >> V.len_bits) + 1u) + 2u;
 
     // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
     // pool order is the single-block candidate (state 2).
@@ -458,21 +504,19 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
                 R.dec = C_SPLIT | (1ull << 8) | ((u64)pstart << 32);
                 return R;
             }
-            if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks || !arena_reserve(V, 1, P, A, ev)) {
+            if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks || !arena_reserve(V, slack, P, A, ev)) {
                 table_overflow(A, ev);
                 R.dec = C_INVALID;
                 return R;
             }
             // S2: Split into the request and the rest; a stitched block keeps the uncut size on record
             pool_remove(V, idx);
-            pool_insert(V, bsize, pstart);
-            pool_insert(V, psize - bsize, pstart + bsize);
+            pool_insert(V, bsize, pstart, A);
+            pool_insert(V, psize - bsize, pstart + bsize, A);
             A.n_split++;
-            st_one(V.arena, V.top, ((u64)pstart << 32) | psize);
-            wave_sync();
-            spool_insert(V, psize, V.top, 1);
-            V.top += 1;
-            A.n_created++;
+            u32 n = arena_put(V, V.top, pstart, psize);
+            spool_insert(V, psize, V.top, n, A);
+            V.top += n;
             bmp_fill(V.bmp, pstart, bsize, true);
             R.ref = pstart;
             R.dec = C_SPLIT | B_6 | (1ull << 8) | ((u64)pstart << 32);
@@ -485,7 +529,7 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
     // Smaller blocks, largest first, until the request is covered (states 3 and 4).  Blocks
     // below the fragmentation limit sit at the tail of the pool and are never stitched.
     u32 lim = V.np;
-    if (P.frag_limit_chunks > 1) lim = count_gt(V.pool, V.np, ((u64)P.frag_limit_chunks << 32) - 1);
+    if (P.frag_limit_chunks > 1) lim = rank_desc(V.pool, V.np, ((u64)P.frag_limit_chunks << 32) - 1);
     u32 sum = 0, k = 0, pos = NONE32;
     for (u32 base = hi_p; base < lim; base += 64) {
         u32 i = base + lane;
@@ -517,7 +561,8 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
             return R;
         }
     }
-    if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, k + 2, P, A, ev)) {
+    if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks ||
+        !arena_reserve(V, k + (bsize >> V.len_bits) + slack, P, A, ev)) {
         table_overflow(A, ev);
         R.dec = C_INVALID;
         return R;
@@ -525,7 +570,7 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
     if (!s3 && k == 0) {
         // nothing cached is usable: the new pBlock serves the request directly
         u32 start = V.n_chunks;
-        pool_insert(V, deficit, start);
+        pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
         bmp_fill(V.bmp, start, deficit, true);
         R.ref = start;
@@ -533,24 +578,32 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
         return R;
     }
     // second pass: the candidates' chunk runs go to the arena in pool order
+    u32 cnt = 0;
     {
-        const u32 endi = s3 ? pos + 1 : lim;
-        u32 w = 0;
+        const u32 endi = s3 ? pos + 1 : lim, maxlen = 1u << V.len_bits;
         for (u32 base = hi_p; base < endi; base += 64) {
             u32 i = base + lane;
             u64 key = i < endi ? V.pool[i] : 0;
             bool inact = i < endi && !bmp_test(V.bmp, ~(u32)key);
+            u32 len = (u32)(key >> 32), start = ~(u32)key;
+            if (i == pos) len -= excess;
             u64 im = ballot(inact);
-            if (inact) {
-                u32 len = (u32)(key >> 32);
-                if (i == pos) len -= excess;
-                V.arena[V.top + w + rank_in(im)] = ((u64)(u32)~(u32)key << 32) | len;
+            if (ballot(inact && len > maxlen) == 0) {
+                if (inact) V.arena[V.top + cnt + rank_in(im)] = (start << V.len_bits) | (len - 1u);
+                cnt += popc64(im);
+            } else {
+                // some candidate is longer than one entry can describe
+                u32 ne = inact ? run_entries(V, len) : 0u, tot, incl = wave_scan_add(ne, &tot);
+                for (u32 q = 0; q < ne; q++) {
+                    u32 l = min(maxlen, len - q * maxlen);
+                    V.arena[V.top + cnt + incl - ne + q] = ((start + q * maxlen) << V.len_bits) | (l - 1u);
+                }
+                cnt += tot;
             }
-            w += popc64(im);
         }
         wave_sync();
     }
-    u32 cnt = k;
+    u32 used = cnt;             // arena entries consumed, including a restore block's
     R.dec = 0;
     if (s3) {
         if (excess) {
@@ -558,31 +611,28 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
             u64 qk = ld_uni(V.pool, pos);
             u32 qsize = (u32)(qk >> 32), qstart = ~(u32)qk;
             pool_remove(V, pos);
-            pool_insert(V, qsize - excess, qstart);
-            pool_insert(V, excess, qstart + qsize - excess);
+            pool_insert(V, qsize - excess, qstart, A);
+            pool_insert(V, excess, qstart + qsize - excess, A);
             A.n_split++;
-            st_one(V.arena, V.top + k, ((u64)qstart << 32) | qsize);
-            wave_sync();
-            spool_insert(V, qsize, V.top + k, 1);
-            A.n_created++;
+            u32 n = arena_put(V, V.top + cnt, qstart, qsize);
+            spool_insert(V, qsize, V.top + cnt, n, A);
+            used += n;
             R.dec |= B_6;
         }
         R.dec |= C_STITCH;
     } else {
         u32 start = V.n_chunks;                 // Alloc: exactly the missing chunks
-        pool_insert(V, deficit, start);
+        pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
-        st_one(V.arena, V.top + k, ((u64)start << 32) | deficit);
-        wave_sync();
-        cnt = k + 1;
+        cnt += arena_put(V, V.top + cnt, start, deficit);
+        used = cnt;
         R.dec |= C_GROW;
     }
     R.ref = V.next_sid;
-    spool_insert(V, bsize, V.top, cnt);
-    A.n_created++;
-    bmp_fill_runs(V.bmp, V.arena + V.top, cnt, true);
-    V.top += cnt + ((s3 && excess) ? 1u : 0u);
-    if (cnt > A.hw_members) A.hw_members = cnt;
+    spool_insert(V, bsize, V.top, cnt, A);
+    bmp_fill_runs(V, V.top, cnt, true);
+    V.top += used;
+    A.hw_members = max(A.hw_members, k + (s3 ? 0u : 1u));
     R.kind = KIND_SBLOCK;
     R.dec |= B_SBLOCK | ((u64)k << 8) | ((u64)R.ref << 32);
     if (stitch_free(V, P, A)) R.dec |= B_7;
@@ -596,9 +646,9 @@ DI void vms_free(VmsD &V, u32 kind, u32 ref, u32 held)
         bmp_fill(V.bmp, ref, held, false);
     } else {
         u64 key = ((u64)held << 32) | (u32)~ref;
-        u32 idx = count_gt(V.skey, V.ns, key);
-        u64 meta = ld_uni(V.smeta, idx);
-        bmp_fill_runs(V.bmp, V.arena + (u32)(meta >> 32), (u32)meta, false);
+        u32 idx = rank_desc(V.skey, V.ns, key);
+        u32 meta = ld_uni(V.smeta, idx);
+        bmp_fill_runs(V, meta >> 16, meta & 0xFFFFu, false);
     }
 }
 
@@ -618,7 +668,6 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
     u32 *slot_req = (u32 *)(lds + P.off_slot_req);
     u32 *slot_a = (u32 *)(lds + P.off_slot_a);
     u32 *slot_b = (u32 *)(lds + P.off_slot_b);
-    u32 *cnt = (u32 *)(lds + P.off_cnt);
 
     SplitPoolD sp;
     sp.fl = (u64 *)(lds + P.off_fl);
@@ -632,18 +681,19 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
         V.pool = (u64 *)(lds + P.off_pool);
         V.bmp = (u32 *)(lds + P.off_bmp);
         V.skey = (u64 *)(lds + P.off_skey);
-        V.smeta = (u64 *)(lds + P.off_smeta);
+        V.smeta = (u32 *)(lds + P.off_smeta);
         V.sstamp = (u32 *)(lds + P.off_sstamp);
-        V.arena = (u64 *)(lds + P.off_arena);
-        V.bounce = (u64 *)(workspace + (size_t)trace * P.ws_stride);
+        V.arena = (u32 *)(lds + P.off_arena);
+        V.bounce = (u32 *)(workspace + (size_t)trace * P.ws_stride);
+        V.len_bits = P.run_len_bits;
         for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
     }
     for (u32 i = lane; i < P.max_slots; i += 64) slot_req[i] = SLOT_UNBOUND;
-    if (lane < 8) cnt[lane] = 0;
     wave_sync();
 
     Acct A;
     acct_init(A);
+    u32 code_count = 0;
     const u32 chunk_units = 1u << P.chunk_shift;
     const u32 n_ev = n_events ? min(uni(n_events[trace]), P.max_events) : P.max_events;
     const u64 *ev_row = events + (size_t)trace * P.max_events;
@@ -699,6 +749,11 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
                             st_one(slot_req, slot, size);
                             A.requested += size;
                             A.active += held_units;
+                            // Sec. 5.1: active and reserved memory are recorded at their peaks; all
+                            // three totals can only rise on an allocation
+                            A.peak_requested = max(A.peak_requested, A.requested);
+                            A.peak_active = max(A.peak_active, A.active);
+                            A.peak_reserved = max(A.peak_reserved, sp.reserved + ((u64)V.n_chunks << P.chunk_shift));
                         }
                     }
                 } else if (req == SLOT_OOM) {
@@ -725,18 +780,11 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
             wave_sync();
             if (A.stop) break;
 
-            // accounting (Sec. 5.1: active and reserved memory, recorded at their peaks)
+            // accounting.  Lane c keeps the event count of decision code c (lane 7: invalid).
             const u32 code = (u32)dec & 15;
             if (code == C_INVALID) A.status |= VMS_ST_INVALID_EVENT;
-            if (lane == 0) atomicAdd(&cnt[code == C_INVALID ? 7 : code], 1u);
+            code_count += lane == (code == C_INVALID ? 7u : code) ? 1u : 0u;
             const u64 reserved = sp.reserved + ((u64)V.n_chunks << P.chunk_shift);
-            A.peak_requested = max(A.peak_requested, A.requested);
-            A.peak_active = max(A.peak_active, A.active);
-            A.peak_reserved = max(A.peak_reserved, reserved);
-            A.hw_free = max(A.hw_free, sp.n);
-            A.hw_pblocks = max(A.hw_pblocks, V.np);
-            A.hw_sblocks = max(A.hw_sblocks, V.ns);
-            A.hw_runs = max(A.hw_runs, V.live_runs);
             const u64 K = 0x9E3779B97F4A7C15ull;
             A.digest = (A.digest ^ dec) * K;
             A.digest = (A.digest ^ A.active) * K;
@@ -750,6 +798,7 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
     }
 
     wave_sync();
+    if (lane < 8) stats[(size_t)POLICY * P.n_traces + trace].n_code[lane] = code_count;
     if (lane == 0) {
         vms_trace_stats &s = stats[(size_t)POLICY * P.n_traces + trace];
         const u64 reserved = sp.reserved + ((u64)V.n_chunks << P.chunk_shift);
@@ -760,7 +809,6 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
         s.final_active = A.active * 512;
         s.final_reserved = reserved * 512;
         s.digest = A.digest;
-        for (int i = 0; i < 8; i++) s.n_code[i] = cnt[i];
         s.n_split = A.n_split;
         s.n_merge = A.n_merge;
         s.n_sblock_created = A.n_created;

@@ -45,6 +45,14 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
     u32 c1, c2;
     count_gt2(arr, 150, ((u64)700 << 32) | 0xFFFFFFFFu, ((u64)700 << 32) - 1, &c1, &c2);
     if (c1 != 100 || c2 != 101) bad |= 32;
+    for (u32 n = 1; n <= 150; n += (n < 70 ? 1 : 7)) {
+        for (u32 probe = 540; probe <= 1003; probe += 1) {
+            u64 key = ((u64)probe << 32) - 1;
+            u32 ref = count_gt(arr, n, key), r = rank_desc(arr, n, key), r1, r2;
+            rank_desc2(arr, n, key + ((u64)2 << 32), key, &r1, &r2);
+            if (r != ref || r2 != ref || r1 != count_gt(arr, n, key + ((u64)2 << 32))) bad |= 256;
+        }
+    }
     shift_up(arr, 70, 150);
     st_one(arr, 70u, (u64)12345);
     wave_sync();
@@ -69,5 +77,5 @@ static int selftest_run()
     if (e == hipSuccess) e = hipMemcpy(&h, d, sizeof h, hipMemcpyDeviceToHost);
     (void)hipFree(d);
     if (e != hipSuccess) return VMS_EHIP;
-    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFF));
+    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFFF));
 }

@@ -65,9 +65,9 @@ void layout(KParams &k, int policy, const vms_config &c)
         k.off_pool = take(c.max_pblocks * 8);
         k.off_bmp = take((c.max_chunks + 31) / 32 * 4);
         k.off_skey = take(c.max_sblocks * 8);
-        k.off_smeta = take(c.max_sblocks * 8);
+        k.off_smeta = take(c.max_sblocks * 4);
         k.off_sstamp = take(c.max_sblocks * 4);
-        k.off_arena = take(c.max_runs * 8);
+        k.off_arena = take(c.max_runs * 4);
     } else {
         k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_arena = 0;
     }
@@ -110,7 +110,9 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (!is_pow2(c.chunk_bytes) || c.chunk_bytes < UNIT || c.chunk_bytes > (1ull << 30)) return VMS_EINVAL;
     if (c.small_limit_bytes > c.chunk_bytes || c.small_limit_bytes % UNIT) return VMS_EINVAL;
     if (c.frag_limit_bytes % c.chunk_bytes) return VMS_EINVAL;
-    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_chunks == 0) return VMS_EINVAL;
+    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_runs > 65536 || c.max_chunks == 0)
+        return VMS_EINVAL;
+    if (c.max_chunks > (1u << 24)) return VMS_EINVAL;
     if (c.max_sblocks < c.spool_threshold + 3) return VMS_EINVAL;
     if ((uint64_t)c.max_chunks * c.chunk_bytes > ENGINE_MAX_BYTES) return VMS_EINVAL;
     if ((uint64_t)c.n_traces * c.max_events > (1ull << 40)) return VMS_EINVAL;
@@ -140,7 +142,10 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.cap_runs = c.max_runs;
         k.cap_chunks = c.max_chunks;
         layout(k, p, c);
-        k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 8, 256) : 0;
+        k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 4, 256) : 0;
+        uint32_t start_bits = 1;
+        while ((1ull << start_bits) < c.max_chunks) start_bits++;
+        k.run_len_bits = 32 - start_bits;
         if ((c.policy_mask & (1u << p)) && k.lds_bytes > LDS_PER_CU) {
             delete h;
             return VMS_ETOOBIG;

@@ -129,6 +129,48 @@ DI void count_gt2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *c1, u32 *c2)
     *c2 = y;
 }
 
+// Rank of key in a[0..n) sorted in DESCENDING order: the number of elements greater than key.
+// 64-ary search: the lanes first probe every stride-th element, then the one block of
+// `stride` elements that contains the boundary (two dependent LDS reads for n <= 4096).
+DI u32 rank_desc(const u64 *a, u32 n, u64 key)
+{
+    const u32 lane = lane_id();
+    if (n <= 64) return popc64(ballot(lane < n && a[lane] > key));
+    if (n > 4096) return count_gt(a, n, key);
+    const u32 stride = (n + 63) >> 6;
+    const u32 pi = lane * stride;
+    const u32 c = popc64(ballot(pi < n && a[pi] > key));    // probes above key form a prefix
+    if (c == 0) return 0;
+    const u32 b0 = (c - 1) * stride;                         // a[b0] > key >= a[b0 + stride]
+    const u32 i = b0 + lane;
+    return b0 + popc64(ballot(lane < stride && i < n && a[i] > key));
+}
+
+// ranks of two keys (k1 >= k2, hence r1 <= r2) sharing the probe pass
+DI void rank_desc2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *r1, u32 *r2)
+{
+    const u32 lane = lane_id();
+    if (n <= 64) {
+        u64 v = lane < n ? a[lane] : 0;
+        *r1 = popc64(ballot(lane < n && v > k1));
+        *r2 = popc64(ballot(lane < n && v > k2));
+        return;
+    }
+    if (n > 4096) {
+        count_gt2(a, n, k1, k2, r1, r2);
+        return;
+    }
+    const u32 stride = (n + 63) >> 6;
+    const u32 pi = lane * stride;
+    const u64 pv = pi < n ? a[pi] : 0;
+    const u32 c1 = popc64(ballot(pi < n && pv > k1)), c2 = popc64(ballot(pi < n && pv > k2));
+    const u32 b1 = c1 ? (c1 - 1) * stride : 0, b2 = c2 ? (c2 - 1) * stride : 0;
+    const u32 i1 = b1 + lane, i2 = b2 + lane;
+    const u64 v1 = (lane < stride && i1 < n) ? a[i1] : 0, v2 = (lane < stride && i2 < n) ? a[i2] : 0;
+    *r1 = c1 ? b1 + popc64(ballot(lane < stride && i1 < n && v1 > k1)) : 0;
+    *r2 = c2 ? b2 + popc64(ballot(lane < stride && i2 < n && v2 > k2)) : 0;
+}
+
 // a[pos..n) -> a[pos+1..n+1), highest tile first
 template <class T>
 DI void shift_up(T *a, u32 pos, u32 n)
