@@ -7,6 +7,7 @@
 // Policies (GMLake, arXiv 2401.08156): the splitting caching allocator of
 // Sec. 2.2 and the stitching allocator of Sec. 3 and Sec. 4.1 (Algorithm 1).
 #pragma once
+#include <type_traits>
 #include "wave_ops.hpp"
 #include "../../include/vms_replay.h"
 
@@ -221,22 +222,35 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //            first_chunk << len_bits | (chunks - 1); a longer run takes several entries.
 //            Compacted through a global-memory buffer when full.
 // ---------------------------------------------------------------------------
-struct VmsD {
+// BIG: for traces whose sBlocks hold more chunk runs than LDS can take, the arena lives in the
+// trace's slice of the global workspace (the other arrays stay in LDS) and smeta[] widens to
+// arena offset << 32 | run count.
+template <bool BIG>
+struct VmsT {
+    typedef typename std::conditional<BIG, u64, u32>::type meta_t;
     u64 *pool;
     u32 *bmp;
     u64 *skey;
-    u32 *smeta, *sstamp;
+    meta_t *smeta;
+    u32 *sstamp;
     u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_runs, next_sid, clock;
     u32 len_bits;               // low bits of a run entry holding chunks - 1
+    static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
+    static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
+    static DI u32 cnt(meta_t m) { return BIG ? (u32)m : (u32)m & 0xFFFFu; }
 };
 
-DI u32 run_start(const VmsD &V, u32 run) { return run >> V.len_bits; }
-DI u32 run_end(const VmsD &V, u32 run) { return (run >> V.len_bits) + (run & ((1u << V.len_bits) - 1u)) + 1u; }
-DI u32 run_entries(const VmsD &V, u32 len) { return (len + (1u << V.len_bits) - 1u) >> V.len_bits; }
+template <bool BIG>
+DI u32 run_start(const VmsT<BIG> &V, u32 run) { return run >> V.len_bits; }
+template <bool BIG>
+DI u32 run_end(const VmsT<BIG> &V, u32 run) { return (run >> V.len_bits) + (run & ((1u << V.len_bits) - 1u)) + 1u; }
+template <bool BIG>
+DI u32 run_entries(const VmsT<BIG> &V, u32 len) { return (len + (1u << V.len_bits) - 1u) >> V.len_bits; }
 
 // write the entries of one run (wave-uniform arguments) at arena[at..]; returns how many
-DI u32 arena_put(VmsD &V, u32 at, u32 start, u32 len)
+template <bool BIG>
+DI u32 arena_put(VmsT<BIG> &V, u32 at, u32 start, u32 len)
 {
     const u32 n = run_entries(V, len), q = lane_id(), maxlen = 1u << V.len_bits;
     if (q < n) {
@@ -272,7 +286,8 @@ DI void bmp_fill(u32 *bmp, u32 start, u32 len, bool set)
 }
 
 // all runs of one sBlock, one lane per run (runs may share a word: atomics)
-DI void bmp_fill_runs(const VmsD &V, u32 off, u32 cnt, bool set)
+template <bool BIG>
+DI void bmp_fill_runs(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
 {
     for (u32 rb = 0; rb < cnt; rb += 64) {
         u32 r = rb + lane_id();
@@ -291,11 +306,12 @@ DI void bmp_fill_runs(const VmsD &V, u32 off, u32 cnt, bool set)
 
 // Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
 // sBlocks side by side): walks the runs and tests the bitmap words they cover.
-DI bool sblock_inactive_lane(const VmsD &V, u32 i)
+template <bool BIG>
+DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
 {
-    u32 meta = V.smeta[i];
-    const u32 *runs = V.arena + (meta >> 16);
-    u32 cnt = meta & 0xFFFFu;
+    auto meta = V.smeta[i];
+    const u32 *runs = V.arena + V.off(meta);
+    u32 cnt = V.cnt(meta);
     for (u32 r = 0; r < cnt; r++) {
         u32 run = runs[r];
         u32 start = run_start(V, run), end = run_end(V, run);
@@ -307,15 +323,16 @@ DI bool sblock_inactive_lane(const VmsD &V, u32 i)
 
 // First inactive sBlock among skey[slo, shi) (pool order), or NONE32.  Sixteen candidates are
 // tested side by side, four lanes per candidate, each lane taking every fourth chunk run.
-DI u32 first_inactive_sblock(const VmsD &V, u32 slo, u32 shi)
+template <bool BIG>
+DI u32 first_inactive_sblock(const VmsT<BIG> &V, u32 slo, u32 shi)
 {
     const u32 lane = lane_id(), sub = lane & 3, grp = lane >> 2;
     for (u32 base = slo; base < shi; base += 16) {
         const u32 i = base + grp;
         const bool valid = i < shi;
-        const u32 meta = valid ? V.smeta[i] : 0;
-        const u32 *runs = V.arena + (meta >> 16);
-        const u32 cnt = meta & 0xFFFFu;
+        const auto meta = valid ? V.smeta[i] : 0;
+        const u32 *runs = V.arena + V.off(meta);
+        const u32 cnt = V.cnt(meta);
         bool busy = false;
         for (u32 r = sub; r < cnt && !busy; r += 4) {
             u32 run = runs[r];
@@ -331,7 +348,8 @@ DI u32 first_inactive_sblock(const VmsD &V, u32 slo, u32 shi)
     return NONE32;
 }
 
-DI void pool_insert(VmsD &V, u32 size, u32 start, Acct &A)
+template <bool BIG>
+DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, Acct &A)
 {
     u64 key = ((u64)size << 32) | (u32)~start;
     u32 pos = rank_desc(V.pool, V.np, key);
@@ -342,14 +360,16 @@ DI void pool_insert(VmsD &V, u32 size, u32 start, Acct &A)
     wave_sync();
 }
 
-DI void pool_remove(VmsD &V, u32 idx)
+template <bool BIG>
+DI void pool_remove(VmsT<BIG> &V, u32 idx)
 {
     shift_down(V.pool, idx, V.np);
     V.np--;
 }
 
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The runs are already in the arena.
-DI void spool_insert(VmsD &V, u32 size, u32 off, u32 cnt, Acct &A)
+template <bool BIG>
+DI void spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
@@ -358,7 +378,7 @@ DI void spool_insert(VmsD &V, u32 size, u32 off, u32 cnt, Acct &A)
     shift_up(V.smeta, pos, V.ns);
     shift_up(V.sstamp, pos, V.ns);
     st_one(V.skey, pos, key);
-    st_one(V.smeta, pos, (off << 16) | cnt);
+    st_one(V.smeta, pos, V.pack(off, cnt));
     st_one(V.sstamp, pos, ++V.clock);
     V.ns++;
     V.live_runs += cnt;
@@ -366,9 +386,10 @@ DI void spool_insert(VmsD &V, u32 size, u32 off, u32 cnt, Acct &A)
     wave_sync();
 }
 
-DI void spool_remove(VmsD &V, u32 idx)
+template <bool BIG>
+DI void spool_remove(VmsT<BIG> &V, u32 idx)
 {
-    V.live_runs -= ld_uni(V.smeta, idx) & 0xFFFFu;
+    V.live_runs -= V.cnt(ld_uni(V.smeta, idx));
     shift_down(V.skey, idx, V.ns);
     shift_down(V.smeta, idx, V.ns);
     shift_down(V.sstamp, idx, V.ns);
@@ -377,24 +398,32 @@ DI void spool_remove(VmsD &V, u32 idx)
 
 // Squeeze the runs of evicted sBlocks out of the arena: copy the live lists to the
 // global buffer in sPool order, then back.
-DI void arena_compact(VmsD &V)
+template <bool BIG>
+DI void arena_compact(VmsT<BIG> &V)
 {
     u32 top = 0;
     for (u32 s = 0; s < V.ns; s++) {
-        u32 meta = ld_uni(V.smeta, s);
-        u32 off = meta >> 16, cnt = meta & 0xFFFFu;
+        auto meta = ld_uni(V.smeta, s);
+        u32 off = V.off(meta), cnt = V.cnt(meta);
         for (u32 r = lane_id(); r < cnt; r += 64) V.bounce[top + r] = V.arena[off + r];
-        st_one(V.smeta, s, (top << 16) | cnt);
+        st_one(V.smeta, s, V.pack(top, cnt));
         top += cnt;
     }
-    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "agent");     // the copies below read other lanes' global writes
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");     // later reads are of other lanes' global writes
     wave_sync();
-    for (u32 r = lane_id(); r < top; r += 64) V.arena[r] = __builtin_nontemporal_load(&V.bounce[r]);
+    if (BIG) {
+        u32 *t = V.arena;       // both halves are global: the copy becomes the arena
+        V.arena = V.bounce;
+        V.bounce = t;
+    } else {
+        for (u32 r = lane_id(); r < top; r += 64) V.arena[r] = V.bounce[r];
+    }
     V.top = top;
     wave_sync();
 }
 
-DI bool arena_reserve(VmsD &V, u32 need, const KParams &P, Acct &A, u32 ev)
+template <bool BIG>
+DI bool arena_reserve(VmsT<BIG> &V, u32 need, const KParams &P, Acct &A, u32 ev)
 {
     if (V.top + need > P.cap_runs && V.live_runs < V.top) arena_compact(V);
     if (V.top + need > P.cap_runs) {
@@ -406,7 +435,8 @@ DI bool arena_reserve(VmsD &V, u32 need, const KParams &P, Acct &A, u32 ev)
 
 // StitchFree (Sec. 3.3.2, Sec. 4.2.3): while more sBlocks than the threshold are cached,
 // release the least recently used one that is inactive.
-DI bool stitch_free(VmsD &V, const KParams &P, Acct &A)
+template <bool BIG>
+DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
 {
     const u32 lane = lane_id();
     bool any = false;
@@ -442,7 +472,8 @@ struct VmsRes {
 
 // One request of bsize chunks on the stitching path: S1 exact match, else BestFit's
 // second loop and the post-processing of its state (Sec. 4.1, Fig. 9).
-DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Acct &A, u32 ev)
+template <bool BIG>
+DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &P, Acct &A, u32 ev)
 {
     const u32 lane = lane_id();
     VmsRes R;
@@ -456,8 +487,8 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
         rank_desc2(V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &slo, &shi);
         const u32 s = first_inactive_sblock(V, slo, shi);
         if (s != NONE32) {
-            u32 meta = ld_uni(V.smeta, s);
-            bmp_fill_runs(V, meta >> 16, meta & 0xFFFFu, true);
+            auto meta = ld_uni(V.smeta, s);
+            bmp_fill_runs(V, V.off(meta), V.cnt(meta), true);
             st_one(V.sstamp, s, ++V.clock);
             wave_sync();
             R.kind = KIND_SBLOCK;
@@ -640,15 +671,16 @@ DI VmsRes vms_alloc(VmsD &V, u32 bsize, u64 reserved_units, const KParams &P, Ac
 }
 
 // Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks.
-DI void vms_free(VmsD &V, u32 kind, u32 ref, u32 held)
+template <bool BIG>
+DI void vms_free(VmsT<BIG> &V, u32 kind, u32 ref, u32 held)
 {
     if (kind == KIND_PBLOCK) {
         bmp_fill(V.bmp, ref, held, false);
     } else {
         u64 key = ((u64)held << 32) | (u32)~ref;
         u32 idx = rank_desc(V.skey, V.ns, key);
-        u32 meta = ld_uni(V.smeta, idx);
-        bmp_fill_runs(V, meta >> 16, meta & 0xFFFFu, false);
+        auto meta = ld_uni(V.smeta, idx);
+        bmp_fill_runs(V, V.off(meta), V.cnt(meta), false);
     }
 }
 
@@ -656,7 +688,7 @@ DI void vms_free(VmsD &V, u32 kind, u32 ref, u32 held)
 // The replay loop of one wavefront.  POLICY 0: splitting allocator only.
 // POLICY 1: stitching allocator with the splitting pool for small requests.
 // ---------------------------------------------------------------------------
-template <int POLICY>
+template <int POLICY, bool BIG>
 __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__restrict__ events,
                                                     const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
                                                     vms_trace_stats *__restrict__ stats, char *__restrict__ workspace)
@@ -675,16 +707,16 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
     sp.cap = P.cap_free;
     sp.reserved = 0;
 
-    VmsD V;
+    VmsT<BIG> V;
     V.np = V.ns = V.n_chunks = V.top = V.live_runs = V.next_sid = V.clock = 0;
     if (POLICY == 1) {
         V.pool = (u64 *)(lds + P.off_pool);
         V.bmp = (u32 *)(lds + P.off_bmp);
         V.skey = (u64 *)(lds + P.off_skey);
-        V.smeta = (u32 *)(lds + P.off_smeta);
+        V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
         V.sstamp = (u32 *)(lds + P.off_sstamp);
-        V.arena = (u32 *)(lds + P.off_arena);
         V.bounce = (u32 *)(workspace + (size_t)trace * P.ws_stride);
+        V.arena = BIG ? V.bounce + P.cap_runs : (u32 *)(lds + P.off_arena);
         V.len_bits = P.run_len_bits;
         for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
     }

@@ -23,9 +23,11 @@ bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 struct vms_replay {
     vms_config cfg;
     KParams kp[2];              // [0] splitting kernel, [1] stitching kernel
+    bool big;                   // sBlock chunk runs in global memory (see VmsT)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
-    hipEvent_t ev[4];           // start, after split kernel, after VMS kernel
+    hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
+    hipStream_t side;           // the splitting kernel runs here, beside the stitching kernel
     hipStream_t last_stream;
     int device;
     int last_hip;
@@ -48,7 +50,7 @@ int hip_fail(vms_replay *h, hipError_t e)
     } while (0)
 
 // Per-wave LDS layout.  The splitting kernel only needs the slot table and its free list.
-void layout(KParams &k, int policy, const vms_config &c)
+void layout(KParams &k, int policy, const vms_config &c, bool big)
 {
     uint32_t off = 0;
     auto take = [&](uint32_t bytes) {
@@ -65,9 +67,9 @@ void layout(KParams &k, int policy, const vms_config &c)
         k.off_pool = take(c.max_pblocks * 8);
         k.off_bmp = take((c.max_chunks + 31) / 32 * 4);
         k.off_skey = take(c.max_sblocks * 8);
-        k.off_smeta = take(c.max_sblocks * 4);
+        k.off_smeta = take(c.max_sblocks * (big ? 8 : 4));
         k.off_sstamp = take(c.max_sblocks * 4);
-        k.off_arena = take(c.max_runs * 4);
+        k.off_arena = big ? 0 : take(c.max_runs * 4);
     } else {
         k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_arena = 0;
     }
@@ -110,7 +112,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (!is_pow2(c.chunk_bytes) || c.chunk_bytes < UNIT || c.chunk_bytes > (1ull << 30)) return VMS_EINVAL;
     if (c.small_limit_bytes > c.chunk_bytes || c.small_limit_bytes % UNIT) return VMS_EINVAL;
     if (c.frag_limit_bytes % c.chunk_bytes) return VMS_EINVAL;
-    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_runs > 65536 || c.max_chunks == 0)
+    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_runs > (1u << 24) || c.max_chunks == 0)
         return VMS_EINVAL;
     if (c.max_chunks > (1u << 24)) return VMS_EINVAL;
     if (c.max_sblocks < c.spool_threshold + 3) return VMS_EINVAL;
@@ -121,6 +123,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (!h) return VMS_ENOMEM;
     memset(h, 0, sizeof *h);
     h->cfg = c;
+    h->big = c.max_runs > 16384;        // more than 64 KB of chunk runs per trace: keep them in HBM
     uint32_t shift = 0;
     while ((UNIT << shift) < c.chunk_bytes) shift++;
     const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)
@@ -141,8 +144,8 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.cap_sblocks = c.max_sblocks;
         k.cap_runs = c.max_runs;
         k.cap_chunks = c.max_chunks;
-        layout(k, p, c);
-        k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 4, 256) : 0;
+        layout(k, p, c, h->big);
+        k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 4 * (h->big ? 2 : 1), 256) : 0;
         uint32_t start_bits = 1;
         while ((1ull << start_bits) < c.max_chunks) start_bits++;
         k.run_len_bits = 32 - start_bits;
@@ -161,13 +164,17 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     // records of a policy that never runs stay zero; a run rewrites every record of its policies
     if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * 2 * (size_t)c.n_traces);
     if (e == hipSuccess) e = hipMalloc((void **)&h->d_summary, sizeof(vms_summary));
-    for (int i = 0; i < 3 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
+    for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)replay_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)replay_kernel<0, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)replay_kernel<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)replay_kernel<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)LDS_PER_CU);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)replay_kernel<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e != hipSuccess) {
         int rc = e == hipErrorOutOfMemory ? VMS_ENOMEM : VMS_EHIP;
@@ -196,21 +203,31 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     if ((c.policy_mask & VMS_POLICY_VMS) && h->ws_bytes && (!d_workspace || ((uintptr_t)d_workspace & 255)))
         return VMS_EWORKSPACE;
     hipStream_t st = (hipStream_t)hip_stream;
+    // Fork: the two policies are independent, so the short splitting kernel runs on a second
+    // stream beside the long stitching kernel and the caller's stream joins it at the end.
     HIP_TRY(h, hipEventRecord(h->ev[0], st));
-    // the stitching kernel is the long one: it goes first so that the short splitting
-    // waves fill the compute units it leaves idle towards its end
+    const bool both = c.policy_mask == (VMS_POLICY_SPLIT | VMS_POLICY_VMS);
+    hipStream_t sst = both ? h->side : st;
+    if (both) HIP_TRY(h, hipStreamWaitEvent(sst, h->ev[0], 0));
     if (c.policy_mask & VMS_POLICY_VMS) {
-        hipLaunchKernelGGL(replay_kernel<1>, dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1], d_events,
-                           d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+        if (h->big)
+            hipLaunchKernelGGL((replay_kernel<1, true>), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
+                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+        else
+            hipLaunchKernelGGL((replay_kernel<1, false>), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
+                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
+    HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL(replay_kernel<0>, dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, st, h->kp[0], d_events,
+        hipLaunchKernelGGL((replay_kernel<0, false>), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0], d_events,
                            d_n_events, d_dec_split, h->d_stats, (char *)nullptr);
         HIP_TRY(h, hipGetLastError());
     }
-    HIP_TRY(h, hipEventRecord(h->ev[2], st));
+    HIP_TRY(h, hipEventRecord(h->ev[3], sst));
+    if (both) HIP_TRY(h, hipStreamWaitEvent(st, h->ev[3], 0));
+    HIP_TRY(h, hipEventRecord(h->ev[4], st));
     h->last_stream = st;
     h->ran = true;
     return VMS_OK;
@@ -241,10 +258,10 @@ int vms_replay_last_kernel_ms(vms_replay *h, float out_ms[3])
 {
     if (!h || !out_ms) return VMS_EINVAL;
     if (!h->ran) return VMS_ESTATE;
-    HIP_TRY(h, hipEventSynchronize(h->ev[2]));
+    HIP_TRY(h, hipEventSynchronize(h->ev[4]));
     HIP_TRY(h, hipEventElapsedTime(&out_ms[1], h->ev[0], h->ev[1]));
-    HIP_TRY(h, hipEventElapsedTime(&out_ms[0], h->ev[1], h->ev[2]));
-    HIP_TRY(h, hipEventElapsedTime(&out_ms[2], h->ev[0], h->ev[2]));
+    HIP_TRY(h, hipEventElapsedTime(&out_ms[0], h->ev[2], h->ev[3]));
+    HIP_TRY(h, hipEventElapsedTime(&out_ms[2], h->ev[0], h->ev[4]));
     return VMS_OK;
 }
 
@@ -253,8 +270,9 @@ void vms_replay_destroy(vms_replay *h)
     if (!h) return;
     if (h->d_stats) (void)hipFree(h->d_stats);
     if (h->d_summary) (void)hipFree(h->d_summary);
-    for (int i = 0; i < 3; i++)
+    for (int i = 0; i < 5; i++)
         if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
+    if (h->side) (void)hipStreamDestroy(h->side);
     delete h;
 }
 

@@ -64,6 +64,30 @@ def test_transformer_slices(cfg_id, nt, ne):
     gpu_util.assert_parity(ev, cfg, label="config %d slice" % cfg_id)
 
 
+def test_runs_in_global_memory_variant():
+    # more than 16384 run entries per trace moves the sBlock chunk runs from LDS to the workspace
+    ev, ms = tg.generate(1, n_traces=64, n_events=2000, seed=21)
+    cfg = gpu_util.make_cfg(64, 2000, ms, max_runs=20000)
+    gpu_util.assert_parity(ev, cfg, label="config 1, runs in HBM")
+    # tiny arena in HBM: forces compaction through the second half of the workspace slice
+    ev, ms = tg.generate(2, n_traces=16, n_events=5000)
+    cfg = gpu_util.make_cfg(16, 5000, ms, max_runs=16500, spool_threshold=64)
+    gpu_util.assert_parity(ev, cfg, label="config 2, runs in HBM")
+
+
+def test_arena_compaction_in_lds():
+    ev, ms = tg.generate(2, n_traces=16, n_events=6000)
+    cfg = gpu_util.make_cfg(16, 6000, ms, max_runs=700, spool_threshold=96, max_sblocks=256)
+    gpu_util.assert_parity(ev, cfg, label="config 2, small arena")
+
+
+def test_config3_slice_with_large_tables():
+    # offloading traces grind pBlocks down to single chunks: thousands of pBlocks, long stitch lists
+    ev, ms = tg.generate(3, n_traces=12, n_events=8000)
+    cfg = gpu_util.make_cfg(12, 8000, ms, max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=16384)
+    gpu_util.assert_parity(ev, cfg, label="config 3 slice")
+
+
 def test_table_overflow_is_reported_not_fatal():
     ev, ms = tg.generate(1, n_traces=4, n_events=1000, seed=3)
     cfg = gpu_util.make_cfg(4, 1000, ms, max_free_blocks=4, max_pblocks=8)
