@@ -29,7 +29,7 @@ struct KParams {
     u32 cap_free, cap_pblocks, cap_sblocks, cap_runs, cap_chunks;
     // byte offsets of the per-wave arrays inside dynamic LDS
     u32 off_slot_req, off_slot_a, off_slot_b, off_fl, off_pool, off_bmp, off_skey, off_smeta, off_sstamp,
-        off_arena, off_cnt;
+        off_arena;
     u32 lds_bytes;
     u32 run_len_bits;           // see VmsD::arena
     u64 ws_stride;              // workspace bytes per trace (sBlock run compaction buffer)
@@ -305,18 +305,27 @@ DI void bmp_fill_runs(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
 }
 
 // Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
-// sBlocks side by side): walks the runs and tests the bitmap words they cover.
+// sBlocks side by side): walks the runs and tests the bitmap words they cover.  A run found
+// active is moved to the front of the list (the order of the runs carries no meaning here), so
+// the next look at a still-active sBlock usually ends at its first run.
 template <bool BIG>
 DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
 {
     auto meta = V.smeta[i];
-    const u32 *runs = V.arena + V.off(meta);
+    u32 *runs = V.arena + V.off(meta);
     u32 cnt = V.cnt(meta);
     for (u32 r = 0; r < cnt; r++) {
         u32 run = runs[r];
         u32 start = run_start(V, run), end = run_end(V, run);
-        for (u32 w = start >> 5; w <= (end - 1) >> 5; w++)
-            if (V.bmp[w] & word_mask(w, start, end)) return false;
+        for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
+            if (V.bmp[w] & word_mask(w, start, end)) {
+                if (r) {
+                    runs[r] = runs[0];
+                    runs[0] = run;
+                }
+                return false;
+            }
+        }
     }
     return true;
 }
@@ -331,20 +340,33 @@ DI u32 first_inactive_sblock(const VmsT<BIG> &V, u32 slo, u32 shi)
         const u32 i = base + grp;
         const bool valid = i < shi;
         const auto meta = valid ? V.smeta[i] : 0;
-        const u32 *runs = V.arena + V.off(meta);
+        u32 *runs = V.arena + V.off(meta);
         const u32 cnt = V.cnt(meta);
-        bool busy = false;
-        for (u32 r = sub; r < cnt && !busy; r += 4) {
+        u32 at = NONE32, busy_run = 0;                  // index and value of the active run this lane met
+        for (u32 r = sub; r < cnt && at == NONE32; r += 4) {
             u32 run = runs[r];
             u32 start = run_start(V, run), end = run_end(V, run);
-            for (u32 w = start >> 5; w <= (end - 1) >> 5 && !busy; w++) busy = (V.bmp[w] & word_mask(w, start, end)) != 0;
+            for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
+                if (V.bmp[w] & word_mask(w, start, end)) {
+                    at = r;
+                    busy_run = run;
+                    break;
+                }
+            }
         }
-        u64 b = ballot(busy);
+        const u64 found = ballot(at != NONE32);
+        // the first lane of a candidate that met an active run moves it to the front of the list
+        if (at != NONE32 && at != 0 && ((found >> (grp * 4)) & ((1u << sub) - 1u)) == 0) {
+            runs[at] = runs[0];
+            runs[0] = busy_run;
+        }
+        u64 b = found;
         b |= b >> 1;
         b |= b >> 2;                                    // bit 4g: some lane of candidate g saw an active chunk
         const u64 free16 = ballot(valid && sub == 0) & ~b;
         if (free16) return base + (first_lane(free16) >> 2);
     }
+    wave_sync();
     return NONE32;
 }
 

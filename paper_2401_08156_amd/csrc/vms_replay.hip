@@ -58,7 +58,6 @@ void layout(KParams &k, int policy, const vms_config &c, bool big)
         off = align_up(off + bytes, 16);
         return at;
     };
-    k.off_cnt = take(8 * 4);
     k.off_slot_req = take(c.max_slots * 4);
     k.off_slot_a = take(c.max_slots * 4);
     k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
