@@ -16,14 +16,6 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# per-config engine table sizes (per trace); see DESIGN.md "Data layout"
-TABLES = {
-    1: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=4096, max_chunks=8192),
-    2: dict(max_free_blocks=256, max_pblocks=640, max_sblocks=640, max_runs=3072, max_chunks=4096),
-    4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=3072, max_chunks=24576),
-}
-WORKLOAD_NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "config4-lora",
-                  5: "config5-mixture"}
 HBM_PEAK_GBS = 8000.0
 BYTES_PER_EVENT_PER_KERNEL = 16       # 8 B event word read + 8 B decision word written
 
@@ -60,7 +52,7 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2401_08156_amd import binding
+    from paper_2401_08156_amd import binding, workloads
     from paper_2401_08156_amd import tracegen as tg
 
     if not torch.cuda.is_available():
@@ -71,38 +63,47 @@ def main():
     base = tg.CONFIGS[args.config]
     n_traces = args.traces or base["n_traces"]
     n_events = args.events or base["n_events"]
-    events, max_slots = tg.generate(args.config, n_traces=n_traces, n_events=n_events, threads=16)
-    cfg = binding.vms_config_default(n_traces, n_events, max_slots)
-    cfg.capacity_bytes = base["capacity_bytes"]
-    for k, v in TABLES.get(args.config, {}).items():
-        setattr(cfg, k, v)
-
-    d_events = torch.from_numpy(events.view(np.int64)).to(dev)
-    d_dec_split = torch.empty_like(d_events)
-    d_dec_vms = torch.empty_like(d_events)
-    rep = binding.Replay(cfg)
+    # config 5 is replayed as three batches (one per generator kind, each with its own table sizes);
+    # every other config is one batch
+    kinds = [2, 3, 4] if args.config == 5 else [None]
+    batches = []
+    for b, kind in enumerate(kinds):
+        nt = len(range(b, n_traces, len(kinds)))
+        events, max_slots = tg.generate(args.config, n_traces=nt, n_events=n_events, first_trace=b,
+                                        trace_stride=len(kinds), threads=16)
+        cfg = workloads.make_config(binding, args.config, nt, n_events, max_slots, kind=kind)
+        d_events = torch.from_numpy(events.view(np.int64)).to(dev)
+        batches.append(dict(events=events, max_slots=max_slots, cfg=cfg, d_events=d_events,
+                            d_split=torch.empty_like(d_events), d_vms=torch.empty_like(d_events),
+                            rep=binding.Replay(cfg)))
     stream = torch.cuda.current_stream(dev)
 
+    def step(acc=None):
+        for bt in batches:
+            bt["rep"].run(bt["d_events"], None, bt["d_split"], bt["d_vms"], stream)
+            if acc is not None:
+                # HIP events recorded by the library on this stream around each kernel; reading them
+                # waits for the batch, which is also what serialises runs on one handle
+                ms = bt["rep"].last_kernel_ms()
+                for k in acc:
+                    acc[k] += ms[k]
+
     for _ in range(args.warmup):
-        rep.run(d_events, None, d_dec_split, d_dec_vms, stream)
+        step()
     torch.cuda.synchronize()
     kernel_ms = dict(split=0.0, vms=0.0, total=0.0)
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        rep.run(d_events, None, d_dec_split, d_dec_vms, stream)
-        # HIP events recorded by the library on this stream around each kernel; reading them waits
-        # for the step, which is also what serialises steps on one handle
-        ms = rep.last_kernel_ms()
-        for k in kernel_ms:
-            kernel_ms[k] += ms[k]
+        step(kernel_ms)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     for k in kernel_ms:
         kernel_ms[k] /= max(args.steps, 1)
 
-    st = rep.stats()
+    rep, cfg, events, max_slots = batches[0]["rep"], batches[0]["cfg"], batches[0]["events"], batches[0]["max_slots"]
+    st = np.concatenate([bt["rep"].stats() for bt in batches], axis=1)
     summ = rep.summary()
-    flagged = int((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=1).sum())
+    flagged = int((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=0).sum())
     if flagged:
         print("bench.py: engine tables overflowed; the measurement is invalid", file=sys.stderr)
         sys.exit(1)
@@ -121,10 +122,10 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
-        "config": {"workload": WORKLOAD_NAMES[args.config], "n_traces": n_traces, "n_events": n_events,
+        "config": {"workload": workloads.NAMES[args.config], "n_traces": n_traces, "n_events": n_events,
                    "policies": "split+vms", "chunk_bytes": int(cfg.chunk_bytes),
                    "spool_threshold": int(cfg.spool_threshold), "frag_limit_bytes": int(cfg.frag_limit_bytes),
-                   "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
+                   "batches": len(batches), "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": "replay_kernel<%d> (%s policy)" % (1 if dom == "vms" else 0, dom),
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -133,9 +134,9 @@ def main():
                              "(8 B event read + 8 B decision written) x events per launch"},
         "table_high_water": {k: int(st[k].max()) for k in ("max_free_blocks", "max_pblocks", "max_sblocks", "max_runs",
                                                             "max_members")},
-        "results": {"mean_fragmentation_split": summ.mean_fragmentation[0],
-                    "mean_fragmentation_vms": summ.mean_fragmentation[1],
-                    "mem_reduction_ratio": summ.mem_reduction_ratio},
+        "results": {"mean_fragmentation_split": float(st["fragmentation"][0].mean()),
+                    "mean_fragmentation_vms": float(st["fragmentation"][1].mean()),
+                    "mem_reduction_ratio_first_batch": summ.mem_reduction_ratio},
     }
     if not args.no_cpu_baseline:
         kw = dict(capacity_bytes=int(cfg.capacity_bytes), spool_threshold=int(cfg.spool_threshold),

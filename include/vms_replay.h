@@ -72,7 +72,13 @@ extern "C" {
 /* status bits of vms_trace_stats.status */
 #define VMS_ST_INVALID_EVENT   1u   /* at least one INVALID decision (a result, not a failure) */
 #define VMS_ST_TABLE_OVERFLOW  2u   /* an engine table (below) was too small: replay of this
-                                       trace stopped early, its results are not valid       */
+                                       trace stopped early, its results are not valid; one
+                                       of the following bits names the table                */
+#define VMS_ST_OVF_FREE_BLOCKS 4u
+#define VMS_ST_OVF_PBLOCKS     8u
+#define VMS_ST_OVF_SBLOCKS     16u
+#define VMS_ST_OVF_RUNS        32u
+#define VMS_ST_OVF_CHUNKS      64u
 
 typedef struct vms_config {
     uint32_t struct_size;        /* sizeof(vms_config)                                      */

@@ -56,9 +56,9 @@ DI void acct_init(Acct &A)
 }
 
 // An engine table is too small for this trace: stop replaying it.
-DI void table_overflow(Acct &A, u32 ev)
+DI void table_overflow(Acct &A, u32 ev, u32 which)
 {
-    A.status |= VMS_ST_TABLE_OVERFLOW;
+    A.status |= VMS_ST_TABLE_OVERFLOW | which;
     if (A.overflow_event == NONE32) A.overflow_event = ev;
     A.stop = true;
 }
@@ -132,7 +132,7 @@ DI SplitRes sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, 
     // step 2: cut off what is not needed; it stays cached as the right neighbour
     if (bsize > size) {
         if (sp.n == sp.cap) {
-            table_overflow(A, ev);
+            table_overflow(A, ev, VMS_ST_OVF_FREE_BLOCKS);
             return r;
         }
         u64 rest = ((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1);
@@ -197,7 +197,7 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         st_one(sp.fl, ridx, key);
     } else {
         if (sp.n == sp.cap) {
-            table_overflow(A, ev);
+            table_overflow(A, ev, VMS_ST_OVF_FREE_BLOCKS);
             return;
         }
         st_one(sp.fl, sp.n, key);
@@ -449,7 +449,7 @@ DI bool arena_reserve(VmsT<BIG> &V, u32 need, const KParams &P, Acct &A, u32 ev)
 {
     if (V.top + need > P.cap_runs && V.live_runs < V.top) arena_compact(V);
     if (V.top + need > P.cap_runs) {
-        table_overflow(A, ev);
+        table_overflow(A, ev, VMS_ST_OVF_RUNS);
         return false;
     }
     return true;
@@ -558,7 +558,7 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
                 return R;
             }
             if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks || !arena_reserve(V, slack, P, A, ev)) {
-                table_overflow(A, ev);
+                table_overflow(A, ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
                 R.dec = C_INVALID;
                 return R;
             }
@@ -609,14 +609,14 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
             return R;
         }
         if (V.n_chunks + deficit > P.cap_chunks) {
-            table_overflow(A, ev);
+            table_overflow(A, ev, VMS_ST_OVF_CHUNKS);
             R.dec = C_INVALID;
             return R;
         }
     }
     if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks ||
         !arena_reserve(V, k + (bsize >> V.len_bits) + slack, P, A, ev)) {
-        table_overflow(A, ev);
+        table_overflow(A, ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
         R.dec = C_INVALID;
         return R;
     }

@@ -49,14 +49,16 @@ def _load():
         build()
         _lib = ctypes.CDLL(_LIB)
         _lib.tracegen_fill.restype = ctypes.c_uint32
-        _lib.tracegen_fill.argtypes = [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32,
+        _lib.tracegen_fill.argtypes = [ctypes.c_int, ctypes.c_uint64, ctypes.c_uint32, ctypes.c_uint32,
                                        ctypes.c_uint32, ctypes.c_uint32, ctypes.c_void_p,
                                        ctypes.c_int]
     return _lib
 
 
-def generate(config, n_traces=None, n_events=None, seed=None, first_trace=0, threads=8, out=None):
-    """Return (events[n_traces, n_events] uint64, max_slots)."""
+def generate(config, n_traces=None, n_events=None, seed=None, first_trace=0, trace_stride=1, threads=8,
+             out=None):
+    """Return (events[n_traces, n_events] uint64, max_slots) for traces first_trace,
+    first_trace + trace_stride, ... of the configuration."""
     base = CONFIGS[config]
     n_traces = base["n_traces"] if n_traces is None else n_traces
     n_events = base["n_events"] if n_events is None else n_events
@@ -66,7 +68,7 @@ def generate(config, n_traces=None, n_events=None, seed=None, first_trace=0, thr
     assert out.dtype == np.uint64 and out.shape == (n_traces, n_events) and out.flags.c_contiguous
     if n_traces == 0:
         return out, 1
-    m = _load().tracegen_fill(config, seed, first_trace, n_traces, n_events,
+    m = _load().tracegen_fill(config, seed, first_trace, trace_stride, n_traces, n_events,
                               out.ctypes.data, threads)
     if m == 0:
         raise ValueError("tracegen_fill: bad argument")

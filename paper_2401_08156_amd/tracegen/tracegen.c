@@ -319,7 +319,7 @@ static uint32_t gen_one(int config, uint64_t seed, uint64_t trace, uint64_t *row
 typedef struct {
     int config;
     uint64_t seed;
-    uint32_t t0, t1, first_trace, n_events;
+    uint32_t t0, t1, first_trace, trace_stride, n_events;
     uint64_t *events;
     uint32_t max_slots;
 } job_t;
@@ -328,7 +328,7 @@ static void *worker(void *arg)
 {
     job_t *j = (job_t *)arg;
     for (uint32_t t = j->t0; t < j->t1; t++) {
-        uint32_t m = gen_one(j->config, j->seed, (uint64_t)j->first_trace + t,
+        uint32_t m = gen_one(j->config, j->seed, (uint64_t)j->first_trace + (uint64_t)t * j->trace_stride,
                              j->events + (size_t)t * j->n_events, j->n_events);
         if (m > j->max_slots) j->max_slots = m;
     }
@@ -337,15 +337,15 @@ static void *worker(void *arg)
 
 /*
  * Fill events[n_traces][n_events] (host memory, row-major) for traces
- * first_trace .. first_trace + n_traces - 1 of configuration `config`
+ * first_trace, first_trace + trace_stride, ... of configuration `config`
  * (1 random, 2 recompute, 3 offload, 4 LoRA, 5 even mixture of 2/3/4).
  * Returns the number of slots needed (1 + the largest slot used), or 0 on a
  * bad argument.  Every row holds exactly n_events events.
  */
-uint32_t tracegen_fill(int config, uint64_t seed, uint32_t first_trace, uint32_t n_traces,
-                       uint32_t n_events, uint64_t *events, int n_threads)
+uint32_t tracegen_fill(int config, uint64_t seed, uint32_t first_trace, uint32_t trace_stride,
+                       uint32_t n_traces, uint32_t n_events, uint64_t *events, int n_threads)
 {
-    if (config < 1 || config > 5 || !events || n_events == 0) return 0;
+    if (config < 1 || config > 5 || !events || n_events == 0 || trace_stride == 0) return 0;
     if (n_threads < 1) n_threads = 1;
     if (n_threads > 64) n_threads = 64;
     if ((uint32_t)n_threads > n_traces) n_threads = (int)(n_traces ? n_traces : 1);
@@ -357,6 +357,7 @@ uint32_t tracegen_fill(int config, uint64_t seed, uint32_t first_trace, uint32_t
         jobs[i].t0 = (uint32_t)((uint64_t)n_traces * i / n_threads);
         jobs[i].t1 = (uint32_t)((uint64_t)n_traces * (i + 1) / n_threads);
         jobs[i].first_trace = first_trace;
+        jobs[i].trace_stride = trace_stride;
         jobs[i].n_events = n_events;
         jobs[i].events = events;
         jobs[i].max_slots = 0;

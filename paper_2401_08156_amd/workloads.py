@@ -1,0 +1,45 @@
+"""The five synthetic workloads and the engine table sizes that fit them.
+
+Table sizes (per trace) are capacity settings of the replay engine, not parameters of the
+allocators: a trace that outgrows them is flagged VMS_ST_TABLE_OVERFLOW instead of being replayed
+wrongly.  The values below hold the high-water marks measured on the full workloads with headroom;
+smaller tables mean less LDS per wavefront and therefore more resident wavefronts per compute unit.
+"""
+from . import tracegen
+
+NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "config4-lora",
+         5: "config5-mixture"}
+
+TABLES = {
+    # config: splitting free list, pBlocks, sBlocks, chunk runs, chunks (x 2 MiB)
+    1: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=4096, max_chunks=8192),
+    2: dict(max_free_blocks=256, max_pblocks=640, max_sblocks=640, max_runs=3072, max_chunks=4096),
+    # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks, runs kept in HBM
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 20, max_chunks=16384),
+    4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=3584, max_chunks=24576),
+}
+# config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
+# events; replayed as three batches, one per kind, each with tables of its own
+TABLES_5 = {
+    2: dict(max_free_blocks=256, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=4096),
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 21, max_chunks=16384),
+    4: dict(max_free_blocks=512, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=24576),
+}
+
+
+def shape(config):
+    c = tracegen.CONFIGS[config]
+    return c["n_traces"], c["n_events"]
+
+
+def make_config(binding, config, n_traces, n_events, max_slots, kind=None, **overrides):
+    """vms_config for a workload (kind: the generator of a config-5 batch)."""
+    cfg = binding.vms_config_default(n_traces, n_events, max_slots)
+    cfg.capacity_bytes = tracegen.CONFIGS[config]["capacity_bytes"]
+    tables = TABLES_5[kind] if config == 5 else TABLES[config]
+    for k, v in tables.items():
+        setattr(cfg, k, v)
+    for k, v in overrides.items():
+        assert hasattr(cfg, k), k
+        setattr(cfg, k, v)
+    return cfg

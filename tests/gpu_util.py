@@ -55,8 +55,8 @@ def assert_parity(events, cfg, n_events=None, threads=8, label=""):
         odec, ost = oracle.replay(events, P, pol, n_events=n_events, threads=threads)
         gst = st[pol]
         bad = np.flatnonzero(gst["status"] & binding.VMS_ST_TABLE_OVERFLOW)
-        assert bad.size == 0, "%s policy %d: table overflow in traces %s at events %s" % (
-            label, pol, bad[:8].tolist(), gst["overflow_event"][bad[:8]].tolist())
+        assert bad.size == 0, "%s policy %d: table overflow in traces %s at events %s, status %s" % (
+            label, pol, bad[:8].tolist(), gst["overflow_event"][bad[:8]].tolist(), gst["status"][bad[:8]].tolist())
         if n_events is None:
             same = gdec == odec
         else:
