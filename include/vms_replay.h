@@ -185,6 +185,40 @@ void vms_replay_destroy(vms_replay *h);
 int vms_replay_last_hip_error(const vms_replay *h);   /* hipError_t of the last VMS_EHIP */
 const char *vms_strerror(int code);
 
+/* What vms_demo_run measured.  Times are host wall-clock milliseconds summed over the calls.   */
+typedef struct vms_demo_report {
+    uint32_t struct_size;        /* sizeof(vms_demo_report), set by the caller               */
+    uint32_t events_replayed;
+    uint32_t failed_event;       /* event at which replay stopped, if the call failed        */
+    int32_t  hip_error;          /* hipError_t of the first failing HIP call, else 0         */
+    uint64_t granularity_bytes;  /* hipMemGetAllocationGranularity (minimum) of the device   */
+    uint64_t chunks_created;     /* physical chunks obtained with hipMemCreate               */
+    uint32_t n_pblocks_created, n_splits, n_stitches, n_sblocks_released;
+    uint32_t sblocks_cached;     /* stitched ranges still mapped at the end                  */
+    uint32_t alias_checks;       /* stitched ranges verified to alias their members' memory  */
+    uint32_t alias_failures;     /* ... and how many did not (must be 0)                     */
+    uint32_t failed_api;         /* which call gave hip_error: 1 reserve, 2 create, 3 map, 4 set
+                                    access, 5 unmap, 6 release, 7 address free, 8 memcpy     */
+    uint64_t n_reserve, n_create, n_map, n_set_access, n_unmap, n_release, n_address_free;
+    double   ms_reserve, ms_create, ms_map, ms_set_access, ms_unmap, ms_release, ms_address_free;
+    /* one 2 GiB block built from chunk_bytes chunks, against hipMalloc(2 GiB): Table 1      */
+    uint64_t table1_bytes;
+    double   table1_hipmalloc_ms, table1_reserve_ms, table1_create_ms, table1_map_ms, table1_set_access_ms;
+} vms_demo_report;
+
+/* Functional demonstration (Sec. 3.3.1, Sec. 2.5): execute the first n_events decisions of ONE
+ * trace of the stitching policy with real device mappings on the current HIP device
+ * (hipMemAddressReserve / hipMemCreate / hipMemMap / hipMemSetAccess / hipMemUnmap /
+ * hipMemRelease / hipMemAddressFree), one physical allocation per chunk.  h_events and
+ * h_dec_vms are HOST arrays: the trace's event words and the decision words vms_replay_run
+ * wrote for it under the same cfg.  Requests served by the small-request pool are skipped.
+ * The decisions are cross-checked against books kept by the demo: VMS_EINVAL (with
+ * failed_event) if they are inconsistent, VMS_EHIP if a HIP call fails (e.g. out of device
+ * memory: the trace's reserved bytes are really allocated).  Everything is unmapped and
+ * released before returning.  Synchronous; host code only, no kernel is launched.              */
+int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms, uint32_t n_events,
+                 vms_demo_report *out);
+
 /* In-wavefront primitives self-test (reductions, scans, sorted insert): runs a
  * small kernel on the current device and returns VMS_OK if every lane layout
  * matches its definition.  Diagnostic; not part of a replay.                  */

@@ -33,6 +33,25 @@ class vms_summary(ctypes.Structure):
                 ("mean_fragmentation", ctypes.c_double * 2), ("mem_reduction_ratio", ctypes.c_double)]
 
 
+class vms_demo_report(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("events_replayed", ctypes.c_uint32),
+                ("failed_event", ctypes.c_uint32), ("hip_error", ctypes.c_int32),
+                ("granularity_bytes", ctypes.c_uint64), ("chunks_created", ctypes.c_uint64),
+                ("n_pblocks_created", ctypes.c_uint32), ("n_splits", ctypes.c_uint32),
+                ("n_stitches", ctypes.c_uint32), ("n_sblocks_released", ctypes.c_uint32),
+                ("sblocks_cached", ctypes.c_uint32), ("alias_checks", ctypes.c_uint32),
+                ("alias_failures", ctypes.c_uint32), ("failed_api", ctypes.c_uint32),
+                ("n_reserve", ctypes.c_uint64), ("n_create", ctypes.c_uint64), ("n_map", ctypes.c_uint64),
+                ("n_set_access", ctypes.c_uint64), ("n_unmap", ctypes.c_uint64), ("n_release", ctypes.c_uint64),
+                ("n_address_free", ctypes.c_uint64),
+                ("ms_reserve", ctypes.c_double), ("ms_create", ctypes.c_double), ("ms_map", ctypes.c_double),
+                ("ms_set_access", ctypes.c_double), ("ms_unmap", ctypes.c_double), ("ms_release", ctypes.c_double),
+                ("ms_address_free", ctypes.c_double),
+                ("table1_bytes", ctypes.c_uint64), ("table1_hipmalloc_ms", ctypes.c_double),
+                ("table1_reserve_ms", ctypes.c_double), ("table1_create_ms", ctypes.c_double),
+                ("table1_map_ms", ctypes.c_double), ("table1_set_access_ms", ctypes.c_double)]
+
+
 # vms_trace_stats as a numpy record (same layout as the C struct)
 STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("peak_reserved", "<u8"),
                         ("final_requested", "<u8"), ("final_active", "<u8"), ("final_reserved", "<u8"),
@@ -89,6 +108,8 @@ def lib():
         L.vms_strerror.argtypes = [ctypes.c_int]
         L.vms_selftest.restype = ctypes.c_int
         L.vms_selftest.argtypes = []
+        L.vms_demo_run.restype = ctypes.c_int
+        L.vms_demo_run.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
         _lib = L
     return _lib
 
@@ -111,6 +132,19 @@ def vms_strerror(code):
 
 def vms_selftest():
     return lib().vms_selftest()
+
+
+def vms_demo_run(cfg, h_events, h_dec_vms, n_events=None):
+    """Execute one trace's stitching decisions with real HIP virtual-memory mappings.
+    h_events / h_dec_vms: 1-D uint64 numpy arrays (host).  Returns (rc, vms_demo_report)."""
+    ev = np.ascontiguousarray(h_events, dtype=np.uint64)
+    dec = np.ascontiguousarray(h_dec_vms, dtype=np.uint64)
+    assert ev.ndim == 1 and ev.shape == dec.shape
+    n = ev.shape[0] if n_events is None else min(int(n_events), ev.shape[0])
+    rep = vms_demo_report()
+    rep.struct_size = ctypes.sizeof(vms_demo_report)
+    rc = lib().vms_demo_run(ctypes.byref(cfg), ev.ctypes.data, dec.ctypes.data, n, ctypes.byref(rep))
+    return rc, rep
 
 
 class Replay:

@@ -1,0 +1,62 @@
+"""Functional stitching demo: one trace's decisions executed with real HIP virtual-memory mappings."""
+import numpy as np
+import pytest
+
+import gpu_util
+from paper_2401_08156_amd import binding, workloads
+from paper_2401_08156_amd import tracegen as tg
+
+pytestmark = pytest.mark.gpu
+MiB = 1 << 20
+
+
+def replay_one(config, n_events, **kw):
+    ev, ms = tg.generate(config, n_traces=1, n_events=n_events, **kw)
+    cfg = workloads.make_config(binding, config, 1, n_events, ms, kind=3 if config == 5 else None)
+    _, dv, st = gpu_util.gpu_replay(ev, cfg)
+    return cfg, ev[0], dv[0], st
+
+
+def test_demo_worked_example_maps_without_new_memory():
+    # 4 MiB + 2 MiB freed blocks serve 6 MiB by stitching: three chunks in total, one stitched range
+    ev = tg.make_events([("A", 0, 4 * MiB), ("A", 1, 2 * MiB), ("F", 0), ("F", 1), ("A", 2, 6 * MiB)])
+    cfg = gpu_util.make_cfg(1, 5, 4)
+    _, dv, _ = gpu_util.gpu_replay(ev[None, :], cfg)
+    rc, rep = binding.vms_demo_run(cfg, ev, dv[0])
+    assert rc == 0, (rc, rep.failed_event, rep.hip_error, rep.failed_api, rep.chunks_created, rep.n_map)
+    assert rep.chunks_created == 3 and rep.n_stitches == 1 and rep.n_splits == 0
+    assert rep.alias_checks == 1 and rep.alias_failures == 0
+    assert rep.n_create == 3 and rep.n_release == 3
+    assert rep.n_map == 3 + 3            # each chunk under its pBlock and again under the stitched range
+    assert rep.table1_bytes == 2 << 30 and rep.table1_hipmalloc_ms > 0
+
+
+def test_demo_config1_trace():
+    cfg, ev, dv, st = replay_one(1, 2000)
+    rc, rep = binding.vms_demo_run(cfg, ev, dv)
+    assert rc == 0, (rc, rep.failed_event, rep.hip_error, rep.failed_api, rep.chunks_created, rep.n_map)
+    assert rep.events_replayed == 2000 and rep.alias_failures == 0 and rep.alias_checks > 0
+    assert rep.chunks_created * cfg.chunk_bytes <= st["final_reserved"][1, 0]
+    assert rep.n_stitches == st["n_sblock_created"][1, 0]
+    assert rep.n_sblocks_released == st["n_sblock_evicted"][1, 0]
+    assert rep.n_release == rep.n_create == rep.chunks_created
+
+
+def test_demo_offload_trace_prefix():
+    # an offloading trace of the config-5 mixture (kind 3): gigabyte-sized staging buffers.  Only a
+    # prefix: with one mapping per 2 MiB chunk the runtime refuses further hipMemSetAccess calls after
+    # some 60,000 mappings, which this trace reaches near event 650.
+    cfg, ev, dv, st = replay_one(5, 400, first_trace=1)
+    rc, rep = binding.vms_demo_run(cfg, ev, dv)
+    assert rc == 0, (rc, rep.failed_event, rep.hip_error, rep.failed_api, rep.chunks_created, rep.n_map)
+    assert rep.alias_failures == 0 and rep.n_stitches == st["n_sblock_created"][1, 0]
+    assert rep.chunks_created * cfg.chunk_bytes == st["final_reserved"][1, 0]    # no small requests here
+
+
+def test_demo_rejects_inconsistent_decisions():
+    cfg, ev, dv, _ = replay_one(1, 600)
+    bad = dv.copy()
+    i = int(np.flatnonzero((bad & np.uint64(15)) == 3)[0])       # a stitch decision: claim one candidate more
+    bad[i] += np.uint64(1 << 8)
+    rc, rep = binding.vms_demo_run(cfg, ev, bad)
+    assert rc == -1 and rep.failed_event == i

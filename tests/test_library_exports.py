@@ -1,0 +1,46 @@
+"""The C-ABI library loads without a GPU and exports every symbol the header declares."""
+import ctypes
+import os
+import re
+
+from paper_2401_08156_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "vms_replay.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vms_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_functions()
+    assert "vms_replay_create" in names and "vms_replay_run" in names and "vms_replay_stats" in names
+    L = binding.lib()
+    for n in names:
+        assert hasattr(L, n), "libvmsreplay.so does not export %s" % n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(binding.vms_config) == 80
+    assert binding.STATS_DTYPE.itemsize == 144
+    assert ctypes.sizeof(binding.vms_summary) == 88
+    assert ctypes.sizeof(binding.vms_demo_report) == 224
+
+
+def test_config_default_and_argument_errors_need_no_gpu():
+    cfg = binding.vms_config_default(7, 100, 9)
+    assert (cfg.struct_size, cfg.n_traces, cfg.max_events, cfg.max_slots) == (80, 7, 100, 9)
+    assert cfg.chunk_bytes == 2 << 20 and cfg.policy_mask == 3 and cfg.spool_threshold == 512
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    assert L.vms_replay_create(None, ctypes.byref(h)) == -1
+    cfg.struct_size = 12
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -2
+    cfg = binding.vms_config_default(7, 100, 9)
+    cfg.chunk_bytes = 3 << 20
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -1
+    assert binding.vms_strerror(-6).startswith("per-trace tables")
+    assert L.vms_replay_workspace_bytes(None) == 0
