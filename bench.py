@@ -3,7 +3,7 @@
 
 A step is one vms_replay_run over the whole workload: every trace replayed under both
 policies, events resident in HBM, decision words and statistics written to HBM.
-Prints one JSON line ("Measurement").
+Prints one JSON line.
 """
 import argparse
 import json
@@ -67,8 +67,8 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (traces are independent; see DESIGN.md for how "
-              "it would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (traces are independent and would shard "
+              "by trace index); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
