@@ -112,9 +112,11 @@ typedef struct vms_trace_stats {        /* one per (policy, trace) */
     uint64_t peak_active;        /* bytes held by live blocks (Sec. 5.1 "active memory")    */
     uint64_t peak_reserved;      /* bytes obtained from the device (Sec. 5.1 "reserved")    */
     uint64_t final_requested, final_active, final_reserved;
-    uint64_t digest;             /* d = 0xCBF29CE484222325; after every event, for x in
-                                    (decision, active/512, reserved/512):
-                                    d = (d ^ x) * 0x9E3779B97F4A7C15 mod 2^64               */
+    uint64_t digest;             /* checksum of the decision stream: the sum over events i
+                                    (from 0) of (decision_i * 0x9E3779B97F4A7C15 +
+                                    (active_i / 512 << 32 | reserved_i / 512)) *
+                                    ((2 i + 1) * 0xD6E8FEB86659FD93)  mod 2^64, with the
+                                    totals taken after event i                               */
     uint32_t n_code[8];          /* events per decision code 0..6; [7] counts INVALID       */
     uint32_t n_split;            /* blocks cut (both kinds of pool)                          */
     uint32_t n_merge;            /* neighbour merges in splitting pools                      */

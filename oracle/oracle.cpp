@@ -310,7 +310,6 @@ struct Replay {
     {
         memset(&st, 0, sizeof st);
         st.first_oom_event = 0xFFFFFFFFu;
-        st.digest = 0xCBF29CE484222325ull;
         slots.resize(p.max_slots);
         chunk_units = p.chunk_bytes / UNIT;
         capacity_units = (p.capacity_bytes ? std::min(p.capacity_bytes, ENGINE_MAX_BYTES) : ENGINE_MAX_BYTES) / UNIT;
@@ -541,10 +540,10 @@ struct Replay {
             st.max_pblocks = std::max(st.max_pblocks, (u32)vp.pblocks.size());
             st.max_sblocks = std::max(st.max_sblocks, (u32)vp.spool.size());
             st.max_total_members = std::max(st.max_total_members, vp.total_members);
-            const u64 K = 0x9E3779B97F4A7C15ull;
-            st.digest = (st.digest ^ dec) * K;
-            st.digest = (st.digest ^ active) * K;
-            st.digest = (st.digest ^ res) * K;
+            // checksum of the whole stream (this build's own; the paper defines none): every event
+            // adds a term that depends on its position, its decision and the totals after it
+            st.digest += (dec * 0x9E3779B97F4A7C15ull + ((active << 32) | res)) *
+                         ((2 * (u64)i + 1) * 0xD6E8FEB86659FD93ull);
             if (decisions) decisions[i] = dec;
             if (series) { series[2 * i] = active * UNIT; series[2 * i + 1] = res * UNIT; }
         }

@@ -1,8 +1,15 @@
 // Replay kernels: one wavefront (= one workgroup of 64 lanes) replays one trace
-// under one policy.  All allocator state of the trace lives in that wave's LDS;
-// scalar state (counters, byte totals, digest) stays wave-uniform so the
+// under one policy.  All allocator state of the trace lives in that wave's LDS
+// and registers; scalar state (counters, byte totals) stays wave-uniform so the
 // compiler keeps it in SGPRs.  Control flow is wave-uniform throughout: the 64
 // lanes only ever split up to scan / shift / mark the pool arrays in parallel.
+//
+// A wave replays alone on its SIMD most of the time, so an event costs
+//   4 cycles x instructions issued  +  ~130 cycles x dependent LDS round trips.
+// The data layout below is chosen to keep both small on the two hot paths
+// (an exact hit on a cached block, and a free): first search level in
+// registers, slot table in registers, per-event results parked in lane j of
+// four registers and digested once per tile of 64 events.
 //
 // Policies (GMLake, arXiv 2401.08156): the splitting caching allocator of
 // Sec. 2.2 and the stitching allocator of Sec. 3 and Sec. 4.1 (Algorithm 1).
@@ -12,7 +19,7 @@
 #include "../../include/vms_replay.h"
 
 enum { C_FREE = 0, C_EXACT = 1, C_SPLIT = 2, C_STITCH = 3, C_GROW = 4, C_OOM = 5, C_FREE_NOOP = 6, C_INVALID = 15 };
-enum : u64 { B_SMALL = 1u << 4, B_SBLOCK = 1u << 5, B_6 = 1u << 6, B_7 = 1u << 7 };
+enum : u32 { B_SMALL = 1u << 4, B_SBLOCK = 1u << 5, B_6 = 1u << 6, B_7 = 1u << 7 };
 enum { SLOT_UNBOUND = 0u, SLOT_OOM = 0xFFFFFFFFu };
 enum { KIND_SMALL = 0u, KIND_PBLOCK = 1u, KIND_SBLOCK = 2u };
 #define NONE32 0xFFFFFFFFu
@@ -24,22 +31,20 @@ struct KParams {
     u32 small_limit_units;
     u32 frag_limit_chunks;
     u32 spool_threshold;
-    u64 capacity_units;
+    u32 capacity_units;         // at most 2^30 (512 GiB)
     u32 max_slots;
     u32 cap_free, cap_pblocks, cap_sblocks, cap_runs, cap_chunks;
     // byte offsets of the per-wave arrays inside dynamic LDS
-    u32 off_slot_req, off_slot_a, off_slot_b, off_fl, off_pool, off_bmp, off_skey, off_smeta, off_sstamp,
-        off_arena;
+    u32 off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
+        off_sstamp, off_swit, off_arena;
     u32 lds_bytes;
-    u32 run_len_bits;           // see VmsD::arena
-    u64 ws_stride;              // workspace bytes per trace (sBlock run compaction buffer)
+    u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
 };
 
-// Running totals of one (trace, policy).
+// Running totals of one (trace, policy); sizes in 512-byte units (at most 2^30).
 struct Acct {
-    u64 requested, active;      // 512-byte units
-    u64 peak_requested, peak_active, peak_reserved;
-    u64 digest;
+    u32 requested, active;
+    u32 peak_requested, peak_active;
     u32 n_split, n_merge, n_created, n_evicted, first_oom, status, overflow_event;
     u32 hw_pblocks, hw_sblocks, hw_free, hw_members, hw_runs;
     bool stop;
@@ -47,8 +52,7 @@ struct Acct {
 
 DI void acct_init(Acct &A)
 {
-    A.requested = A.active = A.peak_requested = A.peak_active = A.peak_reserved = 0;
-    A.digest = 0xCBF29CE484222325ull;
+    A.requested = A.active = A.peak_requested = A.peak_active = 0;
     A.n_split = A.n_merge = A.n_created = A.n_evicted = A.status = 0;
     A.first_oom = A.overflow_event = NONE32;
     A.hw_pblocks = A.hw_sblocks = A.hw_free = A.hw_members = A.hw_runs = 0;
@@ -64,6 +68,56 @@ DI void table_overflow(Acct &A, u32 ev, u32 which)
 }
 
 // ---------------------------------------------------------------------------
+// Slot table: what each handle of the trace currently holds.
+//   req  request size in units; 0 = unbound; 0xFFFFFFFF = its ALLOC hit OOM
+//   a    splitting pools: address << 2 | segment flags; pBlock: first chunk; sBlock: creation number
+//   b    kind | chunks held << 2 (stitching policy only)
+//   c    sBlock: its chunk-run list in the arena, offset << 16 | entries (see VmsT)
+// IN_REGS: the table is four registers, slot s in lane s (traces with at most 64
+// slots): a lookup is a v_readlane, an update a compare-and-select, no LDS round trip.
+// ---------------------------------------------------------------------------
+template <bool IN_REGS>
+struct SlotsT;
+
+template <>
+struct SlotsT<true> {
+    u32 req, a, b, c;
+    DI void init(char *, const KParams &) { req = a = b = c = 0; }
+    DI u32 get_req(u32 s) const { return from_lane(req, s); }
+    DI u32 get_a(u32 s) const { return from_lane(a, s); }
+    DI u32 get_b(u32 s) const { return from_lane(b, s); }
+    DI u32 get_c(u32 s) const { return from_lane(c, s); }
+    DI void set_req(u32 s, u32 v) { req = lane_id() == s ? v : req; }
+    DI void set_a(u32 s, u32 v) { a = lane_id() == s ? v : a; }
+    DI void set_b(u32 s, u32 v) { b = lane_id() == s ? v : b; }
+    DI void set_c(u32 s, u32 v) { c = lane_id() == s ? v : c; }
+    // the arena was compacted: the list that was at `from` is now at `to`
+    DI void moved(u32 from, u32 to, const KParams &) { c = ((b & 3) == KIND_SBLOCK && c == from) ? to : c; }
+};
+
+template <>
+struct SlotsT<false> {
+    u32 *req, *a, *b, *c;
+    DI void init(char *lds, const KParams &P)
+    {
+        req = (u32 *)(lds + P.off_slot_req);
+        a = (u32 *)(lds + P.off_slot_a);
+        b = (u32 *)(lds + P.off_slot_b);
+        c = (u32 *)(lds + P.off_slot_c);
+        for (u32 i = lane_id(); i < P.max_slots; i += 64) req[i] = SLOT_UNBOUND;
+    }
+    DI u32 get_req(u32 s) const { return ld_uni(req, s); }
+    DI u32 get_a(u32 s) const { return ld_uni(a, s); }
+    DI u32 get_b(u32 s) const { return ld_uni(b, s); }
+    DI u32 get_c(u32 s) const { return ld_uni(c, s); }
+    DI void set_req(u32 s, u32 v) { st_one(req, s, v); }
+    DI void set_a(u32 s, u32 v) { st_one(a, s, v); }
+    DI void set_b(u32 s, u32 v) { st_one(b, s, v); }
+    DI void set_c(u32 s, u32 v) { st_one(c, s, v); }
+    DI void moved(u32, u32, const KParams &) {}      // c is not used with the table in LDS
+};
+
+// ---------------------------------------------------------------------------
 // Splitting pool (Sec. 2.2): the inactive blocks of the pool as an unordered
 // LDS array of 64-bit keys
 //     bits 32-62 size (units) | bits 2-31 address (units) | bit 1 first-in-segment | bit 0 last-in-segment
@@ -72,11 +126,13 @@ DI void table_overflow(Acct &A, u32 ev, u32 which)
 // flags travel with the slot that holds it.  The two flags replace neighbour
 // links: a block may merge to the right iff it is not last in its segment and
 // the block starting where it ends is in the array (inactive); same to the left.
+// The array is scanned four tiles of 64 keys at a time, all loads issued before
+// the first is used, so a scan of up to 256 keys costs one LDS round trip.
 // ---------------------------------------------------------------------------
 struct SplitPoolD {
     u64 *fl;
     u32 n, cap;
-    u64 reserved;               // units obtained so far = next segment address
+    u32 reserved;               // units obtained so far = next segment address
 };
 
 struct SplitRes {
@@ -84,46 +140,59 @@ struct SplitRes {
     bool split;
 };
 
-DI SplitRes sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, u32 ev)
+DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, u32 ev, SplitRes &r)
 {
     const u32 lane = lane_id();
-    SplitRes r;
     r.split = false;
     // step 1: best fit = smallest key not below (size, address 0)
-    const u64 thresh = (u64)size << 32;
-    u64 best = ~0ull;
+    u64 best = ~0ull, lastk = 0;
     u32 besti = 0;
-    for (u32 base = 0; base < sp.n; base += 64) {
-        u32 i = base + lane;
-        u64 k = i < sp.n ? sp.fl[i] : ~0ull;
-        if (k >= thresh && k < best) {
-            best = k;
-            besti = i;
+    const u32 last = sp.n - 1;
+    for (u32 base = 0; base < sp.n; base += 256) {
+        u64 k[4];
+#pragma unroll
+        for (u32 t = 0; t < 4; t++) {
+            const u32 i = base + t * 64 + lane;
+            k[t] = sp.fl[i < sp.cap ? i : 0];
+        }
+#pragma unroll
+        for (u32 t = 0; t < 4; t++) {
+            if (base + t * 64 < sp.n) {
+                const u32 i = base + t * 64 + lane;
+                const bool ok = i < sp.n && (u32)(k[t] >> 32) >= size && k[t] < best;
+                best = ok ? k[t] : best;
+                besti = ok ? i : besti;
+                lastk = i == last ? k[t] : lastk;
+            }
         }
     }
-    u32 hi = (u32)(best >> 32);
-    u32 mhi = sp.n ? wave_min_u32(hi) : NONE32;
+    const u32 hi = (u32)(best >> 32);
+    const u32 mhi = sp.n ? wave_min_u32(hi) : NONE32;
     u32 bsize;
     if (mhi != NONE32) {
-        u32 lo = hi == mhi ? (u32)best : NONE32;
-        u32 mlo = wave_min_u32(lo);
-        u32 owner = first_lane(ballot(hi == mhi && lo == mlo));
-        u32 idx = from_lane(besti, owner);
+        const u64 m = ballot(hi == mhi);
+        u32 owner = first_lane(m);
+        if (m & (m - 1)) {                      // several blocks of that size: lowest address
+            const u32 lo = hi == mhi ? (u32)best : NONE32;
+            const u32 mlo = wave_min_u32(lo);
+            owner = first_lane(ballot(hi == mhi && lo == mlo));
+        }
+        const u32 blo = from_lane((u32)best, owner);
+        const u32 idx = from_lane(besti, owner);
         bsize = mhi;
-        r.addr = mlo >> 2;
-        r.flags = mlo & 3;
+        r.addr = blo >> 2;
+        r.flags = blo & 3;
         r.code = C_EXACT;
-        u32 last = sp.n - 1;                    // unordered array: fill the hole with the last key
-        if (lane == 0 && idx != last) sp.fl[idx] = sp.fl[last];
+        if (idx != last) st_one(sp.fl, idx, from_lane64(lastk, last & 63));   // unordered: the last key fills the hole
         sp.n = last;
         wave_sync();
     } else {
         if (!may_grow) {
             r.code = C_OOM;
             r.addr = r.flags = 0;
-            return r;
+            return;
         }
-        r.addr = (u32)sp.reserved;              // "native allocation": a fresh segment
+        r.addr = sp.reserved;                   // "native allocation": a fresh segment
         sp.reserved += seg;
         bsize = seg;
         r.flags = 3;
@@ -133,9 +202,9 @@ DI SplitRes sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, 
     if (bsize > size) {
         if (sp.n == sp.cap) {
             table_overflow(A, ev, VMS_ST_OVF_FREE_BLOCKS);
-            return r;
+            return;
         }
-        u64 rest = ((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1);
+        const u64 rest = ((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1);
         st_one(sp.fl, sp.n, rest);
         sp.n++;
         A.hw_free = max(A.hw_free, sp.n);
@@ -145,7 +214,6 @@ DI SplitRes sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, 
         if (r.code == C_EXACT) r.code = C_SPLIT;
         A.n_split++;
     }
-    return r;
 }
 
 // steps 3 and 4: the block becomes inactive and absorbs inactive neighbours of its segment
@@ -153,22 +221,34 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 {
     const u32 lane = lane_id();
     const bool can_l = !(flags & 2), can_r = !(flags & 1);
+    const u32 end = addr + size;
     u32 lidx = NONE32, ridx = NONE32;
     u64 lkey = 0, rkey = 0;
     if (can_l || can_r) {
-        for (u32 base = 0; base < sp.n; base += 64) {
-            u32 i = base + lane;
-            u64 k = i < sp.n ? sp.fl[i] : 0;
-            u32 ka = (u32)k >> 2, ks = (u32)(k >> 32);
-            u64 mL = ballot(can_l && i < sp.n && ka + ks == addr);
-            u64 mR = ballot(can_r && i < sp.n && ka == addr + size);
-            if (mL) {
-                lidx = base + first_lane(mL);
-                lkey = from_lane64(k, first_lane(mL));
+        for (u32 base = 0; base < sp.n; base += 256) {
+            u64 k[4];
+#pragma unroll
+            for (u32 t = 0; t < 4; t++) {
+                const u32 i = base + t * 64 + lane;
+                k[t] = sp.fl[i < sp.cap ? i : 0];
             }
-            if (mR) {
-                ridx = base + first_lane(mR);
-                rkey = from_lane64(k, first_lane(mR));
+#pragma unroll
+            for (u32 t = 0; t < 4; t++) {
+                if (base + t * 64 < sp.n) {
+                    const u32 i = base + t * 64 + lane;
+                    const u64 kk = i < sp.n ? k[t] : 0;         // key 0 matches nothing (no block ends at 0)
+                    const u32 ka = (u32)kk >> 2, ks = (u32)(kk >> 32);
+                    const u64 mL = ballot(can_l && ks != 0 && ka + ks == addr);
+                    const u64 mR = ballot(can_r && ks != 0 && ka == end);
+                    if (mL) {
+                        lidx = base + t * 64 + first_lane(mL);
+                        lkey = from_lane64(kk, first_lane(mL));
+                    }
+                    if (mR) {
+                        ridx = base + t * 64 + first_lane(mR);
+                        rkey = from_lane64(kk, first_lane(mR));
+                    }
+                }
             }
         }
     }
@@ -184,12 +264,12 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         flags = ((u32)lkey & 2) | (flags & 1);
     }
     A.n_merge += (*ml ? 1u : 0u) + (*mr ? 1u : 0u);
-    u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
+    const u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
     if (*ml) {
         st_one(sp.fl, lidx, key);               // merged block takes the left neighbour's place
         wave_sync();
         if (*mr) {
-            u32 last = sp.n - 1;
+            const u32 last = sp.n - 1;
             if (lane == 0 && ridx != last) sp.fl[ridx] = sp.fl[last];
             sp.n = last;
         }
@@ -215,16 +295,21 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //   bmp[]    one bit per physical chunk: set while the pBlock owning it is active.  A pBlock is
 //            inactive iff the bit of its first chunk is clear; an sBlock is inactive iff all bits
 //            of all its chunk runs are clear (Sec. 3.2: one active pBlock makes the sBlock active).
-//            Handing out / releasing any block is therefore only bit-range work.
+//            Handing out / releasing any block is therefore only bit-range work (LDS atomics whose
+//            result nobody waits for).
 //   skey[]   sBlocks as key  size << 32 | ~creation_number, sorted descending (size descending,
-//            then older first), with smeta[] = arena offset << 16 | run count, sstamp[] = last use.
-//   arena[]  chunk runs of all cached sBlocks, bump-allocated, 32 bits each:
-//            first_chunk << len_bits | (chunks - 1); a longer run takes several entries.
+//            then older first), with smeta[] = arena offset << 16 | entries, sstamp[] = last use,
+//            swit[] = a "witness": the list entry that was seen active last (or NONE32).  While the
+//            witness is still active the sBlock is known to be active after one bitmap read.
+//   arena[]  chunk runs of all cached sBlocks, bump-allocated, cut at bitmap word boundaries:
+//            one 32-bit entry  word << 10 | first bit << 5 | last bit  per bitmap word a run touches.
+//            Testing, setting or clearing an sBlock is one pass over its entries, one lane per entry.
 //            Compacted through a global-memory buffer when full.
+//   pp, sp   first level of the rank searches in pool[] and skey[], held in registers.
 // ---------------------------------------------------------------------------
-// BIG: for traces whose sBlocks hold more chunk runs than LDS can take, the arena lives in the
+// BIG: for traces whose sBlocks hold more entries than LDS can take, the arena lives in the
 // trace's slice of the global workspace (the other arrays stay in LDS) and smeta[] widens to
-// arena offset << 32 | run count.
+// arena offset << 32 | entries.
 template <bool BIG>
 struct VmsT {
     typedef typename std::conditional<BIG, u64, u32>::type meta_t;
@@ -232,31 +317,39 @@ struct VmsT {
     u32 *bmp;
     u64 *skey;
     meta_t *smeta;
-    u32 *sstamp;
+    u32 *sstamp, *swit;
     u32 *arena, *bounce;
-    u32 np, ns, n_chunks, top, live_runs, next_sid, clock;
-    u32 len_bits;               // low bits of a run entry holding chunks - 1
+    u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
+    Probe pp, sp;
+    bool pp_dirty, sp_dirty;
     static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
     static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
     static DI u32 cnt(meta_t m) { return BIG ? (u32)m : (u32)m & 0xFFFFu; }
 };
 
-template <bool BIG>
-DI u32 run_start(const VmsT<BIG> &V, u32 run) { return run >> V.len_bits; }
-template <bool BIG>
-DI u32 run_end(const VmsT<BIG> &V, u32 run) { return (run >> V.len_bits) + (run & ((1u << V.len_bits) - 1u)) + 1u; }
-template <bool BIG>
-DI u32 run_entries(const VmsT<BIG> &V, u32 len) { return (len + (1u << V.len_bits) - 1u) >> V.len_bits; }
+DI u32 from_lane_any(u32 v, u32 l) { return from_lane(v, l); }
+DI u64 from_lane_any(u64 v, u32 l) { return from_lane64(v, l); }
+
+// bits of one list entry inside its bitmap word
+DI u32 emask(u32 e) { return (2u << (e & 31)) - (1u << ((e >> 5) & 31)); }
+
+DI u32 run_words(u32 start, u32 len) { return ((start + len - 1) >> 5) - (start >> 5) + 1; }
+
+// entry q of the run [start, start + len)
+DI u32 run_entry(u32 start, u32 len, u32 q)
+{
+    const u32 w0 = start >> 5, endm1 = start + len - 1, w = w0 + q;
+    const u32 lo = q == 0 ? (start & 31) : 0u;
+    const u32 hi = w == (endm1 >> 5) ? (endm1 & 31) : 31u;
+    return (w << 10) | (lo << 5) | hi;
+}
 
 // write the entries of one run (wave-uniform arguments) at arena[at..]; returns how many
 template <bool BIG>
 DI u32 arena_put(VmsT<BIG> &V, u32 at, u32 start, u32 len)
 {
-    const u32 n = run_entries(V, len), q = lane_id(), maxlen = 1u << V.len_bits;
-    if (q < n) {
-        u32 l = min(maxlen, len - q * maxlen);
-        V.arena[at + q] = ((start + q * maxlen) << V.len_bits) | (l - 1u);
-    }
+    const u32 n = run_words(start, len);
+    for (u32 q = lane_id(); q < n; q += 64) V.arena[at + q] = run_entry(start, len, q);
     wave_sync();
     return n;
 }
@@ -279,95 +372,46 @@ DI void bmp_fill(u32 *bmp, u32 start, u32 len, bool set)
         u32 w = wb + lane_id();
         if (w <= w1) {
             u32 m = word_mask(w, start, end);
-            bmp[w] = set ? (bmp[w] | m) : (bmp[w] & ~m);
+            if (set) atomicOr(&bmp[w], m);
+            else atomicAnd(&bmp[w], ~m);
         }
     }
     wave_sync();
 }
 
-// all runs of one sBlock, one lane per run (runs may share a word: atomics)
+// all entries of one sBlock, one lane per entry (entries may share a word: atomics)
 template <bool BIG>
-DI void bmp_fill_runs(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
+DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
 {
     for (u32 rb = 0; rb < cnt; rb += 64) {
-        u32 r = rb + lane_id();
+        const u32 r = rb + lane_id();
         if (r < cnt) {
-            u32 run = V.arena[off + r];
-            u32 start = run_start(V, run), end = run_end(V, run);
-            for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
-                u32 m = word_mask(w, start, end);
-                if (set) atomicOr(&V.bmp[w], m);
-                else atomicAnd(&V.bmp[w], ~m);
-            }
+            const u32 e = V.arena[off + r];
+            if (set) atomicOr(&V.bmp[e >> 10], emask(e));
+            else atomicAnd(&V.bmp[e >> 10], ~emask(e));
         }
     }
     wave_sync();
 }
 
 // Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
-// sBlocks side by side): walks the runs and tests the bitmap words they cover.  A run found
-// active is moved to the front of the list (the order of the runs carries no meaning here), so
-// the next look at a still-active sBlock usually ends at its first run.
+// sBlocks side by side): the witness first, then the whole list.
 template <bool BIG>
 DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
 {
-    auto meta = V.smeta[i];
-    u32 *runs = V.arena + V.off(meta);
-    u32 cnt = V.cnt(meta);
+    const u32 wit = V.swit[i];
+    if (wit != NONE32 && (V.bmp[wit >> 10] & emask(wit))) return false;
+    const auto meta = V.smeta[i];
+    const u32 *list = V.arena + V.off(meta);
+    const u32 cnt = V.cnt(meta);
     for (u32 r = 0; r < cnt; r++) {
-        u32 run = runs[r];
-        u32 start = run_start(V, run), end = run_end(V, run);
-        for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
-            if (V.bmp[w] & word_mask(w, start, end)) {
-                if (r) {
-                    runs[r] = runs[0];
-                    runs[0] = run;
-                }
-                return false;
-            }
+        const u32 e = list[r];
+        if (V.bmp[e >> 10] & emask(e)) {
+            V.swit[i] = e;
+            return false;
         }
     }
     return true;
-}
-
-// First inactive sBlock among skey[slo, shi) (pool order), or NONE32.  Sixteen candidates are
-// tested side by side, four lanes per candidate, each lane taking every fourth chunk run.
-template <bool BIG>
-DI u32 first_inactive_sblock(const VmsT<BIG> &V, u32 slo, u32 shi)
-{
-    const u32 lane = lane_id(), sub = lane & 3, grp = lane >> 2;
-    for (u32 base = slo; base < shi; base += 16) {
-        const u32 i = base + grp;
-        const bool valid = i < shi;
-        const auto meta = valid ? V.smeta[i] : 0;
-        u32 *runs = V.arena + V.off(meta);
-        const u32 cnt = V.cnt(meta);
-        u32 at = NONE32, busy_run = 0;                  // index and value of the active run this lane met
-        for (u32 r = sub; r < cnt && at == NONE32; r += 4) {
-            u32 run = runs[r];
-            u32 start = run_start(V, run), end = run_end(V, run);
-            for (u32 w = start >> 5; w <= (end - 1) >> 5; w++) {
-                if (V.bmp[w] & word_mask(w, start, end)) {
-                    at = r;
-                    busy_run = run;
-                    break;
-                }
-            }
-        }
-        const u64 found = ballot(at != NONE32);
-        // the first lane of a candidate that met an active run moves it to the front of the list
-        if (at != NONE32 && at != 0 && ((found >> (grp * 4)) & ((1u << sub) - 1u)) == 0) {
-            runs[at] = runs[0];
-            runs[0] = busy_run;
-        }
-        u64 b = found;
-        b |= b >> 1;
-        b |= b >> 2;                                    // bit 4g: some lane of candidate g saw an active chunk
-        const u64 free16 = ballot(valid && sub == 0) & ~b;
-        if (free16) return base + (first_lane(free16) >> 2);
-    }
-    wave_sync();
-    return NONE32;
 }
 
 template <bool BIG>
@@ -378,6 +422,7 @@ DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, Acct &A)
     shift_up(V.pool, pos, V.np);
     st_one(V.pool, pos, key);
     V.np++;
+    V.pp_dirty = true;
     A.hw_pblocks = max(A.hw_pblocks, V.np);
     wave_sync();
 }
@@ -387,11 +432,13 @@ DI void pool_remove(VmsT<BIG> &V, u32 idx)
 {
     shift_down(V.pool, idx, V.np);
     V.np--;
+    V.pp_dirty = true;
 }
 
-// Stitch: the only creator of sBlocks (Sec. 3.3.1).  The runs are already in the arena.
+// Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
+// Returns the position of the new sBlock in skey[].
 template <bool BIG>
-DI void spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
+DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
@@ -399,29 +446,35 @@ DI void spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
     shift_up(V.skey, pos, V.ns);
     shift_up(V.smeta, pos, V.ns);
     shift_up(V.sstamp, pos, V.ns);
+    shift_up(V.swit, pos, V.ns);
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
     st_one(V.sstamp, pos, ++V.clock);
+    st_one(V.swit, pos, NONE32);
     V.ns++;
-    V.live_runs += cnt;
+    V.live_ent += cnt;
+    V.sp_dirty = true;
     A.n_created++;
     wave_sync();
+    return pos;
 }
 
 template <bool BIG>
 DI void spool_remove(VmsT<BIG> &V, u32 idx)
 {
-    V.live_runs -= V.cnt(ld_uni(V.smeta, idx));
+    V.live_ent -= V.cnt(ld_uni(V.smeta, idx));
     shift_down(V.skey, idx, V.ns);
     shift_down(V.smeta, idx, V.ns);
     shift_down(V.sstamp, idx, V.ns);
+    shift_down(V.swit, idx, V.ns);
     V.ns--;
+    V.sp_dirty = true;
 }
 
-// Squeeze the runs of evicted sBlocks out of the arena: copy the live lists to the
-// global buffer in sPool order, then back.
-template <bool BIG>
-DI void arena_compact(VmsT<BIG> &V)
+// Squeeze the entries of evicted sBlocks out of the arena: copy the live lists to the
+// global buffer in sPool order, then back.  Slots holding an sBlock learn its new place.
+template <bool BIG, class Slots>
+DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
 {
     u32 top = 0;
     for (u32 s = 0; s < V.ns; s++) {
@@ -429,6 +482,7 @@ DI void arena_compact(VmsT<BIG> &V)
         u32 off = V.off(meta), cnt = V.cnt(meta);
         for (u32 r = lane_id(); r < cnt; r += 64) V.bounce[top + r] = V.arena[off + r];
         st_one(V.smeta, s, V.pack(top, cnt));
+        if (!BIG) S.moved((u32)meta, (u32)V.pack(top, cnt), P);
         top += cnt;
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");     // later reads are of other lanes' global writes
@@ -444,10 +498,10 @@ DI void arena_compact(VmsT<BIG> &V)
     wave_sync();
 }
 
-template <bool BIG>
-DI bool arena_reserve(VmsT<BIG> &V, u32 need, const KParams &P, Acct &A, u32 ev)
+template <bool BIG, class Slots>
+DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, Acct &A, u32 ev)
 {
-    if (V.top + need > P.cap_runs && V.live_runs < V.top) arena_compact(V);
+    if (V.top + need > P.cap_runs && V.live_ent < V.top) arena_compact(V, S, P);
     if (V.top + need > P.cap_runs) {
         table_overflow(A, ev, VMS_ST_OVF_RUNS);
         return false;
@@ -475,6 +529,7 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
                 }
             }
         }
+        wave_sync();
         u32 m = wave_min_u32(best);
         if (m == NONE32) break;                 // everything cached is in use: the threshold stays exceeded
         u32 victim = from_lane(besti, first_lane(ballot(best == m)));
@@ -483,60 +538,112 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
         any = true;
     }
     A.hw_sblocks = max(A.hw_sblocks, V.ns);     // high-water marks as seen between events
-    A.hw_runs = max(A.hw_runs, V.live_runs);
+    A.hw_runs = max(A.hw_runs, V.live_ent);
     return any;
 }
 
 struct VmsRes {
-    u64 dec;                    // decision word (code C_OOM alone when the request failed)
-    u32 kind, ref, held;        // what the slot now holds: pBlock first chunk / sBlock number, chunks held
+    u32 dec_lo;                 // low decision word (code C_OOM alone when the request failed)
+    u32 ref;                    // pBlock first chunk / sBlock creation number (= high decision word)
+    u32 kind, held;             // what the slot now holds, chunks held
+    u32 list;                   // sBlock: offset << 16 | entries of its list (not BIG)
 };
 
 // One request of bsize chunks on the stitching path: S1 exact match, else BestFit's
 // second loop and the post-processing of its state (Sec. 4.1, Fig. 9).
-template <bool BIG>
-DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &P, Acct &A, u32 ev)
+template <bool BIG, class Slots>
+DI void vms_alloc(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, Acct &A, u32 ev,
+                  VmsRes &R)
 {
     const u32 lane = lane_id();
-    VmsRes R;
     R.kind = KIND_PBLOCK;
     R.held = bsize;
     R.ref = 0;
+    R.list = 0;
 
-    // ---- S1, stitched blocks: the run of equal sizes in skey[], oldest first
-    {
-        u32 slo, shi;
-        rank_desc2(V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &slo, &shi);
-        const u32 s = first_inactive_sblock(V, slo, shi);
-        if (s != NONE32) {
-            auto meta = ld_uni(V.smeta, s);
-            bmp_fill_runs(V, V.off(meta), V.cnt(meta), true);
-            st_one(V.sstamp, s, ++V.clock);
-            wave_sync();
-            R.kind = KIND_SBLOCK;
-            R.ref = ~(u32)ld_uni(V.skey, s);
-            R.dec = C_EXACT | B_SBLOCK | (1ull << 8) | ((u64)R.ref << 32);
-            return R;
-        }
+    if (V.sp_dirty) {
+        probe_refresh(V.sp, V.skey, V.ns);
+        V.sp_dirty = false;
     }
-    // ---- S1, primitive blocks: pool[lo_p, hi_p) are the pBlocks of exactly bsize chunks
-    u32 lo_p, hi_p;
-    rank_desc2(V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &lo_p, &hi_p);
+    if (V.pp_dirty) {
+        probe_refresh(V.pp, V.pool, V.np);
+        V.pp_dirty = false;
+    }
+    // blocks of exactly bsize chunks: skey[slo, shi) and pool[lo_p, hi_p); the four block loads
+    // of the searches are in flight together
+    const u64 k1 = ((u64)bsize << 32) | 0xFFFFFFFFu, k2 = ((u64)bsize << 32) - 1;
+    u32 slo, shi, lo_p, hi_p;
+    {
+        RankReq a = rank_begin(V.sp, V.skey, V.ns, k1), b = rank_begin(V.sp, V.skey, V.ns, k2);
+        RankReq c = rank_begin(V.pp, V.pool, V.np, k1), d = rank_begin(V.pp, V.pool, V.np, k2);
+        slo = rank_end(a, k1);
+        shi = rank_end(b, k2);
+        lo_p = rank_end(c, k1);
+        hi_p = rank_end(d, k2);
+    }
+
+    // ---- S1, stitched blocks, oldest first.  One lane per candidate reads its witness: a
+    // candidate whose witness is still active is out.  The others are tested in pool order with
+    // all lanes over the entries of one list.
+    for (u32 base = slo; base < shi; base += 64) {
+        const u32 i = base + lane;
+        const u32 ic = i < shi ? i : shi - 1;
+        const u32 wit = V.swit[ic];
+        const auto meta = V.smeta[ic];
+        const u32 idn = (u32)V.skey[ic];
+        const u32 wv = V.bmp[wit == NONE32 ? 0u : wit >> 10];
+        const bool known = wit != NONE32 && (wv & emask(wit));
+        u64 unknown = ballot(i < shi && !known);
+        while (unknown) {
+            const u32 l = first_lane(unknown);
+            const u32 c = base + l;
+            const auto m = from_lane_any(meta, l);
+            const u32 off = V.off(m), cnt = V.cnt(m);
+            bool busy = false;
+            u32 ent0 = 0;
+            for (u32 eb = 0; eb < cnt; eb += 64) {
+                const u32 k = eb + lane;
+                const u32 e = V.arena[off + (k < cnt ? k : cnt - 1)];
+                const u32 word = V.bmp[e >> 10];
+                const u64 bm = ballot(k < cnt && (word & emask(e)));
+                if (eb == 0) ent0 = e;
+                if (bm) {
+                    st_one(V.swit, c, from_lane(e, first_lane(bm)));
+                    busy = true;
+                    break;
+                }
+            }
+            if (!busy) {
+                if (cnt <= 64) {
+                    if (lane < cnt) atomicOr(&V.bmp[ent0 >> 10], emask(ent0));
+                } else {
+                    bmp_fill_entries(V, off, cnt, true);
+                }
+                st_one(V.sstamp, c, ++V.clock);
+                wave_sync();
+                R.kind = KIND_SBLOCK;
+                R.ref = ~from_lane(idn, l);
+                R.list = BIG ? 0u : (u32)m;
+                R.dec_lo = C_EXACT | B_SBLOCK | (1u << 8);
+                return;
+            }
+            unknown &= unknown - 1;
+        }
+        wave_sync();
+    }
+    // ---- S1, primitive blocks: the first inactive one in pool order
     for (u32 base = lo_p; base < hi_p; base += 64) {
-        u32 i = base + lane;
-        u64 key = i < hi_p ? V.pool[i] : 0;
-        u64 m = ballot(i < hi_p && !bmp_test(V.bmp, ~(u32)key));
+        const u32 i = base + lane;
+        const u64 key = V.pool[i < hi_p ? i : hi_p - 1];
+        const u64 m = ballot(i < hi_p && !bmp_test(V.bmp, ~(u32)key));
         if (m) {
-            u32 start = ~(u32)from_lane64(key, first_lane(m));
+            const u32 start = ~from_lane((u32)key, first_lane(m));
             bmp_fill(V.bmp, start, bsize, true);
             R.ref = start;
-            R.dec = C_EXACT | (1ull << 8) | ((u64)start << 32);
-            return R;
+            R.dec_lo = C_EXACT | (1u << 8);
+            return;
         }
     }
-
-    // worst-case arena entries of the runs created below, beyond one per candidate
-    const u32 slack = 2u * ((P.cap_chunks >> V.len_bits) + 1u) + 2u;
 
     // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
     // pool order is the single-block candidate (state 2).
@@ -554,13 +661,14 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
                 bmp_fill(V.bmp, pstart, psize, true);
                 R.ref = pstart;
                 R.held = psize;
-                R.dec = C_SPLIT | (1ull << 8) | ((u64)pstart << 32);
-                return R;
+                R.dec_lo = C_SPLIT | (1u << 8);
+                return;
             }
-            if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks || !arena_reserve(V, slack, P, A, ev)) {
+            if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks ||
+                !arena_reserve(V, S, run_words(pstart, psize), P, A, ev)) {
                 table_overflow(A, ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
-                R.dec = C_INVALID;
-                return R;
+                R.dec_lo = C_INVALID;
+                return;
             }
             // S2: Split into the request and the rest; a stitched block keeps the uncut size on record
             pool_remove(V, idx);
@@ -572,9 +680,9 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
             V.top += n;
             bmp_fill(V.bmp, pstart, bsize, true);
             R.ref = pstart;
-            R.dec = C_SPLIT | B_6 | (1ull << 8) | ((u64)pstart << 32);
-            if (stitch_free(V, P, A)) R.dec |= B_7;
-            return R;
+            R.dec_lo = C_SPLIT | B_6 | (1u << 8);
+            if (stitch_free(V, P, A)) R.dec_lo |= B_7;
+            return;
         }
         hi = lo;
     }
@@ -604,21 +712,22 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
     const u32 excess = s3 ? sum - bsize : 0, deficit = s3 ? 0 : bsize - sum;
     if (!s3) {
         // S4 needs new physical chunks; S5 if the device cannot provide them
-        if (reserved_units + ((u64)deficit << P.chunk_shift) > P.capacity_units) {
-            R.dec = C_OOM;
-            return R;
+        if (reserved_units + (deficit << P.chunk_shift) > P.capacity_units) {
+            R.dec_lo = C_OOM;
+            return;
         }
         if (V.n_chunks + deficit > P.cap_chunks) {
             table_overflow(A, ev, VMS_ST_OVF_CHUNKS);
-            R.dec = C_INVALID;
-            return R;
+            R.dec_lo = C_INVALID;
+            return;
         }
     }
-    if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks ||
-        !arena_reserve(V, k + (bsize >> V.len_bits) + slack, P, A, ev)) {
+    // list entries created below: a run of L chunks touches at most L / 32 + 2 bitmap words
+    const u32 need = 2u * k + 3u * (((sum > bsize ? sum : bsize) >> 5) + 2u);
+    if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev)) {
         table_overflow(A, ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
-        R.dec = C_INVALID;
-        return R;
+        R.dec_lo = C_INVALID;
+        return;
     }
     if (!s3 && k == 0) {
         // nothing cached is usable: the new pBlock serves the request directly
@@ -627,37 +736,28 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
         V.n_chunks += deficit;
         bmp_fill(V.bmp, start, deficit, true);
         R.ref = start;
-        R.dec = C_GROW | ((u64)start << 32);
-        return R;
+        R.dec_lo = C_GROW;
+        return;
     }
-    // second pass: the candidates' chunk runs go to the arena in pool order
+    // second pass: the candidates' chunk runs go to the arena in pool order, cut at word boundaries
     u32 cnt = 0;
     {
-        const u32 endi = s3 ? pos + 1 : lim, maxlen = 1u << V.len_bits;
+        const u32 endi = s3 ? pos + 1 : lim;
         for (u32 base = hi_p; base < endi; base += 64) {
             u32 i = base + lane;
             u64 key = i < endi ? V.pool[i] : 0;
             bool inact = i < endi && !bmp_test(V.bmp, ~(u32)key);
             u32 len = (u32)(key >> 32), start = ~(u32)key;
             if (i == pos) len -= excess;
-            u64 im = ballot(inact);
-            if (ballot(inact && len > maxlen) == 0) {
-                if (inact) V.arena[V.top + cnt + rank_in(im)] = (start << V.len_bits) | (len - 1u);
-                cnt += popc64(im);
-            } else {
-                // some candidate is longer than one entry can describe
-                u32 ne = inact ? run_entries(V, len) : 0u, tot, incl = wave_scan_add(ne, &tot);
-                for (u32 q = 0; q < ne; q++) {
-                    u32 l = min(maxlen, len - q * maxlen);
-                    V.arena[V.top + cnt + incl - ne + q] = ((start + q * maxlen) << V.len_bits) | (l - 1u);
-                }
-                cnt += tot;
-            }
+            u32 ne = inact ? run_words(start, len) : 0u, tot, incl = wave_scan_add(ne, &tot);
+            for (u32 q = 0; ballot(q < ne); q++)
+                if (q < ne) V.arena[V.top + cnt + incl - ne + q] = run_entry(start, len, q);
+            cnt += tot;
         }
         wave_sync();
     }
     u32 used = cnt;             // arena entries consumed, including a restore block's
-    R.dec = 0;
+    R.dec_lo = 0;
     if (s3) {
         if (excess) {
             // cut the last candidate so the sum is exact; remember its uncut size (Fig. 9, sBlock 2)
@@ -670,47 +770,60 @@ DI VmsRes vms_alloc(VmsT<BIG> &V, u32 bsize, u64 reserved_units, const KParams &
             u32 n = arena_put(V, V.top + cnt, qstart, qsize);
             spool_insert(V, qsize, V.top + cnt, n, A);
             used += n;
-            R.dec |= B_6;
+            R.dec_lo |= B_6;
         }
-        R.dec |= C_STITCH;
+        R.dec_lo |= C_STITCH;
     } else {
         u32 start = V.n_chunks;                 // Alloc: exactly the missing chunks
         pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
         cnt += arena_put(V, V.top + cnt, start, deficit);
         used = cnt;
-        R.dec |= C_GROW;
+        R.dec_lo |= C_GROW;
     }
     R.ref = V.next_sid;
     spool_insert(V, bsize, V.top, cnt, A);
-    bmp_fill_runs(V, V.top, cnt, true);
+    bmp_fill_entries(V, V.top, cnt, true);
+    R.list = BIG ? 0u : (u32)V.pack(V.top, cnt);
     V.top += used;
     A.hw_members = max(A.hw_members, k + (s3 ? 0u : 1u));
     R.kind = KIND_SBLOCK;
-    R.dec |= B_SBLOCK | ((u64)k << 8) | ((u64)R.ref << 32);
-    if (stitch_free(V, P, A)) R.dec |= B_7;
-    return R;
+    R.dec_lo |= B_SBLOCK | (k << 8);
+    if (stitch_free(V, P, A)) R.dec_lo |= B_7;
 }
 
-// Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks.
-template <bool BIG>
-DI void vms_free(VmsT<BIG> &V, u32 kind, u32 ref, u32 held)
+// Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks.  `list` is the slot's
+// record of where the sBlock's entries are (USE_LIST), else the sBlock is looked up by its key.
+template <bool BIG, bool USE_LIST>
+DI void vms_free(VmsT<BIG> &V, u32 kind, u32 ref, u32 held, u32 list)
 {
     if (kind == KIND_PBLOCK) {
         bmp_fill(V.bmp, ref, held, false);
+    } else if (USE_LIST) {
+        bmp_fill_entries(V, list >> 16, list & 0xFFFFu, false);
     } else {
+        if (V.sp_dirty) {
+            probe_refresh(V.sp, V.skey, V.ns);
+            V.sp_dirty = false;
+        }
         u64 key = ((u64)held << 32) | (u32)~ref;
-        u32 idx = rank_desc(V.skey, V.ns, key);
+        u32 idx = rank_probe(V.sp, V.skey, V.ns, key);
         auto meta = ld_uni(V.smeta, idx);
-        bmp_fill_runs(V, V.off(meta), V.cnt(meta), false);
+        bmp_fill_entries(V, V.off(meta), V.cnt(meta), false);
     }
 }
 
 // ---------------------------------------------------------------------------
 // The replay loop of one wavefront.  POLICY 0: splitting allocator only.
 // POLICY 1: stitching allocator with the splitting pool for small requests.
+// SLOT_REGS: slot table in registers (max_slots <= 64).
+//
+// Per event only the allocator runs; the decision word and the active / reserved totals after
+// the event are parked in lane j of four registers.  Once per tile of 64 events
+// the lanes store the decisions with one coalesced write, count the decision codes and fold
+// their event into the digest, all 64 events side by side.
 // ---------------------------------------------------------------------------
-template <int POLICY, bool BIG>
+template <int POLICY, bool BIG, bool SLOT_REGS>
 __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__restrict__ events,
                                                     const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
                                                     vms_trace_stats *__restrict__ stats, char *__restrict__ workspace)
@@ -718,10 +831,10 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
+    constexpr bool USE_LIST = SLOT_REGS && !BIG;
 
-    u32 *slot_req = (u32 *)(lds + P.off_slot_req);
-    u32 *slot_a = (u32 *)(lds + P.off_slot_a);
-    u32 *slot_b = (u32 *)(lds + P.off_slot_b);
+    SlotsT<SLOT_REGS> S;
+    S.init(lds, P);
 
     SplitPoolD sp;
     sp.fl = (u64 *)(lds + P.off_fl);
@@ -730,24 +843,27 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
     sp.reserved = 0;
 
     VmsT<BIG> V;
-    V.np = V.ns = V.n_chunks = V.top = V.live_runs = V.next_sid = V.clock = 0;
+    V.np = V.ns = V.n_chunks = V.top = V.live_ent = V.next_sid = V.clock = 0;
+    V.pp.v = V.sp.v = 0;
+    V.pp.stride = V.sp.stride = 1;
+    V.pp_dirty = V.sp_dirty = false;
     if (POLICY == 1) {
         V.pool = (u64 *)(lds + P.off_pool);
         V.bmp = (u32 *)(lds + P.off_bmp);
         V.skey = (u64 *)(lds + P.off_skey);
         V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
         V.sstamp = (u32 *)(lds + P.off_sstamp);
+        V.swit = (u32 *)(lds + P.off_swit);
         V.bounce = (u32 *)(workspace + (size_t)trace * P.ws_stride);
         V.arena = BIG ? V.bounce + P.cap_runs : (u32 *)(lds + P.off_arena);
-        V.len_bits = P.run_len_bits;
         for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
     }
-    for (u32 i = lane; i < P.max_slots; i += 64) slot_req[i] = SLOT_UNBOUND;
     wave_sync();
 
     Acct A;
     acct_init(A);
-    u32 code_count = 0;
+    u32 code_count = 0;         // lane c: events with decision code c (lane 7: invalid)
+    u64 dig = 0;                // this lane's share of the digest
     const u32 chunk_units = 1u << P.chunk_shift;
     const u32 n_ev = n_events ? min(uni(n_events[trace]), P.max_events) : P.max_events;
     const u64 *ev_row = events + (size_t)trace * P.max_events;
@@ -758,111 +874,124 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
         const u32 tile = min(64u, n_ev - base);
         const u64 evw = ev_next;
         if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
-        u32 d_lo = 0, d_hi = 0;
-        for (u32 j = 0; j < tile && !A.stop; j++) {
+        u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
+        u32 done = 0;
+        for (u32 j = 0; j < tile; j++) {
             const u32 ev = base + j;
             const u32 w = from_lane((u32)evw, j), slot = from_lane((u32)(evw >> 32), j);
-            const u32 size = w & 0x7FFFFFFFu;
-            const bool is_free = w >> 31;
-            u64 dec = C_INVALID;
+            u32 dlo = C_INVALID, dhi = 0;
             if (slot < P.max_slots) {
-                const u32 req = ld_uni(slot_req, slot);
-                if (!is_free) {
+                const u32 req = S.get_req(slot);
+                if (!(w >> 31)) {
+                    const u32 size = w;
                     if (size != 0 && req == SLOT_UNBOUND) {
-                        const u64 reserved = sp.reserved + ((u64)V.n_chunks << P.chunk_shift);
+                        const u32 reserved = sp.reserved + (V.n_chunks << P.chunk_shift);
                         bool oom = false;
                         u32 held_units = size;
                         if (POLICY == 0 || size < P.small_limit_units) {
-                            u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
-                            SplitRes r = sp_alloc(sp, size, seg, reserved + seg <= P.capacity_units, A, ev);
+                            const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
+                            SplitRes r;
+                            sp_alloc(sp, size, seg, reserved + seg <= P.capacity_units, A, ev, r);
                             if (r.code == C_OOM) {
                                 oom = true;
                             } else {
-                                st_one(slot_a, slot, (r.addr << 2) | r.flags);
-                                if (POLICY == 1) st_one(slot_b, slot, (u32)KIND_SMALL);
-                                dec = r.code | (POLICY == 1 ? B_SMALL : 0) | (r.split ? B_6 : 0) |
-                                      ((u64)(r.code == C_GROW ? 0 : 1) << 8) | ((u64)r.addr << 32);
+                                S.set_a(slot, (r.addr << 2) | r.flags);
+                                if (POLICY == 1) S.set_b(slot, (u32)KIND_SMALL);
+                                dlo = r.code | (POLICY == 1 ? B_SMALL : 0u) | (r.split ? B_6 : 0u) |
+                                      ((r.code == C_GROW ? 0u : 1u) << 8);
+                                dhi = r.addr;
                             }
                         } else {
-                            u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
-                            VmsRes r = vms_alloc(V, bsize, reserved, P, A, ev);
-                            if ((r.dec & 15) == C_OOM) {
+                            const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
+                            VmsRes r;
+                            vms_alloc(V, S, bsize, reserved, P, A, ev, r);
+                            if ((r.dec_lo & 15) == C_OOM) {
                                 oom = true;
                             } else {
-                                st_one(slot_a, slot, r.ref);
-                                st_one(slot_b, slot, r.kind | (r.held << 2));
+                                S.set_a(slot, r.ref);
+                                S.set_b(slot, r.kind | (r.held << 2));
+                                if (USE_LIST) S.set_c(slot, r.list);
                                 held_units = r.held << P.chunk_shift;
-                                dec = r.dec;
+                                dlo = r.dec_lo;
+                                dhi = (r.dec_lo & 15) == C_INVALID ? 0u : r.ref;
                             }
                         }
                         if (oom) {
-                            st_one(slot_req, slot, (u32)SLOT_OOM);
+                            S.set_req(slot, (u32)SLOT_OOM);
                             if (A.first_oom == NONE32) A.first_oom = ev;
-                            dec = C_OOM;
+                            dlo = C_OOM;
+                            dhi = 0;
                         } else if (!A.stop) {
-                            st_one(slot_req, slot, size);
+                            S.set_req(slot, size);
                             A.requested += size;
                             A.active += held_units;
-                            // Sec. 5.1: active and reserved memory are recorded at their peaks; all
-                            // three totals can only rise on an allocation
+                            // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
                             A.peak_requested = max(A.peak_requested, A.requested);
                             A.peak_active = max(A.peak_active, A.active);
-                            A.peak_reserved = max(A.peak_reserved, sp.reserved + ((u64)V.n_chunks << P.chunk_shift));
                         }
                     }
                 } else if (req == SLOT_OOM) {
-                    st_one(slot_req, slot, (u32)SLOT_UNBOUND);
-                    dec = C_FREE_NOOP;
+                    S.set_req(slot, (u32)SLOT_UNBOUND);
+                    dlo = C_FREE_NOOP;
                 } else if (req != SLOT_UNBOUND) {
-                    const u32 a = ld_uni(slot_a, slot);
-                    const u32 b = POLICY == 1 ? ld_uni(slot_b, slot) : (u32)KIND_SMALL;
+                    const u32 a = S.get_a(slot);
+                    const u32 b = POLICY == 1 ? S.get_b(slot) : (u32)KIND_SMALL;
                     u32 held_units = req;
                     if ((b & 3) == KIND_SMALL) {
                         bool ml, mr;
                         sp_free(sp, a >> 2, req, a & 3, &ml, &mr, A, ev);
-                        dec = C_FREE | (POLICY == 1 ? B_SMALL : 0) | (ml ? B_6 : 0) | (mr ? B_7 : 0) | ((u64)(a >> 2) << 32);
+                        dlo = C_FREE | (POLICY == 1 ? B_SMALL : 0u) | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
+                        dhi = a >> 2;
                     } else {
-                        vms_free(V, b & 3, a, b >> 2);
+                        vms_free<BIG, USE_LIST>(V, b & 3, a, b >> 2, USE_LIST ? S.get_c(slot) : 0u);
                         held_units = (b >> 2) << P.chunk_shift;
-                        dec = C_FREE | ((b & 3) == KIND_SBLOCK ? B_SBLOCK : 0) | ((u64)a << 32);
+                        dlo = C_FREE | ((b & 3) == KIND_SBLOCK ? B_SBLOCK : 0u);
+                        dhi = a;
                     }
-                    st_one(slot_req, slot, (u32)SLOT_UNBOUND);
+                    S.set_req(slot, (u32)SLOT_UNBOUND);
                     A.requested -= req;
                     A.active -= held_units;
                 }
             }
             wave_sync();
             if (A.stop) break;
-
-            // accounting.  Lane c keeps the event count of decision code c (lane 7: invalid).
-            const u32 code = (u32)dec & 15;
-            if (code == C_INVALID) A.status |= VMS_ST_INVALID_EVENT;
-            code_count += lane == (code == C_INVALID ? 7u : code) ? 1u : 0u;
-            const u64 reserved = sp.reserved + ((u64)V.n_chunks << P.chunk_shift);
-            const u64 K = 0x9E3779B97F4A7C15ull;
-            A.digest = (A.digest ^ dec) * K;
-            A.digest = (A.digest ^ A.active) * K;
-            A.digest = (A.digest ^ reserved) * K;
-            if (lane == j) {
-                d_lo = (u32)dec;
-                d_hi = (u32)(dec >> 32);
-            }
+            const bool mine = lane == j;
+            v_dlo = mine ? dlo : v_dlo;
+            v_dhi = mine ? dhi : v_dhi;
+            v_act = mine ? A.active : v_act;
+            v_res = mine ? sp.reserved + (V.n_chunks << P.chunk_shift) : v_res;
+            done = j + 1;
         }
-        if (dec_row && lane < tile) dec_row[base + lane] = ((u64)d_hi << 32) | d_lo;
+        // the tile's events, one per lane
+        const bool valid = lane < done;
+        const u64 dec = ((u64)v_dhi << 32) | v_dlo;
+        if (dec_row && valid) dec_row[base + lane] = dec;
+        const u32 code = v_dlo & 15, cidx = code == C_INVALID ? 7u : code;
+#pragma unroll
+        for (u32 c = 0; c < 8; c++) {
+            const u32 n = popc64(ballot(valid && cidx == c));
+            code_count += lane == c ? n : 0u;
+        }
+        if (ballot(valid && code == C_INVALID)) A.status |= VMS_ST_INVALID_EVENT;
+        // digest: sum over events i of (decision * K1 + (active << 32 | reserved)) * ((2 i + 1) * K2)
+        const u64 term = (dec * 0x9E3779B97F4A7C15ull + (((u64)v_act << 32) | v_res)) *
+                         ((2ull * (base + lane) + 1ull) * 0xD6E8FEB86659FD93ull);
+        dig += valid ? term : 0ull;
     }
 
     wave_sync();
+    const u64 digest = wave_sum_u64(dig);
     if (lane < 8) stats[(size_t)POLICY * P.n_traces + trace].n_code[lane] = code_count;
     if (lane == 0) {
         vms_trace_stats &s = stats[(size_t)POLICY * P.n_traces + trace];
-        const u64 reserved = sp.reserved + ((u64)V.n_chunks << P.chunk_shift);
-        s.peak_requested = A.peak_requested * 512;
-        s.peak_active = A.peak_active * 512;
-        s.peak_reserved = A.peak_reserved * 512;
-        s.final_requested = A.requested * 512;
-        s.final_active = A.active * 512;
+        const u64 reserved = sp.reserved + (V.n_chunks << P.chunk_shift);
+        s.peak_requested = (u64)A.peak_requested * 512;
+        s.peak_active = (u64)A.peak_active * 512;
+        s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value
+        s.final_requested = (u64)A.requested * 512;
+        s.final_active = (u64)A.active * 512;
         s.final_reserved = reserved * 512;
-        s.digest = A.digest;
+        s.digest = digest;
         s.n_split = A.n_split;
         s.n_merge = A.n_merge;
         s.n_sblock_created = A.n_created;
@@ -876,7 +1005,7 @@ __global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__rest
         s.max_runs = A.hw_runs;
         s.overflow_event = A.overflow_event;
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
-        s.fragmentation = A.peak_reserved ? 1.0 - (double)A.peak_active / (double)A.peak_reserved : 0.0;
+        s.fragmentation = reserved ? 1.0 - (double)A.peak_active / (double)reserved : 0.0;
     }
 }
 

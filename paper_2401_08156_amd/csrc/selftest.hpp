@@ -52,6 +52,13 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
             rank_desc2(arr, n, key + ((u64)2 << 32), key, &r1, &r2);
             if (r != ref || r2 != ref || r1 != count_gt(arr, n, key + ((u64)2 << 32))) bad |= 256;
         }
+        // the same ranks with the first search level cached in registers
+        Probe pr;
+        probe_refresh(pr, arr, n);
+        for (u32 probe = 540; probe <= 1003; probe += 1) {
+            u64 key = ((u64)probe << 32) - 1;
+            if (rank_probe(pr, arr, n, key) != count_gt(arr, n, key)) bad |= 512;
+        }
     }
     shift_up(arr, 70, 150);
     st_one(arr, 70u, (u64)12345);

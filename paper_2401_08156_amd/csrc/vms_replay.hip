@@ -24,6 +24,7 @@ struct vms_replay {
     vms_config cfg;
     KParams kp[2];              // [0] splitting kernel, [1] stitching kernel
     bool big;                   // sBlock chunk runs in global memory (see VmsT)
+    bool slot_regs;             // slot table in registers (see SlotsT)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
     hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
@@ -49,8 +50,9 @@ int hip_fail(vms_replay *h, hipError_t e)
         if (e_ != hipSuccess) return hip_fail(h, e_); \
     } while (0)
 
-// Per-wave LDS layout.  The splitting kernel only needs the slot table and its free list.
-void layout(KParams &k, int policy, const vms_config &c, bool big)
+// Per-wave LDS layout.  The splitting kernel only needs the slot table and its free list; with at
+// most 64 slots the slot table lives in registers and takes no LDS at all.
+void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_regs)
 {
     uint32_t off = 0;
     auto take = [&](uint32_t bytes) {
@@ -58,9 +60,12 @@ void layout(KParams &k, int policy, const vms_config &c, bool big)
         off = align_up(off + bytes, 16);
         return at;
     };
-    k.off_slot_req = take(c.max_slots * 4);
-    k.off_slot_a = take(c.max_slots * 4);
-    k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
+    k.off_slot_req = k.off_slot_a = k.off_slot_b = k.off_slot_c = 0;
+    if (!slot_regs) {
+        k.off_slot_req = take(c.max_slots * 4);
+        k.off_slot_a = take(c.max_slots * 4);
+        k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
+    }
     k.off_fl = take(c.max_free_blocks * 8);
     if (policy) {
         k.off_pool = take(c.max_pblocks * 8);
@@ -68,11 +73,22 @@ void layout(KParams &k, int policy, const vms_config &c, bool big)
         k.off_skey = take(c.max_sblocks * 8);
         k.off_smeta = take(c.max_sblocks * (big ? 8 : 4));
         k.off_sstamp = take(c.max_sblocks * 4);
+        k.off_swit = take(c.max_sblocks * 4);
         k.off_arena = big ? 0 : take(c.max_runs * 4);
     } else {
-        k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_arena = 0;
+        k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_swit = k.off_arena = 0;
     }
     k.lds_bytes = off;
+}
+
+typedef void (*replay_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
+
+// the kernel variant for a policy: chunk-run lists in HBM or LDS, slot table in LDS or registers
+replay_fn pick_kernel(int policy, bool big, bool slot_regs)
+{
+    if (policy == 0) return slot_regs ? replay_kernel<0, false, true> : replay_kernel<0, false, false>;
+    if (big) return slot_regs ? replay_kernel<1, true, true> : replay_kernel<1, true, false>;
+    return slot_regs ? replay_kernel<1, false, true> : replay_kernel<1, false, false>;
 }
 
 }  // namespace
@@ -123,6 +139,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     memset(h, 0, sizeof *h);
     h->cfg = c;
     h->big = c.max_runs > 16384;        // more than 64 KB of chunk runs per trace: keep them in HBM
+    h->slot_regs = c.max_slots <= 64;
     uint32_t shift = 0;
     while ((UNIT << shift) < c.chunk_bytes) shift++;
     const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)
@@ -136,18 +153,15 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.small_limit_units = (uint32_t)(c.small_limit_bytes / UNIT);
         k.frag_limit_chunks = (uint32_t)(c.frag_limit_bytes / c.chunk_bytes);
         k.spool_threshold = c.spool_threshold;
-        k.capacity_units = cap / UNIT;
+        k.capacity_units = (uint32_t)(cap / UNIT);
         k.max_slots = c.max_slots;
         k.cap_free = c.max_free_blocks;
         k.cap_pblocks = c.max_pblocks;
         k.cap_sblocks = c.max_sblocks;
         k.cap_runs = c.max_runs;
         k.cap_chunks = c.max_chunks;
-        layout(k, p, c, h->big);
+        layout(k, p, c, h->big, h->slot_regs);
         k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 4 * (h->big ? 2 : 1), 256) : 0;
-        uint32_t start_bits = 1;
-        while ((1ull << start_bits) < c.max_chunks) start_bits++;
-        k.run_len_bits = 32 - start_bits;
         if ((c.policy_mask & (1u << p)) && k.lds_bytes > LDS_PER_CU) {
             delete h;
             return VMS_ETOOBIG;
@@ -166,15 +180,9 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)replay_kernel<0, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)LDS_PER_CU);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)replay_kernel<1, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)LDS_PER_CU);
-    if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)replay_kernel<1, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)LDS_PER_CU);
+    for (int p = 0; p < 2 && e == hipSuccess; p++)
+        e = hipFuncSetAttribute((const void *)pick_kernel(p, h->big, h->slot_regs),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_PER_CU);
     if (e != hipSuccess) {
         int rc = e == hipErrorOutOfMemory ? VMS_ENOMEM : VMS_EHIP;
         vms_replay_destroy(h);
@@ -209,19 +217,15 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     hipStream_t sst = both ? h->side : st;
     if (both) HIP_TRY(h, hipStreamWaitEvent(sst, h->ev[0], 0));
     if (c.policy_mask & VMS_POLICY_VMS) {
-        if (h->big)
-            hipLaunchKernelGGL((replay_kernel<1, true>), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
-                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
-        else
-            hipLaunchKernelGGL((replay_kernel<1, false>), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
-                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+        hipLaunchKernelGGL(pick_kernel(1, h->big, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st,
+                           h->kp[1], d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL((replay_kernel<0, false>), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0], d_events,
-                           d_n_events, d_dec_split, h->d_stats, (char *)nullptr);
+        hipLaunchKernelGGL(pick_kernel(0, false, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst,
+                           h->kp[0], d_events, d_n_events, d_dec_split, h->d_stats, (char *)nullptr);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));

@@ -198,3 +198,77 @@ DI void shift_down(T *a, u32 pos, u32 n)
     }
     wave_sync();
 }
+
+// maximum over the 64 lanes, returned wave-uniform
+DI u32 wave_max_u32(u32 v) { return ~wave_min_u32(~v); }
+
+// sum of a 64-bit value over the 64 lanes (mod 2^64), returned wave-uniform
+DI u64 wave_sum_u64(u64 v)
+{
+    u64 s = 0;
+    for (u32 l = 0; l < 64; l++) s += from_lane64(v, l);
+    return s;
+}
+
+// ---- rank search with the first level held in registers ---------------------
+// Probe caches every stride-th key of a descending array (lane l holds
+// a[l * stride], or 0 past the end: keys are never 0).  A rank query then costs
+// one LDS round trip (the block of `stride` keys around the boundary) and
+// none at all for arrays of at most 64 keys.  The cache must be refreshed
+// after the array changes.
+struct Probe {
+    u64 v;          // per lane
+    u32 stride;     // wave-uniform
+};
+
+DI void probe_refresh(Probe &p, const u64 *a, u32 n)
+{
+    p.stride = n > 64 ? (n + 63) >> 6 : 1;
+    const u32 pi = lane_id() * p.stride;
+    const u64 x = a[pi < n ? pi : 0];
+    p.v = pi < n ? x : 0;
+}
+
+struct RankReq {
+    u32 b0;         // block start; the rank itself if !need
+    u64 v;          // this lane's key of the block (0: none)
+    bool need;      // second level pending
+};
+
+// first half: probe ballot and the block load (no wait for the load here)
+DI RankReq rank_begin(const Probe &p, const u64 *a, u32 n, u64 key)
+{
+    RankReq r;
+    const u32 c = popc64(ballot(p.v > key));
+    r.need = p.stride > 1 && c > 0;
+    r.b0 = c;
+    r.v = 0;
+    if (r.need) {
+        r.b0 = (c - 1) * p.stride;
+        if (p.stride <= 64) {
+            const u32 i = r.b0 + lane_id();
+            const u64 x = a[i < n ? i : n - 1];
+            r.v = (lane_id() < p.stride && i < n) ? x : 0;
+        } else {
+            // arrays beyond 4096 keys: count the block in tiles right away
+            u32 cnt = 0;
+            for (u32 o = 0; o < p.stride; o += 64) {
+                const u32 i = r.b0 + o + lane_id();
+                const u64 x = a[i < n ? i : n - 1];
+                cnt += popc64(ballot(o + lane_id() < p.stride && i < n && x > key));
+            }
+            r.b0 += cnt;
+            r.need = false;
+        }
+    }
+    return r;
+}
+
+// second half: a[0..n) sorted descending, returns the number of keys greater than key
+DI u32 rank_end(const RankReq &r, u64 key) { return r.need ? r.b0 + popc64(ballot(r.v > key)) : r.b0; }
+
+DI u32 rank_probe(const Probe &p, const u64 *a, u32 n, u64 key)
+{
+    RankReq r = rank_begin(p, a, n, key);
+    return rank_end(r, key);
+}

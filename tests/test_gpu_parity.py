@@ -77,7 +77,7 @@ def test_runs_in_global_memory_variant():
 
 def test_arena_compaction_in_lds():
     ev, ms = tg.generate(2, n_traces=16, n_events=6000)
-    cfg = gpu_util.make_cfg(16, 6000, ms, max_runs=700, spool_threshold=96, max_sblocks=256)
+    cfg = gpu_util.make_cfg(16, 6000, ms, max_runs=1100, spool_threshold=96, max_sblocks=256)
     gpu_util.assert_parity(ev, cfg, label="config 2, small arena")
 
 

@@ -285,11 +285,11 @@ def test_against_naive_implementation(seed):
 
 
 def test_digest_definition():
-    # d0 = 0xCBF29CE484222325; per event fold decision, active units, reserved units with d = (d ^ x) * K
+    # sum over events i of (decision * K1 + (active units << 32 | reserved units)) * ((2 i + 1) * K2) mod 2^64
     ev, ms = tg.generate(1, n_events=300)
     dec, st, series, _ = oracle.replay_verbose(ev[0], oracle.make_params(ms), oracle.VMS)
-    d, K, M = 0xCBF29CE484222325, 0x9E3779B97F4A7C15, (1 << 64) - 1
+    d, K1, K2, M = 0, 0x9E3779B97F4A7C15, 0xD6E8FEB86659FD93, (1 << 64) - 1
     for i in range(300):
-        for x in (int(dec[i]), int(series[i, 0]) // 512, int(series[i, 1]) // 512):
-            d = ((d ^ x) * K) & M
+        a, r = int(series[i, 0]) // 512, int(series[i, 1]) // 512
+        d = (d + ((int(dec[i]) * K1 + ((a << 32) | r)) & M) * (((2 * i + 1) * K2) & M)) & M
     assert d == int(st["digest"])
