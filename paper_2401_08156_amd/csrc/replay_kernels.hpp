@@ -23,6 +23,7 @@ enum : u32 { B_SMALL = 1u << 4, B_SBLOCK = 1u << 5, B_6 = 1u << 6, B_7 = 1u << 7
 enum { SLOT_UNBOUND = 0u, SLOT_OOM = 0xFFFFFFFFu };
 enum { KIND_SMALL = 0u, KIND_PBLOCK = 1u, KIND_SBLOCK = 2u };
 #define NONE32 0xFFFFFFFFu
+#define WIT_NONE 32u            // a list entry with an empty mask (first bit 1, last bit 0 of word 0): "no witness"
 
 // Launch-constant parameters (passed by value as a kernel argument).
 struct KParams {
@@ -92,7 +93,22 @@ struct SlotsT<true> {
     DI void set_b(u32 s, u32 v) { b = lane_id() == s ? v : b; }
     DI void set_c(u32 s, u32 v) { c = lane_id() == s ? v : c; }
     // the arena was compacted: the list that was at `from` is now at `to`
-    DI void moved(u32 from, u32 to, const KParams &) { c = ((b & 3) == KIND_SBLOCK && c == from) ? to : c; }
+    // the lists of the sBlocks have moved: look each held sBlock up by its key (creation number a,
+    // b >> 2 chunks) in skey[0..ns) (descending) and take its new place from smeta[]
+    DI void relist(const u64 *skey, const u32 *smeta, u32 ns)
+    {
+        if (req + 1u > 1u && (b & 3) == KIND_SBLOCK) {
+            const u64 key = ((u64)(b >> 2) << 32) | (u32)~a;
+            u32 lo = 0, hi = ns;                // first index whose key is not greater than key
+            while (lo < hi) {
+                const u32 mid = (lo + hi) >> 1;
+                if (skey[mid] > key) lo = mid + 1;
+                else hi = mid;
+            }
+            c = smeta[lo];
+        }
+        wave_sync();
+    }
 };
 
 template <>
@@ -114,7 +130,7 @@ struct SlotsT<false> {
     DI void set_a(u32 s, u32 v) { st_one(a, s, v); }
     DI void set_b(u32 s, u32 v) { st_one(b, s, v); }
     DI void set_c(u32 s, u32 v) { st_one(c, s, v); }
-    DI void moved(u32, u32, const KParams &) {}      // c is not used with the table in LDS
+    DI void relist(const u64 *, const u32 *, u32) {}  // c is not used with the table in LDS
 };
 
 // ---------------------------------------------------------------------------
@@ -299,7 +315,7 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //            result nobody waits for).
 //   skey[]   sBlocks as key  size << 32 | ~creation_number, sorted descending (size descending,
 //            then older first), with smeta[] = arena offset << 16 | entries, sstamp[] = last use,
-//            swit[] = a "witness": the list entry that was seen active last (or NONE32).  While the
+//            swit[] = a "witness": the list entry that was seen active last (or WIT_NONE).  While the
 //            witness is still active the sBlock is known to be active after one bitmap read.
 //   arena[]  chunk runs of all cached sBlocks, bump-allocated, cut at bitmap word boundaries:
 //            one 32-bit entry  word << 10 | first bit << 5 | last bit  per bitmap word a run touches.
@@ -321,7 +337,6 @@ struct VmsT {
     u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
     Probe pp, sp;
-    bool pp_dirty, sp_dirty;
     static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
     static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
     static DI u32 cnt(meta_t m) { return BIG ? (u32)m : (u32)m & 0xFFFFu; }
@@ -400,7 +415,7 @@ template <bool BIG>
 DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
 {
     const u32 wit = V.swit[i];
-    if (wit != NONE32 && (V.bmp[wit >> 10] & emask(wit))) return false;
+    if (V.bmp[wit >> 10] & emask(wit)) return false;
     const auto meta = V.smeta[i];
     const u32 *list = V.arena + V.off(meta);
     const u32 cnt = V.cnt(meta);
@@ -422,7 +437,6 @@ DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, Acct &A)
     shift_up(V.pool, pos, V.np);
     st_one(V.pool, pos, key);
     V.np++;
-    V.pp_dirty = true;
     A.hw_pblocks = max(A.hw_pblocks, V.np);
     wave_sync();
 }
@@ -432,7 +446,6 @@ DI void pool_remove(VmsT<BIG> &V, u32 idx)
 {
     shift_down(V.pool, idx, V.np);
     V.np--;
-    V.pp_dirty = true;
 }
 
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
@@ -450,10 +463,9 @@ DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
     st_one(V.sstamp, pos, ++V.clock);
-    st_one(V.swit, pos, NONE32);
+    st_one(V.swit, pos, WIT_NONE);
     V.ns++;
     V.live_ent += cnt;
-    V.sp_dirty = true;
     A.n_created++;
     wave_sync();
     return pos;
@@ -468,7 +480,6 @@ DI void spool_remove(VmsT<BIG> &V, u32 idx)
     shift_down(V.sstamp, idx, V.ns);
     shift_down(V.swit, idx, V.ns);
     V.ns--;
-    V.sp_dirty = true;
 }
 
 // Squeeze the entries of evicted sBlocks out of the arena: copy the live lists to the
@@ -542,6 +553,83 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
     return any;
 }
 
+
+// ---- S1 (Algorithm 1, first loop; Sec. 4.1 state S1), stitched blocks, oldest first.  The
+// sBlocks of exactly bsize chunks start at the rank of (bsize, oldest) in skey[].  One lane per
+// candidate reads its witness: a candidate whose witness is still active is out after two LDS
+// round trips for the whole tile.  The others are tested in pool order with all lanes over the
+// entries of one list; the first inactive one is handed out (ref = creation number, list = where
+// its entries are).
+template <bool BIG>
+DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
+{
+    const u32 lane = lane_id();
+    u32 base = rank_fast<BIG>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
+    for (;;) {
+        const u32 i = base + lane;
+        const u32 ic = i < V.ns ? i : 0u;
+        const u64 key = V.skey[ic];
+        const u32 wit = V.swit[ic];
+        const auto meta = V.smeta[ic];
+        const u64 vm = ballot(i < V.ns && (u32)(key >> 32) == bsize);
+        if (!vm) return false;
+        const u32 wv = pin(V.bmp[wit >> 10]);
+        u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
+        while (unknown) {
+            const u32 l = first_lane(unknown);
+            const auto m = from_lane_any(meta, l);
+            const u32 off = V.off(m), cnt = V.cnt(m);
+            u32 e = V.arena[off + (lane < cnt ? lane : 0u)];
+            const u32 word = pin(V.bmp[e >> 10]);
+            u64 bm = ballot(lane < cnt && (word & emask(e)) != 0);
+            if (cnt > 64 && !bm) {              // long list: the rest of it, a tile at a time
+                for (u32 eb = 64; eb < cnt && !bm; eb += 64) {
+                    const u32 k = eb + lane;
+                    e = V.arena[off + (k < cnt ? k : 0u)];
+                    bm = ballot(k < cnt && (V.bmp[e >> 10] & emask(e)) != 0);
+                }
+                if (!bm) e = V.arena[off + (lane < cnt ? lane : 0u)];
+            }
+            if (!bm) {
+                if (lane < cnt) atomicOr(&V.bmp[e >> 10], emask(e));
+                if (cnt > 64) bmp_fill_entries(V, off + 64, cnt - 64, true);
+                st_one(V.sstamp, base + l, ++V.clock);
+                ref = ~from_lane((u32)key, l);
+                list = (u32)m;
+                return true;
+            }
+            st_one(V.swit, base + l, from_lane(e, first_lane(bm)));
+            unknown &= unknown - 1;
+        }
+        if (~vm) return false;                  // the run of equal sizes ended inside this tile
+        base += 64;
+    }
+}
+
+// ---- S1, primitive blocks: the first inactive pBlock of exactly bsize chunks in pool order
+template <bool BIG>
+DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
+{
+    const u32 lane = lane_id();
+    u32 base = rank_fast<BIG>(V.pp, V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu);
+    for (;;) {
+        const u32 i = base + lane;
+        const u64 key = V.pool[i < V.np ? i : 0u];
+        const bool eq = i < V.np && (u32)(key >> 32) == bsize;
+        const u64 vm = ballot(eq);
+        if (!vm) return false;
+        const u32 st = ~(u32)key;
+        const u32 word = pin(V.bmp[eq ? st >> 5 : 0u]);
+        const u64 m = ballot(eq && !((word >> (st & 31)) & 1u));
+        if (m) {
+            start = from_lane(st, first_lane(m));
+            return true;
+        }
+        if (~vm) return false;
+        base += 64;
+    }
+}
+
 struct VmsRes {
     u32 dec_lo;                 // low decision word (code C_OOM alone when the request failed)
     u32 ref;                    // pBlock first chunk / sBlock creation number (= high decision word)
@@ -549,101 +637,21 @@ struct VmsRes {
     u32 list;                   // sBlock: offset << 16 | entries of its list (not BIG)
 };
 
-// One request of bsize chunks on the stitching path: S1 exact match, else BestFit's
-// second loop and the post-processing of its state (Sec. 4.1, Fig. 9).
+// No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of
+// its state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).  The rare path: a few per cent of
+// the requests of a converged trace.
 template <bool BIG, class Slots>
-DI void vms_alloc(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, Acct &A, u32 ev,
-                  VmsRes &R)
+DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, Acct &A, u32 ev,
+                       VmsRes &R)
 {
     const u32 lane = lane_id();
     R.kind = KIND_PBLOCK;
     R.held = bsize;
     R.ref = 0;
     R.list = 0;
-
-    if (V.sp_dirty) {
-        probe_refresh(V.sp, V.skey, V.ns);
-        V.sp_dirty = false;
-    }
-    if (V.pp_dirty) {
-        probe_refresh(V.pp, V.pool, V.np);
-        V.pp_dirty = false;
-    }
-    // blocks of exactly bsize chunks: skey[slo, shi) and pool[lo_p, hi_p); the four block loads
-    // of the searches are in flight together
-    const u64 k1 = ((u64)bsize << 32) | 0xFFFFFFFFu, k2 = ((u64)bsize << 32) - 1;
-    u32 slo, shi, lo_p, hi_p;
-    {
-        RankReq a = rank_begin(V.sp, V.skey, V.ns, k1), b = rank_begin(V.sp, V.skey, V.ns, k2);
-        RankReq c = rank_begin(V.pp, V.pool, V.np, k1), d = rank_begin(V.pp, V.pool, V.np, k2);
-        slo = rank_end(a, k1);
-        shi = rank_end(b, k2);
-        lo_p = rank_end(c, k1);
-        hi_p = rank_end(d, k2);
-    }
-
-    // ---- S1, stitched blocks, oldest first.  One lane per candidate reads its witness: a
-    // candidate whose witness is still active is out.  The others are tested in pool order with
-    // all lanes over the entries of one list.
-    for (u32 base = slo; base < shi; base += 64) {
-        const u32 i = base + lane;
-        const u32 ic = i < shi ? i : shi - 1;
-        const u32 wit = V.swit[ic];
-        const auto meta = V.smeta[ic];
-        const u32 idn = (u32)V.skey[ic];
-        const u32 wv = V.bmp[wit == NONE32 ? 0u : wit >> 10];
-        const bool known = wit != NONE32 && (wv & emask(wit));
-        u64 unknown = ballot(i < shi && !known);
-        while (unknown) {
-            const u32 l = first_lane(unknown);
-            const u32 c = base + l;
-            const auto m = from_lane_any(meta, l);
-            const u32 off = V.off(m), cnt = V.cnt(m);
-            bool busy = false;
-            u32 ent0 = 0;
-            for (u32 eb = 0; eb < cnt; eb += 64) {
-                const u32 k = eb + lane;
-                const u32 e = V.arena[off + (k < cnt ? k : cnt - 1)];
-                const u32 word = V.bmp[e >> 10];
-                const u64 bm = ballot(k < cnt && (word & emask(e)));
-                if (eb == 0) ent0 = e;
-                if (bm) {
-                    st_one(V.swit, c, from_lane(e, first_lane(bm)));
-                    busy = true;
-                    break;
-                }
-            }
-            if (!busy) {
-                if (cnt <= 64) {
-                    if (lane < cnt) atomicOr(&V.bmp[ent0 >> 10], emask(ent0));
-                } else {
-                    bmp_fill_entries(V, off, cnt, true);
-                }
-                st_one(V.sstamp, c, ++V.clock);
-                wave_sync();
-                R.kind = KIND_SBLOCK;
-                R.ref = ~from_lane(idn, l);
-                R.list = BIG ? 0u : (u32)m;
-                R.dec_lo = C_EXACT | B_SBLOCK | (1u << 8);
-                return;
-            }
-            unknown &= unknown - 1;
-        }
-        wave_sync();
-    }
-    // ---- S1, primitive blocks: the first inactive one in pool order
-    for (u32 base = lo_p; base < hi_p; base += 64) {
-        const u32 i = base + lane;
-        const u64 key = V.pool[i < hi_p ? i : hi_p - 1];
-        const u64 m = ballot(i < hi_p && !bmp_test(V.bmp, ~(u32)key));
-        if (m) {
-            const u32 start = ~from_lane((u32)key, first_lane(m));
-            bmp_fill(V.bmp, start, bsize, true);
-            R.ref = start;
-            R.dec_lo = C_EXACT | (1u << 8);
-            return;
-        }
-    }
+    // pool[lo_p, hi_p) are the pBlocks of exactly bsize chunks (all active, or S1 had taken one)
+    u32 lo_p, hi_p;
+    rank_desc2(V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &lo_p, &hi_p);
 
     // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
     // pool order is the single-block candidate (state 2).
@@ -792,220 +800,624 @@ DI void vms_alloc(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const K
     if (stitch_free(V, P, A)) R.dec_lo |= B_7;
 }
 
-// Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks.  `list` is the slot's
-// record of where the sBlock's entries are (USE_LIST), else the sBlock is looked up by its key.
-template <bool BIG, bool USE_LIST>
-DI void vms_free(VmsT<BIG> &V, u32 kind, u32 ref, u32 held, u32 list)
+// Update (Sec. 3.3.2) of an sBlock that is looked up by its key (slot table in LDS, or lists in HBM)
+template <bool BIG>
+DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
 {
-    if (kind == KIND_PBLOCK) {
-        bmp_fill(V.bmp, ref, held, false);
-    } else if (USE_LIST) {
-        bmp_fill_entries(V, list >> 16, list & 0xFFFFu, false);
-    } else {
-        if (V.sp_dirty) {
-            probe_refresh(V.sp, V.skey, V.ns);
-            V.sp_dirty = false;
-        }
-        u64 key = ((u64)held << 32) | (u32)~ref;
-        u32 idx = rank_probe(V.sp, V.skey, V.ns, key);
-        auto meta = ld_uni(V.smeta, idx);
-        bmp_fill_entries(V, V.off(meta), V.cnt(meta), false);
-    }
+    const u64 key = ((u64)held << 32) | (u32)~ref;
+    const u32 idx = rank_fast<BIG>(V.sp, V.skey, V.ns, key);
+    const auto meta = ld_uni(V.smeta, idx);
+    bmp_fill_entries(V, V.off(meta), V.cnt(meta), false);
 }
 
 // ---------------------------------------------------------------------------
-// The replay loop of one wavefront.  POLICY 0: splitting allocator only.
-// POLICY 1: stitching allocator with the splitting pool for small requests.
-// SLOT_REGS: slot table in registers (max_slots <= 64).
+// Hot and cold halves.  The replay loop keeps only what the two frequent paths need in registers
+// (exact hit on a cached block, free).  Everything else is "cold": it runs in separate,
+// non-inlined functions whose scalar state lives in a small LDS block between calls, so that it
+// costs the replay loop neither registers nor instructions.
+//   lds[0 .. 256)     scalars of the trace (SC_* below), one u32 each
+//   lds[256 .. 512)   copy of the launch parameters, for the cold functions
+// ---------------------------------------------------------------------------
+enum {
+    SC_NP, SC_NS, SC_NCHUNKS, SC_TOP, SC_LIVE, SC_NEXT_SID, SC_CLOCK, SC_SP_N, SC_SP_RESERVED,
+    SC_N_SPLIT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
+    SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
+    SC_R_DEC, SC_R_REF, SC_R_KIND_HELD, SC_R_LIST,      // result of the last cold call
+    SC_COMPACTED,                                       // the arena was compacted since the flag was cleared
+    SC_SWAPPED,                                         // BIG: arena and compaction buffer have changed places
+    SC_COUNT
+};
+#define LDS_SCALARS 0u
+#define LDS_PARAMS 256u
+#define KPARAM_WORDS ((u32)(sizeof(KParams) / 4))
+static_assert(SC_COUNT <= 64 && sizeof(KParams) <= 256 && sizeof(KParams) % 4 == 0, "LDS header layout");
+
+typedef __attribute__((address_space(3))) char lds_char;
+
+// stand-in for the slot table inside the cold functions: they only note that lists have moved
+struct ColdSlots {
+    bool compacted;
+    DI void moved(u32, u32, const KParams &) { compacted = true; }
+};
+
+// scalars <-> registers, one LDS access for all of them
+struct ColdState {
+    u32 v;                      // lane k: scalar k
+    // pinned: every lane must load its scalar even if only one lane goes on to use them
+    DI void load(const char *lds) { v = pin(((const u32 *)(lds + LDS_SCALARS))[lane_id()]); }
+    DI void store(char *lds) const
+    {
+        ((u32 *)(lds + LDS_SCALARS))[lane_id()] = v;
+        wave_sync();
+    }
+    DI u32 get(u32 k) const { return from_lane(v, k); }
+    DI void set(u32 k, u32 x) { v = lane_id() == k ? x : v; }
+};
+
+DI void load_params(KParams &P, const char *lds)
+{
+    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
+    u32 *w = (u32 *)&P;
+#pragma unroll
+    for (u32 k = 0; k < KPARAM_WORDS; k++) w[k] = from_lane(pv, k);
+}
+
+template <bool BIG>
+DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool swapped)
+{
+    V.pool = (u64 *)(lds + P.off_pool);
+    V.bmp = (u32 *)(lds + P.off_bmp);
+    V.skey = (u64 *)(lds + P.off_skey);
+    V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
+    V.sstamp = (u32 *)(lds + P.off_sstamp);
+    V.swit = (u32 *)(lds + P.off_swit);
+    u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs;
+    V.bounce = BIG && swapped ? hi : lo;
+    V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
+}
+
+DI void acct_load(Acct &A, const ColdState &C)
+{
+    A.requested = A.active = A.peak_requested = A.peak_active = 0;      // kept by the replay loop
+    A.n_split = C.get(SC_N_SPLIT);
+    A.n_merge = C.get(SC_N_MERGE);
+    A.n_created = C.get(SC_N_CREATED);
+    A.n_evicted = C.get(SC_N_EVICTED);
+    A.first_oom = C.get(SC_FIRST_OOM);
+    A.status = C.get(SC_STATUS);
+    A.overflow_event = C.get(SC_OVF_EVENT);
+    A.hw_pblocks = C.get(SC_HW_PBLOCKS);
+    A.hw_sblocks = C.get(SC_HW_SBLOCKS);
+    A.hw_free = C.get(SC_HW_FREE);
+    A.hw_members = C.get(SC_HW_MEMBERS);
+    A.hw_runs = C.get(SC_HW_RUNS);
+    A.stop = C.get(SC_STOP) != 0;
+}
+
+DI void acct_store(const Acct &A, ColdState &C)
+{
+    C.set(SC_N_SPLIT, A.n_split);
+    C.set(SC_N_MERGE, A.n_merge);
+    C.set(SC_N_CREATED, A.n_created);
+    C.set(SC_N_EVICTED, A.n_evicted);
+    C.set(SC_FIRST_OOM, A.first_oom);
+    C.set(SC_STATUS, A.status);
+    C.set(SC_OVF_EVENT, A.overflow_event);
+    C.set(SC_HW_PBLOCKS, A.hw_pblocks);
+    C.set(SC_HW_SBLOCKS, A.hw_sblocks);
+    C.set(SC_HW_FREE, A.hw_free);
+    C.set(SC_HW_MEMBERS, A.hw_members);
+    C.set(SC_HW_RUNS, A.hw_runs);
+    C.set(SC_STOP, A.stop ? 1u : 0u);
+}
+
+// Cold call: a request for bsize chunks that no cached block fits exactly (states S2 to S5).
+// The result is left in the SC_R_* scalars.
+template <bool BIG>
+__device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *ws_slice, u32 bsize, u32 reserved_units,
+                                                         u32 clock, u32 ev)
+{
+    char *lds = (char *)ldsp;
+    KParams P;
+    load_params(P, lds);
+    ColdState C;
+    C.load(lds);
+    VmsT<BIG> V;
+    vms_bind(V, lds, ws_slice, P, C.get(SC_SWAPPED) != 0);
+    V.np = C.get(SC_NP);
+    V.ns = C.get(SC_NS);
+    V.n_chunks = C.get(SC_NCHUNKS);
+    V.top = C.get(SC_TOP);
+    V.live_ent = C.get(SC_LIVE);
+    V.next_sid = C.get(SC_NEXT_SID);
+    V.clock = clock;
+    Acct A;
+    acct_load(A, C);
+    ColdSlots S;
+    S.compacted = false;
+    VmsRes R;
+    u32 *arena_before = V.arena;
+    vms_alloc_rest(V, S, bsize, reserved_units, P, A, ev, R);
+    C.set(SC_NP, V.np);
+    C.set(SC_NS, V.ns);
+    C.set(SC_NCHUNKS, V.n_chunks);
+    C.set(SC_TOP, V.top);
+    C.set(SC_LIVE, V.live_ent);
+    C.set(SC_NEXT_SID, V.next_sid);
+    C.set(SC_CLOCK, V.clock);
+    acct_store(A, C);
+    C.set(SC_R_DEC, R.dec_lo);
+    C.set(SC_R_REF, R.ref);
+    C.set(SC_R_KIND_HELD, R.kind | (R.held << 2));
+    C.set(SC_R_LIST, R.list);
+    if (S.compacted) C.set(SC_COMPACTED, 1u);
+    if (BIG && V.arena != arena_before) C.set(SC_SWAPPED, C.get(SC_SWAPPED) ^ 1u);
+    C.store(lds);
+}
+
+// Cold calls of the stitching policy for requests below one chunk: its private splitting pool.
+// alloc: SC_R_DEC = code | split << 8, SC_R_REF = address << 2 | flags.  free: SC_R_DEC = merged
+// left | merged right << 1.
+__device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 size, u32 seg, u32 may_grow, u32 ev)
+{
+    char *lds = (char *)ldsp;
+    ColdState C;
+    C.load(lds);
+    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
+    SplitPoolD sp;
+    sp.fl = (u64 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_fl) / 4)));
+    sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
+    sp.n = C.get(SC_SP_N);
+    sp.reserved = C.get(SC_SP_RESERVED);
+    Acct A;
+    acct_load(A, C);
+    SplitRes r;
+    sp_alloc(sp, size, seg, may_grow != 0, A, ev, r);
+    C.set(SC_SP_N, sp.n);
+    C.set(SC_SP_RESERVED, sp.reserved);
+    acct_store(A, C);
+    C.set(SC_R_DEC, r.code | (r.split ? 1u << 8 : 0u));
+    C.set(SC_R_REF, (r.addr << 2) | r.flags);
+    C.store(lds);
+}
+
+__device__ __attribute__((noinline)) void small_free_cold(lds_char *ldsp, u32 addr, u32 size, u32 flags, u32 ev)
+{
+    char *lds = (char *)ldsp;
+    ColdState C;
+    C.load(lds);
+    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
+    SplitPoolD sp;
+    sp.fl = (u64 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_fl) / 4)));
+    sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
+    sp.n = C.get(SC_SP_N);
+    sp.reserved = C.get(SC_SP_RESERVED);
+    Acct A;
+    acct_load(A, C);
+    bool ml, mr;
+    sp_free(sp, addr, size, flags, &ml, &mr, A, ev);
+    C.set(SC_SP_N, sp.n);
+    acct_store(A, C);
+    C.set(SC_R_DEC, (ml ? 1u : 0u) | (mr ? 2u : 0u));
+    C.store(lds);
+}
+
+// The per-tile work shared by both replay kernels: one event per lane.
+struct TileOut {
+    u32 n_code[8];              // events of this lane per decision code ([7]: invalid)
+    u64 dig;                    // this lane's share of the digest
+    DI void init()
+    {
+#pragma unroll
+        for (u32 c = 0; c < 8; c++) n_code[c] = 0;
+        dig = 0;
+    }
+};
+
+DI void tile_emit(TileOut &T, u64 *dec_row, u32 base, u32 done, u32 v_dlo, u32 v_dhi, u32 v_act, u32 v_res)
+{
+    const u32 lane = lane_id();
+    const bool valid = lane < done;
+    const u64 dec = ((u64)v_dhi << 32) | v_dlo;
+    if (dec_row && valid) dec_row[base + lane] = dec;
+    const u32 code = v_dlo & 15, cidx = !valid ? 8u : (code == C_INVALID ? 7u : code);
+#pragma unroll
+    for (u32 c = 0; c < 8; c++) T.n_code[c] += cidx == c ? 1u : 0u;
+    // digest: sum over events i of (decision * K1 + (active << 32 | reserved)) * ((2 i + 1) * K2)
+    const u64 term = (dec * 0x9E3779B97F4A7C15ull + (((u64)v_act << 32) | v_res)) *
+                     ((2ull * (base + lane) + 1ull) * 0xD6E8FEB86659FD93ull);
+    T.dig += valid ? term : 0ull;
+}
+
+// end of the trace: the lanes' shares become the totals (all lanes return the same values)
+DI u64 tile_totals(const TileOut &T, u32 n_code[8])
+{
+#pragma unroll
+    for (u32 c = 0; c < 8; c++) n_code[c] = (u32)wave_sum_u64(T.n_code[c]);
+    return wave_sum_u64(T.dig);
+}
+
+// ---------------------------------------------------------------------------
+// Replay under the stitching policy (Sec. 3, Sec. 4.1), one wavefront per trace.
+// SLOT_REGS: slot table in registers (max_slots <= 64).  d_params: the launch parameters
+// again, in device memory (copied to LDS for the cold functions).
 //
 // Per event only the allocator runs; the decision word and the active / reserved totals after
-// the event are parked in lane j of four registers.  Once per tile of 64 events
-// the lanes store the decisions with one coalesced write, count the decision codes and fold
-// their event into the digest, all 64 events side by side.
+// the event are parked in lane j of four registers.  Once per tile of 64 events the lanes store
+// the decisions with one coalesced write, count the decision codes and fold their event into
+// the digest, all 64 events side by side.
 // ---------------------------------------------------------------------------
-template <int POLICY, bool BIG, bool SLOT_REGS>
-__global__ __launch_bounds__(64) void replay_kernel(KParams P, const u64 *__restrict__ events,
-                                                    const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
-                                                    vms_trace_stats *__restrict__ stats, char *__restrict__ workspace)
+template <bool BIG, bool SLOT_REGS>
+__global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__restrict__ d_params,
+                                                        const u64 *__restrict__ events, const u32 *__restrict__ n_events,
+                                                        u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
+                                                        char *__restrict__ workspace)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
     constexpr bool USE_LIST = SLOT_REGS && !BIG;
+    char *ws_slice = workspace + (size_t)trace * P.ws_stride;
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
-
-    SplitPoolD sp;
-    sp.fl = (u64 *)(lds + P.off_fl);
-    sp.n = 0;
-    sp.cap = P.cap_free;
-    sp.reserved = 0;
-
+    {
+        // LDS header: scalars, then the parameters
+        u32 init = 0;
+        if (lane == SC_FIRST_OOM || lane == SC_OVF_EVENT) init = NONE32;
+        ((u32 *)(lds + LDS_SCALARS))[lane] = init;
+        ((u32 *)(lds + LDS_PARAMS))[lane] = lane < KPARAM_WORDS ? d_params[lane] : 0u;
+    }
     VmsT<BIG> V;
+    vms_bind(V, lds, ws_slice, P, false);
     V.np = V.ns = V.n_chunks = V.top = V.live_ent = V.next_sid = V.clock = 0;
     V.pp.v = V.sp.v = 0;
     V.pp.stride = V.sp.stride = 1;
-    V.pp_dirty = V.sp_dirty = false;
-    if (POLICY == 1) {
-        V.pool = (u64 *)(lds + P.off_pool);
-        V.bmp = (u32 *)(lds + P.off_bmp);
-        V.skey = (u64 *)(lds + P.off_skey);
-        V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
-        V.sstamp = (u32 *)(lds + P.off_sstamp);
-        V.swit = (u32 *)(lds + P.off_swit);
-        V.bounce = (u32 *)(workspace + (size_t)trace * P.ws_stride);
-        V.arena = BIG ? V.bounce + P.cap_runs : (u32 *)(lds + P.off_arena);
-        for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
-    }
+    for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
     wave_sync();
 
-    Acct A;
-    acct_init(A);
-    u32 code_count = 0;         // lane c: events with decision code c (lane 7: invalid)
-    u64 dig = 0;                // this lane's share of the digest
+    u32 requested = 0, active = 0, peak_requested = 0, peak_active = 0;
+    u32 sp_reserved = 0;        // small-request pool: units reserved so far
+    bool stop = false;
+    TileOut T;
+    T.init();
     const u32 chunk_units = 1u << P.chunk_shift;
     const u32 n_ev = n_events ? min(uni(n_events[trace]), P.max_events) : P.max_events;
     const u64 *ev_row = events + (size_t)trace * P.max_events;
     u64 *dec_row = decisions ? decisions + (size_t)trace * P.max_events : nullptr;
 
     u64 ev_next = lane < n_ev ? ev_row[lane] : 0;
-    for (u32 base = 0; base < n_ev && !A.stop; base += 64) {
+    for (u32 base = 0; base < n_ev; base += 64) {
         const u32 tile = min(64u, n_ev - base);
-        const u64 evw = ev_next;
+        const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
         if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
-        u32 done = 0;
+        u32 done = tile;
+        // every path of an event ends by parking its results in lane j and going on to the next event
+#define EMIT(DLO, DHI)                                                     \
+    {                                                                      \
+        const bool mine = lane == j;                                       \
+        v_dlo = mine ? (DLO) : v_dlo;                                      \
+        v_dhi = mine ? (DHI) : v_dhi;                                      \
+        v_act = mine ? active : v_act;                                     \
+        v_res = mine ? sp_reserved + (V.n_chunks << P.chunk_shift) : v_res; \
+        wave_sync();                                                       \
+        continue;                                                          \
+    }
         for (u32 j = 0; j < tile; j++) {
-            const u32 ev = base + j;
-            const u32 w = from_lane((u32)evw, j), slot = from_lane((u32)(evw >> 32), j);
-            u32 dlo = C_INVALID, dhi = 0;
-            if (slot < P.max_slots) {
-                const u32 req = S.get_req(slot);
-                if (!(w >> 31)) {
-                    const u32 size = w;
-                    if (size != 0 && req == SLOT_UNBOUND) {
-                        const u32 reserved = sp.reserved + (V.n_chunks << P.chunk_shift);
-                        bool oom = false;
-                        u32 held_units = size;
-                        if (POLICY == 0 || size < P.small_limit_units) {
-                            const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
-                            SplitRes r;
-                            sp_alloc(sp, size, seg, reserved + seg <= P.capacity_units, A, ev, r);
-                            if (r.code == C_OOM) {
-                                oom = true;
-                            } else {
-                                S.set_a(slot, (r.addr << 2) | r.flags);
-                                if (POLICY == 1) S.set_b(slot, (u32)KIND_SMALL);
-                                dlo = r.code | (POLICY == 1 ? B_SMALL : 0u) | (r.split ? B_6 : 0u) |
-                                      ((r.code == C_GROW ? 0u : 1u) << 8);
-                                dhi = r.addr;
-                            }
-                        } else {
-                            const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
-                            VmsRes r;
-                            vms_alloc(V, S, bsize, reserved, P, A, ev, r);
-                            if ((r.dec_lo & 15) == C_OOM) {
-                                oom = true;
-                            } else {
-                                S.set_a(slot, r.ref);
-                                S.set_b(slot, r.kind | (r.held << 2));
-                                if (USE_LIST) S.set_c(slot, r.list);
-                                held_units = r.held << P.chunk_shift;
-                                dlo = r.dec_lo;
-                                dhi = (r.dec_lo & 15) == C_INVALID ? 0u : r.ref;
-                            }
-                        }
-                        if (oom) {
-                            S.set_req(slot, (u32)SLOT_OOM);
-                            if (A.first_oom == NONE32) A.first_oom = ev;
-                            dlo = C_OOM;
-                            dhi = 0;
-                        } else if (!A.stop) {
-                            S.set_req(slot, size);
-                            A.requested += size;
-                            A.active += held_units;
-                            // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
-                            A.peak_requested = max(A.peak_requested, A.requested);
-                            A.peak_active = max(A.peak_active, A.active);
-                        }
+            const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
+            if (slot >= P.max_slots) EMIT((u32)C_INVALID, 0u)
+            const u32 req = S.get_req(slot);
+            if ((int)w < 0) {
+                // ---- FREE.  Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks
+                if (req + 1u <= 1u) {                       // unbound, or bound to a request that failed
+                    if (req == SLOT_OOM) {
+                        S.set_req(slot, (u32)SLOT_UNBOUND);
+                        EMIT((u32)C_FREE_NOOP, 0u)
                     }
-                } else if (req == SLOT_OOM) {
-                    S.set_req(slot, (u32)SLOT_UNBOUND);
-                    dlo = C_FREE_NOOP;
-                } else if (req != SLOT_UNBOUND) {
-                    const u32 a = S.get_a(slot);
-                    const u32 b = POLICY == 1 ? S.get_b(slot) : (u32)KIND_SMALL;
-                    u32 held_units = req;
-                    if ((b & 3) == KIND_SMALL) {
-                        bool ml, mr;
-                        sp_free(sp, a >> 2, req, a & 3, &ml, &mr, A, ev);
-                        dlo = C_FREE | (POLICY == 1 ? B_SMALL : 0u) | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
-                        dhi = a >> 2;
+                    EMIT((u32)C_INVALID, 0u)
+                }
+                const u32 a = S.get_a(slot), b = S.get_b(slot);
+                const u32 kind = b & 3;
+                S.set_req(slot, (u32)SLOT_UNBOUND);
+                requested -= req;
+                if (kind == KIND_SBLOCK) {
+                    if (USE_LIST) {
+                        const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
+                        if (lane < cnt) {
+                            const u32 e = V.arena[off + lane];
+                            atomicAnd(&V.bmp[e >> 10], ~emask(e));
+                        }
+                        if (cnt > 64) bmp_fill_entries(V, off + 64, cnt - 64, false);
                     } else {
-                        vms_free<BIG, USE_LIST>(V, b & 3, a, b >> 2, USE_LIST ? S.get_c(slot) : 0u);
-                        held_units = (b >> 2) << P.chunk_shift;
-                        dlo = C_FREE | ((b & 3) == KIND_SBLOCK ? B_SBLOCK : 0u);
-                        dhi = a;
+                        vms_free_by_key(V, a, b >> 2);
                     }
-                    S.set_req(slot, (u32)SLOT_UNBOUND);
-                    A.requested -= req;
-                    A.active -= held_units;
+                    active -= (b >> 2) << P.chunk_shift;
+                    EMIT(C_FREE | B_SBLOCK, a)
+                }
+                if (kind == KIND_PBLOCK) {
+                    bmp_fill(V.bmp, a, b >> 2, false);
+                    active -= (b >> 2) << P.chunk_shift;
+                    EMIT((u32)C_FREE, a)
+                }
+                small_free_cold((lds_char *)lds, a >> 2, req, a & 3, base + j);
+                ColdState C;
+                C.load(lds);
+                const u32 m = C.get(SC_R_DEC);
+                if (C.get(SC_STOP)) {
+                    stop = true;
+                    done = j;
+                    break;
+                }
+                active -= req;
+                EMIT(C_FREE | B_SMALL | (m & 1 ? B_6 : 0u) | (m & 2 ? B_7 : 0u), a >> 2)
+            }
+            // ---- ALLOC
+            const u32 size = w;
+            if (size == 0 || req != SLOT_UNBOUND) EMIT((u32)C_INVALID, 0u)
+            if (size >= P.small_limit_units) {
+                const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
+                u32 ref, list = 0;
+                if (s1_sblock(V, bsize, ref, list)) {
+                    S.set_a(slot, ref);
+                    S.set_b(slot, KIND_SBLOCK | (bsize << 2));
+                    if (USE_LIST) S.set_c(slot, list);
+                    S.set_req(slot, size);
+                    requested += size;
+                    active += bsize << P.chunk_shift;
+                    // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
+                    peak_requested = max(peak_requested, requested);
+                    peak_active = max(peak_active, active);
+                    EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)
+                }
+                if (s1_pblock(V, bsize, ref)) {
+                    bmp_fill(V.bmp, ref, bsize, true);
+                    S.set_a(slot, ref);
+                    S.set_b(slot, KIND_PBLOCK | (bsize << 2));
+                    S.set_req(slot, size);
+                    requested += size;
+                    active += bsize << P.chunk_shift;
+                    peak_requested = max(peak_requested, requested);
+                    peak_active = max(peak_active, active);
+                    EMIT(C_EXACT | (1u << 8), ref)
                 }
             }
+            // ---- the rare cases: no exact fit (states S2 to S5), or a request below one chunk
+            u32 dlo, dhi = 0, held_units = size;
             wave_sync();
-            if (A.stop) break;
-            const bool mine = lane == j;
-            v_dlo = mine ? dlo : v_dlo;
-            v_dhi = mine ? dhi : v_dhi;
-            v_act = mine ? A.active : v_act;
-            v_res = mine ? sp.reserved + (V.n_chunks << P.chunk_shift) : v_res;
-            done = j + 1;
+            if (size >= P.small_limit_units) {
+                const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
+                vms_alloc_cold<BIG>((lds_char *)lds, ws_slice, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), V.clock,
+                                    base + j);
+                ColdState C;
+                C.load(lds);
+                V.np = C.get(SC_NP);
+                V.ns = C.get(SC_NS);
+                V.n_chunks = C.get(SC_NCHUNKS);
+                V.clock = C.get(SC_CLOCK);
+                if (BIG) vms_bind(V, lds, ws_slice, P, C.get(SC_SWAPPED) != 0);
+                // the pools may have changed: renew the first search level of both
+                probe_refresh(V.sp, V.skey, V.ns);
+                probe_refresh(V.pp, V.pool, V.np);
+                if (USE_LIST && C.get(SC_COMPACTED)) {
+                    // lists have moved: every slot holding an sBlock looks its list up again
+                    S.relist(V.skey, (const u32 *)V.smeta, V.ns);
+                    st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_COMPACTED, 0u);
+                }
+                if (C.get(SC_STOP)) {                       // an engine table overflowed: the trace ends here
+                    stop = true;
+                    done = j;
+                    break;
+                }
+                dlo = C.get(SC_R_DEC);
+                if ((dlo & 15) != C_OOM) {
+                    const u32 kh = C.get(SC_R_KIND_HELD);
+                    dhi = C.get(SC_R_REF);
+                    S.set_a(slot, dhi);
+                    S.set_b(slot, kh);
+                    if (USE_LIST) S.set_c(slot, C.get(SC_R_LIST));
+                    held_units = (kh >> 2) << P.chunk_shift;
+                }
+            } else {
+                const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
+                const u32 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
+                small_alloc_cold((lds_char *)lds, size, seg, reserved + seg <= P.capacity_units ? 1u : 0u, base + j);
+                ColdState C;
+                C.load(lds);
+                if (C.get(SC_STOP)) {
+                    stop = true;
+                    done = j;
+                    break;
+                }
+                const u32 rd = C.get(SC_R_DEC), code = rd & 15;
+                sp_reserved = C.get(SC_SP_RESERVED);
+                dlo = C_OOM;
+                if (code != C_OOM) {
+                    const u32 af = C.get(SC_R_REF);
+                    S.set_a(slot, af);
+                    S.set_b(slot, (u32)KIND_SMALL);
+                    dlo = code | B_SMALL | (rd & 0x100 ? B_6 : 0u) | ((code == C_GROW ? 0u : 1u) << 8);
+                    dhi = af >> 2;
+                }
+            }
+            if ((dlo & 15) == C_OOM) {
+                S.set_req(slot, (u32)SLOT_OOM);
+                ColdState C;                                // rare: note the first failed request
+                C.load(lds);
+                if (C.get(SC_FIRST_OOM) == NONE32) st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_FIRST_OOM, base + j);
+                EMIT((u32)C_OOM, 0u)
+            }
+            S.set_req(slot, size);
+            requested += size;
+            active += held_units;
+            peak_requested = max(peak_requested, requested);
+            peak_active = max(peak_active, active);
+            EMIT(dlo, dhi)
         }
-        // the tile's events, one per lane
-        const bool valid = lane < done;
-        const u64 dec = ((u64)v_dhi << 32) | v_dlo;
-        if (dec_row && valid) dec_row[base + lane] = dec;
-        const u32 code = v_dlo & 15, cidx = code == C_INVALID ? 7u : code;
-#pragma unroll
-        for (u32 c = 0; c < 8; c++) {
-            const u32 n = popc64(ballot(valid && cidx == c));
-            code_count += lane == c ? n : 0u;
-        }
-        if (ballot(valid && code == C_INVALID)) A.status |= VMS_ST_INVALID_EVENT;
-        // digest: sum over events i of (decision * K1 + (active << 32 | reserved)) * ((2 i + 1) * K2)
-        const u64 term = (dec * 0x9E3779B97F4A7C15ull + (((u64)v_act << 32) | v_res)) *
-                         ((2ull * (base + lane) + 1ull) * 0xD6E8FEB86659FD93ull);
-        dig += valid ? term : 0ull;
+#undef EMIT
+        tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
+        if (stop) break;
     }
 
     wave_sync();
-    const u64 digest = wave_sum_u64(dig);
-    if (lane < 8) stats[(size_t)POLICY * P.n_traces + trace].n_code[lane] = code_count;
+    u32 n_code[8];
+    const u64 digest = tile_totals(T, n_code);
+    ColdState C;
+    C.load(lds);
     if (lane == 0) {
-        vms_trace_stats &s = stats[(size_t)POLICY * P.n_traces + trace];
-        const u64 reserved = sp.reserved + (V.n_chunks << P.chunk_shift);
+        vms_trace_stats &s = stats[(size_t)P.n_traces + trace];
+#pragma unroll
+        for (u32 c = 0; c < 8; c++) s.n_code[c] = n_code[c];
+        const u64 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
+        s.peak_requested = (u64)peak_requested * 512;
+        s.peak_active = (u64)peak_active * 512;
+        s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value
+        s.final_requested = (u64)requested * 512;
+        s.final_active = (u64)active * 512;
+        s.final_reserved = reserved * 512;
+        s.digest = digest;
+        s.n_split = C.get(SC_N_SPLIT);
+        s.n_merge = C.get(SC_N_MERGE);
+        s.n_sblock_created = C.get(SC_N_CREATED);
+        s.n_sblock_evicted = C.get(SC_N_EVICTED);
+        s.first_oom_event = C.get(SC_FIRST_OOM);
+        s.status = C.get(SC_STATUS) | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
+        s.max_pblocks = C.get(SC_HW_PBLOCKS);
+        s.max_sblocks = C.get(SC_HW_SBLOCKS);
+        s.max_free_blocks = C.get(SC_HW_FREE);
+        s.max_members = C.get(SC_HW_MEMBERS);
+        s.max_runs = C.get(SC_HW_RUNS);
+        s.overflow_event = C.get(SC_OVF_EVENT);
+        // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
+        s.fragmentation = reserved ? 1.0 - (double)peak_active / (double)reserved : 0.0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Replay under the splitting policy (Sec. 2.2), one wavefront per trace.  Both of its paths are
+// hot, so everything is inline and its few scalars stay in registers.
+// ---------------------------------------------------------------------------
+template <bool SLOT_REGS>
+__global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *__restrict__ events,
+                                                          const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
+                                                          vms_trace_stats *__restrict__ stats)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const u32 lane = lane_id();
+    const u32 trace = blockIdx.x;
+
+    SlotsT<SLOT_REGS> S;
+    S.init(lds, P);
+    SplitPoolD sp;
+    sp.fl = (u64 *)(lds + P.off_fl);
+    sp.n = 0;
+    sp.cap = P.cap_free;
+    sp.reserved = 0;
+    wave_sync();
+
+    Acct A;
+    acct_init(A);
+    TileOut T;
+    T.init();
+    const u32 chunk_units = 1u << P.chunk_shift;
+    const u32 n_ev = n_events ? min(uni(n_events[trace]), P.max_events) : P.max_events;
+    const u64 *ev_row = events + (size_t)trace * P.max_events;
+    u64 *dec_row = decisions ? decisions + (size_t)trace * P.max_events : nullptr;
+
+    u64 ev_next = lane < n_ev ? ev_row[lane] : 0;
+    for (u32 base = 0; base < n_ev; base += 64) {
+        const u32 tile = min(64u, n_ev - base);
+        const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
+        if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
+        u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
+        u32 done = tile;
+        for (u32 j = 0; j < tile; j++) {
+            const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
+            u32 dlo = C_INVALID, dhi = 0;
+            do {
+                if (slot >= P.max_slots) break;
+                const u32 req = S.get_req(slot);
+                if ((int)w < 0) {
+                    if (req + 1u <= 1u) {                   // unbound, or bound to a request that failed
+                        if (req == SLOT_OOM) {
+                            S.set_req(slot, (u32)SLOT_UNBOUND);
+                            dlo = C_FREE_NOOP;
+                        }
+                        break;
+                    }
+                    const u32 a = S.get_a(slot);
+                    S.set_req(slot, (u32)SLOT_UNBOUND);
+                    bool ml, mr;
+                    sp_free(sp, a >> 2, req, a & 3, &ml, &mr, A, base + j);
+                    A.requested -= req;
+                    dlo = C_FREE | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
+                    dhi = a >> 2;
+                    break;
+                }
+                const u32 size = w;
+                if (size == 0 || req != SLOT_UNBOUND) break;
+                const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
+                SplitRes r;
+                sp_alloc(sp, size, seg, sp.reserved + seg <= P.capacity_units, A, base + j, r);
+                if (A.stop) break;
+                if (r.code == C_OOM) {
+                    S.set_req(slot, (u32)SLOT_OOM);
+                    if (A.first_oom == NONE32) A.first_oom = base + j;
+                    dlo = C_OOM;
+                    break;
+                }
+                S.set_a(slot, (r.addr << 2) | r.flags);
+                S.set_req(slot, size);
+                dlo = r.code | (r.split ? B_6 : 0u) | ((r.code == C_GROW ? 0u : 1u) << 8);
+                dhi = r.addr;
+                // blocks are cut to the request: active bytes are the requested bytes
+                A.requested += size;
+                A.peak_requested = max(A.peak_requested, A.requested);
+            } while (0);
+            wave_sync();
+            if (A.stop) {                                   // the free list overflowed: the trace ends here
+                done = j;
+                break;
+            }
+            const bool mine = lane == j;
+            v_dlo = mine ? dlo : v_dlo;
+            v_dhi = mine ? dhi : v_dhi;
+            v_act = mine ? A.requested : v_act;
+            v_res = mine ? sp.reserved : v_res;
+        }
+        tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
+        if (A.stop) break;
+    }
+
+    wave_sync();
+    u32 n_code[8];
+    const u64 digest = tile_totals(T, n_code);
+    if (lane == 0) {
+        vms_trace_stats &s = stats[trace];
+#pragma unroll
+        for (u32 c = 0; c < 8; c++) s.n_code[c] = n_code[c];
+        const u64 reserved = sp.reserved;
         s.peak_requested = (u64)A.peak_requested * 512;
-        s.peak_active = (u64)A.peak_active * 512;
+        s.peak_active = (u64)A.peak_requested * 512;
         s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value
         s.final_requested = (u64)A.requested * 512;
-        s.final_active = (u64)A.active * 512;
+        s.final_active = (u64)A.requested * 512;
         s.final_reserved = reserved * 512;
         s.digest = digest;
         s.n_split = A.n_split;
         s.n_merge = A.n_merge;
-        s.n_sblock_created = A.n_created;
-        s.n_sblock_evicted = A.n_evicted;
+        s.n_sblock_created = 0;
+        s.n_sblock_evicted = 0;
         s.first_oom_event = A.first_oom;
-        s.status = A.status;
-        s.max_pblocks = A.hw_pblocks;
-        s.max_sblocks = A.hw_sblocks;
+        s.status = A.status | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
+        s.max_pblocks = 0;
+        s.max_sblocks = 0;
         s.max_free_blocks = A.hw_free;
-        s.max_members = A.hw_members;
-        s.max_runs = A.hw_runs;
+        s.max_members = 0;
+        s.max_runs = 0;
         s.overflow_event = A.overflow_event;
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
-        s.fragmentation = reserved ? 1.0 - (double)A.peak_active / (double)reserved : 0.0;
+        s.fragmentation = reserved ? 1.0 - (double)A.peak_requested / (double)reserved : 0.0;
     }
 }
 

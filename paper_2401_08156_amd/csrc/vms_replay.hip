@@ -27,6 +27,7 @@ struct vms_replay {
     bool slot_regs;             // slot table in registers (see SlotsT)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
+    KParams *d_kp;              // kp[] again, in device memory (the stitching kernel copies it to LDS)
     hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
     hipStream_t side;           // the splitting kernel runs here, beside the stitching kernel
     hipStream_t last_stream;
@@ -61,6 +62,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         return at;
     };
     k.off_slot_req = k.off_slot_a = k.off_slot_b = k.off_slot_c = 0;
+    if (policy) take(512);      // scalars of the trace and a copy of these parameters (see replay_kernels.hpp)
     if (!slot_regs) {
         k.off_slot_req = take(c.max_slots * 4);
         k.off_slot_a = take(c.max_slots * 4);
@@ -81,15 +83,16 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
     k.lds_bytes = off;
 }
 
-typedef void (*replay_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
+typedef void (*vms_fn)(KParams, const u32 *, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
+typedef void (*split_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *);
 
-// the kernel variant for a policy: chunk-run lists in HBM or LDS, slot table in LDS or registers
-replay_fn pick_kernel(int policy, bool big, bool slot_regs)
+// the kernel variants: chunk-run lists in HBM or LDS, slot table in LDS or registers
+vms_fn pick_vms(bool big, bool slot_regs)
 {
-    if (policy == 0) return slot_regs ? replay_kernel<0, false, true> : replay_kernel<0, false, false>;
-    if (big) return slot_regs ? replay_kernel<1, true, true> : replay_kernel<1, true, false>;
-    return slot_regs ? replay_kernel<1, false, true> : replay_kernel<1, false, false>;
+    if (big) return slot_regs ? replay_vms_kernel<true, true> : replay_vms_kernel<true, false>;
+    return slot_regs ? replay_vms_kernel<false, true> : replay_vms_kernel<false, false>;
 }
+split_fn pick_split(bool slot_regs) { return slot_regs ? replay_split_kernel<true> : replay_split_kernel<false>; }
 
 }  // namespace
 
@@ -138,7 +141,9 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (!h) return VMS_ENOMEM;
     memset(h, 0, sizeof *h);
     h->cfg = c;
-    h->big = c.max_runs > 16384;        // more than 64 KB of chunk runs per trace: keep them in HBM
+    // more than 64 KB of chunk-run lists per trace: keep them in HBM; that kernel variant is also
+    // the one whose rank searches cope with pools beyond 4096 blocks
+    h->big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
     h->slot_regs = c.max_slots <= 64;
     uint32_t shift = 0;
     while ((UNIT << shift) < c.chunk_bytes) shift++;
@@ -177,12 +182,17 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     // records of a policy that never runs stay zero; a run rewrites every record of its policies
     if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * 2 * (size_t)c.n_traces);
     if (e == hipSuccess) e = hipMalloc((void **)&h->d_summary, sizeof(vms_summary));
+    if (e == hipSuccess) e = hipMalloc((void **)&h->d_kp, sizeof(h->kp));
+    if (e == hipSuccess) e = hipMemcpy(h->d_kp, h->kp, sizeof(h->kp), hipMemcpyHostToDevice);
     for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
-    for (int p = 0; p < 2 && e == hipSuccess; p++)
-        e = hipFuncSetAttribute((const void *)pick_kernel(p, h->big, h->slot_regs),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_PER_CU);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)pick_split(h->slot_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)LDS_PER_CU);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)pick_vms(h->big, h->slot_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)LDS_PER_CU);
     if (e != hipSuccess) {
         int rc = e == hipErrorOutOfMemory ? VMS_ENOMEM : VMS_EHIP;
         vms_replay_destroy(h);
@@ -217,15 +227,15 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     hipStream_t sst = both ? h->side : st;
     if (both) HIP_TRY(h, hipStreamWaitEvent(sst, h->ev[0], 0));
     if (c.policy_mask & VMS_POLICY_VMS) {
-        hipLaunchKernelGGL(pick_kernel(1, h->big, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st,
-                           h->kp[1], d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+        hipLaunchKernelGGL(pick_vms(h->big, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
+                           (const u32 *)&h->d_kp[1], d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL(pick_kernel(0, false, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst,
-                           h->kp[0], d_events, d_n_events, d_dec_split, h->d_stats, (char *)nullptr);
+        hipLaunchKernelGGL(pick_split(h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0],
+                           d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));
@@ -273,6 +283,7 @@ void vms_replay_destroy(vms_replay *h)
     if (!h) return;
     if (h->d_stats) (void)hipFree(h->d_stats);
     if (h->d_summary) (void)hipFree(h->d_summary);
+    if (h->d_kp) (void)hipFree(h->d_kp);
     for (int i = 0; i < 5; i++)
         if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
     if (h->side) (void)hipStreamDestroy(h->side);
