@@ -24,6 +24,8 @@ enum { SLOT_UNBOUND = 0u, SLOT_OOM = 0xFFFFFFFFu };
 enum { KIND_SMALL = 0u, KIND_PBLOCK = 1u, KIND_SBLOCK = 2u };
 #define NONE32 0xFFFFFFFFu
 #define WIT_NONE 32u            // a list entry with an empty mask (first bit 1, last bit 0 of word 0): "no witness"
+#define ENT_WORD(e) ((e) >> 12)
+#define ENT_PASS(e) (((e) >> 10) & 3u)
 
 // Launch-constant parameters (passed by value as a kernel argument).
 struct KParams {
@@ -37,7 +39,7 @@ struct KParams {
     u32 cap_free, cap_pblocks, cap_sblocks, cap_runs, cap_chunks;
     // byte offsets of the per-wave arrays inside dynamic LDS
     u32 off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
-        off_sstamp, off_swit, off_arena;
+        off_sstamp, off_swit, off_tmp, off_arena;
     u32 lds_bytes;
     u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
 };
@@ -311,15 +313,20 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //   bmp[]    one bit per physical chunk: set while the pBlock owning it is active.  A pBlock is
 //            inactive iff the bit of its first chunk is clear; an sBlock is inactive iff all bits
 //            of all its chunk runs are clear (Sec. 3.2: one active pBlock makes the sBlock active).
-//            Handing out / releasing any block is therefore only bit-range work (LDS atomics whose
-//            result nobody waits for).
+//            Handing out / releasing any block is therefore only bit-range work.
 //   skey[]   sBlocks as key  size << 32 | ~creation_number, sorted descending (size descending,
 //            then older first), with smeta[] = arena offset << 16 | entries, sstamp[] = last use,
 //            swit[] = a "witness": the list entry that was seen active last (or WIT_NONE).  While the
 //            witness is still active the sBlock is known to be active after one bitmap read.
 //   arena[]  chunk runs of all cached sBlocks, bump-allocated, cut at bitmap word boundaries:
-//            one 32-bit entry  word << 10 | first bit << 5 | last bit  per bitmap word a run touches.
-//            Testing, setting or clearing an sBlock is one pass over its entries, one lane per entry.
+//            one 32-bit entry  word << 12 | pass << 10 | first bit << 5 | last bit  per range of
+//            consecutive chunks inside one bitmap word.  Testing, setting or clearing an sBlock is one
+//            pass over its entries, one lane per entry.  Entries with the same pass number lie in
+//            different words, so the lanes can update the bitmap with plain read-modify-write (LDS
+//            atomics turned out several times slower); nearly all entries have pass 0, a second and
+//            third range of the same word get pass 1 and 2, any further ones pass 3 (atomic update).
+//   tmp[]    scratch bitmap of the same size as bmp[], zero between uses: a new list is OR-ed
+//            together here and read back word by word, which merges touching runs.
 //            Compacted through a global-memory buffer when full.
 //   pp, sp   first level of the rank searches in pool[] and skey[], held in registers.
 // ---------------------------------------------------------------------------
@@ -333,7 +340,7 @@ struct VmsT {
     u32 *bmp;
     u64 *skey;
     meta_t *smeta;
-    u32 *sstamp, *swit;
+    u32 *sstamp, *swit, *tmp;
     u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
     Probe pp, sp;
@@ -356,7 +363,7 @@ DI u32 run_entry(u32 start, u32 len, u32 q)
     const u32 w0 = start >> 5, endm1 = start + len - 1, w = w0 + q;
     const u32 lo = q == 0 ? (start & 31) : 0u;
     const u32 hi = w == (endm1 >> 5) ? (endm1 & 31) : 31u;
-    return (w << 10) | (lo << 5) | hi;
+    return (w << 12) | (lo << 5) | hi;
 }
 
 // write the entries of one run (wave-uniform arguments) at arena[at..]; returns how many
@@ -387,26 +394,88 @@ DI void bmp_fill(u32 *bmp, u32 start, u32 len, bool set)
         u32 w = wb + lane_id();
         if (w <= w1) {
             u32 m = word_mask(w, start, end);
-            if (set) atomicOr(&bmp[w], m);
-            else atomicAnd(&bmp[w], ~m);
+            bmp[w] = set ? (bmp[w] | m) : (bmp[w] & ~m);
         }
     }
     wave_sync();
 }
 
-// all entries of one sBlock, one lane per entry (entries may share a word: atomics)
-template <bool BIG>
-DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
+// One pass over one tile of list entries (lane k holds entry e if live): the entries of pass p
+// update their bitmap words, all different, with plain read-modify-write; pass 3 uses atomics.
+DI void entries_pass(u32 *bmp, u32 e, bool live, u32 p, bool set)
 {
-    for (u32 rb = 0; rb < cnt; rb += 64) {
-        const u32 r = rb + lane_id();
-        if (r < cnt) {
-            const u32 e = V.arena[off + r];
-            if (set) atomicOr(&V.bmp[e >> 10], emask(e));
-            else atomicAnd(&V.bmp[e >> 10], ~emask(e));
+    if (live && ENT_PASS(e) == p) {
+        const u32 m = emask(e);
+        if (p == 3) {
+            if (set) atomicOr(&bmp[ENT_WORD(e)], m);
+            else atomicAnd(&bmp[ENT_WORD(e)], ~m);
+        } else {
+            bmp[ENT_WORD(e)] = set ? (bmp[ENT_WORD(e)] | m) : (bmp[ENT_WORD(e)] & ~m);
         }
     }
     wave_sync();
+}
+
+// all entries of one sBlock, one lane per entry.  first_done: pass 0 of the first 64 entries has
+// been applied by the caller.
+template <bool BIG>
+DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set, bool first_done = false)
+{
+    for (u32 rb = 0; rb < cnt; rb += 64) {
+        const u32 r = rb + lane_id();
+        const bool live = r < cnt;
+        const u32 e = V.arena[off + (live ? r : 0u)];
+        const u64 later = ballot(live && ENT_PASS(e) != 0);
+        if (!(first_done && rb == 0)) entries_pass(V.bmp, e, live, 0, set);
+        if (later)
+            for (u32 p = 1; p < 4; p++) entries_pass(V.bmp, e, live, p, set);
+    }
+}
+
+// A new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing) ...
+template <bool BIG>
+DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
+{
+    const u32 end = start + len;
+    const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
+    for (u32 q = 0; ballot(len && w0 + q <= w1); q++)
+        if (len && w0 + q <= w1) atomicOr(&V.tmp[w0 + q], word_mask(w0 + q, start, end));
+    wmin = min(wmin, wave_min_u32(w0));
+    wmax = max(wmax, wave_max_u32(w1));
+    wave_sync();
+}
+
+// ... and read back as entries at arena[at..], one per range of consecutive chunks inside a word
+// (touching runs have merged), leaving tmp[] zero.  Returns the number of entries.
+template <bool BIG>
+DI u32 list_extract(const VmsT<BIG> &V, u32 wmin, u32 wmax, u32 at)
+{
+    u32 cnt = 0;
+    for (u32 wb = wmin; wb <= wmax; wb += 64) {
+        const u32 w = wb + lane_id();
+        u32 m = 0;
+        if (w <= wmax) {
+            m = V.tmp[w];
+            V.tmp[w] = 0;
+        }
+        const u32 nr = (u32)__builtin_popcount(m & ~(m << 1));      // ranges start where a set bit follows a clear one
+        u32 tot;
+        const u32 incl = wave_scan_add(nr, &tot);
+        const u32 o = at + cnt + incl - nr;
+        for (u32 r = 0; ballot(m != 0); r++) {
+            if (m) {
+                const u32 lo = (u32)__builtin_ctz(m);
+                const u32 rest = ~(m >> lo);
+                const u32 len = rest ? (u32)__builtin_ctz(rest) : 32u;
+                const u32 hi = lo + len - 1;
+                V.arena[o + r] = (w << 12) | ((r < 3 ? r : 3u) << 10) | (lo << 5) | hi;
+                m &= ~((2u << hi) - (1u << lo));
+            }
+        }
+        cnt += tot;
+    }
+    wave_sync();
+    return cnt;
 }
 
 // Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
@@ -415,13 +484,13 @@ template <bool BIG>
 DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
 {
     const u32 wit = V.swit[i];
-    if (V.bmp[wit >> 10] & emask(wit)) return false;
+    if (V.bmp[ENT_WORD(wit)] & emask(wit)) return false;
     const auto meta = V.smeta[i];
     const u32 *list = V.arena + V.off(meta);
     const u32 cnt = V.cnt(meta);
     for (u32 r = 0; r < cnt; r++) {
         const u32 e = list[r];
-        if (V.bmp[e >> 10] & emask(e)) {
+        if (V.bmp[ENT_WORD(e)] & emask(e)) {
             V.swit[i] = e;
             return false;
         }
@@ -573,26 +642,33 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
         const auto meta = V.smeta[ic];
         const u64 vm = ballot(i < V.ns && (u32)(key >> 32) == bsize);
         if (!vm) return false;
-        const u32 wv = pin(V.bmp[wit >> 10]);
+        const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
         u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
         while (unknown) {
             const u32 l = first_lane(unknown);
             const auto m = from_lane_any(meta, l);
             const u32 off = V.off(m), cnt = V.cnt(m);
             u32 e = V.arena[off + (lane < cnt ? lane : 0u)];
-            const u32 word = pin(V.bmp[e >> 10]);
+            const u32 word = pin(V.bmp[ENT_WORD(e)]);
             u64 bm = ballot(lane < cnt && (word & emask(e)) != 0);
             if (cnt > 64 && !bm) {              // long list: the rest of it, a tile at a time
                 for (u32 eb = 64; eb < cnt && !bm; eb += 64) {
                     const u32 k = eb + lane;
                     e = V.arena[off + (k < cnt ? k : 0u)];
-                    bm = ballot(k < cnt && (V.bmp[e >> 10] & emask(e)) != 0);
+                    bm = ballot(k < cnt && (V.bmp[ENT_WORD(e)] & emask(e)) != 0);
                 }
-                if (!bm) e = V.arena[off + (lane < cnt ? lane : 0u)];
+                if (!bm) {
+                    bmp_fill_entries(V, off, cnt, true);
+                    st_one(V.sstamp, base + l, ++V.clock);
+                    ref = ~from_lane((u32)key, l);
+                    list = (u32)m;
+                    return true;
+                }
             }
             if (!bm) {
-                if (lane < cnt) atomicOr(&V.bmp[e >> 10], emask(e));
-                if (cnt > 64) bmp_fill_entries(V, off + 64, cnt - 64, true);
+                // inactive: hand it out.  The words of the pass-0 entries were just read
+                if (lane < cnt && ENT_PASS(e) == 0) V.bmp[ENT_WORD(e)] = word | emask(e);
+                if (cnt > 64 || ballot(lane < cnt && ENT_PASS(e) != 0)) bmp_fill_entries(V, off, cnt, true, true);
                 st_one(V.sstamp, base + l, ++V.clock);
                 ref = ~from_lane((u32)key, l);
                 list = (u32)m;
@@ -747,9 +823,11 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         R.dec_lo = C_GROW;
         return;
     }
-    // second pass: the candidates' chunk runs go to the arena in pool order, cut at word boundaries
-    u32 cnt = 0;
+    // second pass: the candidates' chunk runs (and the new pBlock's) are collected in tmp[] and
+    // read back as the list
+    u32 cnt;
     {
+        u32 wmin = NONE32, wmax = 0;
         const u32 endi = s3 ? pos + 1 : lim;
         for (u32 base = hi_p; base < endi; base += 64) {
             u32 i = base + lane;
@@ -757,12 +835,10 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             bool inact = i < endi && !bmp_test(V.bmp, ~(u32)key);
             u32 len = (u32)(key >> 32), start = ~(u32)key;
             if (i == pos) len -= excess;
-            u32 ne = inact ? run_words(start, len) : 0u, tot, incl = wave_scan_add(ne, &tot);
-            for (u32 q = 0; ballot(q < ne); q++)
-                if (q < ne) V.arena[V.top + cnt + incl - ne + q] = run_entry(start, len, q);
-            cnt += tot;
+            list_mark(V, start, inact ? len : 0u, wmin, wmax);
         }
-        wave_sync();
+        if (!s3) list_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
+        cnt = list_extract(V, wmin, wmax, V.top);
     }
     u32 used = cnt;             // arena entries consumed, including a restore block's
     R.dec_lo = 0;
@@ -785,8 +861,6 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         u32 start = V.n_chunks;                 // Alloc: exactly the missing chunks
         pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
-        cnt += arena_put(V, V.top + cnt, start, deficit);
-        used = cnt;
         R.dec_lo |= C_GROW;
     }
     R.ref = V.next_sid;
@@ -871,6 +945,7 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
     V.sstamp = (u32 *)(lds + P.off_sstamp);
     V.swit = (u32 *)(lds + P.off_swit);
+    V.tmp = (u32 *)(lds + P.off_tmp);
     u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs;
     V.bounce = BIG && swapped ? hi : lo;
     V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
@@ -1073,7 +1148,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     V.np = V.ns = V.n_chunks = V.top = V.live_ent = V.next_sid = V.clock = 0;
     V.pp.v = V.sp.v = 0;
     V.pp.stride = V.sp.stride = 1;
-    for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = 0;
+    for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = V.tmp[i] = 0;
     wave_sync();
 
     u32 requested = 0, active = 0, peak_requested = 0, peak_active = 0;
@@ -1124,11 +1199,10 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (kind == KIND_SBLOCK) {
                     if (USE_LIST) {
                         const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
-                        if (lane < cnt) {
-                            const u32 e = V.arena[off + lane];
-                            atomicAnd(&V.bmp[e >> 10], ~emask(e));
-                        }
-                        if (cnt > 64) bmp_fill_entries(V, off + 64, cnt - 64, false);
+                        const u32 e = V.arena[off + (lane < cnt ? lane : 0u)];
+                        const u32 word = pin(V.bmp[ENT_WORD(e)]);
+                        if (lane < cnt && ENT_PASS(e) == 0) V.bmp[ENT_WORD(e)] = word & ~emask(e);
+                        if (cnt > 64 || ballot(lane < cnt && ENT_PASS(e) != 0)) bmp_fill_entries(V, off, cnt, false, true);
                     } else {
                         vms_free_by_key(V, a, b >> 2);
                     }
