@@ -517,6 +517,46 @@ DI void pool_remove(VmsT<BIG> &V, u32 idx)
     V.np--;
 }
 
+// skey[], smeta[], sstamp[] and swit[] move together: entries [pos, n) one place up (highest
+// tile first) or entries (pos, n) one place down (lowest tile first), one LDS round trip per tile
+template <bool BIG>
+DI void spool_shift_up(VmsT<BIG> &V, u32 pos, u32 n)
+{
+    for (u32 hi = n; hi > pos;) {
+        const u32 lo = hi - pos > 64 ? hi - 64 : pos;
+        const u32 i = lo + lane_id();
+        if (i < hi) {
+            const u64 k = V.skey[i];
+            const auto m = V.smeta[i];
+            const u32 st = V.sstamp[i], w = V.swit[i];
+            V.skey[i + 1] = k;
+            V.smeta[i + 1] = m;
+            V.sstamp[i + 1] = st;
+            V.swit[i + 1] = w;
+        }
+        hi = lo;
+    }
+    wave_sync();
+}
+
+template <bool BIG>
+DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
+{
+    for (u32 lo = pos + 1; lo < n; lo += 64) {
+        const u32 i = lo + lane_id();
+        if (i < n) {
+            const u64 k = V.skey[i];
+            const auto m = V.smeta[i];
+            const u32 st = V.sstamp[i], w = V.swit[i];
+            V.skey[i - 1] = k;
+            V.smeta[i - 1] = m;
+            V.sstamp[i - 1] = st;
+            V.swit[i - 1] = w;
+        }
+    }
+    wave_sync();
+}
+
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
 // Returns the position of the new sBlock in skey[].
 template <bool BIG>
@@ -525,10 +565,7 @@ DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
     u32 pos = rank_desc(V.skey, V.ns, key);
-    shift_up(V.skey, pos, V.ns);
-    shift_up(V.smeta, pos, V.ns);
-    shift_up(V.sstamp, pos, V.ns);
-    shift_up(V.swit, pos, V.ns);
+    spool_shift_up(V, pos, V.ns);
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
     st_one(V.sstamp, pos, ++V.clock);
@@ -544,10 +581,7 @@ template <bool BIG>
 DI void spool_remove(VmsT<BIG> &V, u32 idx)
 {
     V.live_ent -= V.cnt(ld_uni(V.smeta, idx));
-    shift_down(V.skey, idx, V.ns);
-    shift_down(V.smeta, idx, V.ns);
-    shift_down(V.sstamp, idx, V.ns);
-    shift_down(V.swit, idx, V.ns);
+    spool_shift_down(V, idx, V.ns);
     V.ns--;
 }
 
@@ -589,30 +623,58 @@ DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, Acct &
     return true;
 }
 
+// Is any chunk of the list arena[off .. off + cnt) active?  All lanes work on the one list; if so,
+// *witness receives an entry that was seen active.
+template <bool BIG>
+DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
+{
+    for (u32 eb = 0; eb < cnt; eb += 64) {
+        const u32 k = eb + lane_id();
+        const u32 e = V.arena[off + (k < cnt ? k : 0u)];
+        const u64 bm = ballot(k < cnt && (V.bmp[ENT_WORD(e)] & emask(e)) != 0);
+        if (bm) {
+            *witness = from_lane(e, first_lane(bm));
+            return true;
+        }
+    }
+    return false;
+}
+
 // StitchFree (Sec. 3.3.2, Sec. 4.2.3): while more sBlocks than the threshold are cached,
-// release the least recently used one that is inactive.
+// release the least recently used one that is inactive.  The lanes first rule out, side by
+// side, every sBlock whose witness is still active; of the rest the least recently used one is
+// tested with all lanes on its list, and so on until one is found inactive.
 template <bool BIG>
 DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
 {
     const u32 lane = lane_id();
     bool any = false;
     while (V.ns > P.spool_threshold) {
-        // every lane tests its own sBlocks; the oldest stamp among the inactive ones wins
-        u32 best = NONE32, besti = 0;
-        for (u32 base = 0; base < V.ns; base += 64) {
-            u32 i = base + lane;
-            if (i < V.ns) {
-                u32 st = V.sstamp[i];
-                if (st < best && sblock_inactive_lane(V, i)) {
+        u32 victim = NONE32;
+        for (;;) {
+            u32 best = NONE32, besti = 0;
+            for (u32 base = 0; base < V.ns; base += 64) {
+                const u32 i = base + lane, ic = i < V.ns ? i : 0u;
+                const u32 st = V.sstamp[ic], wit = V.swit[ic];
+                const bool known = (V.bmp[ENT_WORD(wit)] & emask(wit)) != 0;
+                if (i < V.ns && !known && st < best) {
                     best = st;
                     besti = i;
                 }
             }
+            const u32 m = wave_min_u32(best);
+            if (m == NONE32) break;             // everything cached is in use: the threshold stays exceeded
+            const u32 c = from_lane(besti, first_lane(ballot(best == m)));
+            const auto meta = ld_uni(V.smeta, c);
+            u32 witness;
+            if (!list_busy(V, V.off(meta), V.cnt(meta), &witness)) {
+                victim = c;
+                break;
+            }
+            st_one(V.swit, c, witness);         // active after all: remember where, look again
+            wave_sync();
         }
-        wave_sync();
-        u32 m = wave_min_u32(best);
-        if (m == NONE32) break;                 // everything cached is in use: the threshold stays exceeded
-        u32 victim = from_lane(besti, first_lane(ballot(best == m)));
+        if (victim == NONE32) break;
         spool_remove(V, victim);
         A.n_evicted++;
         any = true;
