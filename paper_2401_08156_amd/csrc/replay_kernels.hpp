@@ -432,7 +432,8 @@ DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set, bool fi
     }
 }
 
-// A new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing) ...
+// A new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing;
+// wmin / wmax: per-lane range of the bitmap words touched so far) ...
 template <bool BIG>
 DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 {
@@ -440,9 +441,8 @@ DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
     const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
     for (u32 q = 0; ballot(len && w0 + q <= w1); q++)
         if (len && w0 + q <= w1) atomicOr(&V.tmp[w0 + q], word_mask(w0 + q, start, end));
-    wmin = min(wmin, wave_min_u32(w0));
-    wmax = max(wmax, wave_max_u32(w1));
-    wave_sync();
+    wmin = min(wmin, w0);
+    wmax = max(wmax, w1);
 }
 
 // ... and read back as entries at arena[at..], one per range of consecutive chunks inside a word
@@ -510,11 +510,27 @@ DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, Acct &A)
     wave_sync();
 }
 
+// Split (Sec. 3.3.1): the pBlock at pool[idx] is replaced by its two pieces, both smaller and
+// therefore further down in pool order.  Only the keys between the old place and the new
+// places move: down by one up to the larger piece, up by one after the smaller piece.
 template <bool BIG>
-DI void pool_remove(VmsT<BIG> &V, u32 idx)
+DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32 start_b, Acct &A)
 {
-    shift_down(V.pool, idx, V.np);
-    V.np--;
+    u64 k1 = ((u64)size_a << 32) | (u32)~start_a, k2 = ((u64)size_b << 32) | (u32)~start_b;
+    if (k1 < k2) {
+        const u64 t = k1;
+        k1 = k2;
+        k2 = t;
+    }
+    u32 r1, r2;                                 // ranks among the old keys (the cut block counts in both)
+    rank_desc2(V.pool, V.np, k1, k2, &r1, &r2);
+    shift_down(V.pool, idx, r1);                // pool[idx+1 .. r1) -> pool[idx .. r1-1)
+    shift_up(V.pool, r2, V.np);                 // pool[r2 .. np) -> pool[r2+1 .. np+1)
+    st_one(V.pool, r1 - 1, k1);
+    st_one(V.pool, r2, k2);
+    V.np++;
+    A.hw_pblocks = max(A.hw_pblocks, V.np);
+    wave_sync();
 }
 
 // skey[], smeta[], sstamp[] and swit[] move together: entries [pos, n) one place up (highest
@@ -817,9 +833,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
                 return;
             }
             // S2: Split into the request and the rest; a stitched block keeps the uncut size on record
-            pool_remove(V, idx);
-            pool_insert(V, bsize, pstart, A);
-            pool_insert(V, psize - bsize, pstart + bsize, A);
+            pool_cut(V, idx, bsize, pstart, psize - bsize, pstart + bsize, A);
             A.n_split++;
             u32 n = arena_put(V, V.top, pstart, psize);
             spool_insert(V, psize, V.top, n, A);
@@ -900,7 +914,8 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             list_mark(V, start, inact ? len : 0u, wmin, wmax);
         }
         if (!s3) list_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
-        cnt = list_extract(V, wmin, wmax, V.top);
+        wave_sync();
+        cnt = list_extract(V, wave_min_u32(wmin), wave_max_u32(wmax), V.top);
     }
     u32 used = cnt;             // arena entries consumed, including a restore block's
     R.dec_lo = 0;
@@ -909,9 +924,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             // cut the last candidate so the sum is exact; remember its uncut size (Fig. 9, sBlock 2)
             u64 qk = ld_uni(V.pool, pos);
             u32 qsize = (u32)(qk >> 32), qstart = ~(u32)qk;
-            pool_remove(V, pos);
-            pool_insert(V, qsize - excess, qstart, A);
-            pool_insert(V, excess, qstart + qsize - excess, A);
+            pool_cut(V, pos, qsize - excess, qstart, excess, qstart + qsize - excess, A);
             A.n_split++;
             u32 n = arena_put(V, V.top + cnt, qstart, qsize);
             spool_insert(V, qsize, V.top + cnt, n, A);
