@@ -343,6 +343,7 @@ struct VmsT {
     u32 *sstamp, *swit, *tmp;
     u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
+    u32 e_skip;                 // a list entry with an empty mask on the spare word behind the bitmap
     Probe pp, sp;
     static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
     static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
@@ -599,6 +600,8 @@ DI void spool_remove(VmsT<BIG> &V, u32 idx)
     V.live_ent -= V.cnt(ld_uni(V.smeta, idx));
     spool_shift_down(V, idx, V.ns);
     V.ns--;
+    st_one(V.skey, V.ns, (u64)0);               // zero keys follow the live ones (see rank_fast)
+    wave_sync();
 }
 
 // Squeeze the entries of evicted sBlocks out of the arena: copy the live lists to the
@@ -713,12 +716,12 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
     const u32 lane = lane_id();
     u32 base = rank_fast<BIG>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
     for (;;) {
+        // skey[] is followed by zero keys and swit[] by harmless entries: no index is clamped
         const u32 i = base + lane;
-        const u32 ic = i < V.ns ? i : 0u;
-        const u64 key = V.skey[ic];
-        const u32 wit = V.swit[ic];
-        const auto meta = V.smeta[ic];
-        const u64 vm = ballot(i < V.ns && (u32)(key >> 32) == bsize);
+        const u64 key = V.skey[i];
+        const u32 wit = V.swit[i];
+        const auto meta = V.smeta[i];
+        const u64 vm = ballot((u32)(key >> 32) == bsize);
         if (!vm) return false;
         const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
         u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
@@ -726,10 +729,12 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
             const u32 l = first_lane(unknown);
             const auto m = from_lane_any(meta, l);
             const u32 off = V.off(m), cnt = V.cnt(m);
-            u32 e = V.arena[off + (lane < cnt ? lane : 0u)];
+            // lanes past the end of the list hold an entry with an empty mask on the spare word
+            const u32 e0 = pin(V.arena[off + lane]);
+            u32 e = lane < cnt ? e0 : V.e_skip;
             const u32 word = pin(V.bmp[ENT_WORD(e)]);
-            u64 bm = ballot(lane < cnt && (word & emask(e)) != 0);
-            if (cnt > 64 && !bm) {              // long list: the rest of it, a tile at a time
+            u64 bm = ballot((word & emask(e)) != 0);
+            if (cnt > 64) {                     // long list: the rest of it, a tile at a time
                 for (u32 eb = 64; eb < cnt && !bm; eb += 64) {
                     const u32 k = eb + lane;
                     e = V.arena[off + (k < cnt ? k : 0u)];
@@ -744,9 +749,10 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
                 }
             }
             if (!bm) {
-                // inactive: hand it out.  The words of the pass-0 entries were just read
-                if (lane < cnt && ENT_PASS(e) == 0) V.bmp[ENT_WORD(e)] = word | emask(e);
-                if (cnt > 64 || ballot(lane < cnt && ENT_PASS(e) != 0)) bmp_fill_entries(V, off, cnt, true, true);
+                // inactive: hand it out.  The words of the entries were just read; if all are of
+                // pass 0 they are all different (the idle lanes rewrite the spare word)
+                if (!ballot(ENT_PASS(e) != 0)) V.bmp[ENT_WORD(e)] = word | emask(e);
+                else bmp_fill_entries(V, off, cnt, true);
                 st_one(V.sstamp, base + l, ++V.clock);
                 ref = ~from_lane((u32)key, l);
                 list = (u32)m;
@@ -768,8 +774,8 @@ DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
     u32 base = rank_fast<BIG>(V.pp, V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu);
     for (;;) {
         const u32 i = base + lane;
-        const u64 key = V.pool[i < V.np ? i : 0u];
-        const bool eq = i < V.np && (u32)(key >> 32) == bsize;
+        const u64 key = V.pool[i];                  // zero keys follow the pool
+        const bool eq = (u32)(key >> 32) == bsize;
         const u64 vm = ballot(eq);
         if (!vm) return false;
         const u32 st = ~(u32)key;
@@ -1021,7 +1027,8 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.sstamp = (u32 *)(lds + P.off_sstamp);
     V.swit = (u32 *)(lds + P.off_swit);
     V.tmp = (u32 *)(lds + P.off_tmp);
-    u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs;
+    V.e_skip = (((P.cap_chunks + 31) / 32) << 12) | WIT_NONE;
+    u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs + 64;
     V.bounce = BIG && swapped ? hi : lo;
     V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
 }
@@ -1224,6 +1231,17 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     V.pp.v = V.sp.v = 0;
     V.pp.stride = V.sp.stride = 1;
     for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = V.tmp[i] = 0;
+    // the searches read up to 64 places past the live part of pool[], skey[], swit[] and arena[]
+    // without clamping: zero keys there, and witnesses / entries on words that exist
+    for (u32 i = lane; i < P.cap_pblocks + 64; i += 64) V.pool[i] = 0;
+    for (u32 i = lane; i < P.cap_sblocks + 64; i += 64) {
+        V.skey[i] = 0;
+        V.swit[i] = WIT_NONE;
+        V.smeta[i] = 0;
+    }
+    if (!BIG)
+        for (u32 i = lane; i < P.cap_runs + 64; i += 64) V.arena[i] = WIT_NONE;
+    st_one(V.bmp, (P.cap_chunks + 31) / 32, 0u);                // the spare word
     wave_sync();
 
     u32 requested = 0, active = 0, peak_requested = 0, peak_active = 0;
@@ -1274,10 +1292,15 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (kind == KIND_SBLOCK) {
                     if (USE_LIST) {
                         const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
-                        const u32 e = V.arena[off + (lane < cnt ? lane : 0u)];
-                        const u32 word = pin(V.bmp[ENT_WORD(e)]);
-                        if (lane < cnt && ENT_PASS(e) == 0) V.bmp[ENT_WORD(e)] = word & ~emask(e);
-                        if (cnt > 64 || ballot(lane < cnt && ENT_PASS(e) != 0)) bmp_fill_entries(V, off, cnt, false, true);
+                        const u32 e0 = pin(V.arena[off + lane]);
+                        const u32 e = lane < cnt ? e0 : V.e_skip;
+                        if (cnt <= 64 && !ballot(ENT_PASS(e) != 0)) {
+                            // all entries of pass 0: all different words (idle lanes rewrite the spare word)
+                            const u32 word = pin(V.bmp[ENT_WORD(e)]);
+                            V.bmp[ENT_WORD(e)] = word & ~emask(e);
+                        } else {
+                            bmp_fill_entries(V, off, cnt, false);
+                        }
                     } else {
                         vms_free_by_key(V, a, b >> 2);
                     }

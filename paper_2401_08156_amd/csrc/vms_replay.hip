@@ -70,14 +70,15 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
     }
     k.off_fl = take(c.max_free_blocks * 8);
     if (policy) {
-        k.off_pool = take(c.max_pblocks * 8);
-        k.off_bmp = take((c.max_chunks + 31) / 32 * 4);
-        k.off_skey = take(c.max_sblocks * 8);
-        k.off_smeta = take(c.max_sblocks * (big ? 8 : 4));
-        k.off_sstamp = take(c.max_sblocks * 4);
-        k.off_swit = take(c.max_sblocks * 4);
+        // 64 spare places behind each searched array: reads there need no bounds check
+        k.off_pool = take((c.max_pblocks + 64) * 8);
+        k.off_bmp = take((c.max_chunks + 31) / 32 * 4 + 4);     // and one spare bitmap word
+        k.off_skey = take((c.max_sblocks + 64) * 8);
+        k.off_smeta = take((c.max_sblocks + 64) * (big ? 8 : 4));
+        k.off_sstamp = take((c.max_sblocks + 64) * 4);
+        k.off_swit = take((c.max_sblocks + 64) * 4);
         k.off_tmp = take((c.max_chunks + 31) / 32 * 4);
-        k.off_arena = big ? 0 : take(c.max_runs * 4);
+        k.off_arena = big ? 0 : take((c.max_runs + 64) * 4);
     } else {
         k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_swit = k.off_tmp = k.off_arena = 0;
     }
@@ -167,7 +168,8 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.cap_runs = c.max_runs;
         k.cap_chunks = c.max_chunks;
         layout(k, p, c, h->big, h->slot_regs);
-        k.ws_stride = p ? (uint64_t)align_up(c.max_runs * 4 * (h->big ? 2 : 1), 256) : 0;
+        // compaction buffer, and for the big variant the lists themselves (each with 64 spare entries)
+        k.ws_stride = p ? (uint64_t)align_up((c.max_runs + 64) * 4 * (h->big ? 2 : 1), 256) : 0;
         if ((c.policy_mask & (1u << p)) && k.lds_bytes > LDS_PER_CU) {
             delete h;
             return VMS_ETOOBIG;

@@ -273,7 +273,9 @@ DI u32 rank_probe(const Probe &p, const u64 *a, u32 n, u64 key)
     return rank_end(r, key);
 }
 
-// The rank with one block load and no branch on the way.  WIDE: the array may hold more than
+// The rank with one block load and no branch on the way.  The array must be followed by at
+// least 64 zero keys (a[n .. n + 64) == 0), so that no index needs clamping: every key from the
+// block start on that is greater than key lies in the block.  WIDE: the array may hold more than
 // 4096 keys (then the general route is taken when it does).
 template <bool WIDE>
 DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
@@ -281,9 +283,7 @@ DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
     if (WIDE && p.stride > 64) return rank_probe(p, a, n, key);
     const u32 c = popc64(ballot(p.v > key));
     const u32 b0 = (c ? c - 1 : 0u) * p.stride;
-    const u32 i = b0 + lane_id();
-    const u64 x = a[i < n ? i : 0u];
-    return b0 + popc64(ballot(lane_id() < p.stride && i < n && x > key));
+    return b0 + popc64(ballot(a[b0 + lane_id()] > key));
 }
 
 // keeps a loaded value where it is: the compiler may not sink the load into a later branch
