@@ -586,7 +586,9 @@ DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
     st_one(V.sstamp, pos, ++V.clock);
-    st_one(V.swit, pos, WIT_NONE);
+    // every sBlock starts out active (it is handed out, or the first part of the block it records
+    // is): its first entry is a valid witness from the end of this event on
+    st_one(V.swit, pos, ld_uni(V.arena, off));
     V.ns++;
     V.live_ent += cnt;
     A.n_created++;
