@@ -44,31 +44,64 @@ struct KParams {
     u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
 };
 
-// Running totals of one (trace, policy); sizes in 512-byte units (at most 2^30).
-struct Acct {
-    u32 requested, active;
-    u32 peak_requested, peak_active;
-    u32 n_split, n_merge, n_created, n_evicted, first_oom, status, overflow_event;
-    u32 hw_pblocks, hw_sblocks, hw_free, hw_members, hw_runs;
-    bool stop;
+// Scalars of one trace that live in LDS (stitching kernel): index k is the u32 at lds[4 k].  The
+// first SC_STATE_COUNT are loaded and stored as a set around the cold functions; the counters
+// after them are only ever updated in place.
+enum {
+    SC_NP, SC_NS, SC_NCHUNKS, SC_TOP, SC_LIVE, SC_NEXT_SID, SC_CLOCK, SC_SP_N, SC_SP_RESERVED,
+    SC_R_DEC, SC_R_REF, SC_R_KIND_HELD, SC_R_LIST,      // result of the last cold call
+    SC_COMPACTED,                                       // the arena was compacted since the flag was cleared
+    SC_SWAPPED,                                         // BIG: arena and compaction buffer have changed places
+    SC_STATE_COUNT,
+    SC_N_SPLIT = SC_STATE_COUNT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
+    SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
+    SC_COUNT
 };
 
-DI void acct_init(Acct &A)
-{
-    A.requested = A.active = A.peak_requested = A.peak_active = 0;
-    A.n_split = A.n_merge = A.n_created = A.n_evicted = A.status = 0;
-    A.first_oom = A.overflow_event = NONE32;
-    A.hw_pblocks = A.hw_sblocks = A.hw_free = A.hw_members = A.hw_runs = 0;
-    A.stop = false;
-}
+// Event counters and high-water marks of one (trace, policy), addressed by the SC_* indices.
+// Two holders with the same interface: registers (splitting kernel, everything inline) and the
+// LDS scalars (cold functions of the stitching kernel: updated in place, nothing to load or store).
+struct AcctRegs {
+    u32 f[SC_COUNT];
+    bool stop;
+    DI void init()
+    {
+#pragma unroll
+        for (u32 k = 0; k < SC_COUNT; k++) f[k] = 0;
+        f[SC_FIRST_OOM] = f[SC_OVF_EVENT] = NONE32;
+        stop = false;
+    }
+    DI void add(u32 k, u32 x) { f[k] += x; }
+    DI void peak(u32 k, u32 v) { f[k] = max(f[k], v); }
+    // An engine table is too small for this trace: stop replaying it.
+    DI void overflow(u32 ev, u32 which)
+    {
+        f[SC_STATUS] |= VMS_ST_TABLE_OVERFLOW | which;
+        if (f[SC_OVF_EVENT] == NONE32) f[SC_OVF_EVENT] = ev;
+        stop = true;
+    }
+};
 
-// An engine table is too small for this trace: stop replaying it.
-DI void table_overflow(Acct &A, u32 ev, u32 which)
-{
-    A.status |= VMS_ST_TABLE_OVERFLOW | which;
-    if (A.overflow_event == NONE32) A.overflow_event = ev;
-    A.stop = true;
-}
+struct AcctLds {
+    u32 *sc;
+    DI void add(u32 k, u32 x)
+    {
+        if (lane_id() == 0) atomicAdd(&sc[k], x);
+    }
+    DI void peak(u32 k, u32 v)
+    {
+        if (lane_id() == 0) atomicMax(&sc[k], v);
+    }
+    DI void overflow(u32 ev, u32 which)
+    {
+        if (lane_id() == 0) {
+            atomicOr(&sc[SC_STATUS], VMS_ST_TABLE_OVERFLOW | which);
+            atomicMin(&sc[SC_OVF_EVENT], ev);
+            sc[SC_STOP] = 1;
+        }
+        wave_sync();
+    }
+};
 
 // ---------------------------------------------------------------------------
 // Slot table: what each handle of the trace currently holds.
@@ -158,7 +191,8 @@ struct SplitRes {
     bool split;
 };
 
-DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, u32 ev, SplitRes &r)
+template <class AcctT>
+DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r)
 {
     const u32 lane = lane_id();
     r.split = false;
@@ -219,23 +253,24 @@ DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, Acct &A, u32 
     // step 2: cut off what is not needed; it stays cached as the right neighbour
     if (bsize > size) {
         if (sp.n == sp.cap) {
-            table_overflow(A, ev, VMS_ST_OVF_FREE_BLOCKS);
+            A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
             return;
         }
         const u64 rest = ((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1);
         st_one(sp.fl, sp.n, rest);
         sp.n++;
-        A.hw_free = max(A.hw_free, sp.n);
+        A.peak(SC_HW_FREE, sp.n);
         wave_sync();
         r.flags &= 2;
         r.split = true;
         if (r.code == C_EXACT) r.code = C_SPLIT;
-        A.n_split++;
+        A.add(SC_N_SPLIT, 1);
     }
 }
 
 // steps 3 and 4: the block becomes inactive and absorbs inactive neighbours of its segment
-DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *mr, Acct &A, u32 ev)
+template <class AcctT>
+DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *mr, AcctT &A, u32 ev)
 {
     const u32 lane = lane_id();
     const bool can_l = !(flags & 2), can_r = !(flags & 1);
@@ -281,7 +316,7 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         size += (u32)(lkey >> 32);
         flags = ((u32)lkey & 2) | (flags & 1);
     }
-    A.n_merge += (*ml ? 1u : 0u) + (*mr ? 1u : 0u);
+    A.add(SC_N_MERGE, (*ml ? 1u : 0u) + (*mr ? 1u : 0u));
     const u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
     if (*ml) {
         st_one(sp.fl, lidx, key);               // merged block takes the left neighbour's place
@@ -295,12 +330,12 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         st_one(sp.fl, ridx, key);
     } else {
         if (sp.n == sp.cap) {
-            table_overflow(A, ev, VMS_ST_OVF_FREE_BLOCKS);
+            A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
             return;
         }
         st_one(sp.fl, sp.n, key);
         sp.n++;
-        A.hw_free = max(A.hw_free, sp.n);
+        A.peak(SC_HW_FREE, sp.n);
     }
     wave_sync();
 }
@@ -499,23 +534,23 @@ DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
     return true;
 }
 
-template <bool BIG>
-DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, Acct &A)
+template <bool BIG, class AcctT>
+DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, AcctT &A)
 {
     u64 key = ((u64)size << 32) | (u32)~start;
     u32 pos = rank_desc(V.pool, V.np, key);
     shift_up(V.pool, pos, V.np);
     st_one(V.pool, pos, key);
     V.np++;
-    A.hw_pblocks = max(A.hw_pblocks, V.np);
+    A.peak(SC_HW_PBLOCKS, V.np);
     wave_sync();
 }
 
 // Split (Sec. 3.3.1): the pBlock at pool[idx] is replaced by its two pieces, both smaller and
 // therefore further down in pool order.  Only the keys between the old place and the new
 // places move: down by one up to the larger piece, up by one after the smaller piece.
-template <bool BIG>
-DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32 start_b, Acct &A)
+template <bool BIG, class AcctT>
+DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32 start_b, AcctT &A)
 {
     u64 k1 = ((u64)size_a << 32) | (u32)~start_a, k2 = ((u64)size_b << 32) | (u32)~start_b;
     if (k1 < k2) {
@@ -530,7 +565,7 @@ DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32
     st_one(V.pool, r1 - 1, k1);
     st_one(V.pool, r2, k2);
     V.np++;
-    A.hw_pblocks = max(A.hw_pblocks, V.np);
+    A.peak(SC_HW_PBLOCKS, V.np);
     wave_sync();
 }
 
@@ -576,8 +611,8 @@ DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
 
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
 // Returns the position of the new sBlock in skey[].
-template <bool BIG>
-DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
+template <bool BIG, class AcctT>
+DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, AcctT &A)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
@@ -591,7 +626,7 @@ DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, Acct &A)
     st_one(V.swit, pos, ld_uni(V.arena, off));
     V.ns++;
     V.live_ent += cnt;
-    A.n_created++;
+    A.add(SC_N_CREATED, 1);
     wave_sync();
     return pos;
 }
@@ -633,12 +668,12 @@ DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
     wave_sync();
 }
 
-template <bool BIG, class Slots>
-DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, Acct &A, u32 ev)
+template <bool BIG, class Slots, class AcctT>
+DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, AcctT &A, u32 ev)
 {
     if (V.top + need > P.cap_runs && V.live_ent < V.top) arena_compact(V, S, P);
     if (V.top + need > P.cap_runs) {
-        table_overflow(A, ev, VMS_ST_OVF_RUNS);
+        A.overflow(ev, VMS_ST_OVF_RUNS);
         return false;
     }
     return true;
@@ -665,8 +700,8 @@ DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
 // release the least recently used one that is inactive.  The lanes first rule out, side by
 // side, every sBlock whose witness is still active; of the rest the least recently used one is
 // tested with all lanes on its list, and so on until one is found inactive.
-template <bool BIG>
-DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
+template <bool BIG, class AcctT>
+DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
 {
     const u32 lane = lane_id();
     bool any = false;
@@ -697,11 +732,11 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, Acct &A)
         }
         if (victim == NONE32) break;
         spool_remove(V, victim);
-        A.n_evicted++;
+        A.add(SC_N_EVICTED, 1);
         any = true;
     }
-    A.hw_sblocks = max(A.hw_sblocks, V.ns);     // high-water marks as seen between events
-    A.hw_runs = max(A.hw_runs, V.live_ent);
+    A.peak(SC_HW_SBLOCKS, V.ns);     // high-water marks as seen between events
+    A.peak(SC_HW_RUNS, V.live_ent);
     return any;
 }
 
@@ -802,8 +837,8 @@ struct VmsRes {
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of
 // its state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).  The rare path: a few per cent of
 // the requests of a converged trace.
-template <bool BIG, class Slots>
-DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, Acct &A, u32 ev,
+template <bool BIG, class Slots, class AcctT>
+DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, AcctT &A, u32 ev,
                        VmsRes &R)
 {
     const u32 lane = lane_id();
@@ -836,13 +871,13 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             }
             if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks ||
                 !arena_reserve(V, S, run_words(pstart, psize), P, A, ev)) {
-                table_overflow(A, ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
+                A.overflow(ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
                 R.dec_lo = C_INVALID;
                 return;
             }
             // S2: Split into the request and the rest; a stitched block keeps the uncut size on record
             pool_cut(V, idx, bsize, pstart, psize - bsize, pstart + bsize, A);
-            A.n_split++;
+            A.add(SC_N_SPLIT, 1);
             u32 n = arena_put(V, V.top, pstart, psize);
             spool_insert(V, psize, V.top, n, A);
             V.top += n;
@@ -885,7 +920,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             return;
         }
         if (V.n_chunks + deficit > P.cap_chunks) {
-            table_overflow(A, ev, VMS_ST_OVF_CHUNKS);
+            A.overflow(ev, VMS_ST_OVF_CHUNKS);
             R.dec_lo = C_INVALID;
             return;
         }
@@ -893,7 +928,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     // list entries created below: a run of L chunks touches at most L / 32 + 2 bitmap words
     const u32 need = 2u * k + 3u * (((sum > bsize ? sum : bsize) >> 5) + 2u);
     if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev)) {
-        table_overflow(A, ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
+        A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
         R.dec_lo = C_INVALID;
         return;
     }
@@ -933,7 +968,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             u64 qk = ld_uni(V.pool, pos);
             u32 qsize = (u32)(qk >> 32), qstart = ~(u32)qk;
             pool_cut(V, pos, qsize - excess, qstart, excess, qstart + qsize - excess, A);
-            A.n_split++;
+            A.add(SC_N_SPLIT, 1);
             u32 n = arena_put(V, V.top + cnt, qstart, qsize);
             spool_insert(V, qsize, V.top + cnt, n, A);
             used += n;
@@ -951,7 +986,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     bmp_fill_entries(V, V.top, cnt, true);
     R.list = BIG ? 0u : (u32)V.pack(V.top, cnt);
     V.top += used;
-    A.hw_members = max(A.hw_members, k + (s3 ? 0u : 1u));
+    A.peak(SC_HW_MEMBERS, k + (s3 ? 0u : 1u));
     R.kind = KIND_SBLOCK;
     R.dec_lo |= B_SBLOCK | (k << 8);
     if (stitch_free(V, P, A)) R.dec_lo |= B_7;
@@ -975,15 +1010,6 @@ DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
 //   lds[0 .. 256)     scalars of the trace (SC_* below), one u32 each
 //   lds[256 .. 512)   copy of the launch parameters, for the cold functions
 // ---------------------------------------------------------------------------
-enum {
-    SC_NP, SC_NS, SC_NCHUNKS, SC_TOP, SC_LIVE, SC_NEXT_SID, SC_CLOCK, SC_SP_N, SC_SP_RESERVED,
-    SC_N_SPLIT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
-    SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
-    SC_R_DEC, SC_R_REF, SC_R_KIND_HELD, SC_R_LIST,      // result of the last cold call
-    SC_COMPACTED,                                       // the arena was compacted since the flag was cleared
-    SC_SWAPPED,                                         // BIG: arena and compaction buffer have changed places
-    SC_COUNT
-};
 #define LDS_SCALARS 0u
 #define LDS_PARAMS 256u
 #define KPARAM_WORDS ((u32)(sizeof(KParams) / 4))
@@ -1002,9 +1028,9 @@ struct ColdState {
     u32 v;                      // lane k: scalar k
     // pinned: every lane must load its scalar even if only one lane goes on to use them
     DI void load(const char *lds) { v = pin(((const u32 *)(lds + LDS_SCALARS))[lane_id()]); }
-    DI void store(char *lds) const
+    DI void store(char *lds) const          // the counters behind the state are updated in place, never from here
     {
-        ((u32 *)(lds + LDS_SCALARS))[lane_id()] = v;
+        if (lane_id() < SC_STATE_COUNT) ((u32 *)(lds + LDS_SCALARS))[lane_id()] = v;
         wave_sync();
     }
     DI u32 get(u32 k) const { return from_lane(v, k); }
@@ -1035,41 +1061,6 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
 }
 
-DI void acct_load(Acct &A, const ColdState &C)
-{
-    A.requested = A.active = A.peak_requested = A.peak_active = 0;      // kept by the replay loop
-    A.n_split = C.get(SC_N_SPLIT);
-    A.n_merge = C.get(SC_N_MERGE);
-    A.n_created = C.get(SC_N_CREATED);
-    A.n_evicted = C.get(SC_N_EVICTED);
-    A.first_oom = C.get(SC_FIRST_OOM);
-    A.status = C.get(SC_STATUS);
-    A.overflow_event = C.get(SC_OVF_EVENT);
-    A.hw_pblocks = C.get(SC_HW_PBLOCKS);
-    A.hw_sblocks = C.get(SC_HW_SBLOCKS);
-    A.hw_free = C.get(SC_HW_FREE);
-    A.hw_members = C.get(SC_HW_MEMBERS);
-    A.hw_runs = C.get(SC_HW_RUNS);
-    A.stop = C.get(SC_STOP) != 0;
-}
-
-DI void acct_store(const Acct &A, ColdState &C)
-{
-    C.set(SC_N_SPLIT, A.n_split);
-    C.set(SC_N_MERGE, A.n_merge);
-    C.set(SC_N_CREATED, A.n_created);
-    C.set(SC_N_EVICTED, A.n_evicted);
-    C.set(SC_FIRST_OOM, A.first_oom);
-    C.set(SC_STATUS, A.status);
-    C.set(SC_OVF_EVENT, A.overflow_event);
-    C.set(SC_HW_PBLOCKS, A.hw_pblocks);
-    C.set(SC_HW_SBLOCKS, A.hw_sblocks);
-    C.set(SC_HW_FREE, A.hw_free);
-    C.set(SC_HW_MEMBERS, A.hw_members);
-    C.set(SC_HW_RUNS, A.hw_runs);
-    C.set(SC_STOP, A.stop ? 1u : 0u);
-}
-
 // Cold call: a request for bsize chunks that no cached block fits exactly (states S2 to S5).
 // The result is left in the SC_R_* scalars.
 template <bool BIG>
@@ -1090,8 +1081,8 @@ __device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *w
     V.live_ent = C.get(SC_LIVE);
     V.next_sid = C.get(SC_NEXT_SID);
     V.clock = clock;
-    Acct A;
-    acct_load(A, C);
+    AcctLds A;
+    A.sc = (u32 *)(lds + LDS_SCALARS);
     ColdSlots S;
     S.compacted = false;
     VmsRes R;
@@ -1104,7 +1095,6 @@ __device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *w
     C.set(SC_LIVE, V.live_ent);
     C.set(SC_NEXT_SID, V.next_sid);
     C.set(SC_CLOCK, V.clock);
-    acct_store(A, C);
     C.set(SC_R_DEC, R.dec_lo);
     C.set(SC_R_REF, R.ref);
     C.set(SC_R_KIND_HELD, R.kind | (R.held << 2));
@@ -1128,13 +1118,12 @@ __device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 s
     sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
     sp.n = C.get(SC_SP_N);
     sp.reserved = C.get(SC_SP_RESERVED);
-    Acct A;
-    acct_load(A, C);
+    AcctLds A;
+    A.sc = (u32 *)(lds + LDS_SCALARS);
     SplitRes r;
     sp_alloc(sp, size, seg, may_grow != 0, A, ev, r);
     C.set(SC_SP_N, sp.n);
     C.set(SC_SP_RESERVED, sp.reserved);
-    acct_store(A, C);
     C.set(SC_R_DEC, r.code | (r.split ? 1u << 8 : 0u));
     C.set(SC_R_REF, (r.addr << 2) | r.flags);
     C.store(lds);
@@ -1151,12 +1140,11 @@ __device__ __attribute__((noinline)) void small_free_cold(lds_char *ldsp, u32 ad
     sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
     sp.n = C.get(SC_SP_N);
     sp.reserved = C.get(SC_SP_RESERVED);
-    Acct A;
-    acct_load(A, C);
+    AcctLds A;
+    A.sc = (u32 *)(lds + LDS_SCALARS);
     bool ml, mr;
     sp_free(sp, addr, size, flags, &ml, &mr, A, ev);
     C.set(SC_SP_N, sp.n);
-    acct_store(A, C);
     C.set(SC_R_DEC, (ml ? 1u : 0u) | (mr ? 2u : 0u));
     C.store(lds);
 }
@@ -1489,8 +1477,9 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
     sp.reserved = 0;
     wave_sync();
 
-    Acct A;
-    acct_init(A);
+    AcctRegs A;
+    A.init();
+    u32 requested = 0, peak_requested = 0;
     TileOut T;
     T.init();
     const u32 chunk_units = 1u << P.chunk_shift;
@@ -1523,7 +1512,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                     S.set_req(slot, (u32)SLOT_UNBOUND);
                     bool ml, mr;
                     sp_free(sp, a >> 2, req, a & 3, &ml, &mr, A, base + j);
-                    A.requested -= req;
+                    requested -= req;
                     dlo = C_FREE | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
                     dhi = a >> 2;
                     break;
@@ -1536,7 +1525,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                 if (A.stop) break;
                 if (r.code == C_OOM) {
                     S.set_req(slot, (u32)SLOT_OOM);
-                    if (A.first_oom == NONE32) A.first_oom = base + j;
+                    if (A.f[SC_FIRST_OOM] == NONE32) A.f[SC_FIRST_OOM] = base + j;
                     dlo = C_OOM;
                     break;
                 }
@@ -1545,8 +1534,8 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                 dlo = r.code | (r.split ? B_6 : 0u) | ((r.code == C_GROW ? 0u : 1u) << 8);
                 dhi = r.addr;
                 // blocks are cut to the request: active bytes are the requested bytes
-                A.requested += size;
-                A.peak_requested = max(A.peak_requested, A.requested);
+                requested += size;
+                peak_requested = max(peak_requested, requested);
             } while (0);
             wave_sync();
             if (A.stop) {                                   // the free list overflowed: the trace ends here
@@ -1556,7 +1545,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
             const bool mine = lane == j;
             v_dlo = mine ? dlo : v_dlo;
             v_dhi = mine ? dhi : v_dhi;
-            v_act = mine ? A.requested : v_act;
+            v_act = mine ? requested : v_act;
             v_res = mine ? sp.reserved : v_res;
         }
         tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
@@ -1571,27 +1560,27 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
 #pragma unroll
         for (u32 c = 0; c < 8; c++) s.n_code[c] = n_code[c];
         const u64 reserved = sp.reserved;
-        s.peak_requested = (u64)A.peak_requested * 512;
-        s.peak_active = (u64)A.peak_requested * 512;
+        s.peak_requested = (u64)peak_requested * 512;
+        s.peak_active = (u64)peak_requested * 512;
         s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value
-        s.final_requested = (u64)A.requested * 512;
-        s.final_active = (u64)A.requested * 512;
+        s.final_requested = (u64)requested * 512;
+        s.final_active = (u64)requested * 512;
         s.final_reserved = reserved * 512;
         s.digest = digest;
-        s.n_split = A.n_split;
-        s.n_merge = A.n_merge;
+        s.n_split = A.f[SC_N_SPLIT];
+        s.n_merge = A.f[SC_N_MERGE];
         s.n_sblock_created = 0;
         s.n_sblock_evicted = 0;
-        s.first_oom_event = A.first_oom;
-        s.status = A.status | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
+        s.first_oom_event = A.f[SC_FIRST_OOM];
+        s.status = A.f[SC_STATUS] | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
         s.max_pblocks = 0;
         s.max_sblocks = 0;
-        s.max_free_blocks = A.hw_free;
+        s.max_free_blocks = A.f[SC_HW_FREE];
         s.max_members = 0;
         s.max_runs = 0;
-        s.overflow_event = A.overflow_event;
+        s.overflow_event = A.f[SC_OVF_EVENT];
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
-        s.fragmentation = reserved ? 1.0 - (double)A.peak_requested / (double)reserved : 0.0;
+        s.fragmentation = reserved ? 1.0 - (double)peak_requested / (double)reserved : 0.0;
     }
 }
 
