@@ -191,30 +191,33 @@ struct SplitRes {
     bool split;
 };
 
+// fl[] is followed by zero keys (128 places past cap): a scan reads whole tiles without
+// clamping, and a zero key neither fits a request nor neighbours a block.
 template <class AcctT>
 DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r)
 {
     const u32 lane = lane_id();
     r.split = false;
     // step 1: best fit = smallest key not below (size, address 0)
-    u64 best = ~0ull, lastk = 0;
+    u64 best = ~0ull;
     u32 besti = 0;
     const u32 last = sp.n - 1;
+    const u64 lastk = sp.fl[sp.n ? last : 0u];          // every lane reads the last key: it will fill the hole
     for (u32 base = 0; base < sp.n; base += 256) {
         u64 k[4];
-#pragma unroll
-        for (u32 t = 0; t < 4; t++) {
-            const u32 i = base + t * 64 + lane;
-            k[t] = sp.fl[i < sp.cap ? i : 0];
+        k[0] = sp.fl[base + lane];
+        k[1] = sp.fl[base + 64 + lane];
+        k[2] = k[3] = 0;
+        if (base + 128 < sp.n) {
+            k[2] = sp.fl[base + 128 + lane];
+            k[3] = sp.fl[base + 192 + lane];
         }
 #pragma unroll
         for (u32 t = 0; t < 4; t++) {
-            if (base + t * 64 < sp.n) {
-                const u32 i = base + t * 64 + lane;
-                const bool ok = i < sp.n && (u32)(k[t] >> 32) >= size && k[t] < best;
+            if (t < 2 || base + 128 < sp.n) {
+                const bool ok = (u32)(k[t] >> 32) >= size && k[t] < best;
                 best = ok ? k[t] : best;
-                besti = ok ? i : besti;
-                lastk = i == last ? k[t] : lastk;
+                besti = ok ? base + t * 64 + lane : besti;
             }
         }
     }
@@ -227,7 +230,7 @@ DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, AcctT &A, u32
         if (m & (m - 1)) {                      // several blocks of that size: lowest address
             const u32 lo = hi == mhi ? (u32)best : NONE32;
             const u32 mlo = wave_min_u32(lo);
-            owner = first_lane(ballot(hi == mhi && lo == mlo));
+            owner = first_lane(ballot(lo == mlo));
         }
         const u32 blo = from_lane((u32)best, owner);
         const u32 idx = from_lane(besti, owner);
@@ -235,7 +238,10 @@ DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, AcctT &A, u32
         r.addr = blo >> 2;
         r.flags = blo & 3;
         r.code = C_EXACT;
-        if (idx != last) st_one(sp.fl, idx, from_lane64(lastk, last & 63));   // unordered: the last key fills the hole
+        if (lane == 0) {                        // unordered: the last key fills the hole, a zero its place
+            if (idx != last) sp.fl[idx] = lastk;
+            sp.fl[last] = 0;
+        }
         sp.n = last;
         wave_sync();
     } else {
@@ -280,26 +286,26 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
     if (can_l || can_r) {
         for (u32 base = 0; base < sp.n; base += 256) {
             u64 k[4];
-#pragma unroll
-            for (u32 t = 0; t < 4; t++) {
-                const u32 i = base + t * 64 + lane;
-                k[t] = sp.fl[i < sp.cap ? i : 0];
+            k[0] = sp.fl[base + lane];
+            k[1] = sp.fl[base + 64 + lane];
+            k[2] = k[3] = 0;
+            if (base + 128 < sp.n) {
+                k[2] = sp.fl[base + 128 + lane];
+                k[3] = sp.fl[base + 192 + lane];
             }
 #pragma unroll
             for (u32 t = 0; t < 4; t++) {
-                if (base + t * 64 < sp.n) {
-                    const u32 i = base + t * 64 + lane;
-                    const u64 kk = i < sp.n ? k[t] : 0;         // key 0 matches nothing (no block ends at 0)
-                    const u32 ka = (u32)kk >> 2, ks = (u32)(kk >> 32);
-                    const u64 mL = ballot(can_l && ks != 0 && ka + ks == addr);
-                    const u64 mR = ballot(can_r && ks != 0 && ka == end);
-                    if (mL) {
+                if (t < 2 || base + 128 < sp.n) {
+                    // a zero key matches nothing: no block ends at 0 that could merge, none starts at an end
+                    const u32 ka = (u32)k[t] >> 2, ks = (u32)(k[t] >> 32);
+                    const u64 mL = ballot(ka + ks == addr), mR = ballot(ka == end);
+                    if (can_l && mL) {
                         lidx = base + t * 64 + first_lane(mL);
-                        lkey = from_lane64(kk, first_lane(mL));
+                        lkey = from_lane64(k[t], first_lane(mL));
                     }
-                    if (mR) {
+                    if (can_r && mR) {
                         ridx = base + t * 64 + first_lane(mR);
-                        rkey = from_lane64(kk, first_lane(mR));
+                        rkey = from_lane64(k[t], first_lane(mR));
                     }
                 }
             }
@@ -323,7 +329,10 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         wave_sync();
         if (*mr) {
             const u32 last = sp.n - 1;
-            if (lane == 0 && ridx != last) sp.fl[ridx] = sp.fl[last];
+            if (lane == 0) {
+                if (ridx != last) sp.fl[ridx] = sp.fl[last];
+                sp.fl[last] = 0;
+            }
             sp.n = last;
         }
     } else if (*mr) {
@@ -1223,6 +1232,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = V.tmp[i] = 0;
     // the searches read up to 64 places past the live part of pool[], skey[], swit[] and arena[]
     // without clamping: zero keys there, and witnesses / entries on words that exist
+    for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;
     for (u32 i = lane; i < P.cap_pblocks + 64; i += 64) V.pool[i] = 0;
     for (u32 i = lane; i < P.cap_sblocks + 64; i += 64) {
         V.skey[i] = 0;
@@ -1475,6 +1485,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
     sp.n = 0;
     sp.cap = P.cap_free;
     sp.reserved = 0;
+    for (u32 i = lane; i < P.cap_free + 128; i += 64) sp.fl[i] = 0;    // zero keys behind the live ones
     wave_sync();
 
     AcctRegs A;

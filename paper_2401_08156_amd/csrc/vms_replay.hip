@@ -68,7 +68,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         k.off_slot_a = take(c.max_slots * 4);
         k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
     }
-    k.off_fl = take(c.max_free_blocks * 8);
+    k.off_fl = take((c.max_free_blocks + 128) * 8);       // 128 spare places: scans read whole tiles
     if (policy) {
         // 64 spare places behind each searched array: reads there need no bounds check
         k.off_pool = take((c.max_pblocks + 64) * 8);

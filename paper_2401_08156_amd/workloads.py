@@ -13,7 +13,7 @@ NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "
 TABLES = {
     # config: splitting free list, pBlocks, sBlocks, chunk-run list entries, chunks (x 2 MiB)
     1: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=4096, max_chunks=8192),
-    2: dict(max_free_blocks=256, max_pblocks=544, max_sblocks=576, max_runs=4096, max_chunks=4096),
+    2: dict(max_free_blocks=192, max_pblocks=544, max_sblocks=576, max_runs=3840, max_chunks=4096),
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks, runs kept in HBM
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 20, max_chunks=16384),
     4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=5120, max_chunks=24576),
