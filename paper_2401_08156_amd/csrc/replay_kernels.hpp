@@ -1260,7 +1260,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
         const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
         if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
-        u32 done = tile;
+        u32 done = tile, todo = tile;       // todo drops to 0 when an engine table overflows: the trace ends there
         // every path of an event ends by parking its results in lane j and going on to the next event
 #define EMIT(DLO, DHI)                                                     \
     {                                                                      \
@@ -1272,7 +1272,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
         wave_sync();                                                       \
         continue;                                                          \
     }
-        for (u32 j = 0; j < tile; j++) {
+        for (u32 j = 0; j < todo; j++) {
             const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
             if (slot >= P.max_slots) EMIT((u32)C_INVALID, 0u)
             const u32 req = S.get_req(slot);
@@ -1319,7 +1319,8 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (C.get(SC_STOP)) {
                     stop = true;
                     done = j;
-                    break;
+                    todo = 0;
+                    continue;
                 }
                 active -= req;
                 EMIT(C_FREE | B_SMALL | (m & 1 ? B_6 : 0u) | (m & 2 ? B_7 : 0u), a >> 2)
@@ -1379,7 +1380,8 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (C.get(SC_STOP)) {                       // an engine table overflowed: the trace ends here
                     stop = true;
                     done = j;
-                    break;
+                    todo = 0;
+                    continue;
                 }
                 dlo = C.get(SC_R_DEC);
                 if ((dlo & 15) != C_OOM) {
@@ -1399,7 +1401,8 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (C.get(SC_STOP)) {
                     stop = true;
                     done = j;
-                    break;
+                    todo = 0;
+                    continue;
                 }
                 const u32 rd = C.get(SC_R_DEC), code = rd & 15;
                 sp_reserved = C.get(SC_SP_RESERVED);
