@@ -221,6 +221,27 @@ typedef struct vms_demo_report {
 int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms, uint32_t n_events,
                  vms_demo_report *out);
 
+/* What vms_vmm_latency measured: host wall-clock milliseconds, the best of the rounds, summed over
+ * the calls of one kind (n_chunks calls for create / map / set access / unmap / release).        */
+typedef struct vms_vmm_latency_report {
+    uint32_t struct_size;        /* sizeof(vms_vmm_latency_report), set by the caller              */
+    int32_t  hip_error;          /* hipError_t of the first failing HIP call, else 0               */
+    uint64_t block_bytes, chunk_bytes, n_chunks, granularity_bytes;
+    double   hipmalloc_ms, hipfree_ms;                       /* the native allocator, same size     */
+    double   reserve_ms, create_ms, map_ms, set_access_ms;   /* the four columns of Table 1         */
+    double   unmap_ms, release_ms;
+} vms_vmm_latency_report;
+
+/* Latency of the virtual memory management calls on the current HIP device (Sec. 2.5, Fig. 6 and
+ * Table 1 of the paper): a block of block_bytes is built from physical chunks of chunk_bytes
+ * (hipMemAddressReserve once; hipMemCreate, hipMemMap and hipMemSetAccess once per chunk), taken
+ * apart again, and compared with hipMalloc + hipFree of block_bytes; `repeats` rounds, the best
+ * time of each call class is reported.  chunk_bytes must be a multiple of the device's
+ * allocation granularity and divide block_bytes; at most 2^20 chunks.  The block is really
+ * allocated: VMS_EHIP (with hip_error) if the device cannot provide it.  Everything is released
+ * before returning.  Synchronous; host code only, no kernel is launched.                          */
+int vms_vmm_latency(uint64_t block_bytes, uint64_t chunk_bytes, uint32_t repeats, vms_vmm_latency_report *out);
+
 /* In-wavefront primitives self-test (reductions, scans, sorted insert): runs a
  * small kernel on the current device and returns VMS_OK if every lane layout
  * matches its definition.  Diagnostic; not part of a replay.                  */

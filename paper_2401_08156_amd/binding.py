@@ -52,6 +52,15 @@ class vms_demo_report(ctypes.Structure):
                 ("table1_map_ms", ctypes.c_double), ("table1_set_access_ms", ctypes.c_double)]
 
 
+class vms_vmm_latency_report(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("hip_error", ctypes.c_int32),
+                ("block_bytes", ctypes.c_uint64), ("chunk_bytes", ctypes.c_uint64), ("n_chunks", ctypes.c_uint64),
+                ("granularity_bytes", ctypes.c_uint64),
+                ("hipmalloc_ms", ctypes.c_double), ("hipfree_ms", ctypes.c_double),
+                ("reserve_ms", ctypes.c_double), ("create_ms", ctypes.c_double), ("map_ms", ctypes.c_double),
+                ("set_access_ms", ctypes.c_double), ("unmap_ms", ctypes.c_double), ("release_ms", ctypes.c_double)]
+
+
 # vms_trace_stats as a numpy record (same layout as the C struct)
 STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("peak_reserved", "<u8"),
                         ("final_requested", "<u8"), ("final_active", "<u8"), ("final_reserved", "<u8"),
@@ -67,7 +76,7 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
            "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms",
            "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
-           "vms_demo_run"]
+           "vms_demo_run", "vms_vmm_latency"]
 
 _lib = None
 
@@ -110,6 +119,8 @@ def lib():
         L.vms_selftest.argtypes = []
         L.vms_demo_run.restype = ctypes.c_int
         L.vms_demo_run.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
+        L.vms_vmm_latency.restype = ctypes.c_int
+        L.vms_vmm_latency.argtypes = [u64, u64, u32, ctypes.POINTER(vms_vmm_latency_report)]
         _lib = L
     return _lib
 
@@ -144,6 +155,14 @@ def vms_demo_run(cfg, h_events, h_dec_vms, n_events=None):
     rep = vms_demo_report()
     rep.struct_size = ctypes.sizeof(vms_demo_report)
     rc = lib().vms_demo_run(ctypes.byref(cfg), ev.ctypes.data, dec.ctypes.data, n, ctypes.byref(rep))
+    return rc, rep
+
+
+def vms_vmm_latency(block_bytes, chunk_bytes, repeats=3):
+    """Time the HIP virtual-memory calls for one block built from chunks.  Returns (rc, report)."""
+    rep = vms_vmm_latency_report()
+    rep.struct_size = ctypes.sizeof(vms_vmm_latency_report)
+    rc = lib().vms_vmm_latency(int(block_bytes), int(chunk_bytes), int(repeats), ctypes.byref(rep))
     return rc, rep
 
 

@@ -431,3 +431,100 @@ extern "C" int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, con
     if (rc == VMS_OK) table1(*out, d.prop, d.access, (size_t)2 << 30, cfg->chunk_bytes);
     return rc;
 }
+
+// The latency table of Sec. 2.5 (Fig. 6, Table 1) on this device: one block of block_bytes built
+// from chunks of chunk_bytes, each driver call class timed and the best of `repeats` rounds kept,
+// beside hipMalloc + hipFree of the same size.
+extern "C" int vms_vmm_latency(uint64_t block_bytes, uint64_t chunk_bytes, uint32_t repeats, vms_vmm_latency_report *out)
+{
+    if (!out || out->struct_size != sizeof(vms_vmm_latency_report)) return out ? VMS_ESTRUCT : VMS_EINVAL;
+    memset((char *)out + sizeof(uint32_t), 0, sizeof *out - sizeof(uint32_t));
+    if (!block_bytes || !chunk_bytes || block_bytes % chunk_bytes || !repeats || block_bytes / chunk_bytes > (1u << 20))
+        return VMS_EINVAL;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return VMS_EHIP;
+    hipMemAllocationProp prop;
+    memset(&prop, 0, sizeof prop);
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = dev;
+    hipMemAccessDesc access;
+    memset(&access, 0, sizeof access);
+    access.location = prop.location;
+    access.flags = hipMemAccessFlagsProtReadWrite;
+    size_t gran = 0;
+    hipError_t e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum);
+    if (e != hipSuccess) {
+        out->hip_error = (int)e;
+        return VMS_EHIP;
+    }
+    out->granularity_bytes = gran;
+    if (gran == 0 || chunk_bytes % gran) return VMS_EINVAL;
+    out->block_bytes = block_bytes;
+    out->chunk_bytes = chunk_bytes;
+    out->n_chunks = block_bytes / chunk_bytes;
+
+    using clk = std::chrono::steady_clock;
+    auto ms = [](clk::time_point a, clk::time_point b) { return std::chrono::duration<double, std::milli>(b - a).count(); };
+    const size_t n = (size_t)out->n_chunks, bytes = (size_t)block_bytes, chunk = (size_t)chunk_bytes;
+    std::vector<hipMemGenericAllocationHandle_t> hs(n);
+    double best[8];
+    for (double &b : best) b = 1e300;
+    for (uint32_t round = 0; round < repeats; round++) {
+        void *p = nullptr;
+        auto a0 = clk::now();
+        e = hipMalloc(&p, bytes);
+        auto a1 = clk::now();
+        if (e != hipSuccess) {
+            out->hip_error = (int)e;
+            return VMS_EHIP;
+        }
+        (void)hipFree(p);
+        auto a2 = clk::now();
+        best[0] = std::min(best[0], ms(a0, a1));
+        best[1] = std::min(best[1], ms(a1, a2));
+
+        void *va = nullptr;
+        auto t0 = clk::now();
+        e = hipMemAddressReserve(&va, bytes, 0, nullptr, 0);
+        auto t1 = clk::now();
+        if (e != hipSuccess) {
+            out->hip_error = (int)e;
+            return VMS_EHIP;
+        }
+        size_t made = 0, mapped = 0;
+        for (; made < n && e == hipSuccess; made++) e = hipMemCreate(&hs[made], chunk, &prop, 0);
+        if (e != hipSuccess) made--;
+        auto t2 = clk::now();
+        for (; mapped < n && e == hipSuccess; mapped++) e = hipMemMap((char *)va + mapped * chunk, chunk, 0, hs[mapped], 0);
+        if (e != hipSuccess && mapped) mapped--;
+        auto t3 = clk::now();
+        for (size_t i = 0; i < n && e == hipSuccess; i++) e = hipMemSetAccess((char *)va + i * chunk, chunk, &access, 1);
+        auto t4 = clk::now();
+        // give everything back, whatever happened
+        for (size_t i = 0; i < mapped; i++) (void)hipMemUnmap((char *)va + i * chunk, chunk);
+        auto t5 = clk::now();
+        for (size_t i = 0; i < made; i++) (void)hipMemRelease(hs[i]);
+        auto t6 = clk::now();
+        (void)hipMemAddressFree(va, bytes);
+        if (e != hipSuccess) {
+            out->hip_error = (int)e;
+            return VMS_EHIP;
+        }
+        best[2] = std::min(best[2], ms(t0, t1));
+        best[3] = std::min(best[3], ms(t1, t2));
+        best[4] = std::min(best[4], ms(t2, t3));
+        best[5] = std::min(best[5], ms(t3, t4));
+        best[6] = std::min(best[6], ms(t4, t5));
+        best[7] = std::min(best[7], ms(t5, t6));
+    }
+    out->hipmalloc_ms = best[0];
+    out->hipfree_ms = best[1];
+    out->reserve_ms = best[2];
+    out->create_ms = best[3];
+    out->map_ms = best[4];
+    out->set_access_ms = best[5];
+    out->unmap_ms = best[6];
+    out->release_ms = best[7];
+    return VMS_OK;
+}

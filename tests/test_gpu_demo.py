@@ -60,3 +60,18 @@ def test_demo_rejects_inconsistent_decisions():
     bad[i] += np.uint64(1 << 8)
     rc, rep = binding.vms_demo_run(cfg, ev, bad)
     assert rc == -1 and rep.failed_event == i
+
+
+def test_vmm_latency_table_small_block():
+    # the analogue of the paper's Table 1 on a small block: 256 MiB from 2 MiB and from 64 MiB chunks
+    from paper_2401_08156_amd import vmm_table
+    rows = vmm_table.measure(256 * MiB, [2 * MiB, 64 * MiB], repeats=2)
+    assert [r["n_chunks"] for r in rows] == [128, 4]
+    for r in rows:
+        assert r["ms"]["hipmalloc"] > 0 and r["ms"]["total"] > 0
+        assert all(v >= 0 for v in r["ms"].values())
+    # more calls for the same block cannot be cheaper per block by much: create + map + set access grow with the chunk count
+    assert rows[0]["ms"]["total"] > rows[1]["ms"]["total"] * 0.5
+    # argument errors come back as codes
+    rc, rep = binding.vms_vmm_latency(3 * MiB, 2 * MiB, 1)
+    assert rc == -1

@@ -28,6 +28,7 @@ def test_struct_layouts_match_the_header():
     assert binding.STATS_DTYPE.itemsize == 144
     assert ctypes.sizeof(binding.vms_summary) == 88
     assert ctypes.sizeof(binding.vms_demo_report) == 224
+    assert ctypes.sizeof(binding.vms_vmm_latency_report) == 104
 
 
 def test_config_default_and_argument_errors_need_no_gpu():
