@@ -27,6 +27,10 @@ CONFIGS = {
     3: dict(n_traces=4_096, n_events=50_000, seed=3, capacity_bytes=0),
     4: dict(n_traces=4_096, n_events=50_000, seed=4, capacity_bytes=0),
     5: dict(n_traces=16_384, n_events=100_000, seed=5, capacity_bytes=288 << 30),
+    # strictly periodic variants of 2, 3, 4 (every step has sequence length 2048): convergence studies
+    12: dict(n_traces=1_024, n_events=20_000, seed=2, capacity_bytes=0),
+    13: dict(n_traces=4_096, n_events=50_000, seed=3, capacity_bytes=0),
+    14: dict(n_traces=4_096, n_events=50_000, seed=4, capacity_bytes=0),
 }
 
 

@@ -151,6 +151,7 @@ typedef struct {
     uint64_t micro_batch;     /* b                                           */
     int staging;              /* config 3: transient offload buffers         */
     int lora;                 /* config 4: frozen weights + adapters         */
+    int periodic;             /* every step has the same sequence length     */
 } model_t;
 
 #define MAX_PENDING 4096
@@ -241,6 +242,7 @@ static void gen_transformer(sink_t *s, rng_t *r, const model_t *m)
 
     while (!sink_full(s)) {
         uint64_t seq = 1024 + 256 * (rng_next(r) % 13);        /* 1024 .. 4096 */
+        if (m->periodic) seq = 2048;                           /* strictly periodic variant */
         uint64_t T1 = m->micro_batch * seq * m->hidden * 2;    /* [b,s,h] bf16 */
         uint64_t T4 = 4 * T1;                                  /* [b,s,4h]     */
         uint64_t Ta = m->micro_batch * seq * rank * 2;         /* [b,s,rank]   */
@@ -291,9 +293,9 @@ static void gen_transformer(sink_t *s, rng_t *r, const model_t *m)
 
 /* ---- public entry -------------------------------------------------------- */
 
-static const model_t MODEL_RECOMPUTE = { 32, 4096, 4, 0, 0 };
-static const model_t MODEL_OFFLOAD   = { 40, 5120, 4, 1, 0 };
-static const model_t MODEL_LORA      = { 32, 4096, 4, 0, 1 };
+static const model_t MODEL_RECOMPUTE = { 32, 4096, 4, 0, 0, 0 };
+static const model_t MODEL_OFFLOAD   = { 40, 5120, 4, 1, 0, 0 };
+static const model_t MODEL_LORA      = { 32, 4096, 4, 0, 1, 0 };
 
 static uint32_t gen_one(int config, uint64_t seed, uint64_t trace, uint64_t *row, uint32_t n_events)
 {
@@ -303,14 +305,19 @@ static uint32_t gen_one(int config, uint64_t seed, uint64_t trace, uint64_t *row
     s.cap = n_events;
     rng_t r;
     rng_seed(&r, seed, trace);
-    int kind = config;
+    int kind = config % 10;
     if (config == 5) kind = 2 + (int)(trace % 3);
+    model_t m = MODEL_RECOMPUTE;
     switch (kind) {
     case 1: gen_random(&s, &r); break;
-    case 2: gen_transformer(&s, &r, &MODEL_RECOMPUTE); break;
-    case 3: gen_transformer(&s, &r, &MODEL_OFFLOAD); break;
-    case 4: gen_transformer(&s, &r, &MODEL_LORA); break;
+    case 2: m = MODEL_RECOMPUTE; break;
+    case 3: m = MODEL_OFFLOAD; break;
+    case 4: m = MODEL_LORA; break;
     default: break;
+    }
+    if (kind >= 2 && kind <= 4) {
+        m.periodic = config >= 10;          /* 12, 13, 14: the same recipes with a fixed sequence length */
+        gen_transformer(&s, &r, &m);
     }
     free(s.heap);
     return s.max_slot_used + 1;
@@ -338,14 +345,16 @@ static void *worker(void *arg)
 /*
  * Fill events[n_traces][n_events] (host memory, row-major) for traces
  * first_trace, first_trace + trace_stride, ... of configuration `config`
- * (1 random, 2 recompute, 3 offload, 4 LoRA, 5 even mixture of 2/3/4).
+ * (1 random, 2 recompute, 3 offload, 4 LoRA, 5 even mixture of 2/3/4;
+ * 12, 13, 14: recipes 2, 3, 4 with the same sequence length in every step).
  * Returns the number of slots needed (1 + the largest slot used), or 0 on a
  * bad argument.  Every row holds exactly n_events events.
  */
 uint32_t tracegen_fill(int config, uint64_t seed, uint32_t first_trace, uint32_t trace_stride,
                        uint32_t n_traces, uint32_t n_events, uint64_t *events, int n_threads)
 {
-    if (config < 1 || config > 5 || !events || n_events == 0 || trace_stride == 0) return 0;
+    if (!((config >= 1 && config <= 5) || (config >= 12 && config <= 14)) || !events || n_events == 0 || trace_stride == 0)
+        return 0;
     if (n_threads < 1) n_threads = 1;
     if (n_threads > 64) n_threads = 64;
     if ((uint32_t)n_threads > n_traces) n_threads = (int)(n_traces ? n_traces : 1);

@@ -36,7 +36,7 @@ def make_config(binding, config, n_traces, n_events, max_slots, kind=None, **ove
     """vms_config for a workload (kind: the generator of a config-5 batch)."""
     cfg = binding.vms_config_default(n_traces, n_events, max_slots)
     cfg.capacity_bytes = tracegen.CONFIGS[config]["capacity_bytes"]
-    tables = TABLES_5[kind] if config == 5 else TABLES[config]
+    tables = TABLES_5[kind] if config == 5 else TABLES[config % 10]
     for k, v in tables.items():
         setattr(cfg, k, v)
     for k, v in overrides.items():

@@ -94,3 +94,18 @@ def test_table_overflow_is_reported_not_fatal():
     _, _, st = gpu_util.gpu_replay(ev, cfg)
     assert (st["status"] & binding.VMS_ST_TABLE_OVERFLOW).all()
     assert (st["overflow_event"] < 1000).all()
+
+
+def test_periodic_trace_converges_on_gpu():
+    # Sec. 4.2.2 / Sec. 5.5: on a strictly periodic stream the stitching allocator ends up with exact
+    # hits only (here within the first few steps) and its reserved memory stops growing
+    ev, ms = tg.generate(12, n_traces=16, n_events=5000)
+    cfg = gpu_util.make_cfg(16, 5000, ms)
+    st = gpu_util.assert_parity(ev, cfg, label="periodic recompute")
+    _, dv, _ = gpu_util.gpu_replay(ev, cfg)
+    is_alloc = (ev & np.uint64(1 << 31)) == 0
+    code = (dv & np.uint64(15)).astype(int)
+    late = np.zeros_like(is_alloc)
+    late[:, 4 * 448:] = True                     # after four training steps of 448 events
+    assert (code[is_alloc & late] == 1).all()
+    assert (st["fragmentation"][1] == 0.0).all()
