@@ -27,6 +27,8 @@ CONFIGS = {
     3: dict(n_traces=4_096, n_events=50_000, seed=3, capacity_bytes=0),
     4: dict(n_traces=4_096, n_events=50_000, seed=4, capacity_bytes=0),
     5: dict(n_traces=16_384, n_events=100_000, seed=5, capacity_bytes=288 << 30),
+    # one rank of ZeRO-3 + LoRA + recomputation over 2^(trace mod 5) devices (Sec. 2.4, Sec. 5.3.2)
+    6: dict(n_traces=1_280, n_events=20_000, seed=6, capacity_bytes=0),
     # strictly periodic variants of 2, 3, 4 (every step has sequence length 2048): convergence studies
     12: dict(n_traces=1_024, n_events=20_000, seed=2, capacity_bytes=0),
     13: dict(n_traces=4_096, n_events=50_000, seed=3, capacity_bytes=0),

@@ -291,6 +291,94 @@ static void gen_transformer(sink_t *s, rng_t *r, const model_t *m)
     free(pend);
 }
 
+/* ---- ZeRO-3 data parallelism over N devices (Sec. 2.4, Sec. 5.3.2) -------- */
+
+/*
+ * One rank's stream under parameter / gradient / optimizer-state partitioning
+ * with LoRA and recomputation.  Persistent tensors are the rank's 1/N shards,
+ * so they shrink as N grows; before a layer runs (forward, and again for the
+ * recomputing backward) its four weight matrices are gathered into transient
+ * full-size buffers, the next layer's being fetched one layer ahead, and are
+ * released when the layer is done.  Adapter gradients are produced full-size
+ * and reduced into a kept 1/N shard.  With N = 1 nothing is gathered.
+ */
+static uint64_t shard(uint64_t bytes, uint64_t n) { return (bytes + n - 1) / n; }
+
+static void gather_layer(ctx_t *c, const uint64_t w[4], uint32_t buf[4])
+{
+    for (int k = 0; k < 4; k++) buf[k] = A(c, w[k]);
+}
+
+static void release_layer(ctx_t *c, uint32_t buf[4])
+{
+    for (int k = 0; k < 4; k++) { F(c, buf[k]); buf[k] = NO_SLOT; }
+}
+
+static void gen_zero3(sink_t *s, rng_t *r, const model_t *m, uint64_t world)
+{
+    ctx_t c = { s, r, m, NULL };
+    const unsigned L = m->layers;
+    const uint64_t h = m->hidden;
+    const uint64_t w[4] = { 3 * h * h * 2, h * h * 2, 4 * h * h * 2, 4 * h * h * 2 };  /* qkv, proj, up, down; 2 B */
+    const uint64_t rank = 8ull << (rng_next(r) & 3);
+    const uint64_t adapter = rank * h * 4;                                        /* fp32 */
+    uint32_t ckpt[MAX_LAYERS];
+    uint32_t *grads = (uint32_t *)malloc(sizeof(uint32_t) * L * ADAPT_PER_LAYER);
+
+    /* persistent: frozen weight shards, then adapter shards with two optimizer moments each */
+    for (unsigned l = 0; l < L; l++)
+        for (int k = 0; k < 4; k++) (void)A(&c, shard(w[k], world));
+    for (unsigned i = 0; i < L * ADAPT_PER_LAYER * 3; i++) (void)A(&c, shard(adapter, world));
+
+    while (!sink_full(s)) {
+        uint64_t seq = 1024 + 256 * (rng_next(r) % 13);
+        uint64_t T1 = m->micro_batch * seq * h * 2, T4 = 4 * T1;
+        uint32_t cur[4] = { NO_SLOT, NO_SLOT, NO_SLOT, NO_SLOT }, nxt[4] = { NO_SLOT, NO_SLOT, NO_SLOT, NO_SLOT };
+        uint32_t out_prev = NO_SLOT;
+
+        if (world > 1) gather_layer(&c, w, cur);
+        for (unsigned l = 0; l < L && !sink_full(s); l++) {
+            ckpt[l] = A(&c, T1);
+            if (world > 1 && l + 1 < L) gather_layer(&c, w, nxt);
+            uint32_t mid = A(&c, T4);
+            uint32_t out = A(&c, T1);
+            F(&c, mid);
+            if (out_prev != NO_SLOT) F(&c, out_prev);
+            out_prev = out;
+            if (world > 1) { release_layer(&c, cur); memcpy(cur, nxt, sizeof cur); }
+        }
+        uint32_t g1_next = out_prev;
+        unsigned n_grads = 0;
+        if (world > 1) gather_layer(&c, w, cur);
+        for (unsigned l = L; l-- > 0 && !sink_full(s);) {
+            uint32_t r1 = A(&c, T1);
+            if (world > 1 && l > 0) gather_layer(&c, w, nxt);
+            uint32_t r4 = A(&c, T4);
+            uint32_t g4 = A(&c, T4);
+            uint32_t g1 = A(&c, T1);
+            for (int j = 0; j < ADAPT_PER_LAYER; j++) {
+                uint32_t full = A(&c, adapter);
+                if (world > 1) {
+                    grads[n_grads++] = A(&c, shard(adapter, world));
+                    F(&c, full);
+                } else {
+                    grads[n_grads++] = full;
+                }
+            }
+            F(&c, r4);
+            F(&c, g4);
+            F(&c, r1);
+            F(&c, g1_next);
+            F(&c, ckpt[l]);
+            g1_next = g1;
+            if (world > 1) { release_layer(&c, cur); memcpy(cur, nxt, sizeof cur); }
+        }
+        F(&c, g1_next);
+        for (unsigned i = 0; i < n_grads && !sink_full(s); i++) F(&c, grads[i]);
+    }
+    free(grads);
+}
+
 /* ---- public entry -------------------------------------------------------- */
 
 static const model_t MODEL_RECOMPUTE = { 32, 4096, 4, 0, 0, 0 };
@@ -313,6 +401,7 @@ static uint32_t gen_one(int config, uint64_t seed, uint64_t trace, uint64_t *row
     case 2: m = MODEL_RECOMPUTE; break;
     case 3: m = MODEL_OFFLOAD; break;
     case 4: m = MODEL_LORA; break;
+    case 6: gen_zero3(&s, &r, &MODEL_RECOMPUTE, 1ull << (trace % 5)); break;   /* 1, 2, 4, 8, 16 devices */
     default: break;
     }
     if (kind >= 2 && kind <= 4) {
@@ -346,6 +435,7 @@ static void *worker(void *arg)
  * Fill events[n_traces][n_events] (host memory, row-major) for traces
  * first_trace, first_trace + trace_stride, ... of configuration `config`
  * (1 random, 2 recompute, 3 offload, 4 LoRA, 5 even mixture of 2/3/4;
+ * 6: one rank of ZeRO-3 over 2^(trace mod 5) devices;
  * 12, 13, 14: recipes 2, 3, 4 with the same sequence length in every step).
  * Returns the number of slots needed (1 + the largest slot used), or 0 on a
  * bad argument.  Every row holds exactly n_events events.
@@ -353,7 +443,7 @@ static void *worker(void *arg)
 uint32_t tracegen_fill(int config, uint64_t seed, uint32_t first_trace, uint32_t trace_stride,
                        uint32_t n_traces, uint32_t n_events, uint64_t *events, int n_threads)
 {
-    if (!((config >= 1 && config <= 5) || (config >= 12 && config <= 14)) || !events || n_events == 0 || trace_stride == 0)
+    if (!((config >= 1 && config <= 6) || (config >= 12 && config <= 14)) || !events || n_events == 0 || trace_stride == 0)
         return 0;
     if (n_threads < 1) n_threads = 1;
     if (n_threads > 64) n_threads = 64;

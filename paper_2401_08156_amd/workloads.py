@@ -1,4 +1,4 @@
-"""The five synthetic workloads and the engine table sizes that fit them.
+"""The synthetic workloads and the engine table sizes that fit them.
 
 Table sizes (per trace) are capacity settings of the replay engine, not parameters of the
 allocators: a trace that outgrows them is flagged VMS_ST_TABLE_OVERFLOW instead of being replayed
@@ -8,7 +8,7 @@ smaller tables mean less LDS per wavefront and therefore more resident wavefront
 from . import tracegen
 
 NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "config4-lora",
-         5: "config5-mixture"}
+         5: "config5-mixture", 6: "config6-zero3-scaleout"}
 
 TABLES = {
     # config: splitting free list, pBlocks, sBlocks, chunk-run list entries, chunks (x 2 MiB)
@@ -17,6 +17,7 @@ TABLES = {
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks, runs kept in HBM
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 20, max_chunks=16384),
     4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=5120, max_chunks=24576),
+    6: dict(max_free_blocks=320, max_pblocks=1024, max_sblocks=640, max_runs=5120, max_chunks=16384),
 }
 # config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
 # events; replayed as three batches, one per kind, each with tables of its own

@@ -109,3 +109,13 @@ def test_periodic_trace_converges_on_gpu():
     late[:, 4 * 448:] = True                     # after four training steps of 448 events
     assert (code[is_alloc & late] == 1).all()
     assert (st["fragmentation"][1] == 0.0).all()
+
+
+def test_zero3_scaleout_slice():
+    # one rank of ZeRO-3 over 1, 2, 4, 8, 16 devices (Sec. 2.4, Sec. 5.3.2): shards shrink with the device
+    # count, gathered weights come and go; three traces per device count
+    from paper_2401_08156_amd import workloads
+    ev, ms = tg.generate(6, n_traces=15, n_events=6000)
+    cfg = workloads.make_config(binding, 6, 15, 6000, ms)
+    st = gpu_util.assert_parity(ev, cfg, label="config 6 slice")
+    assert st["status"].max() == 0

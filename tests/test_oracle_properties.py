@@ -52,7 +52,7 @@ def small_random_trace(rng, n, size_choices, p_free=0.45):
 
 # ---------------------------------------------------------------- closed forms
 
-@pytest.mark.parametrize("cfg,nt,ne", [(1, 1, 2000), (2, 3, 3000), (3, 2, 1500), (4, 2, 4000)])
+@pytest.mark.parametrize("cfg,nt,ne", [(1, 1, 2000), (2, 3, 3000), (3, 2, 1500), (4, 2, 4000), (6, 5, 3000)])
 def test_peak_requested_and_split_active_are_prefix_sums(cfg, nt, ne):
     ev, ms = tg.generate(cfg, n_traces=nt, n_events=ne)
     P = oracle.make_params(ms)
@@ -199,8 +199,8 @@ def test_invariants_config1():
 
 
 def test_invariants_transformer_slices():
-    for cfg in (2, 3, 4):
-        ev, ms = tg.generate(cfg, n_traces=1, n_events=1200)
+    for cfg in (2, 3, 4, 6):
+        ev, ms = tg.generate(cfg, n_traces=1, n_events=1200, first_trace=3)
         check_invariants(ev[0], oracle.VMS, oracle.make_params(ms))
         check_invariants(ev[0], oracle.SPLIT, oracle.make_params(ms))
 
