@@ -1,4 +1,4 @@
-"""ctypes binding of include/vms_replay.h: same names, argument marshalling only.
+"""ctypes binding of include/vms_replay.h and include/vms_live.h: same names, argument marshalling only.
 
 Every step of the replay runs in the HIP kernels of libvmsreplay.so; PyTorch is
 used for device memory and the stream.  There is no CPU fallback: a missing or
@@ -61,6 +61,25 @@ class vms_vmm_latency_report(ctypes.Structure):
                 ("set_access_ms", ctypes.c_double), ("unmap_ms", ctypes.c_double), ("release_ms", ctypes.c_double)]
 
 
+class vms_live_config(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("spool_threshold", ctypes.c_uint32),
+                ("chunk_bytes", ctypes.c_uint64), ("small_limit_bytes", ctypes.c_uint64),
+                ("frag_limit_bytes", ctypes.c_uint64), ("capacity_bytes", ctypes.c_uint64),
+                ("sync_before_unmap", ctypes.c_uint32), ("reserved0", ctypes.c_uint32)]
+
+
+class vms_live_api_report(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("hip_error", ctypes.c_int32),
+                ("n_reserve", ctypes.c_uint64), ("n_create", ctypes.c_uint64), ("n_map", ctypes.c_uint64),
+                ("n_set_access", ctypes.c_uint64), ("n_unmap", ctypes.c_uint64), ("n_release", ctypes.c_uint64),
+                ("n_address_free", ctypes.c_uint64),
+                ("ms_reserve", ctypes.c_double), ("ms_create", ctypes.c_double), ("ms_map", ctypes.c_double),
+                ("ms_set_access", ctypes.c_double), ("ms_unmap", ctypes.c_double), ("ms_release", ctypes.c_double),
+                ("ms_address_free", ctypes.c_double),
+                ("n_malloc", ctypes.c_uint64), ("n_free", ctypes.c_uint64),
+                ("ms_malloc", ctypes.c_double), ("ms_free", ctypes.c_double)]
+
+
 # vms_trace_stats as a numpy record (same layout as the C struct)
 STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("peak_reserved", "<u8"),
                         ("final_requested", "<u8"), ("final_active", "<u8"), ("final_reserved", "<u8"),
@@ -76,7 +95,10 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
            "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms",
            "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
-           "vms_demo_run", "vms_vmm_latency"]
+           "vms_demo_run", "vms_vmm_latency",
+           "vms_live_config_default", "vms_live_create", "vms_live_malloc", "vms_live_free", "vms_live_run_trace",
+           "vms_live_slot", "vms_live_stats", "vms_live_destroy", "vms_torch_malloc", "vms_torch_free",
+           "vms_torch_allocator"]
 
 _lib = None
 
@@ -121,6 +143,28 @@ def lib():
         L.vms_demo_run.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
         L.vms_vmm_latency.restype = ctypes.c_int
         L.vms_vmm_latency.argtypes = [u64, u64, u32, ctypes.POINTER(vms_vmm_latency_report)]
+        L.vms_live_config_default.restype = None
+        L.vms_live_config_default.argtypes = [ctypes.POINTER(vms_live_config)]
+        L.vms_live_create.restype = ctypes.c_int
+        L.vms_live_create.argtypes = [ctypes.POINTER(vms_live_config), ctypes.POINTER(vp)]
+        L.vms_live_malloc.restype = ctypes.c_int
+        L.vms_live_malloc.argtypes = [vp, u64, ctypes.POINTER(vp), ctypes.POINTER(u64)]
+        L.vms_live_free.restype = ctypes.c_int
+        L.vms_live_free.argtypes = [vp, vp, ctypes.POINTER(u64)]
+        L.vms_live_run_trace.restype = ctypes.c_int
+        L.vms_live_run_trace.argtypes = [vp, vp, u32, u32, vp]
+        L.vms_live_slot.restype = ctypes.c_int
+        L.vms_live_slot.argtypes = [vp, u32, ctypes.POINTER(vp), ctypes.POINTER(u64)]
+        L.vms_live_stats.restype = ctypes.c_int
+        L.vms_live_stats.argtypes = [vp, vp, ctypes.POINTER(vms_live_api_report)]
+        L.vms_live_destroy.restype = None
+        L.vms_live_destroy.argtypes = [vp]
+        L.vms_torch_malloc.restype = vp
+        L.vms_torch_malloc.argtypes = [ctypes.c_ssize_t, ctypes.c_int, vp]
+        L.vms_torch_free.restype = None
+        L.vms_torch_free.argtypes = [vp, ctypes.c_ssize_t, ctypes.c_int, vp]
+        L.vms_torch_allocator.restype = vp
+        L.vms_torch_allocator.argtypes = [ctypes.c_int]
         _lib = L
     return _lib
 
@@ -242,3 +286,92 @@ class Replay:
             self.close()
         except Exception:
             pass
+
+
+def vms_live_config_default():
+    cfg = vms_live_config()
+    lib().vms_live_config_default(ctypes.byref(cfg))
+    return cfg
+
+
+def _live_stats(handle):
+    out = np.zeros(1, dtype=STATS_DTYPE)
+    api = vms_live_api_report()
+    api.struct_size = ctypes.sizeof(vms_live_api_report)
+    rc = lib().vms_live_stats(handle, out.ctypes.data, ctypes.byref(api))
+    if rc != VMS_OK:
+        raise VmsError(rc, "vms_live_stats")
+    return out[0], api
+
+
+class LiveAllocator:
+    """One vms_live handle: the stitching allocator serving real device memory on the current device."""
+
+    def __init__(self, cfg=None):
+        self.cfg = cfg if cfg is not None else vms_live_config_default()
+        self._h = ctypes.c_void_p()
+        rc = lib().vms_live_create(ctypes.byref(self.cfg), ctypes.byref(self._h))
+        if rc != VMS_OK:
+            self._h = None
+            raise VmsError(rc, "vms_live_create")
+
+    def malloc(self, nbytes):
+        """Returns (device address or None, decision word)."""
+        ptr, dec = ctypes.c_void_p(), ctypes.c_uint64()
+        rc = lib().vms_live_malloc(self._h, int(nbytes), ctypes.byref(ptr), ctypes.byref(dec))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_live_malloc")
+        return ptr.value, int(dec.value)
+
+    def free(self, ptr):
+        dec = ctypes.c_uint64()
+        rc = lib().vms_live_free(self._h, ctypes.c_void_p(ptr), ctypes.byref(dec))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_live_free")
+        return int(dec.value)
+
+    def run_trace(self, h_events, max_slots):
+        """Serve a whole trace of event words (1-D uint64 numpy array); returns the decision words."""
+        ev = np.ascontiguousarray(h_events, dtype=np.uint64)
+        assert ev.ndim == 1
+        dec = np.zeros_like(ev)
+        rc = lib().vms_live_run_trace(self._h, ev.ctypes.data, ev.shape[0], int(max_slots), dec.ctypes.data)
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_live_run_trace")
+        return dec
+
+    def slot(self, slot):
+        ptr, nbytes = ctypes.c_void_p(), ctypes.c_uint64()
+        rc = lib().vms_live_slot(self._h, int(slot), ctypes.byref(ptr), ctypes.byref(nbytes))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_live_slot")
+        return ptr.value, int(nbytes.value)
+
+    def stats(self):
+        """(vms_trace_stats record, vms_live_api_report)."""
+        return _live_stats(self._h)
+
+    def close(self):
+        if self._h:
+            lib().vms_live_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def torch_allocator_stats(device=0):
+    """Statistics of the allocator behind vms_torch_malloc for a device (None before its first request)."""
+    h = lib().vms_torch_allocator(int(device))
+    return _live_stats(ctypes.c_void_p(h)) if h else None
+
+
+def torch_pluggable_allocator():
+    """torch.cuda.memory.CUDAPluggableAllocator over vms_torch_malloc / vms_torch_free; install it with
+    torch.cuda.memory.change_current_allocator() before the process touches device memory."""
+    import torch
+    lib()
+    return torch.cuda.memory.CUDAPluggableAllocator(_build.LIB, "vms_torch_malloc", "vms_torch_free")

@@ -5,8 +5,8 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libvmsreplay.so")
-SOURCES = ["vms_replay.hip", "vms_demo.hip"]
-HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h"]
+SOURCES = ["vms_replay.hip", "vms_demo.hip", "vms_live.hip"]
+HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h", "../../include/vms_live.h"]
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-Wall",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

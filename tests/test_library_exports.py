@@ -9,9 +9,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "vms_replay.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(vms_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("vms_replay.h", "vms_live.h"):
+        text = open(os.path.join(ROOT, "include", header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(vms_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported_and_bound():
@@ -29,6 +32,8 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding.vms_summary) == 88
     assert ctypes.sizeof(binding.vms_demo_report) == 224
     assert ctypes.sizeof(binding.vms_vmm_latency_report) == 104
+    assert ctypes.sizeof(binding.vms_live_config) == 48
+    assert ctypes.sizeof(binding.vms_live_api_report) == 152
 
 
 def test_config_default_and_argument_errors_need_no_gpu():
