@@ -8,8 +8,12 @@ LIB = os.path.join(_HERE, "libvmsreplay.so")
 SOURCES = ["vms_replay.hip", "vms_demo.hip", "vms_live.hip"]
 HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h", "../../include/vms_live.h"]
 
+# The replay loops branch on wave-uniform conditions only (whatever would switch lanes off is written
+# with selects or kept in non-inlined functions).  With the option below LLVM leaves such regions as
+# they are instead of rebuilding them around exec-mask style flow blocks: fewer branches per event.
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-Wall",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-mllvm", "-structurizecfg-skip-uniform-regions=1"]
 
 
 def _stale():

@@ -132,16 +132,20 @@ struct SlotsT<true> {
     // b >> 2 chunks) in skey[0..ns) (descending) and take its new place from smeta[]
     DI void relist(const u64 *skey, const u32 *smeta, u32 ns)
     {
-        if (req + 1u > 1u && (b & 3) == KIND_SBLOCK) {
-            const u64 key = ((u64)(b >> 2) << 32) | (u32)~a;
-            u32 lo = 0, hi = ns;                // first index whose key is not greater than key
-            while (lo < hi) {
-                const u32 mid = (lo + hi) >> 1;
-                if (skey[mid] > key) lo = mid + 1;
-                else hi = mid;
-            }
-            c = smeta[lo];
+        // every lane searches (13 halvings cover 4096 sBlocks), lanes without an sBlock for nothing:
+        // no lane is switched off, so the caller keeps its wave-uniform control flow
+        const bool holds = req + 1u > 1u && (b & 3) == KIND_SBLOCK;
+        const u64 key = ((u64)(b >> 2) << 32) | (u32)~a;
+        u32 lo = 0, hi = ns;                    // first index whose key is not greater than key
+#pragma unroll 1
+        for (u32 it = 0; it < 13; it++) {
+            const u32 mid = (lo + hi) >> 1;     // < ns while lo < hi; else a place that exists
+            const bool open = lo < hi, greater = skey[mid] > key;
+            lo = open && greater ? mid + 1 : lo;
+            hi = open && !greater ? mid : hi;
         }
+        const u32 found = pin(smeta[lo]);
+        c = holds ? found : c;
         wave_sync();
     }
 };
@@ -238,10 +242,8 @@ DI void sp_alloc(SplitPoolD &sp, u32 size, u32 seg, bool may_grow, AcctT &A, u32
         r.addr = blo >> 2;
         r.flags = blo & 3;
         r.code = C_EXACT;
-        if (lane == 0) {                        // unordered: the last key fills the hole, a zero its place
-            if (idx != last) sp.fl[idx] = lastk;
-            sp.fl[last] = 0;
-        }
+        if (idx != last) st_one(sp.fl, idx, lastk);     // unordered: the last key fills the hole, a zero its place
+        st_one(sp.fl, last, (u64)0);
         sp.n = last;
         wave_sync();
     } else {
@@ -329,10 +331,9 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
         wave_sync();
         if (*mr) {
             const u32 last = sp.n - 1;
-            if (lane == 0) {
-                if (ridx != last) sp.fl[ridx] = sp.fl[last];
-                sp.fl[last] = 0;
-            }
+            const u64 lastk = ld_uni(sp.fl, last);
+            if (ridx != last) st_one(sp.fl, ridx, lastk);
+            st_one(sp.fl, last, (u64)0);
             sp.n = last;
         }
     } else if (*mr) {
@@ -431,16 +432,18 @@ DI u32 word_mask(u32 w, u32 start, u32 end)    // bits of word w inside [start, 
     return (n == 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)) << b0;
 }
 
-// one run, the lanes take one bitmap word each
-DI void bmp_fill(u32 *bmp, u32 start, u32 len, bool set)
+// one run, the lanes take one bitmap word each; lanes past its end rewrite the spare word behind
+// the bitmap (no divergent branch)
+DI void bmp_fill(u32 *bmp, u32 spare, u32 start, u32 len, bool set)
 {
     const u32 end = start + len, w0 = start >> 5, w1 = (end - 1) >> 5;
     for (u32 wb = w0; wb <= w1; wb += 64) {
-        u32 w = wb + lane_id();
-        if (w <= w1) {
-            u32 m = word_mask(w, start, end);
-            bmp[w] = set ? (bmp[w] | m) : (bmp[w] & ~m);
-        }
+        const u32 w = wb + lane_id();
+        const bool in = w <= w1;
+        const u32 mw = pin(word_mask(w, start, end));          // computed by every lane: no branch
+        const u32 m = in ? mw : 0u, wi = in ? w : spare;
+        const u32 old = pin(bmp[wi]);
+        bmp[wi] = set ? (old | m) : (old & ~m);
     }
     wave_sync();
 }
@@ -461,8 +464,16 @@ DI void entries_pass(u32 *bmp, u32 e, bool live, u32 p, bool set)
     wave_sync();
 }
 
+// passes 1 to 3 of one tile of entries: rare, and the only part with lanes switched off, so it
+// is kept out of line (the callers stay free of divergent branches)
+typedef __attribute__((address_space(3))) u32 lds_u32;
+__device__ __attribute__((noinline)) void entries_later(lds_u32 *bmp, u32 e, u32 live, u32 set)
+{
+    for (u32 p = 1; p < 4; p++) entries_pass((u32 *)bmp, e, live != 0, p, set != 0);
+}
+
 // all entries of one sBlock, one lane per entry.  first_done: pass 0 of the first 64 entries has
-// been applied by the caller.
+// been applied by the caller.  Lanes without an entry of pass 0 rewrite the spare word.
 template <bool BIG>
 DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set, bool first_done = false)
 {
@@ -471,9 +482,13 @@ DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set, bool fi
         const bool live = r < cnt;
         const u32 e = V.arena[off + (live ? r : 0u)];
         const u64 later = ballot(live && ENT_PASS(e) != 0);
-        if (!(first_done && rb == 0)) entries_pass(V.bmp, e, live, 0, set);
-        if (later)
-            for (u32 p = 1; p < 4; p++) entries_pass(V.bmp, e, live, p, set);
+        if (!(first_done && rb == 0)) {
+            const u32 e0 = live && ENT_PASS(e) == 0 ? e : V.e_skip;
+            const u32 word = V.bmp[ENT_WORD(e0)];
+            V.bmp[ENT_WORD(e0)] = set ? (word | emask(e0)) : (word & ~emask(e0));
+            wave_sync();
+        }
+        if (later) entries_later((lds_u32 *)V.bmp, e, live ? 1u : 0u, set ? 1u : 0u);
     }
 }
 
@@ -783,8 +798,10 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
             if (cnt > 64) {                     // long list: the rest of it, a tile at a time
                 for (u32 eb = 64; eb < cnt && !bm; eb += 64) {
                     const u32 k = eb + lane;
-                    e = V.arena[off + (k < cnt ? k : 0u)];
-                    bm = ballot(k < cnt && (V.bmp[ENT_WORD(e)] & emask(e)) != 0);
+                    const u32 ek = pin(V.arena[off + (k < cnt ? k : 0u)]);
+                    e = k < cnt ? ek : V.e_skip;
+                    const u32 wk = pin(V.bmp[ENT_WORD(e)]);
+                    bm = ballot((wk & emask(e)) != 0);
                 }
                 if (!bm) {
                     bmp_fill_entries(V, off, cnt, true);
@@ -872,7 +889,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             u32 psize = (u32)(pk >> 32), pstart = ~(u32)pk;
             if (psize < P.frag_limit_chunks) {
                 // below the fragmentation limit: not worth cutting, hand it out whole (Sec. 4.2.3)
-                bmp_fill(V.bmp, pstart, psize, true);
+                bmp_fill(V.bmp, ENT_WORD(V.e_skip), pstart, psize, true);
                 R.ref = pstart;
                 R.held = psize;
                 R.dec_lo = C_SPLIT | (1u << 8);
@@ -890,7 +907,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             u32 n = arena_put(V, V.top, pstart, psize);
             spool_insert(V, psize, V.top, n, A);
             V.top += n;
-            bmp_fill(V.bmp, pstart, bsize, true);
+            bmp_fill(V.bmp, ENT_WORD(V.e_skip), pstart, bsize, true);
             R.ref = pstart;
             R.dec_lo = C_SPLIT | B_6 | (1u << 8);
             if (stitch_free(V, P, A)) R.dec_lo |= B_7;
@@ -946,7 +963,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         u32 start = V.n_chunks;
         pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
-        bmp_fill(V.bmp, start, deficit, true);
+        bmp_fill(V.bmp, ENT_WORD(V.e_skip), start, deficit, true);
         R.ref = start;
         R.dec_lo = C_GROW;
         return;
@@ -1170,12 +1187,21 @@ struct TileOut {
     }
 };
 
+// the last tile of a trace (or the tile in which a table overflowed): only the lanes below `done` store
+__device__ __attribute__((noinline)) void emit_partial(u64 *dst, u64 dec, u32 done)
+{
+    if (lane_id() < done) dst[lane_id()] = dec;
+}
+
 DI void tile_emit(TileOut &T, u64 *dec_row, u32 base, u32 done, u32 v_dlo, u32 v_dhi, u32 v_act, u32 v_res)
 {
     const u32 lane = lane_id();
     const bool valid = lane < done;
     const u64 dec = ((u64)v_dhi << 32) | v_dlo;
-    if (dec_row && valid) dec_row[base + lane] = dec;
+    if (dec_row) {
+        if (done == 64) dec_row[base + lane] = dec;         // a full tile: one coalesced store, no lane off
+        else emit_partial(dec_row + base, dec, done);
+    }
     const u32 code = v_dlo & 15, cidx = !valid ? 8u : (code == C_INVALID ? 7u : code);
 #pragma unroll
     for (u32 c = 0; c < 8; c++) T.n_code[c] += cidx == c ? 1u : 0u;
@@ -1258,7 +1284,11 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     for (u32 base = 0; base < n_ev; base += 64) {
         const u32 tile = min(64u, n_ev - base);
         const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
-        if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
+        if (base + 64 < n_ev) {                             // prefetch; lanes past the end re-read the last event
+            const u32 nx = base + 64 + lane;
+            const u64 x = pin64(ev_row[min(nx, n_ev - 1)]);
+            ev_next = nx < n_ev ? x : 0;
+        }
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
         u32 done = tile, todo = tile;       // todo drops to 0 when an engine table overflows: the trace ends there
         // every path of an event ends by parking its results in lane j and going on to the next event
@@ -1308,7 +1338,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                     EMIT(C_FREE | B_SBLOCK, a)
                 }
                 if (kind == KIND_PBLOCK) {
-                    bmp_fill(V.bmp, a, b >> 2, false);
+                    bmp_fill(V.bmp, ENT_WORD(V.e_skip), a, b >> 2, false);
                     active -= (b >> 2) << P.chunk_shift;
                     EMIT((u32)C_FREE, a)
                 }
@@ -1344,7 +1374,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                     EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)
                 }
                 if (s1_pblock(V, bsize, ref)) {
-                    bmp_fill(V.bmp, ref, bsize, true);
+                    bmp_fill(V.bmp, ENT_WORD(V.e_skip), ref, bsize, true);
                     S.set_a(slot, ref);
                     S.set_b(slot, KIND_PBLOCK | (bsize << 2));
                     S.set_req(slot, size);
@@ -1505,7 +1535,11 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
     for (u32 base = 0; base < n_ev; base += 64) {
         const u32 tile = min(64u, n_ev - base);
         const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
-        if (base + 64 < n_ev) ev_next = base + 64 + lane < n_ev ? ev_row[base + 64 + lane] : 0;   // prefetch
+        if (base + 64 < n_ev) {                             // prefetch; lanes past the end re-read the last event
+            const u32 nx = base + 64 + lane;
+            const u64 x = pin64(ev_row[min(nx, n_ev - 1)]);
+            ev_next = nx < n_ev ? x : 0;
+        }
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
         u32 done = tile;
         for (u32 j = 0; j < tile; j++) {

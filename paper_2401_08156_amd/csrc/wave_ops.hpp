@@ -97,10 +97,13 @@ DI u32 wave_scan_add(u32 v, u32 *total)
 DI u32 ld_uni(const u32 *a, u32 i) { return uni(a[i]); }
 DI u64 ld_uni(const u64 *a, u32 i) { return uni64(a[i]); }
 
+// store of a wave-uniform value at a wave-uniform place: every lane writes it (one address, one
+// value: no bank conflict, measured cheaper than a store under a one-lane mask, and no
+// divergent branch)
 template <class T>
 DI void st_one(T *a, u32 i, T v)
 {
-    if (lane_id() == 0) a[i] = v;
+    a[i] = v;
 }
 
 // number of elements of a[0..n) that are greater than key
@@ -288,6 +291,11 @@ DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
 
 // keeps a loaded value where it is: the compiler may not sink the load into a later branch
 DI u32 pin(u32 x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+DI u64 pin64(u64 x)
 {
     asm volatile("" : "+v"(x));
     return x;
