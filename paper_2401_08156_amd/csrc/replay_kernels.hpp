@@ -84,21 +84,14 @@ struct AcctRegs {
 
 struct AcctLds {
     u32 *sc;
-    DI void add(u32 k, u32 x)
-    {
-        if (lane_id() == 0) atomicAdd(&sc[k], x);
-    }
-    DI void peak(u32 k, u32 v)
-    {
-        if (lane_id() == 0) atomicMax(&sc[k], v);
-    }
+    // one wavefront owns the scalars: every lane does the same read-modify-write (no lane is switched off)
+    DI void add(u32 k, u32 x) { st_one(sc, k, ld_uni(sc, k) + x); }
+    DI void peak(u32 k, u32 v) { st_one(sc, k, max(ld_uni(sc, k), v)); }
     DI void overflow(u32 ev, u32 which)
     {
-        if (lane_id() == 0) {
-            atomicOr(&sc[SC_STATUS], VMS_ST_TABLE_OVERFLOW | which);
-            atomicMin(&sc[SC_OVF_EVENT], ev);
-            sc[SC_STOP] = 1;
-        }
+        st_one(sc, (u32)SC_STATUS, ld_uni(sc, (u32)SC_STATUS) | VMS_ST_TABLE_OVERFLOW | which);
+        st_one(sc, (u32)SC_OVF_EVENT, min(ld_uni(sc, (u32)SC_OVF_EVENT), ev));
+        st_one(sc, (u32)SC_STOP, 1u);
         wave_sync();
     }
 };
@@ -417,7 +410,11 @@ template <bool BIG>
 DI u32 arena_put(VmsT<BIG> &V, u32 at, u32 start, u32 len)
 {
     const u32 n = run_words(start, len);
-    for (u32 q = lane_id(); q < n; q += 64) V.arena[at + q] = run_entry(start, len, q);
+    for (u32 qb = 0; qb < n; qb += 64) {
+        // lanes past the run write its last entry again
+        const u32 q = min(qb + lane_id(), n - 1);
+        V.arena[at + q] = run_entry(start, len, q);
+    }
     wave_sync();
     return n;
 }
@@ -469,6 +466,7 @@ DI void entries_pass(u32 *bmp, u32 e, bool live, u32 p, bool set)
 typedef __attribute__((address_space(3))) u32 lds_u32;
 __device__ __attribute__((noinline)) void entries_later(lds_u32 *bmp, u32 e, u32 live, u32 set)
 {
+    set = uni(set);
     for (u32 p = 1; p < 4; p++) entries_pass((u32 *)bmp, e, live != 0, p, set != 0);
 }
 
@@ -499,8 +497,12 @@ DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 {
     const u32 end = start + len;
     const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
-    for (u32 q = 0; ballot(len && w0 + q <= w1); q++)
-        if (len && w0 + q <= w1) atomicOr(&V.tmp[w0 + q], word_mask(w0 + q, start, end));
+    for (u32 q = 0; ballot(len && w0 + q <= w1); q++) {
+        // lanes with nothing left OR a zero into a word of their own
+        const bool in = len && w0 + q <= w1;
+        const u32 mw = pin(word_mask(w0 + q, start, end));
+        atomicOr(&V.tmp[in ? w0 + q : ENT_WORD(V.e_skip) + lane_id()], in ? mw : 0u);   // 64 spare words follow tmp[]
+    }
     wmin = min(wmin, w0);
     wmax = max(wmax, w1);
 }
@@ -508,29 +510,29 @@ DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 // ... and read back as entries at arena[at..], one per range of consecutive chunks inside a word
 // (touching runs have merged), leaving tmp[] zero.  Returns the number of entries.
 template <bool BIG>
-DI u32 list_extract(const VmsT<BIG> &V, u32 wmin, u32 wmax, u32 at)
+DI u32 list_extract(const VmsT<BIG> &V, u32 wmin, u32 wmax, u32 at, u32 spare)
 {
     u32 cnt = 0;
     for (u32 wb = wmin; wb <= wmax; wb += 64) {
-        const u32 w = wb + lane_id();
-        u32 m = 0;
-        if (w <= wmax) {
-            m = V.tmp[w];
-            V.tmp[w] = 0;
-        }
+        const u32 w = min(wb + lane_id(), wmax);     // lanes past the end: the last word again, taken as empty
+        const u32 mw = pin(V.tmp[w]);
+        u32 m = wb + lane_id() <= wmax ? mw : 0u;
+        wave_sync();
+        V.tmp[w] = 0;
         const u32 nr = (u32)__builtin_popcount(m & ~(m << 1));      // ranges start where a set bit follows a clear one
         u32 tot;
         const u32 incl = wave_scan_add(nr, &tot);
         const u32 o = at + cnt + incl - nr;
         for (u32 r = 0; ballot(m != 0); r++) {
-            if (m) {
-                const u32 lo = (u32)__builtin_ctz(m);
-                const u32 rest = ~(m >> lo);
-                const u32 len = rest ? (u32)__builtin_ctz(rest) : 32u;
-                const u32 hi = lo + len - 1;
-                V.arena[o + r] = (w << 12) | ((r < 3 ? r : 3u) << 10) | (lo << 5) | hi;
-                m &= ~((2u << hi) - (1u << lo));
-            }
+            // a lane whose word is used up writes into the spare places behind the arena
+            const bool some = m != 0;
+            const u32 mm = some ? m : 1u;
+            const u32 lo = (u32)__builtin_ctz(mm);
+            const u32 rest = ~(mm >> lo);
+            const u32 len = rest ? (u32)__builtin_ctz(rest) : 32u;
+            const u32 hi = lo + len - 1;
+            V.arena[some ? o + r : spare + lane_id()] = (w << 12) | ((r < 3 ? r : 3u) << 10) | (lo << 5) | hi;
+            m = some ? m & ~((2u << hi) - (1u << lo)) : 0u;
         }
         cnt += tot;
     }
@@ -600,16 +602,14 @@ DI void spool_shift_up(VmsT<BIG> &V, u32 pos, u32 n)
 {
     for (u32 hi = n; hi > pos;) {
         const u32 lo = hi - pos > 64 ? hi - 64 : pos;
-        const u32 i = lo + lane_id();
-        if (i < hi) {
-            const u64 k = V.skey[i];
-            const auto m = V.smeta[i];
-            const u32 st = V.sstamp[i], w = V.swit[i];
-            V.skey[i + 1] = k;
-            V.smeta[i + 1] = m;
-            V.sstamp[i + 1] = st;
-            V.swit[i + 1] = w;
-        }
+        const u32 i = lo + lane_id(), src = i < hi ? i : i + 1;   // lanes above the part that moves: see shift_up
+        const u64 k = V.skey[src];
+        const auto m = V.smeta[src];
+        const u32 st = V.sstamp[src], w = V.swit[src];
+        V.skey[i + 1] = k;
+        V.smeta[i + 1] = m;
+        V.sstamp[i + 1] = st;
+        V.swit[i + 1] = w;
         hi = lo;
     }
     wave_sync();
@@ -619,16 +619,14 @@ template <bool BIG>
 DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
 {
     for (u32 lo = pos + 1; lo < n; lo += 64) {
-        const u32 i = lo + lane_id();
-        if (i < n) {
-            const u64 k = V.skey[i];
-            const auto m = V.smeta[i];
-            const u32 st = V.sstamp[i], w = V.swit[i];
-            V.skey[i - 1] = k;
-            V.smeta[i - 1] = m;
-            V.sstamp[i - 1] = st;
-            V.swit[i - 1] = w;
-        }
+        const u32 i = lo + lane_id(), dst = i < n ? i - 1 : i;   // lanes past the end: see shift_down
+        const u64 k = V.skey[i];
+        const auto m = V.smeta[i];
+        const u32 st = V.sstamp[i], w = V.swit[i];
+        V.skey[dst] = k;
+        V.smeta[dst] = m;
+        V.sstamp[dst] = st;
+        V.swit[dst] = w;
     }
     wave_sync();
 }
@@ -674,7 +672,10 @@ DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
     for (u32 s = 0; s < V.ns; s++) {
         auto meta = ld_uni(V.smeta, s);
         u32 off = V.off(meta), cnt = V.cnt(meta);
-        for (u32 r = lane_id(); r < cnt; r += 64) V.bounce[top + r] = V.arena[off + r];
+        for (u32 rb = 0; rb < cnt; rb += 64) {          // lanes past the end copy the last entry again
+            const u32 r = min(rb + lane_id(), cnt - 1);
+            V.bounce[top + r] = V.arena[off + r];
+        }
         st_one(V.smeta, s, V.pack(top, cnt));
         if (!BIG) S.moved((u32)meta, (u32)V.pack(top, cnt), P);
         top += cnt;
@@ -686,7 +687,10 @@ DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
         V.arena = V.bounce;
         V.bounce = t;
     } else {
-        for (u32 r = lane_id(); r < top; r += 64) V.arena[r] = V.bounce[r];
+        for (u32 rb = 0; rb < top; rb += 64) {
+            const u32 r = min(rb + lane_id(), top - 1);
+            V.arena[r] = V.bounce[r];
+        }
     }
     V.top = top;
     wave_sync();
@@ -710,8 +714,10 @@ DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
         const u32 k = eb + lane_id();
-        const u32 e = V.arena[off + (k < cnt ? k : 0u)];
-        const u64 bm = ballot(k < cnt && (V.bmp[ENT_WORD(e)] & emask(e)) != 0);
+        const u32 ek = pin(V.arena[off + (k < cnt ? k : 0u)]);
+        const u32 e = k < cnt ? ek : V.e_skip;
+        const u32 wk = pin(V.bmp[ENT_WORD(e)]);
+        const u64 bm = ballot((wk & emask(e)) != 0);
         if (bm) {
             *witness = from_lane(e, first_lane(bm));
             return true;
@@ -736,11 +742,10 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
             for (u32 base = 0; base < V.ns; base += 64) {
                 const u32 i = base + lane, ic = i < V.ns ? i : 0u;
                 const u32 st = V.sstamp[ic], wit = V.swit[ic];
-                const bool known = (V.bmp[ENT_WORD(wit)] & emask(wit)) != 0;
-                if (i < V.ns && !known && st < best) {
-                    best = st;
-                    besti = i;
-                }
+                const u32 ww = pin(V.bmp[ENT_WORD(wit)]);
+                const bool better = (i < V.ns) & ((ww & emask(wit)) == 0) & (st < best);
+                best = better ? st : best;
+                besti = better ? i : besti;
             }
             const u32 m = wave_min_u32(best);
             if (m == NONE32) break;             // everything cached is in use: the threshold stays exceeded
@@ -880,9 +885,11 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     // pool order is the single-block candidate (state 2).
     for (u32 hi = lo_p; hi > 0;) {
         u32 lo = hi > 64 ? hi - 64 : 0;
-        bool v = lane < hi - lo;
-        u64 key = v ? V.pool[hi - 1 - lane] : 0;
-        u64 m = ballot(v && !bmp_test(V.bmp, ~(u32)key));
+        const bool v = lane < hi - lo;
+        const u64 key = V.pool[v ? hi - 1 - lane : 0u];
+        const u32 fc = v ? ~(u32)key : 0u;                  // first chunk (chunk 0 for lanes without a block)
+        const u32 kw = pin(V.bmp[fc >> 5]);
+        const u64 m = ballot(v && !((kw >> (fc & 31)) & 1u));
         if (m) {
             u32 l = first_lane(m), idx = hi - 1 - l;
             u64 pk = from_lane64(key, l);
@@ -922,9 +929,11 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     if (P.frag_limit_chunks > 1) lim = rank_desc(V.pool, V.np, ((u64)P.frag_limit_chunks << 32) - 1);
     u32 sum = 0, k = 0, pos = NONE32;
     for (u32 base = hi_p; base < lim; base += 64) {
-        u32 i = base + lane;
-        u64 key = i < lim ? V.pool[i] : 0;
-        bool inact = i < lim && !bmp_test(V.bmp, ~(u32)key);
+        const u32 i = base + lane;
+        const u64 key = V.pool[i < lim ? i : 0u];
+        const u32 fc = i < lim ? ~(u32)key : 0u;
+        const u32 kw = pin(V.bmp[fc >> 5]);
+        const bool inact = i < lim && !((kw >> (fc & 31)) & 1u);
         u32 tot, incl = wave_scan_add(inact ? (u32)(key >> 32) : 0u, &tot);
         u64 im = ballot(inact);
         if (sum + tot >= bsize) {
@@ -975,16 +984,18 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         u32 wmin = NONE32, wmax = 0;
         const u32 endi = s3 ? pos + 1 : lim;
         for (u32 base = hi_p; base < endi; base += 64) {
-            u32 i = base + lane;
-            u64 key = i < endi ? V.pool[i] : 0;
-            bool inact = i < endi && !bmp_test(V.bmp, ~(u32)key);
+            const u32 i = base + lane;
+            const u64 key = V.pool[i < endi ? i : 0u];
+            const u32 fc = i < endi ? ~(u32)key : 0u;
+            const u32 kw = pin(V.bmp[fc >> 5]);
+            const bool inact = i < endi && !((kw >> (fc & 31)) & 1u);
             u32 len = (u32)(key >> 32), start = ~(u32)key;
             if (i == pos) len -= excess;
             list_mark(V, start, inact ? len : 0u, wmin, wmax);
         }
         if (!s3) list_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
         wave_sync();
-        cnt = list_extract(V, wave_min_u32(wmin), wave_max_u32(wmax), V.top);
+        cnt = list_extract(V, wave_min_u32(wmin), wave_max_u32(wmax), V.top, P.cap_runs);
     }
     u32 used = cnt;             // arena entries consumed, including a restore block's
     R.dec_lo = 0;
@@ -1056,7 +1067,9 @@ struct ColdState {
     DI void load(const char *lds) { v = pin(((const u32 *)(lds + LDS_SCALARS))[lane_id()]); }
     DI void store(char *lds) const          // the counters behind the state are updated in place, never from here
     {
-        if (lane_id() < SC_STATE_COUNT) ((u32 *)(lds + LDS_SCALARS))[lane_id()] = v;
+        u32 *sc = (u32 *)(lds + LDS_SCALARS);
+        const u32 cur = pin(sc[lane_id()]);          // the counters keep what is there
+        sc[lane_id()] = lane_id() < SC_STATE_COUNT ? v : cur;
         wave_sync();
     }
     DI u32 get(u32 k) const { return from_lane(v, k); }
@@ -1093,6 +1106,11 @@ template <bool BIG>
 __device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *ws_slice, u32 bsize, u32 reserved_units,
                                                          u32 clock, u32 ev)
 {
+    // arguments arrive in vector registers: tell the compiler that they are the same in every lane
+    bsize = uni(bsize);
+    reserved_units = uni(reserved_units);
+    clock = uni(clock);
+    ev = uni(ev);
     char *lds = (char *)ldsp;
     KParams P;
     load_params(P, lds);
@@ -1135,6 +1153,10 @@ __device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *w
 // left | merged right << 1.
 __device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 size, u32 seg, u32 may_grow, u32 ev)
 {
+    size = uni(size);
+    seg = uni(seg);
+    may_grow = uni(may_grow);
+    ev = uni(ev);
     char *lds = (char *)ldsp;
     ColdState C;
     C.load(lds);
@@ -1157,6 +1179,10 @@ __device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 s
 
 __device__ __attribute__((noinline)) void small_free_cold(lds_char *ldsp, u32 addr, u32 size, u32 flags, u32 ev)
 {
+    addr = uni(addr);
+    size = uni(size);
+    flags = uni(flags);
+    ev = uni(ev);
     char *lds = (char *)ldsp;
     ColdState C;
     C.load(lds);
@@ -1256,6 +1282,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     V.pp.v = V.sp.v = 0;
     V.pp.stride = V.sp.stride = 1;
     for (u32 i = lane; i < (P.cap_chunks + 31) / 32; i += 64) V.bmp[i] = V.tmp[i] = 0;
+    V.tmp[(P.cap_chunks + 31) / 32 + lane] = 0;             // 64 spare words: where idle lanes OR their zeros
     // the searches read up to 64 places past the live part of pool[], skey[], swit[] and arena[]
     // without clamping: zero keys there, and witnesses / entries on words that exist
     for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;

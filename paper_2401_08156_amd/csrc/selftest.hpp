@@ -38,14 +38,16 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
         if (from_lane(v, (round * 9) & 63) != in[(round * 9) & 63]) bad |= 16;
         wave_sync();
     }
-    // sorted-array helpers on a descending array of 150 keys
-    for (u32 i = lane; i < 150; i += 64) arr[i] = (u64)(1000 - 3 * i) << 32;
+    // sorted-array helpers on a descending array of 150 keys, followed by zero keys as they require
+    for (u32 i = lane; i < 256; i += 64) arr[i] = i < 150 ? (u64)(1000 - 3 * i) << 32 : 0;
     wave_sync();
     if (count_gt(arr, 150, (u64)700 << 32) != 100) bad |= 32;     // 1000-3i > 700  <=>  i < 100
     u32 c1, c2;
     count_gt2(arr, 150, ((u64)700 << 32) | 0xFFFFFFFFu, ((u64)700 << 32) - 1, &c1, &c2);
     if (c1 != 100 || c2 != 101) bad |= 32;
     for (u32 n = 1; n <= 150; n += (n < 70 ? 1 : 7)) {
+        for (u32 i = lane; i < 256; i += 64) arr[i] = i < n ? (u64)(1000 - 3 * i) << 32 : 0;
+        wave_sync();
         for (u32 probe = 540; probe <= 1003; probe += 1) {
             u64 key = ((u64)probe << 32) - 1;
             u32 ref = count_gt(arr, n, key), r = rank_desc(arr, n, key), r1, r2;
@@ -60,6 +62,8 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
             if (rank_probe(pr, arr, n, key) != count_gt(arr, n, key)) bad |= 512;
         }
     }
+    for (u32 i = lane; i < 256; i += 64) arr[i] = i < 150 ? (u64)(1000 - 3 * i) << 32 : 0;
+    wave_sync();
     shift_up(arr, 70, 150);
     st_one(arr, 70u, (u64)12345);
     wave_sync();
@@ -70,6 +74,8 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
     shift_down(arr, 70, 151);
     for (u32 i = 0; i < 150; i++)
         if (arr[i] != (u64)(1000 - 3 * i) << 32) bad |= 128;
+    for (u32 i = 151; i < 256; i++)
+        if (arr[i] != 0) bad |= 128;                // the spare places stay zero (arr[150] keeps the moved key's copy)
     u64 any = ballot(bad != 0);
     if (lane == 0) *fail = any ? (bad | 0x80000000u) : 0;
     if (any && bad) atomicOr(fail, bad);

@@ -77,7 +77,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         k.off_smeta = take((c.max_sblocks + 64) * (big ? 8 : 4));
         k.off_sstamp = take((c.max_sblocks + 64) * 4);
         k.off_swit = take((c.max_sblocks + 64) * 4);
-        k.off_tmp = take((c.max_chunks + 31) / 32 * 4);
+        k.off_tmp = take((c.max_chunks + 31) / 32 * 4 + 256);   // and 64 spare words
         k.off_arena = big ? 0 : take((c.max_runs + 64) * 4);
     } else {
         k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_swit = k.off_tmp = k.off_arena = 0;

@@ -86,7 +86,7 @@ DI u32 wave_scan_add(u32 v, u32 *total)
     v += dpp_zero<DPP_ROW_SHR8>(v);                    // inclusive scan inside each row of 16
     u32 t0 = from_lane(v, 15), t1 = from_lane(v, 31), t2 = from_lane(v, 47), t3 = from_lane(v, 63);
     u32 row = lane_id() >> 4;
-    u32 add = row == 0 ? 0u : (row == 1 ? t0 : (row == 2 ? t0 + t1 : t0 + t1 + t2));
+    u32 add = (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);     // three selects, no branch
     *total = t0 + t1 + t2 + t3;
     return v + add;
 }
@@ -106,15 +106,15 @@ DI void st_one(T *a, u32 i, T v)
     a[i] = v;
 }
 
+// The searches and shifts below work on arrays that are followed by 64 spare places holding zero
+// keys (live keys are never zero): whole tiles are read without clamping, a key past the end
+// compares as "not greater", and no lane is ever switched off.
+
 // number of elements of a[0..n) that are greater than key
 DI u32 count_gt(const u64 *a, u32 n, u64 key)
 {
     u32 c = 0;
-    for (u32 base = 0; base < n; base += 64) {
-        u32 i = base + lane_id();
-        bool p = i < n && a[i] > key;
-        c += popc64(ballot(p));
-    }
+    for (u32 base = 0; base < n; base += 64) c += popc64(ballot(a[base + lane_id()] > key));
     return c;
 }
 
@@ -123,10 +123,9 @@ DI void count_gt2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *c1, u32 *c2)
 {
     u32 x = 0, y = 0;
     for (u32 base = 0; base < n; base += 64) {
-        u32 i = base + lane_id();
-        u64 v = i < n ? a[i] : 0;
-        x += popc64(ballot(i < n && v > k1));
-        y += popc64(ballot(i < n && v > k2));
+        const u64 v = a[base + lane_id()];
+        x += popc64(ballot(v > k1));
+        y += popc64(ballot(v > k2));
     }
     *c1 = x;
     *c2 = y;
@@ -138,15 +137,12 @@ DI void count_gt2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *c1, u32 *c2)
 DI u32 rank_desc(const u64 *a, u32 n, u64 key)
 {
     const u32 lane = lane_id();
-    if (n <= 64) return popc64(ballot(lane < n && a[lane] > key));
+    if (n <= 64) return popc64(ballot(a[lane] > key));
     if (n > 4096) return count_gt(a, n, key);
     const u32 stride = (n + 63) >> 6;
-    const u32 pi = lane * stride;
-    const u32 c = popc64(ballot(pi < n && a[pi] > key));    // probes above key form a prefix
-    if (c == 0) return 0;
-    const u32 b0 = (c - 1) * stride;                         // a[b0] > key >= a[b0 + stride]
-    const u32 i = b0 + lane;
-    return b0 + popc64(ballot(lane < stride && i < n && a[i] > key));
+    const u32 c = popc64(ballot(a[lane * stride] > key));    // probes above key form a prefix
+    const u32 b0 = (c ? c - 1 : 0u) * stride;                // a[b0] > key >= a[b0 + stride] (if c)
+    return b0 + popc64(ballot(a[b0 + lane] > key));          // keys from b0 + stride on are not greater
 }
 
 // ranks of two keys (k1 >= k2, hence r1 <= r2) sharing the probe pass
@@ -154,9 +150,9 @@ DI void rank_desc2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *r1, u32 *r2)
 {
     const u32 lane = lane_id();
     if (n <= 64) {
-        u64 v = lane < n ? a[lane] : 0;
-        *r1 = popc64(ballot(lane < n && v > k1));
-        *r2 = popc64(ballot(lane < n && v > k2));
+        const u64 v = a[lane];
+        *r1 = popc64(ballot(v > k1));
+        *r2 = popc64(ballot(v > k2));
         return;
     }
     if (n > 4096) {
@@ -164,40 +160,38 @@ DI void rank_desc2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *r1, u32 *r2)
         return;
     }
     const u32 stride = (n + 63) >> 6;
-    const u32 pi = lane * stride;
-    const u64 pv = pi < n ? a[pi] : 0;
-    const u32 c1 = popc64(ballot(pi < n && pv > k1)), c2 = popc64(ballot(pi < n && pv > k2));
-    const u32 b1 = c1 ? (c1 - 1) * stride : 0, b2 = c2 ? (c2 - 1) * stride : 0;
-    const u32 i1 = b1 + lane, i2 = b2 + lane;
-    const u64 v1 = (lane < stride && i1 < n) ? a[i1] : 0, v2 = (lane < stride && i2 < n) ? a[i2] : 0;
-    *r1 = c1 ? b1 + popc64(ballot(lane < stride && i1 < n && v1 > k1)) : 0;
-    *r2 = c2 ? b2 + popc64(ballot(lane < stride && i2 < n && v2 > k2)) : 0;
+    const u64 pv = a[lane * stride];
+    const u32 c1 = popc64(ballot(pv > k1)), c2 = popc64(ballot(pv > k2));
+    const u32 b1 = (c1 ? c1 - 1 : 0u) * stride, b2 = (c2 ? c2 - 1 : 0u) * stride;
+    const u64 v1 = a[b1 + lane], v2 = a[b2 + lane];
+    *r1 = b1 + popc64(ballot(v1 > k1));
+    *r2 = b2 + popc64(ballot(v2 > k2));
 }
 
-// a[pos..n) -> a[pos+1..n+1), highest tile first
+// a[pos..n) -> a[pos+1..n+1), highest tile first.  Lanes above the part that moves rewrite
+// the place above their own with what it holds (places that are final already).
 template <class T>
 DI void shift_up(T *a, u32 pos, u32 n)
 {
     for (u32 hi = n; hi > pos;) {
-        u32 lo = hi - pos > 64 ? hi - 64 : pos;
-        u32 i = lo + lane_id();
-        bool v = i < hi;
-        T x = v ? a[i] : T(0);
-        if (v) a[i + 1] = x;
+        const u32 lo = hi - pos > 64 ? hi - 64 : pos;
+        const u32 i = lo + lane_id();
+        const T x = a[i < hi ? i : i + 1];
+        a[i + 1] = x;
         hi = lo;
     }
     wave_sync();
 }
 
-// a[pos+1..n) -> a[pos..n-1), lowest tile first
+// a[pos+1..n) -> a[pos..n-1), lowest tile first.  Lanes past the end rewrite their own
+// (spare, zero) place.
 template <class T>
 DI void shift_down(T *a, u32 pos, u32 n)
 {
     for (u32 lo = pos + 1; lo < n; lo += 64) {
-        u32 i = lo + lane_id();
-        bool v = i < n;
-        T x = v ? a[i] : T(0);
-        if (v) a[i - 1] = x;
+        const u32 i = lo + lane_id();
+        const T x = a[i];
+        a[i < n ? i - 1 : i] = x;
     }
     wave_sync();
 }
