@@ -25,7 +25,6 @@ enum { KIND_SMALL = 0u, KIND_PBLOCK = 1u, KIND_SBLOCK = 2u };
 #define NONE32 0xFFFFFFFFu
 #define WIT_NONE 32u            // a list entry with an empty mask (first bit 1, last bit 0 of word 0): "no witness"
 #define ENT_WORD(e) ((e) >> 12)
-#define ENT_PASS(e) (((e) >> 10) & 3u)
 
 // Launch-constant parameters (passed by value as a kernel argument).
 struct KParams {
@@ -357,13 +356,12 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
 //            swit[] = a "witness": the list entry that was seen active last (or WIT_NONE).  While the
 //            witness is still active the sBlock is known to be active after one bitmap read.
 //   arena[]  chunk runs of all cached sBlocks, bump-allocated, cut at bitmap word boundaries:
-//            one 32-bit entry  word << 12 | pass << 10 | first bit << 5 | last bit  per range of
-//            consecutive chunks inside one bitmap word.  Testing, setting or clearing an sBlock is one
-//            pass over its entries, one lane per entry.  Entries with the same pass number lie in
-//            different words, so the lanes can update the bitmap with plain read-modify-write (LDS
-//            atomics turned out several times slower); nearly all entries have pass 0, a second and
-//            third range of the same word get pass 1 and 2, any further ones pass 3 (atomic update).
-//   tmp[]    scratch bitmap of the same size as bmp[], zero between uses: a new list is OR-ed
+//            one 32-bit entry  word << 12 | first bit << 5 | last bit  per range of consecutive
+//            chunks inside one bitmap word (bits 10-11 number the ranges of one word; unused).
+//            Testing, setting or clearing an sBlock is one step over its entries, one lane per
+//            entry: the test reads the words, set and clear are LDS atomics without a result, so
+//            several ranges of one word need no ordering and a FREE waits for nothing but its list.
+//   tmp[]    scratch bitmap of the same size as bmp[] (+ 64 spare words), zero between uses: a new list is OR-ed
 //            together here and read back word by word, which merges touching runs.
 //            Compacted through a global-memory buffer when full.
 //   pp, sp   first level of the rank searches in pool[] and skey[], held in registers.
@@ -379,6 +377,7 @@ struct VmsT {
     u64 *skey;
     meta_t *smeta;
     u32 *sstamp, *swit, *tmp;
+    u32 *idle;                  // 64 spare words behind tmp[]: targets of lanes that have nothing to update
     u32 *arena, *bounce;
     u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
     u32 e_skip;                 // a list entry with an empty mask on the spare word behind the bitmap
@@ -445,49 +444,28 @@ DI void bmp_fill(u32 *bmp, u32 spare, u32 start, u32 len, bool set)
     wave_sync();
 }
 
-// One pass over one tile of list entries (lane k holds entry e if live): the entries of pass p
-// update their bitmap words, all different, with plain read-modify-write; pass 3 uses atomics.
-DI void entries_pass(u32 *bmp, u32 e, bool live, u32 p, bool set)
-{
-    if (live && ENT_PASS(e) == p) {
-        const u32 m = emask(e);
-        if (p == 3) {
-            if (set) atomicOr(&bmp[ENT_WORD(e)], m);
-            else atomicAnd(&bmp[ENT_WORD(e)], ~m);
-        } else {
-            bmp[ENT_WORD(e)] = set ? (bmp[ENT_WORD(e)] | m) : (bmp[ENT_WORD(e)] & ~m);
-        }
-    }
-    wave_sync();
-}
-
-// passes 1 to 3 of one tile of entries: rare, and the only part with lanes switched off, so it
-// is kept out of line (the callers stay free of divergent branches)
-typedef __attribute__((address_space(3))) u32 lds_u32;
-__device__ __attribute__((noinline)) void entries_later(lds_u32 *bmp, u32 e, u32 live, u32 set)
-{
-    set = uni(set);
-    for (u32 p = 1; p < 4; p++) entries_pass((u32 *)bmp, e, live != 0, p, set != 0);
-}
-
-// all entries of one sBlock, one lane per entry.  first_done: pass 0 of the first 64 entries has
-// been applied by the caller.  Lanes without an entry of pass 0 rewrite the spare word.
+// One tile of list entries, one lane per entry (e, if live): their bits are set or cleared with LDS
+// atomics that return nothing, so entries that share a bitmap word need no ordering and the wave
+// does not wait for the result.  Lanes without an entry OR a zero into a spare word of their own.
 template <bool BIG>
-DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set, bool first_done = false)
+DI void entries_apply(const VmsT<BIG> &V, u32 e, bool live, bool set)
+{
+    u32 *t = live ? &V.bmp[ENT_WORD(e)] : &V.idle[lane_id()];
+    const u32 m = live ? emask(e) : 0u;
+    if (set) atomicOr(t, m);
+    else atomicAnd(t, ~m);
+}
+
+// all entries of one sBlock
+template <bool BIG>
+DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
 {
     for (u32 rb = 0; rb < cnt; rb += 64) {
         const u32 r = rb + lane_id();
-        const bool live = r < cnt;
-        const u32 e = V.arena[off + (live ? r : 0u)];
-        const u64 later = ballot(live && ENT_PASS(e) != 0);
-        if (!(first_done && rb == 0)) {
-            const u32 e0 = live && ENT_PASS(e) == 0 ? e : V.e_skip;
-            const u32 word = V.bmp[ENT_WORD(e0)];
-            V.bmp[ENT_WORD(e0)] = set ? (word | emask(e0)) : (word & ~emask(e0));
-            wave_sync();
-        }
-        if (later) entries_later((lds_u32 *)V.bmp, e, live ? 1u : 0u, set ? 1u : 0u);
+        const u32 e = V.arena[off + (r < cnt ? r : 0u)];
+        entries_apply(V, e, r < cnt, set);
     }
+    wave_sync();
 }
 
 // A new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing;
@@ -501,7 +479,7 @@ DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
         // lanes with nothing left OR a zero into a word of their own
         const bool in = len && w0 + q <= w1;
         const u32 mw = pin(word_mask(w0 + q, start, end));
-        atomicOr(&V.tmp[in ? w0 + q : ENT_WORD(V.e_skip) + lane_id()], in ? mw : 0u);   // 64 spare words follow tmp[]
+        atomicOr(in ? &V.tmp[w0 + q] : &V.idle[lane_id()], in ? mw : 0u);
     }
     wmin = min(wmin, w0);
     wmax = max(wmax, w1);
@@ -775,12 +753,11 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
 // candidate reads its witness: a candidate whose witness is still active is out after two LDS
 // round trips for the whole tile.  The others are tested in pool order with all lanes over the
 // entries of one list; the first inactive one is handed out (ref = creation number, list = where
-// its entries are).
+// its entries are).  This is the general route, from the tile that starts at `base`.
 template <bool BIG>
-DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
+DI bool s1_sblock_from(VmsT<BIG> &V, u32 bsize, u32 base, u32 &ref, u32 &list)
 {
     const u32 lane = lane_id();
-    u32 base = rank_fast<BIG>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
     for (;;) {
         // skey[] is followed by zero keys and swit[] by harmless entries: no index is clamped
         const u32 i = base + lane;
@@ -817,10 +794,7 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
                 }
             }
             if (!bm) {
-                // inactive: hand it out.  The words of the entries were just read; if all are of
-                // pass 0 they are all different (the idle lanes rewrite the spare word)
-                if (!ballot(ENT_PASS(e) != 0)) V.bmp[ENT_WORD(e)] = word | emask(e);
-                else bmp_fill_entries(V, off, cnt, true);
+                entries_apply(V, e, lane < cnt, true);      // inactive: hand it out
                 st_one(V.sstamp, base + l, ++V.clock);
                 ref = ~from_lane((u32)key, l);
                 list = (u32)m;
@@ -834,12 +808,64 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
     }
 }
 
-// ---- S1, primitive blocks: the first inactive pBlock of exactly bsize chunks in pool order
+// The usual route costs four dependent LDS round trips: the block of keys that the rank search
+// reads (first level in registers) is taken as the first tile of candidates right away, together
+// with their witnesses and list places; then the witnesses' bitmap words; then the list of the
+// first candidate not ruled out; then the bitmap words of its entries.  Anything unusual (a long
+// list, a candidate that turns out active, a run of equal sizes that
+// leaves the tile) goes the general route.
+template <bool BIG>
+DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
+{
+    const u32 lane = lane_id();
+    const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
+    if (V.sp.stride >= 64) return s1_sblock_from(V, bsize, rank_fast<BIG>(V.sp, V.skey, V.ns, q), ref, list);
+    // keys greater than q end at most `stride` < 64 places into the block: the first sBlock of bsize
+    // chunks, if there is one, lies inside the tile
+    const u32 c = popc64(ballot(V.sp.v > q));
+    const u32 b0 = (c ? c - 1 : 0u) * V.sp.stride;
+    const u32 i = b0 + lane;
+    const u64 key = V.skey[i];
+    const u32 wit = V.swit[i];
+    const auto meta = V.smeta[i];
+    const u64 vm = ballot((u32)(key >> 32) == bsize);
+    if (!vm) return false;
+    const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
+    const u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
+    if (!unknown) {
+        if (~vm >> 63) return false;            // the run of equal sizes ended inside the tile: all known active
+        return s1_sblock_from(V, bsize, b0 + 64, ref, list);
+    }
+    const u32 l = first_lane(unknown);
+    const auto m = from_lane_any(meta, l);
+    const u32 off = V.off(m), cnt = V.cnt(m);
+    const u32 e0 = pin(V.arena[off + lane]);
+    const u32 e = lane < cnt ? e0 : V.e_skip;
+    const u32 word = pin(V.bmp[ENT_WORD(e)]);
+    if (cnt <= 64 && !ballot((word & emask(e)) != 0)) {
+        entries_apply(V, e, lane < cnt, true);
+        st_one(V.sstamp, b0 + l, ++V.clock);
+        ref = ~from_lane((u32)key, l);
+        list = (u32)m;
+        return true;
+    }
+    return s1_sblock_from(V, bsize, b0 + l, ref, list);
+}
+
+// ---- S1, primitive blocks: the first inactive pBlock of exactly bsize chunks in pool order.  As
+// above, the block of the rank search doubles as the first tile of candidates.
 template <bool BIG>
 DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
 {
     const u32 lane = lane_id();
-    u32 base = rank_fast<BIG>(V.pp, V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu);
+    const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
+    u32 base;
+    if (V.pp.stride >= 64) {
+        base = rank_fast<BIG>(V.pp, V.pool, V.np, q);
+    } else {
+        const u32 c = popc64(ballot(V.pp.v > q));
+        base = (c ? c - 1 : 0u) * V.pp.stride;  // the first pBlock of bsize chunks lies inside this tile
+    }
     for (;;) {
         const u32 i = base + lane;
         const u64 key = V.pool[i];                  // zero keys follow the pool
@@ -853,7 +879,7 @@ DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
             start = from_lane(st, first_lane(m));
             return true;
         }
-        if (~vm) return false;
+        if (~vm >> 63) return false;                // the run ended inside the tile
         base += 64;
     }
 }
@@ -1094,6 +1120,7 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.sstamp = (u32 *)(lds + P.off_sstamp);
     V.swit = (u32 *)(lds + P.off_swit);
     V.tmp = (u32 *)(lds + P.off_tmp);
+    V.idle = V.tmp + (P.cap_chunks + 31) / 32;
     V.e_skip = (((P.cap_chunks + 31) / 32) << 12) | WIT_NONE;
     u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs + 64;
     V.bounce = BIG && swapped ? hi : lo;
@@ -1349,15 +1376,9 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 if (kind == KIND_SBLOCK) {
                     if (USE_LIST) {
                         const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
-                        const u32 e0 = pin(V.arena[off + lane]);
-                        const u32 e = lane < cnt ? e0 : V.e_skip;
-                        if (cnt <= 64 && !ballot(ENT_PASS(e) != 0)) {
-                            // all entries of pass 0: all different words (idle lanes rewrite the spare word)
-                            const u32 word = pin(V.bmp[ENT_WORD(e)]);
-                            V.bmp[ENT_WORD(e)] = word & ~emask(e);
-                        } else {
-                            bmp_fill_entries(V, off, cnt, false);
-                        }
+                        // one list read, then the entries' bits cleared without waiting for anything
+                        if (cnt <= 64) entries_apply(V, V.arena[off + lane], lane < cnt, false);
+                        else bmp_fill_entries(V, off, cnt, false);
                     } else {
                         vms_free_by_key(V, a, b >> 2);
                     }
