@@ -342,6 +342,176 @@ DI void sp_free(SplitPoolD &sp, u32 addr, u32 size, u32 flags, bool *ml, bool *m
     wave_sync();
 }
 
+// The two holders of a splitting pool behind one interface: the LDS array above, and, for pools of
+// at most 64 * TILES inactive blocks, registers.
+struct SplitLds {
+    SplitPoolD sp;
+    DI void init(char *lds, const KParams &P)
+    {
+        sp.fl = (u64 *)(lds + P.off_fl);
+        sp.n = 0;
+        sp.cap = P.cap_free;
+        sp.reserved = 0;
+        for (u32 i = lane_id(); i < P.cap_free + 128; i += 64) sp.fl[i] = 0;    // zero keys behind the live ones
+        wave_sync();
+    }
+    DI u32 reserved() const { return sp.reserved; }
+    template <class AcctT>
+    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r) { sp_alloc(sp, size, seg, may_grow, A, ev, r); }
+    template <class AcctT>
+    DI void release(u32 addr, u32 size, u32 flags, bool *ml, bool *mr, AcctT &A, u32 ev) { sp_free(sp, addr, size, flags, ml, mr, A, ev); }
+};
+
+// The inactive blocks in registers: key t * 64 + l of the array is k[t] of lane l, 0 = empty place.
+// The order of the array means nothing (best fit and the neighbour searches look at every key), so a
+// block that leaves just zeroes its place and a new one takes the first empty place.  No LDS access
+// at all: a request is compares, one or two wave-wide minima and a few lane selects.
+template <u32 TILES>
+struct SplitRegs {
+    u64 k[TILES];
+    u32 n, cap, res;
+    DI void init(char *, const KParams &P)
+    {
+#pragma unroll
+        for (u32 t = 0; t < TILES; t++) k[t] = 0;
+        n = 0;
+        cap = P.cap_free;
+        res = 0;
+    }
+    DI u32 reserved() const { return res; }
+    DI void put(u32 tv, u32 l, u64 key)         // place tv (its value in lane l) of lane l := key
+    {
+        const bool mine = lane_id() == l;
+#pragma unroll
+        for (u32 q = 0; q < TILES; q++) k[q] = (mine && tv == q) ? key : k[q];
+    }
+    DI void insert(u64 key)                     // into an empty place (n < cap <= 64 * TILES: there is one)
+    {
+        bool any = false;
+#pragma unroll
+        for (u32 q = 0; q < TILES; q++) any = any || k[q] == 0;
+        bool todo = lane_id() == first_lane(ballot(any));       // the first lane with room, its first empty place
+#pragma unroll
+        for (u32 q = 0; q < TILES; q++) {
+            const bool here = todo && k[q] == 0;
+            k[q] = here ? key : k[q];
+            todo = todo && !here;
+        }
+        n++;
+    }
+    template <class AcctT>
+    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r)
+    {
+        r.split = false;
+        // step 1: best fit = smallest key not below (size, address 0); an empty place never fits
+        u64 best = ~0ull;
+        u32 bt = 0;
+#pragma unroll
+        for (u32 t = 0; t < TILES; t++) {
+            const bool ok = (u32)(k[t] >> 32) >= size && k[t] < best;
+            best = ok ? k[t] : best;
+            bt = ok ? t : bt;
+        }
+        const u32 hi = (u32)(best >> 32);
+        const u32 mhi = wave_min_u32(hi);
+        u32 bsize;
+        if (mhi != NONE32) {
+            const u64 m = ballot(hi == mhi);
+            u32 owner = first_lane(m);
+            if (m & (m - 1)) {                  // several blocks of that size: lowest address
+                const u32 lo = hi == mhi ? (u32)best : NONE32;
+                const u32 mlo = wave_min_u32(lo);
+                owner = first_lane(ballot(lo == mlo));
+            }
+            const u32 blo = from_lane((u32)best, owner);
+            bsize = mhi;
+            r.addr = blo >> 2;
+            r.flags = blo & 3;
+            r.code = C_EXACT;
+            put(bt, owner, 0);
+            n--;
+        } else {
+            if (!may_grow) {
+                r.code = C_OOM;
+                r.addr = r.flags = 0;
+                return;
+            }
+            r.addr = res;                       // "native allocation": a fresh segment
+            res += seg;
+            bsize = seg;
+            r.flags = 3;
+            r.code = C_GROW;
+        }
+        // step 2: cut off what is not needed; it stays cached as the right neighbour
+        if (bsize > size) {
+            if (n == cap) {
+                A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
+                return;
+            }
+            insert(((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1));
+            A.peak(SC_HW_FREE, n);
+            r.flags &= 2;
+            r.split = true;
+            if (r.code == C_EXACT) r.code = C_SPLIT;
+            A.add(SC_N_SPLIT, 1);
+        }
+    }
+    // steps 3 and 4: the block becomes inactive and absorbs inactive neighbours of its segment
+    template <class AcctT>
+    DI void release(u32 addr, u32 size, u32 flags, bool *ml, bool *mr, AcctT &A, u32 ev)
+    {
+        const bool can_l = !(flags & 2), can_r = !(flags & 1);
+        const u32 end = addr + size;
+        // at most one block ends where this one starts and at most one starts where it ends: every
+        // lane folds its places into one candidate per side, two ballots decide
+        u64 lk = 0, rk = 0;
+        u32 ltv = 0, rtv = 0;
+#pragma unroll
+        for (u32 t = 0; t < TILES; t++) {
+            // an empty place matches nothing: no block ends at 0 that could merge, none starts at an end
+            const u32 ka = (u32)k[t] >> 2, ks = (u32)(k[t] >> 32);
+            const bool isl = ka + ks == addr, isr = ka == end;
+            lk = isl ? k[t] : lk;
+            ltv = isl ? t : ltv;
+            rk = isr ? k[t] : rk;
+            rtv = isr ? t : rtv;
+        }
+        const u64 mL = can_l ? ballot(lk != 0) : 0, mR = can_r ? ballot(rk != 0) : 0;
+        const u32 ll = first_lane(mL | (1ull << 63)), rl = first_lane(mR | (1ull << 63));
+        const u32 lt = mL ? 0u : NONE32, rt = mR ? 0u : NONE32;
+        const u64 lkey = from_lane64(lk, ll), rkey = from_lane64(rk, rl);
+        *ml = lt != NONE32;
+        *mr = rt != NONE32;
+        if (*mr) {
+            size += (u32)(rkey >> 32);
+            flags = (flags & 2) | ((u32)rkey & 1);
+        }
+        if (*ml) {
+            addr = (u32)lkey >> 2;
+            size += (u32)(lkey >> 32);
+            flags = ((u32)lkey & 2) | (flags & 1);
+        }
+        A.add(SC_N_MERGE, (*ml ? 1u : 0u) + (*mr ? 1u : 0u));
+        const u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
+        if (*ml) {
+            put(ltv, ll, key);                  // the merged block takes the left neighbour's place
+            if (*mr) {
+                put(rtv, rl, 0);
+                n--;
+            }
+        } else if (*mr) {
+            put(rtv, rl, key);
+        } else {
+            if (n == cap) {
+                A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
+                return;
+            }
+            insert(key);
+            A.peak(SC_HW_FREE, n);
+        }
+    }
+};
+
 // ---------------------------------------------------------------------------
 // Virtual memory pool (Sec. 3.2) in LDS.
 //   pool[]   every pBlock (active or not) as key  size << 32 | ~first_chunk, sorted descending:
@@ -1550,7 +1720,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
 // Replay under the splitting policy (Sec. 2.2), one wavefront per trace.  Both of its paths are
 // hot, so everything is inline and its few scalars stay in registers.
 // ---------------------------------------------------------------------------
-template <bool SLOT_REGS>
+template <bool SLOT_REGS, u32 FL_TILES>
 __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *__restrict__ events,
                                                           const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
                                                           vms_trace_stats *__restrict__ stats)
@@ -1561,13 +1731,9 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
-    SplitPoolD sp;
-    sp.fl = (u64 *)(lds + P.off_fl);
-    sp.n = 0;
-    sp.cap = P.cap_free;
-    sp.reserved = 0;
-    for (u32 i = lane; i < P.cap_free + 128; i += 64) sp.fl[i] = 0;    // zero keys behind the live ones
-    wave_sync();
+    // FL_TILES: the inactive blocks live in registers (pools of at most 64 * FL_TILES blocks), else in LDS
+    typename std::conditional<FL_TILES == 0, SplitLds, SplitRegs<(FL_TILES ? FL_TILES : 1u)>>::type sp;
+    sp.init(lds, P);
 
     AcctRegs A;
     A.init();
@@ -1607,7 +1773,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                     const u32 a = S.get_a(slot);
                     S.set_req(slot, (u32)SLOT_UNBOUND);
                     bool ml, mr;
-                    sp_free(sp, a >> 2, req, a & 3, &ml, &mr, A, base + j);
+                    sp.release(a >> 2, req, a & 3, &ml, &mr, A, base + j);
                     requested -= req;
                     dlo = C_FREE | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
                     dhi = a >> 2;
@@ -1617,7 +1783,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                 if (size == 0 || req != SLOT_UNBOUND) break;
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
                 SplitRes r;
-                sp_alloc(sp, size, seg, sp.reserved + seg <= P.capacity_units, A, base + j, r);
+                sp.alloc(size, seg, sp.reserved() + seg <= P.capacity_units, A, base + j, r);
                 if (A.stop) break;
                 if (r.code == C_OOM) {
                     S.set_req(slot, (u32)SLOT_OOM);
@@ -1642,7 +1808,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
             v_dlo = mine ? dlo : v_dlo;
             v_dhi = mine ? dhi : v_dhi;
             v_act = mine ? requested : v_act;
-            v_res = mine ? sp.reserved : v_res;
+            v_res = mine ? sp.reserved() : v_res;
         }
         tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
         if (A.stop) break;
@@ -1655,7 +1821,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
         vms_trace_stats &s = stats[trace];
 #pragma unroll
         for (u32 c = 0; c < 8; c++) s.n_code[c] = n_code[c];
-        const u64 reserved = sp.reserved;
+        const u64 reserved = sp.reserved();
         s.peak_requested = (u64)peak_requested * 512;
         s.peak_active = (u64)peak_requested * 512;
         s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value

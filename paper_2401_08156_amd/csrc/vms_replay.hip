@@ -25,6 +25,7 @@ struct vms_replay {
     KParams kp[2];              // [0] splitting kernel, [1] stitching kernel
     bool big;                   // sBlock chunk runs in global memory (see VmsT)
     bool slot_regs;             // slot table in registers (see SlotsT)
+    bool fl_regs;               // splitting policy: inactive blocks in registers (see SplitRegs)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
     KParams *d_kp;              // kp[] again, in device memory (the stitching kernel copies it to LDS)
@@ -68,7 +69,8 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         k.off_slot_a = take(c.max_slots * 4);
         k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
     }
-    k.off_fl = take((c.max_free_blocks + 128) * 8);       // 128 spare places: scans read whole tiles
+    // the splitting policy keeps small pools in registers: no LDS array then
+    k.off_fl = (!policy && c.max_free_blocks <= 192) ? 0 : take((c.max_free_blocks + 128) * 8);   // 128 spare places: scans read whole tiles
     if (policy) {
         // 64 spare places behind each searched array: reads there need no bounds check
         k.off_pool = take((c.max_pblocks + 64) * 8);
@@ -94,7 +96,12 @@ vms_fn pick_vms(bool big, bool slot_regs)
     if (big) return slot_regs ? replay_vms_kernel<true, true> : replay_vms_kernel<true, false>;
     return slot_regs ? replay_vms_kernel<false, true> : replay_vms_kernel<false, false>;
 }
-split_fn pick_split(bool slot_regs) { return slot_regs ? replay_split_kernel<true> : replay_split_kernel<false>; }
+// fl_regs: the splitting pool's inactive blocks fit three registers per lane (at most 192 blocks)
+split_fn pick_split(bool slot_regs, bool fl_regs)
+{
+    if (fl_regs) return slot_regs ? replay_split_kernel<true, 3> : replay_split_kernel<false, 3>;
+    return slot_regs ? replay_split_kernel<true, 0> : replay_split_kernel<false, 0>;
+}
 
 }  // namespace
 
@@ -147,6 +154,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     // the one whose rank searches cope with pools beyond 4096 blocks
     h->big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
     h->slot_regs = c.max_slots <= 64;
+    h->fl_regs = c.max_free_blocks <= 192;
     uint32_t shift = 0;
     while ((UNIT << shift) < c.chunk_bytes) shift++;
     const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)
@@ -191,7 +199,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)pick_split(h->slot_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)pick_split(h->slot_regs, h->fl_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)pick_vms(h->big, h->slot_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -237,7 +245,7 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL(pick_split(h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0],
+        hipLaunchKernelGGL(pick_split(h->slot_regs, h->fl_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0],
                            d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }
