@@ -13,7 +13,8 @@ HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/
 # they are instead of rebuilding them around exec-mask style flow blocks: fewer branches per event.
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC", "-Wall",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-mllvm", "-structurizecfg-skip-uniform-regions=1"]
+               "-mllvm", "-structurizecfg-skip-uniform-regions=1",
+               "-Wno-inline-asm"]       # write_lane() names m0, which the compiler reserves but does not use here
 
 
 def _stale():

@@ -115,10 +115,10 @@ struct SlotsT<true> {
     DI u32 get_a(u32 s) const { return from_lane(a, s); }
     DI u32 get_b(u32 s) const { return from_lane(b, s); }
     DI u32 get_c(u32 s) const { return from_lane(c, s); }
-    DI void set_req(u32 s, u32 v) { req = lane_id() == s ? v : req; }
-    DI void set_a(u32 s, u32 v) { a = lane_id() == s ? v : a; }
-    DI void set_b(u32 s, u32 v) { b = lane_id() == s ? v : b; }
-    DI void set_c(u32 s, u32 v) { c = lane_id() == s ? v : c; }
+    DI void set_req(u32 s, u32 v) { req = write_lane(req, v, s); }
+    DI void set_a(u32 s, u32 v) { a = write_lane(a, v, s); }
+    DI void set_b(u32 s, u32 v) { b = write_lane(b, v, s); }
+    DI void set_c(u32 s, u32 v) { c = write_lane(c, v, s); }
     // the arena was compacted: the list that was at `from` is now at `to`
     // the lists of the sBlocks have moved: look each held sBlock up by its key (creation number a,
     // b >> 2 chunks) in skey[0..ns) (descending) and take its new place from smeta[]
@@ -1518,11 +1518,8 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
         // every path of an event ends by parking its results in lane j and going on to the next event
 #define EMIT(DLO, DHI)                                                     \
     {                                                                      \
-        const bool mine = lane == j;                                       \
-        v_dlo = mine ? (DLO) : v_dlo;                                      \
-        v_dhi = mine ? (DHI) : v_dhi;                                      \
-        v_act = mine ? active : v_act;                                     \
-        v_res = mine ? sp_reserved + (V.n_chunks << P.chunk_shift) : v_res; \
+        write_lane4(v_dlo, v_dhi, v_act, v_res, (DLO), (DHI), active,      \
+                    sp_reserved + (V.n_chunks << P.chunk_shift), j);       \
         wave_sync();                                                       \
         continue;                                                          \
     }
@@ -1804,11 +1801,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                 done = j;
                 break;
             }
-            const bool mine = lane == j;
-            v_dlo = mine ? dlo : v_dlo;
-            v_dhi = mine ? dhi : v_dhi;
-            v_act = mine ? requested : v_act;
-            v_res = mine ? sp.reserved() : v_res;
+            write_lane4(v_dlo, v_dhi, v_act, v_res, dlo, dhi, requested, sp.reserved(), j);
         }
         tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
         if (A.stop) break;
