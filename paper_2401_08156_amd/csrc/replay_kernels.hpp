@@ -875,9 +875,12 @@ DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
 }
 
 // StitchFree (Sec. 3.3.2, Sec. 4.2.3): while more sBlocks than the threshold are cached,
-// release the least recently used one that is inactive.  The lanes first rule out, side by
-// side, every sBlock whose witness is still active; of the rest the least recently used one is
-// tested with all lanes on its list, and so on until one is found inactive.
+// release the least recently used one that is inactive.  One scan rules out, side by side, every
+// sBlock whose witness is still active (four tiles at a time: all stamps and witnesses are loaded,
+// then all witness words, two LDS round trips per 256 sBlocks) and leaves in every lane the two
+// least recently used of the sBlocks it saw.  The oldest of all is tested with all lanes on its
+// list; if it is active after all, its lane falls back on its second and the search goes on
+// without a new scan (a lane that runs out of its two forces one).
 template <bool BIG, class AcctT>
 DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
 {
@@ -885,27 +888,56 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
     bool any = false;
     while (V.ns > P.spool_threshold) {
         u32 victim = NONE32;
+        bool rescan = true;
+        u32 b1 = NONE32, i1 = 0, b2 = NONE32, i2 = 0;
+        bool spent = false;                     // this lane has given up its best once since the scan
         for (;;) {
-            u32 best = NONE32, besti = 0;
-            for (u32 base = 0; base < V.ns; base += 64) {
-                const u32 i = base + lane, ic = i < V.ns ? i : 0u;
-                const u32 st = V.sstamp[ic], wit = V.swit[ic];
-                const u32 ww = pin(V.bmp[ENT_WORD(wit)]);
-                const bool better = (i < V.ns) & ((ww & emask(wit)) == 0) & (st < best);
-                best = better ? st : best;
-                besti = better ? i : besti;
+            if (rescan) {
+                b1 = b2 = NONE32;
+                i1 = i2 = 0;
+                spent = false;
+                for (u32 g = 0; g < V.ns; g += 256) {
+                    u32 st[4], wit[4], ww[4];
+#pragma unroll
+                    for (u32 t = 0; t < 4; t++) {
+                        const u32 i = g + t * 64 + lane, ic = i < V.ns ? i : 0u;
+                        st[t] = V.sstamp[ic];
+                        wit[t] = V.swit[ic];
+                    }
+#pragma unroll
+                    for (u32 t = 0; t < 4; t++) ww[t] = pin(V.bmp[ENT_WORD(wit[t])]);
+#pragma unroll
+                    for (u32 t = 0; t < 4; t++) {
+                        const u32 i = g + t * 64 + lane;
+                        const bool ok = (i < V.ns) & ((ww[t] & emask(wit[t])) == 0);
+                        const u32 sv = ok ? st[t] : NONE32;
+                        const bool lt1 = sv < b1, lt2 = sv < b2;
+                        b2 = lt1 ? b1 : (lt2 ? sv : b2);
+                        i2 = lt1 ? i1 : (lt2 ? i : i2);
+                        b1 = lt1 ? sv : b1;
+                        i1 = lt1 ? i : i1;
+                    }
+                }
+                rescan = false;
             }
-            const u32 m = wave_min_u32(best);
+            const u32 m = wave_min_u32(b1);
             if (m == NONE32) break;             // everything cached is in use: the threshold stays exceeded
-            const u32 c = from_lane(besti, first_lane(ballot(best == m)));
+            const u32 owner = first_lane(ballot(b1 == m));
+            const u32 c = from_lane(i1, owner);
             const auto meta = ld_uni(V.smeta, c);
             u32 witness;
             if (!list_busy(V, V.off(meta), V.cnt(meta), &witness)) {
                 victim = c;
                 break;
             }
-            st_one(V.swit, c, witness);         // active after all: remember where, look again
+            st_one(V.swit, c, witness);         // active after all: remember where, look further
             wave_sync();
+            rescan = from_lane(spent ? 1u : 0u, owner) != 0;
+            const bool mine = lane == owner;
+            b1 = mine ? b2 : b1;
+            i1 = mine ? i2 : i1;
+            b2 = mine ? NONE32 : b2;
+            spent = spent || mine;
         }
         if (victim == NONE32) break;
         spool_remove(V, victim);
