@@ -44,13 +44,12 @@ struct KParams {
 };
 
 // Scalars of one trace that live in LDS (stitching kernel): index k is the u32 at lds[4 k].  The
-// first SC_STATE_COUNT are loaded and stored as a set around the cold functions; the counters
-// after them are only ever updated in place.
+// first SC_STATE_COUNT are state that only the rare paths need (loaded and stored around them); the
+// counters after them are only ever updated in place.
 enum {
-    SC_NP, SC_NS, SC_NCHUNKS, SC_TOP, SC_LIVE, SC_NEXT_SID, SC_CLOCK, SC_SP_N, SC_SP_RESERVED,
-    SC_R_DEC, SC_R_REF, SC_R_KIND_HELD, SC_R_LIST,      // result of the last cold call
-    SC_COMPACTED,                                       // the arena was compacted since the flag was cleared
-    SC_SWAPPED,                                         // BIG: arena and compaction buffer have changed places
+    SC_TOP, SC_LIVE, SC_NEXT_SID,                       // arena top, live list entries, next creation number
+    SC_SP_N, SC_SP_RESERVED,                            // the splitting pool for requests below one chunk
+    SC_R_DEC, SC_R_REF,                                 // result of the last call into that pool
     SC_STATE_COUNT,
     SC_N_SPLIT = SC_STATE_COUNT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
     SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
@@ -1269,11 +1268,11 @@ DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
 
 // ---------------------------------------------------------------------------
 // Hot and cold halves.  The replay loop keeps only what the two frequent paths need in registers
-// (exact hit on a cached block, free).  Everything else is "cold": it runs in separate,
-// non-inlined functions whose scalar state lives in a small LDS block between calls, so that it
-// costs the replay loop neither registers nor instructions.
-//   lds[0 .. 256)     scalars of the trace (SC_* below), one u32 each
-//   lds[256 .. 512)   copy of the launch parameters, for the cold functions
+// (exact hit on a cached block, free).  The states S2 to S5 are inlined behind an unlikely branch
+// and keep the three scalars only they need in LDS; the splitting pool for requests below one
+// chunk runs in separate, non-inlined functions whose state lives in LDS between calls.
+//   lds[0 .. 256)     scalars of the trace (SC_* above), one u32 each
+//   lds[256 .. 512)   copy of the launch parameters, for the non-inlined functions
 // ---------------------------------------------------------------------------
 #define LDS_SCALARS 0u
 #define LDS_PARAMS 256u
@@ -1329,52 +1328,32 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
 }
 
-// Cold call: a request for bsize chunks that no cached block fits exactly (states S2 to S5).
-// The result is left in the SC_R_* scalars.
+// A request for bsize chunks that no cached block fits exactly (states S2 to S5): inlined into the
+// replay loop (a call would cost more in saved registers than the few per cent of the requests
+// that come here can repay), working on the loop's own pool state; the three scalars that only
+// this path needs (arena top, live entries, next creation number) wait in LDS in between.
+// Returns false if an engine table overflowed (the trace ends).
 template <bool BIG>
-__device__ __attribute__((noinline)) void vms_alloc_cold(lds_char *ldsp, char *ws_slice, u32 bsize, u32 reserved_units,
-                                                         u32 clock, u32 ev)
+DI bool vms_alloc_cold(char *lds, VmsT<BIG> &V, const KParams &P, u32 bsize, u32 reserved_units, u32 ev, VmsRes &R,
+                       bool &compacted)
 {
-    // arguments arrive in vector registers: tell the compiler that they are the same in every lane
-    bsize = uni(bsize);
-    reserved_units = uni(reserved_units);
-    clock = uni(clock);
-    ev = uni(ev);
-    char *lds = (char *)ldsp;
-    KParams P;
-    load_params(P, lds);
+    u32 *sc = (u32 *)(lds + LDS_SCALARS);
     ColdState C;
     C.load(lds);
-    VmsT<BIG> V;
-    vms_bind(V, lds, ws_slice, P, C.get(SC_SWAPPED) != 0);
-    V.np = C.get(SC_NP);
-    V.ns = C.get(SC_NS);
-    V.n_chunks = C.get(SC_NCHUNKS);
     V.top = C.get(SC_TOP);
     V.live_ent = C.get(SC_LIVE);
     V.next_sid = C.get(SC_NEXT_SID);
-    V.clock = clock;
     AcctLds A;
-    A.sc = (u32 *)(lds + LDS_SCALARS);
+    A.sc = sc;
     ColdSlots S;
     S.compacted = false;
-    VmsRes R;
-    u32 *arena_before = V.arena;
     vms_alloc_rest(V, S, bsize, reserved_units, P, A, ev, R);
-    C.set(SC_NP, V.np);
-    C.set(SC_NS, V.ns);
-    C.set(SC_NCHUNKS, V.n_chunks);
-    C.set(SC_TOP, V.top);
-    C.set(SC_LIVE, V.live_ent);
-    C.set(SC_NEXT_SID, V.next_sid);
-    C.set(SC_CLOCK, V.clock);
-    C.set(SC_R_DEC, R.dec_lo);
-    C.set(SC_R_REF, R.ref);
-    C.set(SC_R_KIND_HELD, R.kind | (R.held << 2));
-    C.set(SC_R_LIST, R.list);
-    if (S.compacted) C.set(SC_COMPACTED, 1u);
-    if (BIG && V.arena != arena_before) C.set(SC_SWAPPED, C.get(SC_SWAPPED) ^ 1u);
-    C.store(lds);
+    st_one(sc, (u32)SC_TOP, V.top);
+    st_one(sc, (u32)SC_LIVE, V.live_ent);
+    st_one(sc, (u32)SC_NEXT_SID, V.next_sid);
+    wave_sync();
+    compacted = S.compacted;
+    return ld_uni(sc, (u32)SC_STOP) == 0;
 }
 
 // Cold calls of the stitching policy for requests below one chunk: its private splitting pool.
@@ -1637,37 +1616,28 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
             wave_sync();
             if (size >= P.small_limit_units) {
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
-                vms_alloc_cold<BIG>((lds_char *)lds, ws_slice, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), V.clock,
-                                    base + j);
-                ColdState C;
-                C.load(lds);
-                V.np = C.get(SC_NP);
-                V.ns = C.get(SC_NS);
-                V.n_chunks = C.get(SC_NCHUNKS);
-                V.clock = C.get(SC_CLOCK);
-                if (BIG) vms_bind(V, lds, ws_slice, P, C.get(SC_SWAPPED) != 0);
+                VmsRes R;
+                bool compacted;
+                const bool went = vms_alloc_cold<BIG>(lds, V, P, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), base + j,
+                                                      R, compacted);
                 // the pools may have changed: renew the first search level of both
                 probe_refresh(V.sp, V.skey, V.ns);
                 probe_refresh(V.pp, V.pool, V.np);
-                if (USE_LIST && C.get(SC_COMPACTED)) {
-                    // lists have moved: every slot holding an sBlock looks its list up again
-                    S.relist(V.skey, (const u32 *)V.smeta, V.ns);
-                    st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_COMPACTED, 0u);
-                }
-                if (C.get(SC_STOP)) {                       // an engine table overflowed: the trace ends here
+                // lists have moved: every slot holding an sBlock looks its list up again
+                if (USE_LIST && compacted) S.relist(V.skey, (const u32 *)V.smeta, V.ns);
+                if (!went) {                                // an engine table overflowed: the trace ends here
                     stop = true;
                     done = j;
                     todo = 0;
                     continue;
                 }
-                dlo = C.get(SC_R_DEC);
+                dlo = R.dec_lo;
                 if ((dlo & 15) != C_OOM) {
-                    const u32 kh = C.get(SC_R_KIND_HELD);
-                    dhi = C.get(SC_R_REF);
+                    dhi = R.ref;
                     S.set_a(slot, dhi);
-                    S.set_b(slot, kh);
-                    if (USE_LIST) S.set_c(slot, C.get(SC_R_LIST));
-                    held_units = (kh >> 2) << P.chunk_shift;
+                    S.set_b(slot, R.kind | (R.held << 2));
+                    if (USE_LIST) S.set_c(slot, R.list);
+                    held_units = R.held << P.chunk_shift;
                 }
             } else {
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
