@@ -1755,8 +1755,11 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
         }
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
         u32 done = tile;
+        u32 w_next = from_lane(ev_lo, 0), slot_next = from_lane(ev_hi, 0);     // one event ahead
         for (u32 j = 0; j < tile; j++) {
-            const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
+            const u32 w = w_next, slot = slot_next;
+            w_next = from_lane(ev_lo, (j + 1) & 63);
+            slot_next = from_lane(ev_hi, (j + 1) & 63);
             u32 dlo = C_INVALID, dhi = 0;
             do {
                 if (slot >= P.max_slots) break;
