@@ -378,11 +378,12 @@ struct SplitRegs {
         res = 0;
     }
     DI u32 reserved() const { return res; }
-    DI void put(u32 tv, u32 l, u64 key)         // place tv (its value in lane l) of lane l := key
+    // keys are unique (they contain the address): the place that holds `from` (not 0) takes `to`,
+    // found by comparing every place with it, with no book-keeping of where a key sits
+    DI void swap_key(u64 from, u64 to)
     {
-        const bool mine = lane_id() == l;
 #pragma unroll
-        for (u32 q = 0; q < TILES; q++) k[q] = (mine && tv == q) ? key : k[q];
+        for (u32 q = 0; q < TILES; q++) k[q] = k[q] == from ? to : k[q];
     }
     DI void insert(u64 key)                     // into an empty place (n < cap <= 64 * TILES: there is one)
     {
@@ -404,12 +405,10 @@ struct SplitRegs {
         r.split = false;
         // step 1: best fit = smallest key not below (size, address 0); an empty place never fits
         u64 best = ~0ull;
-        u32 bt = 0;
 #pragma unroll
         for (u32 t = 0; t < TILES; t++) {
             const bool ok = (u32)(k[t] >> 32) >= size && k[t] < best;
             best = ok ? k[t] : best;
-            bt = ok ? t : bt;
         }
         const u32 hi = (u32)(best >> 32);
         const u32 mhi = wave_min_u32(hi);
@@ -423,12 +422,24 @@ struct SplitRegs {
                 owner = first_lane(ballot(lo == mlo));
             }
             const u32 blo = from_lane((u32)best, owner);
-            bsize = mhi;
+            const u64 chosen = ((u64)mhi << 32) | blo;
             r.addr = blo >> 2;
             r.flags = blo & 3;
-            r.code = C_EXACT;
-            put(bt, owner, 0);
-            n--;
+            if (mhi > size) {
+                // step 2: cut off what is not needed; it stays cached as the right neighbour, in the
+                // place the block had
+                swap_key(chosen, ((u64)(mhi - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1));
+                A.peak(SC_HW_FREE, n);
+                r.flags &= 2;
+                r.split = true;
+                r.code = C_SPLIT;
+                A.add(SC_N_SPLIT, 1);
+            } else {
+                swap_key(chosen, 0);
+                n--;
+                r.code = C_EXACT;
+            }
+            return;
         } else {
             if (!may_grow) {
                 r.code = C_OOM;
@@ -441,8 +452,7 @@ struct SplitRegs {
             r.flags = 3;
             r.code = C_GROW;
         }
-        // step 2: cut off what is not needed; it stays cached as the right neighbour
-        if (bsize > size) {
+        if (bsize > size) {                     // the rest of a fresh segment
             if (n == cap) {
                 A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
                 return;
@@ -451,7 +461,6 @@ struct SplitRegs {
             A.peak(SC_HW_FREE, n);
             r.flags &= 2;
             r.split = true;
-            if (r.code == C_EXACT) r.code = C_SPLIT;
             A.add(SC_N_SPLIT, 1);
         }
     }
@@ -464,23 +473,17 @@ struct SplitRegs {
         // at most one block ends where this one starts and at most one starts where it ends: every
         // lane folds its places into one candidate per side, two ballots decide
         u64 lk = 0, rk = 0;
-        u32 ltv = 0, rtv = 0;
 #pragma unroll
         for (u32 t = 0; t < TILES; t++) {
             // an empty place matches nothing: no block ends at 0 that could merge, none starts at an end
             const u32 ka = (u32)k[t] >> 2, ks = (u32)(k[t] >> 32);
-            const bool isl = ka + ks == addr, isr = ka == end;
-            lk = isl ? k[t] : lk;
-            ltv = isl ? t : ltv;
-            rk = isr ? k[t] : rk;
-            rtv = isr ? t : rtv;
+            lk = ka + ks == addr ? k[t] : lk;
+            rk = ka == end ? k[t] : rk;
         }
         const u64 mL = can_l ? ballot(lk != 0) : 0, mR = can_r ? ballot(rk != 0) : 0;
-        const u32 ll = first_lane(mL | (1ull << 63)), rl = first_lane(mR | (1ull << 63));
-        const u32 lt = mL ? 0u : NONE32, rt = mR ? 0u : NONE32;
-        const u64 lkey = from_lane64(lk, ll), rkey = from_lane64(rk, rl);
-        *ml = lt != NONE32;
-        *mr = rt != NONE32;
+        const u64 lkey = from_lane64(lk, first_lane(mL | (1ull << 63))), rkey = from_lane64(rk, first_lane(mR | (1ull << 63)));
+        *ml = mL != 0;
+        *mr = mR != 0;
         if (*mr) {
             size += (u32)(rkey >> 32);
             flags = (flags & 2) | ((u32)rkey & 1);
@@ -493,13 +496,13 @@ struct SplitRegs {
         A.add(SC_N_MERGE, (*ml ? 1u : 0u) + (*mr ? 1u : 0u));
         const u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
         if (*ml) {
-            put(ltv, ll, key);                  // the merged block takes the left neighbour's place
+            swap_key(lkey, key);                // the merged block takes the left neighbour's place
             if (*mr) {
-                put(rtv, rl, 0);
+                swap_key(rkey, 0);
                 n--;
             }
         } else if (*mr) {
-            put(rtv, rl, key);
+            swap_key(rkey, key);
         } else {
             if (n == cap) {
                 A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
