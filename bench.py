@@ -150,7 +150,7 @@ def main():
                    "spool_threshold": int(cfg.spool_threshold), "frag_limit_bytes": int(cfg.frag_limit_bytes),
                    "batches": len(batches), "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
         "kernel_ms": kernel_ms,
-        "roofline": {"bound": "hbm", "kernel": "replay_kernel<%d> (%s policy)" % (1 if dom == "vms" else 0, dom),
+        "roofline": {"bound": "hbm", "kernel": "replay_vms_kernel (stitching policy)" if dom == "vms" else "replay_split_kernel (splitting policy)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": recorded_traffic(args.config) if dom == "vms" and n_traces == base["n_traces"]
                      and n_events == base["n_events"] else None,
