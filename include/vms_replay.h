@@ -242,6 +242,24 @@ typedef struct vms_vmm_latency_report {
  * before returning.  Synchronous; host code only, no kernel is launched.                          */
 int vms_vmm_latency(uint64_t block_bytes, uint64_t chunk_bytes, uint32_t repeats, vms_vmm_latency_report *out);
 
+/* What vms_measure_peaks measured on the current device.                                            */
+typedef struct vms_peaks_report {
+    uint32_t struct_size;        /* sizeof(vms_peaks_report), set by the caller                    */
+    int32_t  hip_error;          /* hipError_t of the first failing HIP call, else 0               */
+    uint32_t compute_units, clock_mhz;
+    uint64_t copy_bytes;         /* bytes read + written by the copy kernel per launch             */
+    double   copy_ms, hbm_copy_gbs;
+    uint64_t lds_bytes;          /* bytes read from LDS by the read loop per launch                */
+    double   lds_ms, lds_read_gbs;
+} vms_peaks_report;
+
+/* Two micro-benchmarks for the proportions of Sec. 5.1-style reports on the device at hand: a
+ * plain 1 GiB device-to-device copy kernel (HBM bandwidth actually reachable, read + write) and a
+ * conflict-free 16-byte-per-lane LDS read loop on every compute unit (LDS bandwidth actually
+ * reachable).  Allocates 2 GiB of device memory for the duration of the call; best of three timed
+ * rounds each.  Synchronous, on the default stream.                                                */
+int vms_measure_peaks(vms_peaks_report *out);
+
 /* In-wavefront primitives self-test (reductions, scans, sorted insert): runs a
  * small kernel on the current device and returns VMS_OK if every lane layout
  * matches its definition.  Diagnostic; not part of a replay.                  */

@@ -61,6 +61,13 @@ class vms_vmm_latency_report(ctypes.Structure):
                 ("set_access_ms", ctypes.c_double), ("unmap_ms", ctypes.c_double), ("release_ms", ctypes.c_double)]
 
 
+class vms_peaks_report(ctypes.Structure):
+    _fields_ = [("struct_size", ctypes.c_uint32), ("hip_error", ctypes.c_int32),
+                ("compute_units", ctypes.c_uint32), ("clock_mhz", ctypes.c_uint32),
+                ("copy_bytes", ctypes.c_uint64), ("copy_ms", ctypes.c_double), ("hbm_copy_gbs", ctypes.c_double),
+                ("lds_bytes", ctypes.c_uint64), ("lds_ms", ctypes.c_double), ("lds_read_gbs", ctypes.c_double)]
+
+
 class vms_live_config(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("spool_threshold", ctypes.c_uint32),
                 ("chunk_bytes", ctypes.c_uint64), ("small_limit_bytes", ctypes.c_uint64),
@@ -95,7 +102,7 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
            "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms",
            "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
-           "vms_demo_run", "vms_vmm_latency",
+           "vms_demo_run", "vms_vmm_latency", "vms_measure_peaks",
            "vms_live_config_default", "vms_live_create", "vms_live_malloc", "vms_live_free", "vms_live_run_trace",
            "vms_live_slot", "vms_live_stats", "vms_live_destroy", "vms_torch_malloc", "vms_torch_free",
            "vms_torch_allocator"]
@@ -143,6 +150,8 @@ def lib():
         L.vms_demo_run.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
         L.vms_vmm_latency.restype = ctypes.c_int
         L.vms_vmm_latency.argtypes = [u64, u64, u32, ctypes.POINTER(vms_vmm_latency_report)]
+        L.vms_measure_peaks.restype = ctypes.c_int
+        L.vms_measure_peaks.argtypes = [ctypes.POINTER(vms_peaks_report)]
         L.vms_live_config_default.restype = None
         L.vms_live_config_default.argtypes = [ctypes.POINTER(vms_live_config)]
         L.vms_live_create.restype = ctypes.c_int
@@ -207,6 +216,14 @@ def vms_vmm_latency(block_bytes, chunk_bytes, repeats=3):
     rep = vms_vmm_latency_report()
     rep.struct_size = ctypes.sizeof(vms_vmm_latency_report)
     rc = lib().vms_vmm_latency(int(block_bytes), int(chunk_bytes), int(repeats), ctypes.byref(rep))
+    return rc, rep
+
+
+def vms_measure_peaks():
+    """HBM copy and LDS read bandwidth reachable on the current device.  Returns (rc, report)."""
+    rep = vms_peaks_report()
+    rep.struct_size = ctypes.sizeof(vms_peaks_report)
+    rc = lib().vms_measure_peaks(ctypes.byref(rep))
     return rc, rep
 
 

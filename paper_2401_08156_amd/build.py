@@ -5,7 +5,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libvmsreplay.so")
-SOURCES = ["vms_replay.hip", "vms_demo.hip", "vms_live.hip"]
+SOURCES = ["vms_replay.hip", "vms_demo.hip", "vms_live.hip", "vms_peaks.hip"]
 HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h", "../../include/vms_live.h"]
 
 # The replay loops branch on wave-uniform conditions only (whatever would switch lanes off is written

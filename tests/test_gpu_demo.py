@@ -75,3 +75,12 @@ def test_vmm_latency_table_small_block():
     # argument errors come back as codes
     rc, rep = binding.vms_vmm_latency(3 * MiB, 2 * MiB, 1)
     assert rc == -1
+
+
+def test_measured_peaks_are_plausible():
+    rc, rep = binding.vms_measure_peaks()
+    assert rc == 0 and rep.hip_error == 0
+    assert rep.compute_units >= 64
+    # a copy kernel reaches a good part of the published 8 TB/s, LDS several times more
+    assert 1000 < rep.hbm_copy_gbs < 8000
+    assert rep.lds_read_gbs > rep.hbm_copy_gbs
