@@ -413,7 +413,7 @@ struct SplitRegs {
         const u32 hi = (u32)(best >> 32);
         const u32 mhi = wave_min_u32(hi);
         u32 bsize;
-        if (mhi != NONE32) {
+        if (LIKELY(mhi != NONE32)) {
             const u64 m = ballot(hi == mhi);
             u32 owner = first_lane(m);
             if (m & (m - 1)) {                  // several blocks of that size: lowest address
@@ -1023,7 +1023,7 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
 {
     const u32 lane = lane_id();
     const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
-    if (V.sp.stride >= 64) return s1_sblock_from(V, bsize, rank_fast<BIG>(V.sp, V.skey, V.ns, q), ref, list);
+    if (UNLIKELY(V.sp.stride >= 64)) return s1_sblock_from(V, bsize, rank_fast<BIG>(V.sp, V.skey, V.ns, q), ref, list);
     // keys greater than q end at most `stride` < 64 places into the block: the first sBlock of bsize
     // chunks, if there is one, lies inside the tile
     const u32 c = popc64(ballot(V.sp.v > q));
@@ -1033,10 +1033,10 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
     const u32 wit = V.swit[i];
     const auto meta = V.smeta[i];
     const u64 vm = ballot((u32)(key >> 32) == bsize);
-    if (!vm) return false;
+    if (UNLIKELY(!vm)) return false;
     const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
     const u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
-    if (!unknown) {
+    if (UNLIKELY(!unknown)) {
         if (~vm >> 63) return false;            // the run of equal sizes ended inside the tile: all known active
         return s1_sblock_from(V, bsize, b0 + 64, ref, list);
     }
@@ -1046,7 +1046,7 @@ DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
     const u32 e0 = pin(V.arena[off + lane]);
     const u32 e = lane < cnt ? e0 : V.e_skip;
     const u32 word = pin(V.bmp[ENT_WORD(e)]);
-    if (cnt <= 64 && !ballot((word & emask(e)) != 0)) {
+    if (LIKELY(cnt <= 64 && !ballot((word & emask(e)) != 0))) {
         entries_apply(V, e, lane < cnt, true);
         st_one(V.sstamp, b0 + l, ++V.clock);
         ref = ~from_lane((u32)key, l);
@@ -1539,11 +1539,11 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
     }
         for (u32 j = 0; j < todo; j++) {
             const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
-            if (slot >= P.max_slots) EMIT((u32)C_INVALID, 0u)
+            if (UNLIKELY(slot >= P.max_slots)) EMIT((u32)C_INVALID, 0u)
             const u32 req = S.get_req(slot);
             if ((int)w < 0) {
                 // ---- FREE.  Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks
-                if (req + 1u <= 1u) {                       // unbound, or bound to a request that failed
+                if (UNLIKELY(req + 1u <= 1u)) {             // unbound, or bound to a request that failed
                     if (req == SLOT_OOM) {
                         S.set_req(slot, (u32)SLOT_UNBOUND);
                         EMIT((u32)C_FREE_NOOP, 0u)
@@ -1554,11 +1554,11 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 const u32 kind = b & 3;
                 S.set_req(slot, (u32)SLOT_UNBOUND);
                 requested -= req;
-                if (kind == KIND_SBLOCK) {
+                if (LIKELY(kind == KIND_SBLOCK)) {
                     if (USE_LIST) {
                         const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
                         // one list read, then the entries' bits cleared without waiting for anything
-                        if (cnt <= 64) entries_apply(V, V.arena[off + lane], lane < cnt, false);
+                        if (LIKELY(cnt <= 64)) entries_apply(V, V.arena[off + lane], lane < cnt, false);
                         else bmp_fill_entries(V, off, cnt, false);
                     } else {
                         vms_free_by_key(V, a, b >> 2);
@@ -1586,11 +1586,11 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
             }
             // ---- ALLOC
             const u32 size = w;
-            if (size == 0 || req != SLOT_UNBOUND) EMIT((u32)C_INVALID, 0u)
+            if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) EMIT((u32)C_INVALID, 0u)
             if (size >= P.small_limit_units) {
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
-                if (s1_sblock(V, bsize, ref, list)) {
+                if (LIKELY(s1_sblock(V, bsize, ref, list))) {
                     S.set_a(slot, ref);
                     S.set_b(slot, KIND_SBLOCK | (bsize << 2));
                     if (USE_LIST) S.set_c(slot, list);
@@ -1765,10 +1765,10 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
             slot_next = from_lane(ev_hi, (j + 1) & 63);
             u32 dlo = C_INVALID, dhi = 0;
             do {
-                if (slot >= P.max_slots) break;
+                if (UNLIKELY(slot >= P.max_slots)) break;
                 const u32 req = S.get_req(slot);
                 if ((int)w < 0) {
-                    if (req + 1u <= 1u) {                   // unbound, or bound to a request that failed
+                    if (UNLIKELY(req + 1u <= 1u)) {         // unbound, or bound to a request that failed
                         if (req == SLOT_OOM) {
                             S.set_req(slot, (u32)SLOT_UNBOUND);
                             dlo = C_FREE_NOOP;
@@ -1785,12 +1785,12 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                     break;
                 }
                 const u32 size = w;
-                if (size == 0 || req != SLOT_UNBOUND) break;
+                if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) break;
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
                 SplitRes r;
                 sp.alloc(size, seg, sp.reserved() + seg <= P.capacity_units, A, base + j, r);
-                if (A.stop) break;
-                if (r.code == C_OOM) {
+                if (UNLIKELY(A.stop)) break;
+                if (UNLIKELY(r.code == C_OOM)) {
                     S.set_req(slot, (u32)SLOT_OOM);
                     if (A.f[SC_FIRST_OOM] == NONE32) A.f[SC_FIRST_OOM] = base + j;
                     dlo = C_OOM;
@@ -1805,7 +1805,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                 peak_requested = max(peak_requested, requested);
             } while (0);
             wave_sync();
-            if (A.stop) {                                   // the free list overflowed: the trace ends here
+            if (UNLIKELY(A.stop)) {                         // the free list overflowed: the trace ends here
                 done = j;
                 break;
             }

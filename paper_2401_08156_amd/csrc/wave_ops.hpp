@@ -301,6 +301,10 @@ DI void write_lane4(u32 &a, u32 &b, u32 &c, u32 &d, u32 va, u32 vb, u32 vc, u32 
         : "m0");
 }
 
+// which way a wave-uniform branch usually goes: the usual way becomes the fall-through
+#define LIKELY(x) __builtin_expect(!!(x), 1)
+#define UNLIKELY(x) __builtin_expect(!!(x), 0)
+
 // keeps a loaded value where it is: the compiler may not sink the load into a later branch
 DI u32 pin(u32 x)
 {
