@@ -849,8 +849,8 @@ DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
 template <bool BIG, class Slots, class AcctT>
 DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, AcctT &A, u32 ev)
 {
-    if (V.top + need > P.cap_runs && V.live_ent < V.top) arena_compact(V, S, P);
-    if (V.top + need > P.cap_runs) {
+    if (UNLIKELY(V.top + need > P.cap_runs && V.live_ent < V.top)) arena_compact(V, S, P);
+    if (UNLIKELY(V.top + need > P.cap_runs)) {
         A.overflow(ev, VMS_ST_OVF_RUNS);
         return false;
     }
@@ -1079,7 +1079,7 @@ DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
         const u32 st = ~(u32)key;
         const u32 word = pin(V.bmp[eq ? st >> 5 : 0u]);
         const u64 m = ballot(eq && !((word >> (st & 31)) & 1u));
-        if (m) {
+        if (LIKELY(m)) {
             start = from_lane(st, first_lane(m));
             return true;
         }
@@ -1124,7 +1124,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             u32 l = first_lane(m), idx = hi - 1 - l;
             u64 pk = from_lane64(key, l);
             u32 psize = (u32)(pk >> 32), pstart = ~(u32)pk;
-            if (psize < P.frag_limit_chunks) {
+            if (UNLIKELY(psize < P.frag_limit_chunks)) {
                 // below the fragmentation limit: not worth cutting, hand it out whole (Sec. 4.2.3)
                 bmp_fill(V.bmp, ENT_WORD(V.e_skip), pstart, psize, true);
                 R.ref = pstart;
@@ -1132,8 +1132,8 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
                 R.dec_lo = C_SPLIT | (1u << 8);
                 return;
             }
-            if (V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks ||
-                !arena_reserve(V, S, run_words(pstart, psize), P, A, ev)) {
+            if (UNLIKELY(V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks ||
+                         !arena_reserve(V, S, run_words(pstart, psize), P, A, ev))) {
                 A.overflow(ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
                 R.dec_lo = C_INVALID;
                 return;
@@ -1156,7 +1156,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     // Smaller blocks, largest first, until the request is covered (states 3 and 4).  Blocks
     // below the fragmentation limit sit at the tail of the pool and are never stitched.
     u32 lim = V.np;
-    if (P.frag_limit_chunks > 1) lim = rank_desc(V.pool, V.np, ((u64)P.frag_limit_chunks << 32) - 1);
+    if (UNLIKELY(P.frag_limit_chunks > 1)) lim = rank_desc(V.pool, V.np, ((u64)P.frag_limit_chunks << 32) - 1);
     u32 sum = 0, k = 0, pos = NONE32;
     for (u32 base = hi_p; base < lim; base += 64) {
         const u32 i = base + lane;
@@ -1180,11 +1180,11 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     const u32 excess = s3 ? sum - bsize : 0, deficit = s3 ? 0 : bsize - sum;
     if (!s3) {
         // S4 needs new physical chunks; S5 if the device cannot provide them
-        if (reserved_units + (deficit << P.chunk_shift) > P.capacity_units) {
+        if (UNLIKELY(reserved_units + (deficit << P.chunk_shift) > P.capacity_units)) {
             R.dec_lo = C_OOM;
             return;
         }
-        if (V.n_chunks + deficit > P.cap_chunks) {
+        if (UNLIKELY(V.n_chunks + deficit > P.cap_chunks)) {
             A.overflow(ev, VMS_ST_OVF_CHUNKS);
             R.dec_lo = C_INVALID;
             return;
@@ -1192,7 +1192,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     }
     // list entries created below: a run of L chunks touches at most L / 32 + 2 bitmap words
     const u32 need = 2u * k + 3u * (((sum > bsize ? sum : bsize) >> 5) + 2u);
-    if (V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev)) {
+    if (UNLIKELY(V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev))) {
         A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
         R.dec_lo = C_INVALID;
         return;
@@ -1554,7 +1554,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 const u32 kind = b & 3;
                 S.set_req(slot, (u32)SLOT_UNBOUND);
                 requested -= req;
-                if (LIKELY(kind == KIND_SBLOCK)) {
+                if (LIKELY((kind & KIND_SBLOCK) != 0)) {    // (a bit test: the usual case stays the fall-through)
                     if (USE_LIST) {
                         const u32 list = S.get_c(slot), off = list >> 16, cnt = list & 0xFFFFu;
                         // one list read, then the entries' bits cleared without waiting for anything
@@ -1587,7 +1587,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
             // ---- ALLOC
             const u32 size = w;
             if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) EMIT((u32)C_INVALID, 0u)
-            if (size >= P.small_limit_units) {
+            if (LIKELY(size >= P.small_limit_units)) {
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
                 if (LIKELY(s1_sblock(V, bsize, ref, list))) {
@@ -1627,15 +1627,15 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                 probe_refresh(V.sp, V.skey, V.ns);
                 probe_refresh(V.pp, V.pool, V.np);
                 // lists have moved: every slot holding an sBlock looks its list up again
-                if (USE_LIST && compacted) S.relist(V.skey, (const u32 *)V.smeta, V.ns);
-                if (!went) {                                // an engine table overflowed: the trace ends here
+                if (USE_LIST && UNLIKELY(compacted)) S.relist(V.skey, (const u32 *)V.smeta, V.ns);
+                if (UNLIKELY(!went)) {                                // an engine table overflowed: the trace ends here
                     stop = true;
                     done = j;
                     todo = 0;
                     continue;
                 }
                 dlo = R.dec_lo;
-                if ((dlo & 15) != C_OOM) {
+                if (LIKELY((dlo & 15) != C_OOM)) {
                     dhi = R.ref;
                     S.set_a(slot, dhi);
                     S.set_b(slot, R.kind | (R.held << 2));
@@ -1665,7 +1665,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                     dhi = af >> 2;
                 }
             }
-            if ((dlo & 15) == C_OOM) {
+            if (UNLIKELY((dlo & 15) == C_OOM)) {
                 S.set_req(slot, (u32)SLOT_OOM);
                 ColdState C;                                // rare: note the first failed request
                 C.load(lds);
