@@ -82,9 +82,11 @@ struct AcctRegs {
 
 struct AcctLds {
     u32 *sc;
-    // one wavefront owns the scalars: every lane does the same read-modify-write (no lane is switched off)
-    DI void add(u32 k, u32 x) { st_one(sc, k, ld_uni(sc, k) + x); }
-    DI void peak(u32 k, u32 v) { st_one(sc, k, max(ld_uni(sc, k), v)); }
+    u32 *idle;                  // 64 spare words: what the lanes other than lane 0 aim at
+    // LDS atomics without a result: nothing to wait for.  Lane 0 updates the scalar, the other lanes
+    // a spare word each (no lane is switched off, no two lanes meet at one address)
+    DI void add(u32 k, u32 x) { atomicAdd(lane_id() == 0 ? &sc[k] : &idle[lane_id()], x); }
+    DI void peak(u32 k, u32 v) { atomicMax(lane_id() == 0 ? &sc[k] : &idle[lane_id()], v); }
     DI void overflow(u32 ev, u32 which)
     {
         st_one(sc, (u32)SC_STATUS, ld_uni(sc, (u32)SC_STATUS) | VMS_ST_TABLE_OVERFLOW | which);
@@ -1348,6 +1350,7 @@ DI bool vms_alloc_cold(char *lds, VmsT<BIG> &V, const KParams &P, u32 bsize, u32
     V.next_sid = C.get(SC_NEXT_SID);
     AcctLds A;
     A.sc = sc;
+    A.idle = V.idle;
     ColdSlots S;
     S.compacted = false;
     vms_alloc_rest(V, S, bsize, reserved_units, P, A, ev, R);
@@ -1379,6 +1382,8 @@ __device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 s
     sp.reserved = C.get(SC_SP_RESERVED);
     AcctLds A;
     A.sc = (u32 *)(lds + LDS_SCALARS);
+    A.idle = (u32 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_tmp) / 4))) +
+             (from_lane(pv, (u32)(offsetof(KParams, cap_chunks) / 4)) + 31) / 32;
     SplitRes r;
     sp_alloc(sp, size, seg, may_grow != 0, A, ev, r);
     C.set(SC_SP_N, sp.n);
@@ -1405,6 +1410,8 @@ __device__ __attribute__((noinline)) void small_free_cold(lds_char *ldsp, u32 ad
     sp.reserved = C.get(SC_SP_RESERVED);
     AcctLds A;
     A.sc = (u32 *)(lds + LDS_SCALARS);
+    A.idle = (u32 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_tmp) / 4))) +
+             (from_lane(pv, (u32)(offsetof(KParams, cap_chunks) / 4)) + 31) / 32;
     bool ml, mr;
     sp_free(sp, addr, size, flags, &ml, &mr, A, ev);
     C.set(SC_SP_N, sp.n);
