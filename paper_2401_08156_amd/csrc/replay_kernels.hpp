@@ -48,8 +48,7 @@ struct KParams {
 // counters after them are only ever updated in place.
 enum {
     SC_TOP, SC_LIVE, SC_NEXT_SID,                       // arena top, live list entries, next creation number
-    SC_SP_N, SC_SP_RESERVED,                            // the splitting pool for requests below one chunk
-    SC_R_DEC, SC_R_REF,                                 // result of the last call into that pool
+    SC_SP_N,                                            // blocks in the splitting pool for requests below one chunk
     SC_STATE_COUNT,
     SC_N_SPLIT = SC_STATE_COUNT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
     SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
@@ -1273,16 +1272,12 @@ DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
 
 // ---------------------------------------------------------------------------
 // Hot and cold halves.  The replay loop keeps only what the two frequent paths need in registers
-// (exact hit on a cached block, free).  The states S2 to S5 are inlined behind an unlikely branch
-// and keep the three scalars only they need in LDS; the splitting pool for requests below one
-// chunk runs in separate, non-inlined functions whose state lives in LDS between calls.
-//   lds[0 .. 256)     scalars of the trace (SC_* above), one u32 each
-//   lds[256 .. 512)   copy of the launch parameters, for the non-inlined functions
+// (exact hit on a cached block, free).  The states S2 to S5 and the splitting pool for requests below
+// one chunk sit behind unlikely branches and keep the scalars only they need in the first 256 bytes of
+// LDS (SC_* above, one u32 each), where the event counters are updated in place as well.
 // ---------------------------------------------------------------------------
 #define LDS_SCALARS 0u
-#define LDS_PARAMS 256u
-#define KPARAM_WORDS ((u32)(sizeof(KParams) / 4))
-static_assert(SC_COUNT <= 64 && sizeof(KParams) <= 256 && sizeof(KParams) % 4 == 0, "LDS header layout");
+static_assert(SC_COUNT <= 64, "LDS header layout");
 
 typedef __attribute__((address_space(3))) char lds_char;
 
@@ -1307,14 +1302,6 @@ struct ColdState {
     DI u32 get(u32 k) const { return from_lane(v, k); }
     DI void set(u32 k, u32 x) { v = lane_id() == k ? x : v; }
 };
-
-DI void load_params(KParams &P, const char *lds)
-{
-    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
-    u32 *w = (u32 *)&P;
-#pragma unroll
-    for (u32 k = 0; k < KPARAM_WORDS; k++) w[k] = from_lane(pv, k);
-}
 
 template <bool BIG>
 DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool swapped)
@@ -1362,61 +1349,40 @@ DI bool vms_alloc_cold(char *lds, VmsT<BIG> &V, const KParams &P, u32 bsize, u32
     return ld_uni(sc, (u32)SC_STOP) == 0;
 }
 
-// Cold calls of the stitching policy for requests below one chunk: its private splitting pool.
-// alloc: SC_R_DEC = code | split << 8, SC_R_REF = address << 2 | flags.  free: SC_R_DEC = merged
-// left | merged right << 1.
-__device__ __attribute__((noinline)) void small_alloc_cold(lds_char *ldsp, u32 size, u32 seg, u32 may_grow, u32 ev)
+// Requests below one chunk under the stitching policy: its private splitting pool (Sec. 3.1), whose
+// two scalars (blocks in the list, units reserved) wait in LDS between requests.
+DI void small_alloc(char *lds, const KParams &P, u32 *idle, u32 size, u32 seg, bool may_grow, u32 ev, SplitRes &r,
+                    u32 &sp_reserved)
 {
-    size = uni(size);
-    seg = uni(seg);
-    may_grow = uni(may_grow);
-    ev = uni(ev);
-    char *lds = (char *)ldsp;
-    ColdState C;
-    C.load(lds);
-    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
+    u32 *sc = (u32 *)(lds + LDS_SCALARS);
     SplitPoolD sp;
-    sp.fl = (u64 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_fl) / 4)));
-    sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
-    sp.n = C.get(SC_SP_N);
-    sp.reserved = C.get(SC_SP_RESERVED);
+    sp.fl = (u64 *)(lds + P.off_fl);
+    sp.cap = P.cap_free;
+    sp.n = ld_uni(sc, (u32)SC_SP_N);
+    sp.reserved = sp_reserved;
     AcctLds A;
-    A.sc = (u32 *)(lds + LDS_SCALARS);
-    A.idle = (u32 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_tmp) / 4))) +
-             (from_lane(pv, (u32)(offsetof(KParams, cap_chunks) / 4)) + 31) / 32;
-    SplitRes r;
-    sp_alloc(sp, size, seg, may_grow != 0, A, ev, r);
-    C.set(SC_SP_N, sp.n);
-    C.set(SC_SP_RESERVED, sp.reserved);
-    C.set(SC_R_DEC, r.code | (r.split ? 1u << 8 : 0u));
-    C.set(SC_R_REF, (r.addr << 2) | r.flags);
-    C.store(lds);
+    A.sc = sc;
+    A.idle = idle;
+    sp_alloc(sp, size, seg, may_grow, A, ev, r);
+    st_one(sc, (u32)SC_SP_N, sp.n);
+    sp_reserved = sp.reserved;
+    wave_sync();
 }
 
-__device__ __attribute__((noinline)) void small_free_cold(lds_char *ldsp, u32 addr, u32 size, u32 flags, u32 ev)
+DI void small_free(char *lds, const KParams &P, u32 *idle, u32 addr, u32 size, u32 flags, u32 ev, bool *ml, bool *mr)
 {
-    addr = uni(addr);
-    size = uni(size);
-    flags = uni(flags);
-    ev = uni(ev);
-    char *lds = (char *)ldsp;
-    ColdState C;
-    C.load(lds);
-    const u32 pv = pin(((const u32 *)(lds + LDS_PARAMS))[lane_id() < KPARAM_WORDS ? lane_id() : 0u]);
+    u32 *sc = (u32 *)(lds + LDS_SCALARS);
     SplitPoolD sp;
-    sp.fl = (u64 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_fl) / 4)));
-    sp.cap = from_lane(pv, (u32)(offsetof(KParams, cap_free) / 4));
-    sp.n = C.get(SC_SP_N);
-    sp.reserved = C.get(SC_SP_RESERVED);
+    sp.fl = (u64 *)(lds + P.off_fl);
+    sp.cap = P.cap_free;
+    sp.n = ld_uni(sc, (u32)SC_SP_N);
+    sp.reserved = 0;            // not used by a release
     AcctLds A;
-    A.sc = (u32 *)(lds + LDS_SCALARS);
-    A.idle = (u32 *)(lds + from_lane(pv, (u32)(offsetof(KParams, off_tmp) / 4))) +
-             (from_lane(pv, (u32)(offsetof(KParams, cap_chunks) / 4)) + 31) / 32;
-    bool ml, mr;
-    sp_free(sp, addr, size, flags, &ml, &mr, A, ev);
-    C.set(SC_SP_N, sp.n);
-    C.set(SC_R_DEC, (ml ? 1u : 0u) | (mr ? 2u : 0u));
-    C.store(lds);
+    A.sc = sc;
+    A.idle = idle;
+    sp_free(sp, addr, size, flags, ml, mr, A, ev);
+    st_one(sc, (u32)SC_SP_N, sp.n);
+    wave_sync();
 }
 
 // The per-tile work shared by both replay kernels: one event per lane.
@@ -1465,8 +1431,7 @@ DI u64 tile_totals(const TileOut &T, u32 n_code[8])
 
 // ---------------------------------------------------------------------------
 // Replay under the stitching policy (Sec. 3, Sec. 4.1), one wavefront per trace.
-// SLOT_REGS: slot table in registers (max_slots <= 64).  d_params: the launch parameters
-// again, in device memory (copied to LDS for the cold functions).
+// SLOT_REGS: slot table in registers (max_slots <= 64).
 //
 // Per event only the allocator runs; the decision word and the active / reserved totals after
 // the event are parked in lane j of four registers.  Once per tile of 64 events the lanes store
@@ -1474,8 +1439,8 @@ DI u64 tile_totals(const TileOut &T, u32 n_code[8])
 // the digest, all 64 events side by side.
 // ---------------------------------------------------------------------------
 template <bool BIG, bool SLOT_REGS>
-__global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__restrict__ d_params,
-                                                        const u64 *__restrict__ events, const u32 *__restrict__ n_events,
+__global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__restrict__ events,
+                                                        const u32 *__restrict__ n_events,
                                                         u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
                                                         char *__restrict__ workspace)
 {
@@ -1487,13 +1452,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
-    {
-        // LDS header: scalars, then the parameters
-        u32 init = 0;
-        if (lane == SC_FIRST_OOM || lane == SC_OVF_EVENT) init = NONE32;
-        ((u32 *)(lds + LDS_SCALARS))[lane] = init;
-        ((u32 *)(lds + LDS_PARAMS))[lane] = lane < KPARAM_WORDS ? d_params[lane] : 0u;
-    }
+    ((u32 *)(lds + LDS_SCALARS))[lane] = lane == SC_FIRST_OOM || lane == SC_OVF_EVENT ? NONE32 : 0u;     // LDS header
     VmsT<BIG> V;
     vms_bind(V, lds, ws_slice, P, false);
     V.np = V.ns = V.n_chunks = V.top = V.live_ent = V.next_sid = V.clock = 0;
@@ -1578,18 +1537,16 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
                     active -= (b >> 2) << P.chunk_shift;
                     EMIT((u32)C_FREE, a)
                 }
-                small_free_cold((lds_char *)lds, a >> 2, req, a & 3, base + j);
-                ColdState C;
-                C.load(lds);
-                const u32 m = C.get(SC_R_DEC);
-                if (C.get(SC_STOP)) {
+                bool ml, mr;
+                small_free(lds, P, V.idle, a >> 2, req, a & 3, base + j, &ml, &mr);
+                if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
                     stop = true;
                     done = j;
                     todo = 0;
                     continue;
                 }
                 active -= req;
-                EMIT(C_FREE | B_SMALL | (m & 1 ? B_6 : 0u) | (m & 2 ? B_7 : 0u), a >> 2)
+                EMIT(C_FREE | B_SMALL | (ml ? B_6 : 0u) | (mr ? B_7 : 0u), a >> 2)
             }
             // ---- ALLOC
             const u32 size = w;
@@ -1652,24 +1609,21 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u32 *__
             } else {
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
                 const u32 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
-                small_alloc_cold((lds_char *)lds, size, seg, reserved + seg <= P.capacity_units ? 1u : 0u, base + j);
-                ColdState C;
-                C.load(lds);
-                if (C.get(SC_STOP)) {
+                SplitRes r;
+                small_alloc(lds, P, V.idle, size, seg, reserved + seg <= P.capacity_units, base + j, r, sp_reserved);
+                if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
                     stop = true;
                     done = j;
                     todo = 0;
                     continue;
                 }
-                const u32 rd = C.get(SC_R_DEC), code = rd & 15;
-                sp_reserved = C.get(SC_SP_RESERVED);
                 dlo = C_OOM;
-                if (code != C_OOM) {
-                    const u32 af = C.get(SC_R_REF);
+                if (r.code != C_OOM) {
+                    const u32 af = (r.addr << 2) | r.flags;
                     S.set_a(slot, af);
                     S.set_b(slot, (u32)KIND_SMALL);
-                    dlo = code | B_SMALL | (rd & 0x100 ? B_6 : 0u) | ((code == C_GROW ? 0u : 1u) << 8);
-                    dhi = af >> 2;
+                    dlo = r.code | B_SMALL | (r.split ? B_6 : 0u) | ((r.code == C_GROW ? 0u : 1u) << 8);
+                    dhi = r.addr;
                 }
             }
             if (UNLIKELY((dlo & 15) == C_OOM)) {

@@ -28,7 +28,6 @@ struct vms_replay {
     bool fl_regs;               // splitting policy: inactive blocks in registers (see SplitRegs)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
-    KParams *d_kp;              // kp[] again, in device memory (the stitching kernel copies it to LDS)
     hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
     hipStream_t side;           // the splitting kernel runs here, beside the stitching kernel
     hipStream_t last_stream;
@@ -63,7 +62,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         return at;
     };
     k.off_slot_req = k.off_slot_a = k.off_slot_b = k.off_slot_c = 0;
-    if (policy) take(512);      // scalars of the trace and a copy of these parameters (see replay_kernels.hpp)
+    if (policy) take(256);      // scalars of the trace (see replay_kernels.hpp)
     if (!slot_regs) {
         k.off_slot_req = take(c.max_slots * 4);
         k.off_slot_a = take(c.max_slots * 4);
@@ -87,7 +86,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
     k.lds_bytes = off;
 }
 
-typedef void (*vms_fn)(KParams, const u32 *, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
+typedef void (*vms_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
 typedef void (*split_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *);
 
 // the kernel variants: chunk-run lists in HBM or LDS, slot table in LDS or registers
@@ -193,8 +192,6 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     // records of a policy that never runs stay zero; a run rewrites every record of its policies
     if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * 2 * (size_t)c.n_traces);
     if (e == hipSuccess) e = hipMalloc((void **)&h->d_summary, sizeof(vms_summary));
-    if (e == hipSuccess) e = hipMalloc((void **)&h->d_kp, sizeof(h->kp));
-    if (e == hipSuccess) e = hipMemcpy(h->d_kp, h->kp, sizeof(h->kp), hipMemcpyHostToDevice);
     for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
@@ -239,7 +236,7 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     if (both) HIP_TRY(h, hipStreamWaitEvent(sst, h->ev[0], 0));
     if (c.policy_mask & VMS_POLICY_VMS) {
         hipLaunchKernelGGL(pick_vms(h->big, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
-                           (const u32 *)&h->d_kp[1], d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+                           d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
@@ -294,7 +291,6 @@ void vms_replay_destroy(vms_replay *h)
     if (!h) return;
     if (h->d_stats) (void)hipFree(h->d_stats);
     if (h->d_summary) (void)hipFree(h->d_summary);
-    if (h->d_kp) (void)hipFree(h->d_kp);
     for (int i = 0; i < 5; i++)
         if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
     if (h->side) (void)hipStreamDestroy(h->side);
