@@ -119,6 +119,7 @@ struct SlotsT<true> {
     DI void set_a(u32 s, u32 v) { a = write_lane(a, v, s); }
     DI void set_b(u32 s, u32 v) { b = write_lane(b, v, s); }
     DI void set_c(u32 s, u32 v) { c = write_lane(c, v, s); }
+    DI void bind(u32 s, u32 vreq, u32 va, u32 vb, u32 vc) { write_lane4(req, a, b, c, vreq, va, vb, vc, s); }
     // the arena was compacted: the list that was at `from` is now at `to`
     // the lists of the sBlocks have moved: look each held sBlock up by its key (creation number a,
     // b >> 2 chunks) in skey[0..ns) (descending) and take its new place from smeta[]
@@ -161,6 +162,12 @@ struct SlotsT<false> {
     DI void set_a(u32 s, u32 v) { st_one(a, s, v); }
     DI void set_b(u32 s, u32 v) { st_one(b, s, v); }
     DI void set_c(u32 s, u32 v) { st_one(c, s, v); }
+    DI void bind(u32 s, u32 vreq, u32 va, u32 vb, u32)
+    {
+        st_one(req, s, vreq);
+        st_one(a, s, va);
+        st_one(b, s, vb);           // c is not used with the table in LDS
+    }
     DI void relist(const u64 *, const u32 *, u32) {}  // c is not used with the table in LDS
 };
 
@@ -1555,10 +1562,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
                 if (LIKELY(s1_sblock(V, bsize, ref, list))) {
-                    S.set_a(slot, ref);
-                    S.set_b(slot, KIND_SBLOCK | (bsize << 2));
-                    if (USE_LIST) S.set_c(slot, list);
-                    S.set_req(slot, size);
+                    S.bind(slot, size, ref, KIND_SBLOCK | (bsize << 2), list);
                     requested += size;
                     active += bsize << P.chunk_shift;
                     // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
