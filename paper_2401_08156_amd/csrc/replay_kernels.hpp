@@ -433,7 +433,7 @@ struct SplitRegs {
             const u64 chosen = ((u64)mhi << 32) | blo;
             r.addr = blo >> 2;
             r.flags = blo & 3;
-            if (mhi > size) {
+            if (LIKELY(mhi > size)) {
                 // step 2: cut off what is not needed; it stays cached as the right neighbour, in the
                 // place the block had
                 swap_key(chosen, ((u64)(mhi - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1));
@@ -503,7 +503,7 @@ struct SplitRegs {
         }
         A.add(SC_N_MERGE, (*ml ? 1u : 0u) + (*mr ? 1u : 0u));
         const u64 key = ((u64)size << 32) | ((u64)addr << 2) | flags;
-        if (*ml) {
+        if (UNLIKELY(*ml)) {
             swap_key(lkey, key);                // the merged block takes the left neighbour's place
             if (*mr) {
                 swap_key(rkey, 0);
