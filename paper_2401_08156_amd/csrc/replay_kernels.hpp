@@ -44,8 +44,8 @@ struct KParams {
 };
 
 // Scalars of one trace that live in LDS (stitching kernel): index k is the u32 at lds[4 k].  The
-// first SC_STATE_COUNT are state that only the rare paths need (loaded and stored around them); the
-// counters after them are only ever updated in place.
+// first SC_STATE_COUNT are state that only the rare paths need (read when they start, written back
+// when they end); the counters after them are only ever updated in place.
 enum {
     SC_TOP, SC_LIVE, SC_NEXT_SID,                       // arena top, live list entries, next creation number
     SC_SP_N,                                            // blocks in the splitting pool for requests below one chunk
@@ -57,7 +57,7 @@ enum {
 
 // Event counters and high-water marks of one (trace, policy), addressed by the SC_* indices.
 // Two holders with the same interface: registers (splitting kernel, everything inline) and the
-// LDS scalars (cold functions of the stitching kernel: updated in place, nothing to load or store).
+// LDS scalars (rare paths of the stitching kernel: updated in place, nothing to load or store).
 struct AcctRegs {
     u32 f[SC_COUNT];
     bool stop;
@@ -1286,28 +1286,18 @@ DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
 #define LDS_SCALARS 0u
 static_assert(SC_COUNT <= 64, "LDS header layout");
 
-typedef __attribute__((address_space(3))) char lds_char;
-
-// stand-in for the slot table inside the cold functions: they only note that lists have moved
+// stand-in for the slot table inside the rare paths: they only note that lists have moved
 struct ColdSlots {
     bool compacted;
     DI void moved(u32, u32, const KParams &) { compacted = true; }
 };
 
-// scalars <-> registers, one LDS access for all of them
+// the LDS scalars in registers, one LDS access for all of them: lane k holds scalar k
 struct ColdState {
-    u32 v;                      // lane k: scalar k
+    u32 v;
     // pinned: every lane must load its scalar even if only one lane goes on to use them
     DI void load(const char *lds) { v = pin(((const u32 *)(lds + LDS_SCALARS))[lane_id()]); }
-    DI void store(char *lds) const          // the counters behind the state are updated in place, never from here
-    {
-        u32 *sc = (u32 *)(lds + LDS_SCALARS);
-        const u32 cur = pin(sc[lane_id()]);          // the counters keep what is there
-        sc[lane_id()] = lane_id() < SC_STATE_COUNT ? v : cur;
-        wave_sync();
-    }
     DI u32 get(u32 k) const { return from_lane(v, k); }
-    DI void set(u32 k, u32 x) { v = lane_id() == k ? x : v; }
 };
 
 template <bool BIG>
