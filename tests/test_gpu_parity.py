@@ -30,6 +30,18 @@ def test_config1_variants_many_seeds(kw):
     gpu_util.assert_parity(ev, cfg, label="config 1 %s" % kw)
 
 
+def test_splitting_pool_in_registers():
+    # pools of at most 192 inactive blocks are held in registers by the splitting kernel: random traces
+    # with many merges on both sides, and a table so small that it overflows (reported, not fatal)
+    ev, ms = tg.generate(1, n_traces=64, n_events=1500, seed=17)
+    cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=192)
+    st = gpu_util.assert_parity(ev, cfg, label="config 1, register pool")
+    assert st["n_merge"][0].min() > 0 and st["max_free_blocks"][0].max() <= 192
+    cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=6)
+    _, _, st = gpu_util.gpu_replay(ev, cfg)
+    assert (st["status"][0] & binding.VMS_ST_TABLE_OVERFLOW).all()
+
+
 def test_worked_examples_on_gpu():
     import glob
     import os
