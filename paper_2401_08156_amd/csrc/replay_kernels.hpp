@@ -886,8 +886,8 @@ DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
 
 // StitchFree (Sec. 3.3.2, Sec. 4.2.3): while more sBlocks than the threshold are cached,
 // release the least recently used one that is inactive.  One scan rules out, side by side, every
-// sBlock whose witness is still active (four tiles at a time: all stamps and witnesses are loaded,
-// then all witness words, two LDS round trips per 256 sBlocks) and leaves in every lane the two
+// sBlock whose witness is still active (three tiles at a time: all stamps and witnesses are loaded,
+// then all witness words, two LDS round trips per 192 sBlocks) and leaves in every lane the two
 // least recently used of the sBlocks it saw.  The oldest of all is tested with all lanes on its
 // list; if it is active after all, its lane falls back on its second and the search goes on
 // without a new scan (a lane that runs out of its two forces one).
@@ -906,18 +906,18 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
                 b1 = b2 = NONE32;
                 i1 = i2 = 0;
                 spent = false;
-                for (u32 g = 0; g < V.ns; g += 256) {
-                    u32 st[4], wit[4], ww[4];
+                for (u32 g = 0; g < V.ns; g += 192) {
+                    u32 st[3], wit[3], ww[3];
 #pragma unroll
-                    for (u32 t = 0; t < 4; t++) {
+                    for (u32 t = 0; t < 3; t++) {
                         const u32 i = g + t * 64 + lane, ic = i < V.ns ? i : 0u;
                         st[t] = V.sstamp[ic];
                         wit[t] = V.swit[ic];
                     }
 #pragma unroll
-                    for (u32 t = 0; t < 4; t++) ww[t] = pin(V.bmp[ENT_WORD(wit[t])]);
+                    for (u32 t = 0; t < 3; t++) ww[t] = pin(V.bmp[ENT_WORD(wit[t])]);
 #pragma unroll
-                    for (u32 t = 0; t < 4; t++) {
+                    for (u32 t = 0; t < 3; t++) {
                         const u32 i = g + t * 64 + lane;
                         const bool ok = (i < V.ns) & ((ww[t] & emask(wit[t])) == 0);
                         const u32 sv = ok ? st[t] : NONE32;
@@ -1117,7 +1117,19 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     R.list = 0;
     // pool[lo_p, hi_p) are the pBlocks of exactly bsize chunks (all active, or S1 had taken one)
     u32 lo_p, hi_p;
-    rank_desc2(V.pool, V.np, ((u64)bsize << 32) | 0xFFFFFFFFu, ((u64)bsize << 32) - 1, &lo_p, &hi_p);
+    {
+        const u64 k1 = ((u64)bsize << 32) | 0xFFFFFFFFu, k2 = ((u64)bsize << 32) - 1;
+        if (LIKELY(V.pp.stride <= 64)) {
+            // the first search level is in registers and still describes the pool: one LDS round trip
+            const u32 c1 = popc64(ballot(V.pp.v > k1)), c2 = popc64(ballot(V.pp.v > k2));
+            const u32 b1 = (c1 ? c1 - 1 : 0u) * V.pp.stride, b2 = (c2 ? c2 - 1 : 0u) * V.pp.stride;
+            const u64 v1 = V.pool[b1 + lane], v2 = V.pool[b2 + lane];
+            lo_p = b1 + popc64(ballot(v1 > k1));
+            hi_p = b2 + popc64(ballot(v2 > k2));
+        } else {
+            rank_desc2(V.pool, V.np, k1, k2, &lo_p, &hi_p);
+        }
+    }
 
     // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
     // pool order is the single-block candidate (state 2).
