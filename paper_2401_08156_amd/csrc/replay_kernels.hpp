@@ -792,11 +792,12 @@ DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
 // Returns the position of the new sBlock in skey[].
 template <bool BIG, class AcctT>
-DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, AcctT &A)
+DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, AcctT &A, bool probe_valid)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
-    u32 pos = rank_desc(V.skey, V.ns, key);
+    // probe_valid: skey[] has not changed since its first search level was put into registers
+    u32 pos = probe_valid ? rank_fast<BIG>(V.sp, V.skey, V.ns, key) : rank_desc(V.skey, V.ns, key);
     spool_shift_up(V, pos, V.ns);
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
@@ -1162,7 +1163,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             pool_cut(V, idx, bsize, pstart, psize - bsize, pstart + bsize, A);
             A.add(SC_N_SPLIT, 1);
             u32 n = arena_put(V, V.top, pstart, psize);
-            spool_insert(V, psize, V.top, n, A);
+            spool_insert(V, psize, V.top, n, A, true);
             V.top += n;
             bmp_fill(V.bmp, ENT_WORD(V.e_skip), pstart, bsize, true);
             R.ref = pstart;
@@ -1257,7 +1258,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             pool_cut(V, pos, qsize - excess, qstart, excess, qstart + qsize - excess, A);
             A.add(SC_N_SPLIT, 1);
             u32 n = arena_put(V, V.top + cnt, qstart, qsize);
-            spool_insert(V, qsize, V.top + cnt, n, A);
+            spool_insert(V, qsize, V.top + cnt, n, A, true);
             used += n;
             R.dec_lo |= B_6;
         }
@@ -1269,7 +1270,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         R.dec_lo |= C_GROW;
     }
     R.ref = V.next_sid;
-    spool_insert(V, bsize, V.top, cnt, A);
+    spool_insert(V, bsize, V.top, cnt, A, !(s3 && excess));
     bmp_fill_entries(V, V.top, cnt, true);
     R.list = BIG ? 0u : (u32)V.pack(V.top, cnt);
     V.top += used;
