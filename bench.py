@@ -149,6 +149,7 @@ def main():
                    "policies": "split+vms", "chunk_bytes": int(cfg.chunk_bytes),
                    "spool_threshold": int(cfg.spool_threshold), "frag_limit_bytes": int(cfg.frag_limit_bytes),
                    "batches": len(batches), "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
+        "policy_events_per_s": 2 * total_events / (dt / args.steps),     # every event is decided under both policies
         "kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "kernel": "replay_vms_kernel (stitching policy)" if dom == "vms" else "replay_split_kernel (splitting policy)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
