@@ -128,6 +128,15 @@ def main():
     summ = rep.summary()
     flagged = int((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=0).sum())
     if flagged:
+        names = dict(free_blocks=binding.VMS_ST_OVF_FREE_BLOCKS, pblocks=binding.VMS_ST_OVF_PBLOCKS,
+                     sblocks=binding.VMS_ST_OVF_SBLOCKS, runs=binding.VMS_ST_OVF_RUNS,
+                     chunks=binding.VMS_ST_OVF_CHUNKS)
+        for bt, kind in zip(batches, kinds):
+            s = bt["rep"].stats()["status"]
+            which = {k: int(((s & v) != 0).any(axis=0).sum()) for k, v in names.items()}
+            high = {k: int(bt["rep"].stats()["max_" + k].max()) for k in names if k != "chunks"}
+            print("bench.py: batch %s: traces over a table: %s; high-water marks reached: %s" % (kind, which, high),
+                  file=sys.stderr)
         print("bench.py: engine tables overflowed; the measurement is invalid", file=sys.stderr)
         sys.exit(1)
 

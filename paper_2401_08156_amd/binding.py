@@ -14,6 +14,7 @@ from . import build as _build
 VMS_OK = 0
 VMS_POLICY_SPLIT, VMS_POLICY_VMS = 1, 2
 VMS_ST_INVALID_EVENT, VMS_ST_TABLE_OVERFLOW = 1, 2
+VMS_ST_OVF_FREE_BLOCKS, VMS_ST_OVF_PBLOCKS, VMS_ST_OVF_SBLOCKS, VMS_ST_OVF_RUNS, VMS_ST_OVF_CHUNKS = 4, 8, 16, 32, 64
 
 
 class vms_config(ctypes.Structure):

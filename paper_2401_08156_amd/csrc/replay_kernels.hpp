@@ -40,6 +40,7 @@ struct KParams {
     u32 off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
         off_sstamp, off_swit, off_tmp, off_arena;
     u32 lds_bytes;
+    u32 ws_stamp_off;           // BIG only: not 0 = sstamp[] lives at this byte offset of the trace's workspace slice
     u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
 };
 
@@ -1320,7 +1321,7 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
     V.bmp = (u32 *)(lds + P.off_bmp);
     V.skey = (u64 *)(lds + P.off_skey);
     V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
-    V.sstamp = (u32 *)(lds + P.off_sstamp);
+    V.sstamp = BIG && P.ws_stamp_off ? (u32 *)(ws_slice + P.ws_stamp_off) : (u32 *)(lds + P.off_sstamp);
     V.swit = (u32 *)(lds + P.off_swit);
     V.tmp = (u32 *)(lds + P.off_tmp);
     V.idle = V.tmp + (P.cap_chunks + 31) / 32;

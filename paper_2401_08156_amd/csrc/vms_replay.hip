@@ -53,7 +53,9 @@ int hip_fail(vms_replay *h, hipError_t e)
 
 // Per-wave LDS layout.  The splitting kernel only needs the slot table and its free list; with at
 // most 64 slots the slot table lives in registers and takes no LDS at all.
-void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_regs)
+// stamps_ws: the last-use stamps of the sBlocks move to the trace's slice of the global workspace
+// (tables that would not fit the LDS otherwise; the hot path only ever stores to them).
+void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_regs, bool stamps_ws)
 {
     uint32_t off = 0;
     auto take = [&](uint32_t bytes) {
@@ -76,7 +78,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         k.off_bmp = take((c.max_chunks + 31) / 32 * 4 + 4);     // and one spare bitmap word
         k.off_skey = take((c.max_sblocks + 64) * 8);
         k.off_smeta = take((c.max_sblocks + 64) * (big ? 8 : 4));
-        k.off_sstamp = take((c.max_sblocks + 64) * 4);
+        k.off_sstamp = stamps_ws ? 0 : take((c.max_sblocks + 64) * 4);
         k.off_swit = take((c.max_sblocks + 64) * 4);
         k.off_tmp = take((c.max_chunks + 31) / 32 * 4 + 256);   // and 64 spare words
         k.off_arena = big ? 0 : take((c.max_runs + 64) * 4);
@@ -174,9 +176,15 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.cap_sblocks = c.max_sblocks;
         k.cap_runs = c.max_runs;
         k.cap_chunks = c.max_chunks;
-        layout(k, p, c, h->big, h->slot_regs);
+        layout(k, p, c, h->big, h->slot_regs, false);
         // compaction buffer, and for the big variant the lists themselves (each with 64 spare entries)
         k.ws_stride = p ? (uint64_t)align_up((c.max_runs + 64) * 4 * (h->big ? 2 : 1), 256) : 0;
+        k.ws_stamp_off = 0;
+        if (p && h->big && k.lds_bytes > LDS_PER_CU) {
+            layout(k, p, c, h->big, h->slot_regs, true);
+            k.ws_stamp_off = (uint32_t)k.ws_stride;     // behind the lists: never 0
+            k.ws_stride += align_up((c.max_sblocks + 64) * 4, 256);
+        }
         if ((c.policy_mask & (1u << p)) && k.lds_bytes > LDS_PER_CU) {
             delete h;
             return VMS_ETOOBIG;

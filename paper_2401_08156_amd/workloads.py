@@ -22,8 +22,8 @@ TABLES = {
 # config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
 # events; replayed as three batches, one per kind, each with tables of its own
 TABLES_5 = {
-    2: dict(max_free_blocks=256, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=4096),
-    3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 21, max_chunks=16384),
+    2: dict(max_free_blocks=192, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=4096),
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=4352, max_runs=1 << 21, max_chunks=16384),
     4: dict(max_free_blocks=512, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=24576),
 }
 

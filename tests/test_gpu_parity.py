@@ -100,6 +100,16 @@ def test_config3_slice_with_large_tables():
     gpu_util.assert_parity(ev, cfg, label="config 3 slice")
 
 
+def test_stamps_in_workspace_when_tables_exceed_lds():
+    # tables this large do not fit 160 KB of LDS with the last-use stamps in it: the stamps move to
+    # the workspace; low thresholds keep StitchFree (their only reader) busy
+    for seed, threshold in ((5, 128), (6, 32)):
+        ev, ms = tg.generate(3, n_traces=8, n_events=8000, seed=seed)
+        cfg = gpu_util.make_cfg(8, 8000, ms, max_free_blocks=64, max_pblocks=8192, max_sblocks=4352,
+                                max_runs=1 << 18, max_chunks=16384, spool_threshold=threshold)
+        gpu_util.assert_parity(ev, cfg, label="config 3 slice, stamps in HBM, threshold %d" % threshold)
+
+
 def test_table_overflow_is_reported_not_fatal():
     ev, ms = tg.generate(1, n_traces=4, n_events=1000, seed=3)
     cfg = gpu_util.make_cfg(4, 1000, ms, max_free_blocks=4, max_pblocks=8)
