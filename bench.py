@@ -50,9 +50,16 @@ def cpu_baseline(events, cfg_kw, max_slots, sample_traces):
     for pol in (oracle.SPLIT, oracle.VMS):
         oracle.replay(ev, P, pol, want_decisions=True, threads=cores)
     dt = time.perf_counter() - t0
+    # the same on one core, over a share of the sample that takes about as long
+    one = ev[:max(1, ev.shape[0] // max(cores, 1))]
+    t0 = time.perf_counter()
+    for pol in (oracle.SPLIT, oracle.VMS):
+        oracle.replay(one, P, pol, want_decisions=True, threads=1)
+    dt_one = time.perf_counter() - t0
     return dict(value=ev.size / dt, unit="events/s", cores=min(cores, sample_traces), kind="oracle",
                 sample="%d of %d traces x %d events, both policies, decisions written" % (
-                    ev.shape[0], events.shape[0], ev.shape[1]))
+                    ev.shape[0], events.shape[0], ev.shape[1]),
+                one_core_value=one.size / dt_one, one_core_sample="%d traces" % one.shape[0])
 
 
 def main():
@@ -160,6 +167,8 @@ def main():
                    "batches": len(batches), "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
         "policy_events_per_s": 2 * total_events / (dt / args.steps),     # every event is decided under both policies
         "kernel_ms": kernel_ms,
+        # a single trace is a single wavefront per policy: a latency figure, not a throughput
+        "ns_per_event": ms_per_step * 1e6 / n_events if n_traces == 1 else None,
         "roofline": {"bound": "hbm", "kernel": "replay_vms_kernel (stitching policy)" if dom == "vms" else "replay_split_kernel (splitting policy)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": recorded_traffic(args.config) if dom == "vms" and n_traces == base["n_traces"]
