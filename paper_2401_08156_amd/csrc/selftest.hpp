@@ -1,6 +1,6 @@
 // Self-test of the wavefront primitives: each is compared, on the device, with a
 // serial evaluation of its definition by lane 0.  Every access is to a fixed
-// 256-entry LDS array, so the test cannot touch memory it does not own.
+// LDS array of 256 or 832 entries, so the test cannot touch memory it does not own.
 #pragma once
 #include "wave_ops.hpp"
 #include "../../include/vms_replay.h"
@@ -9,6 +9,7 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
 {
     __shared__ u32 in[64], out[64];
     __shared__ u64 arr[256];
+    __shared__ u64 big[832];
     const u32 lane = lane_id();
     u32 bad = 0;
     for (u32 round = 0; round < 8; round++) {
@@ -76,6 +77,25 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
         if (arr[i] != (u64)(1000 - 3 * i) << 32) bad |= 128;
     for (u32 i = 151; i < 256; i++)
         if (arr[i] != 0) bad |= 128;                // the spare places stay zero (arr[150] keeps the moved key's copy)
+    // the same over many tiles: 700 keys, 64 spare places, moved from places 0, 37 and 699
+    for (u32 pos = 0; pos < 700; pos = pos == 0 ? 37 : (pos == 37 ? 699 : 700)) {
+        for (u32 i = lane; i < 832; i += 64) big[i] = i < 700 ? (u64)(5000 - 3 * i) << 32 : 0;
+        wave_sync();
+        shift_up(big, pos, 700);
+        st_one(big, pos, (u64)12345);
+        wave_sync();
+        for (u32 i = 0; i < 701; i++) {
+            u64 want = i < pos ? (u64)(5000 - 3 * i) << 32 : (i == pos ? (u64)12345 : (u64)(5000 - 3 * (i - 1)) << 32);
+            if (big[i] != want) bad |= 1024;
+        }
+        for (u32 i = 701; i < 832; i++)
+            if (big[i] != 0) bad |= 1024;
+        shift_down(big, pos, 701);
+        for (u32 i = 0; i < 700; i++)
+            if (big[i] != (u64)(5000 - 3 * i) << 32) bad |= 2048;
+        for (u32 i = 701; i < 832; i++)
+            if (big[i] != 0) bad |= 2048;
+    }
     u64 any = ballot(bad != 0);
     if (lane == 0) *fail = any ? (bad | 0x80000000u) : 0;
     if (any && bad) atomicOr(fail, bad);
