@@ -16,15 +16,15 @@ TABLES = {
     2: dict(max_free_blocks=192, max_pblocks=544, max_sblocks=576, max_runs=3840, max_chunks=4096),
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks, runs kept in HBM
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 20, max_chunks=16384),
-    4: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=5120, max_chunks=24576),
-    6: dict(max_free_blocks=320, max_pblocks=1024, max_sblocks=640, max_runs=5120, max_chunks=16384),
+    4: dict(max_free_blocks=320, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576),
+    6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
 }
 # config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
 # events; replayed as three batches, one per kind, each with tables of its own
 TABLES_5 = {
-    2: dict(max_free_blocks=192, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=4096),
+    2: dict(max_free_blocks=192, max_pblocks=640, max_sblocks=640, max_runs=5120, max_chunks=4096),
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=4352, max_runs=1 << 21, max_chunks=16384),
-    4: dict(max_free_blocks=512, max_pblocks=2048, max_sblocks=768, max_runs=8192, max_chunks=24576),
+    4: dict(max_free_blocks=320, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576),
 }
 
 
