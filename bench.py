@@ -74,7 +74,7 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (traces are independent and would shard "
+        print("bench.py: the replay engine runs on one GPU only (traces are independent and would shard "
               "by trace index); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 

@@ -540,7 +540,7 @@ struct Replay {
             st.max_pblocks = std::max(st.max_pblocks, (u32)vp.pblocks.size());
             st.max_sblocks = std::max(st.max_sblocks, (u32)vp.spool.size());
             st.max_total_members = std::max(st.max_total_members, vp.total_members);
-            // checksum of the whole stream (this build's own; the paper defines none): every event
+            // checksum of the whole stream (defined here; the paper defines none): every event
             // adds a term that depends on its position, its decision and the totals after it
             st.digest += (dec * 0x9E3779B97F4A7C15ull + ((active << 32) | res)) *
                          ((2 * (u64)i + 1) * 0xD6E8FEB86659FD93ull);
