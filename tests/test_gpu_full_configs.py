@@ -1,6 +1,6 @@
-"""The five workloads at their full sizes, in the launch configuration bench.py times.
+"""The workloads at their full sizes, in the launch configuration bench.py times.
 
-Configs 1, 2 and 4 are compared with the oracle on every trace, every event.  Configs 3 and 5
+Configs 1, 2, 4 and 6 are compared with the oracle on every trace, every event.  Configs 3 and 5
 (whose offloading traces take the oracle seconds each) run on the GPU at full trace length, are
 compared with the oracle on a sample of traces, and are checked on all traces through properties
 that hold at any size (Sec. 4.2.1: the stitching allocator's reserved peak equals its active peak
@@ -30,7 +30,7 @@ def check_properties(st, all_requests_large):
         assert (st["fragmentation"][1] == 0.0).all()
 
 
-@pytest.mark.parametrize("config", [1, 2, 4])
+@pytest.mark.parametrize("config", [1, 2, 4, 6])
 def test_full_config_every_trace(config):
     n_traces, n_events = workloads.shape(config)
     ev, ms = tg.generate(config, threads=16)
