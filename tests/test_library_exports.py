@@ -51,3 +51,29 @@ def test_config_default_and_argument_errors_need_no_gpu():
     assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -1
     assert binding.vms_strerror(-6).startswith("per-trace tables")
     assert L.vms_replay_workspace_bytes(None) == 0
+
+
+def test_tables_that_exceed_the_lds_are_refused_before_any_device_call():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    # lists in LDS (at most 16,384 run entries): 4,000 pBlocks + 4,000 sBlocks + 16,000 entries do not fit 160 KB
+    cfg = binding.vms_config_default(4, 100, 9)
+    cfg.max_pblocks, cfg.max_sblocks, cfg.max_runs = 4000, 4000, 16000
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6 and not h.value
+    # the splitting policy alone needs none of these tables
+    cfg.policy_mask = 1
+    rc = L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h))
+    assert rc in (0, -5)                        # -5: no device here; the layout itself was accepted
+    if rc == 0:
+        L.vms_replay_destroy(h)
+    # lists in the workspace: the tables of the largest offloading traces fit once the last-use stamps
+    # go to the workspace too ...
+    cfg = binding.vms_config_default(4, 100, 9)
+    cfg.max_free_blocks, cfg.max_pblocks, cfg.max_sblocks, cfg.max_runs, cfg.max_chunks = 64, 8192, 4352, 1 << 21, 16384
+    rc = L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h))
+    assert rc in (0, -5)
+    if rc == 0:
+        L.vms_replay_destroy(h)
+    # ... and beyond that nothing helps
+    cfg.max_sblocks = 6000
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6
