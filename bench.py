@@ -71,7 +71,7 @@ def main():
     ap.add_argument("--traces", type=int, default=None)
     ap.add_argument("--events", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=256)
+    ap.add_argument("--cpu-sample", type=int, default=1024, help="traces the oracle is timed on (the default workload has 1,024: all of it)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the replay engine runs on one GPU only (traces are independent and would shard "
