@@ -18,6 +18,10 @@ HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
                # one wavefront per SIMD and trace: schedule for latency (instruction-level parallelism inside the
                # wave), not for occupancy; measured 3 % (stitching) and 8 % (splitting kernel) faster
                "-mllvm", "-amdgpu-sched-strategy=max-ilp", "-mllvm", "-enable-post-misched=0",
+               # no lifetime markers for locals: with them every `continue` out of a scope that holds a local
+               # whose address was taken goes through a shared clean-up block and a switch on where to go next,
+               # which LLVM does not thread away in these kernels (one flag test and two branches per event)
+               "-Xclang", "-disable-lifetime-markers",
                "-Wno-inline-asm"]       # write_lane() names m0, which the compiler reserves but does not use here
 
 

@@ -566,6 +566,11 @@ struct VmsT {
     static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
     static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
     static DI u32 cnt(meta_t m) { return BIG ? (u32)m : (u32)m & 0xFFFFu; }
+    static DI meta_t pinm(meta_t m)             // pin() for a list place
+    {
+        if constexpr (BIG) return pin64(m);
+        else return pin(m);
+    }
 };
 
 DI u32 from_lane_any(u32 v, u32 l) { return from_lane(v, l); }
@@ -1022,49 +1027,12 @@ DI bool s1_sblock_from(VmsT<BIG> &V, u32 bsize, u32 base, u32 &ref, u32 &list)
     }
 }
 
-// The usual route costs four dependent LDS round trips: the block of keys that the rank search
-// reads (first level in registers) is taken as the first tile of candidates right away, together
-// with their witnesses and list places; then the witnesses' bitmap words; then the list of the
-// first candidate not ruled out; then the bitmap words of its entries.  Anything unusual (a long
-// list, a candidate that turns out active, a run of equal sizes that
-// leaves the tile) goes the general route.
-template <bool BIG>
-DI bool s1_sblock(VmsT<BIG> &V, u32 bsize, u32 &ref, u32 &list)
-{
-    const u32 lane = lane_id();
-    const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
-    if (UNLIKELY(V.sp.stride >= 64)) return s1_sblock_from(V, bsize, rank_fast<BIG>(V.sp, V.skey, V.ns, q), ref, list);
-    // keys greater than q end at most `stride` < 64 places into the block: the first sBlock of bsize
-    // chunks, if there is one, lies inside the tile
-    const u32 c = popc64(ballot(V.sp.v > q));
-    const u32 b0 = (c ? c - 1 : 0u) * V.sp.stride;
-    const u32 i = b0 + lane;
-    const u64 key = V.skey[i];
-    const u32 wit = V.swit[i];
-    const auto meta = V.smeta[i];
-    const u64 vm = ballot((u32)(key >> 32) == bsize);
-    if (UNLIKELY(!vm)) return false;
-    const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
-    const u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
-    if (UNLIKELY(!unknown)) {
-        if (~vm >> 63) return false;            // the run of equal sizes ended inside the tile: all known active
-        return s1_sblock_from(V, bsize, b0 + 64, ref, list);
-    }
-    const u32 l = first_lane(unknown);
-    const auto m = from_lane_any(meta, l);
-    const u32 off = V.off(m), cnt = V.cnt(m);
-    const u32 e0 = pin(V.arena[off + lane]);
-    const u32 e = lane < cnt ? e0 : V.e_skip;
-    const u32 word = pin(V.bmp[ENT_WORD(e)]);
-    if (LIKELY(cnt <= 64 && !ballot((word & emask(e)) != 0))) {
-        entries_apply(V, e, lane < cnt, true);
-        st_one(V.sstamp, b0 + l, ++V.clock);
-        ref = ~from_lane((u32)key, l);
-        list = (u32)m;
-        return true;
-    }
-    return s1_sblock_from(V, bsize, b0 + l, ref, list);
-}
+// (The usual route is written out in the replay loop and costs four dependent LDS round trips:
+// the block of keys that the rank search reads, first level in registers, is taken as the first
+// tile of candidates right away, together with their witnesses and list places; then the
+// witnesses' bitmap words; then the list of the first candidate not ruled out; then the bitmap
+// words of its entries.  Anything unusual - a long list, a candidate that turns out active, a run
+// of equal sizes that leaves the tile - comes here.)
 
 // ---- S1, primitive blocks: the first inactive pBlock of exactly bsize chunks in pool order.  As
 // above, the block of the rank search doubles as the first tile of candidates.
@@ -1565,15 +1533,67 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
             if (LIKELY(size >= P.small_limit_units)) {
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
-                if (LIKELY(s1_sblock(V, bsize, ref, list))) {
-                    S.bind(slot, size, ref, KIND_SBLOCK | (bsize << 2), list);
-                    requested += size;
-                    active += bsize << P.chunk_shift;
-                    // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
-                    peak_requested = max(peak_requested, requested);
-                    peak_active = max(peak_active, active);
-                    EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)
+                // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
+#define S1_SBLOCK_HIT                                                      \
+    {                                                                      \
+        S.bind(slot, size, ref, KIND_SBLOCK | (bsize << 2), list);         \
+        requested += size;                                                 \
+        active += bsize << P.chunk_shift;                                  \
+        peak_requested = max(peak_requested, requested);                   \
+        peak_active = max(peak_active, active);                            \
+        EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)                          \
+    }
+                // S1 on stitched blocks, the usual way (see s1_sblock_from for the general route).  It is
+                // written out here, not called, so that the hit leaves for the next event from where it
+                // is found: returned through a function it would meet the other outcomes again and
+                // cost a flag and two branches to tell them apart.
+                u32 from = NONE32;              // where the general route goes on; NONE32: no inactive sBlock of this size
+                switch (0) {
+                default:
+                    const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
+                    if (UNLIKELY(V.sp.stride >= 64)) {
+                        from = rank_fast<BIG>(V.sp, V.skey, V.ns, q);
+                        break;
+                    }
+                    // keys greater than q end at most `stride` < 64 places into the block: the first
+                    // sBlock of bsize chunks, if there is one, lies inside the tile
+                    const u32 c = popc64(ballot(V.sp.v > q));
+                    const u32 b0 = (c ? c - 1 : 0u) * V.sp.stride;
+                    const u32 i = b0 + lane;
+                    // (pinned, after all three loads are on their way: one round trip, not the last two
+                    // behind the branch)
+                    const u64 key = V.skey[i];
+                    const u32 wit0 = V.swit[i];
+                    const auto meta0 = V.smeta[i];
+                    const u32 wit = pin(wit0);
+                    const auto meta = VmsT<BIG>::pinm(meta0);
+                    const u64 vm = ballot((u32)(key >> 32) == bsize);
+                    if (UNLIKELY(!vm)) break;
+                    const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
+                    const u64 unknown = vm & ~ballot((wv & emask(wit)) != 0);
+                    if (UNLIKELY(!unknown)) {
+                        if (~vm >> 63) break;   // the run of equal sizes ended inside the tile: all known active
+                        from = b0 + 64;
+                        break;
+                    }
+                    const u32 l = first_lane(unknown);
+                    const auto m = from_lane_any(meta, l);
+                    const u32 off = V.off(m), cnt = V.cnt(m);
+                    const u32 e0 = pin(V.arena[off + lane]);
+                    const u32 e = lane < cnt ? e0 : V.e_skip;
+                    const u32 word = pin(V.bmp[ENT_WORD(e)]);
+                    if (LIKELY(cnt <= 64 && !ballot((word & emask(e)) != 0))) {
+                        entries_apply(V, e, lane < cnt, true);
+                        st_one(V.sstamp, b0 + l, ++V.clock);
+                        ref = ~from_lane((u32)key, l);
+                        list = (u32)m;
+                        S1_SBLOCK_HIT
+                    }
+                    from = b0 + l;
                 }
+                if (UNLIKELY(from != NONE32))
+                    if (s1_sblock_from(V, bsize, from, ref, list)) S1_SBLOCK_HIT
+#undef S1_SBLOCK_HIT
                 if (s1_pblock(V, bsize, ref)) {
                     bmp_fill(V.bmp, ENT_WORD(V.e_skip), ref, bsize, true);
                     S.set_a(slot, ref);

@@ -288,7 +288,8 @@ DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
 // register too (one scalar register operand per vector instruction).
 DI u32 write_lane(u32 vec, u32 val, u32 lane)
 {
-    asm("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(vec) : "s"(val), "s"(lane) : "m0");
+    // (uni(): a value the compiler cannot prove wave-uniform would arrive in a vector register)
+    asm("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(vec) : "s"(uni(val)), "s"(uni(lane)) : "m0");
     return vec;
 }
 // four vectors, the same lane
@@ -297,7 +298,7 @@ DI void write_lane4(u32 &a, u32 &b, u32 &c, u32 &d, u32 va, u32 vb, u32 vc, u32 
     asm("s_mov_b32 m0, %8\n\ts_nop 0\n\tv_writelane_b32 %0, %4, m0\n\tv_writelane_b32 %1, %5, m0\n\t"
         "v_writelane_b32 %2, %6, m0\n\tv_writelane_b32 %3, %7, m0"
         : "+v"(a), "+v"(b), "+v"(c), "+v"(d)
-        : "s"(va), "s"(vb), "s"(vc), "s"(vd), "s"(lane)
+        : "s"(uni(va)), "s"(uni(vb)), "s"(uni(vc)), "s"(uni(vd)), "s"(uni(lane))
         : "m0");
 }
 
