@@ -364,10 +364,24 @@ struct SplitLds {
         wave_sync();
     }
     DI u32 reserved() const { return sp.reserved; }
-    template <class AcctT>
-    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r) { sp_alloc(sp, size, seg, may_grow, A, ev, r); }
-    template <class AcctT>
-    DI void release(u32 addr, u32 size, u32 flags, bool *ml, bool *mr, AcctT &A, u32 ev) { sp_free(sp, addr, size, flags, ml, mr, A, ev); }
+    // done(code, addr, flags, split) once the request is decided (code C_OOM: it failed), ovf() if
+    // the table is full instead (see SplitRegs)
+    template <class AcctT, class Done, class Ovf>
+    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, Done done, Ovf ovf)
+    {
+        SplitRes r;
+        sp_alloc(sp, size, seg, may_grow, A, ev, r);
+        if (UNLIKELY(A.stop)) ovf();
+        else done(r.code, r.addr, r.flags, r.split);
+    }
+    template <class AcctT, class Done, class Ovf>
+    DI void release(u32 addr, u32 size, u32 flags, AcctT &A, u32 ev, Done done, Ovf ovf)
+    {
+        bool ml, mr;
+        sp_free(sp, addr, size, flags, &ml, &mr, A, ev);
+        if (UNLIKELY(A.stop)) ovf();
+        else done(ml, mr);
+    }
 };
 
 // The inactive blocks in registers: key t * 64 + l of the array is k[t] of lane l, 0 = empty place.
@@ -408,10 +422,12 @@ struct SplitRegs {
         }
         n++;
     }
-    template <class AcctT>
-    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, SplitRes &r)
+    // Every outcome ends in a call of its own: done(code, addr, flags, split) once the request is
+    // decided (code C_OOM: it failed) or ovf() if the table is full.  Results handed back through
+    // one return would meet again in flags that the caller has to test, event after event.
+    template <class AcctT, class Done, class Ovf>
+    DI void alloc(u32 size, u32 seg, bool may_grow, AcctT &A, u32 ev, Done done, Ovf ovf)
     {
-        r.split = false;
         // step 1: best fit = smallest key not below (size, address 0); an empty place never fits
         u64 best = ~0ull;
 #pragma unroll
@@ -421,7 +437,6 @@ struct SplitRegs {
         }
         const u32 hi = (u32)(best >> 32);
         const u32 mhi = wave_min_u32(hi);
-        u32 bsize;
         if (LIKELY(mhi != NONE32)) {
             const u64 m = ballot(hi == mhi);
             u32 owner = first_lane(m);
@@ -432,51 +447,47 @@ struct SplitRegs {
             }
             const u32 blo = from_lane((u32)best, owner);
             const u64 chosen = ((u64)mhi << 32) | blo;
-            r.addr = blo >> 2;
-            r.flags = blo & 3;
+            const u32 addr = blo >> 2, flags = blo & 3;
             if (LIKELY(mhi > size)) {
                 // step 2: cut off what is not needed; it stays cached as the right neighbour, in the
                 // place the block had
-                swap_key(chosen, ((u64)(mhi - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1));
+                swap_key(chosen, ((u64)(mhi - size) << 32) | ((u64)(addr + size) << 2) | (flags & 1));
                 A.peak(SC_HW_FREE, n);
-                r.flags &= 2;
-                r.split = true;
-                r.code = C_SPLIT;
                 A.add(SC_N_SPLIT, 1);
-            } else {
-                swap_key(chosen, 0);
-                n--;
-                r.code = C_EXACT;
-            }
-            return;
-        } else {
-            if (!may_grow) {
-                r.code = C_OOM;
-                r.addr = r.flags = 0;
+                done((u32)C_SPLIT, addr, flags & 2, true);
                 return;
             }
-            r.addr = res;                       // "native allocation": a fresh segment
-            res += seg;
-            bsize = seg;
-            r.flags = 3;
-            r.code = C_GROW;
+            swap_key(chosen, 0);
+            n--;
+            done((u32)C_EXACT, addr, flags, false);
+            return;
         }
-        if (bsize > size) {                     // the rest of a fresh segment
+        if (!may_grow) {
+            done((u32)C_OOM, 0u, 0u, false);
+            return;
+        }
+        const u32 addr = res;                   // "native allocation": a fresh segment
+        res += seg;
+        if (seg > size) {                       // the rest of a fresh segment
             if (n == cap) {
                 A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
+                ovf();
                 return;
             }
-            insert(((u64)(bsize - size) << 32) | ((u64)(r.addr + size) << 2) | (r.flags & 1));
+            insert(((u64)(seg - size) << 32) | ((u64)(addr + size) << 2) | 1u);
             A.peak(SC_HW_FREE, n);
-            r.flags &= 2;
-            r.split = true;
             A.add(SC_N_SPLIT, 1);
+            done((u32)C_GROW, addr, 2u, true);
+            return;
         }
+        done((u32)C_GROW, addr, 3u, false);
     }
     // steps 3 and 4: the block becomes inactive and absorbs inactive neighbours of its segment
-    template <class AcctT>
-    DI void release(u32 addr, u32 size, u32 flags, bool *ml, bool *mr, AcctT &A, u32 ev)
+    template <class AcctT, class Done, class Ovf>
+    DI void release(u32 addr, u32 size, u32 flags, AcctT &A, u32 ev, Done done, Ovf ovf)
     {
+        bool ml_, mr_;
+        bool *ml = &ml_, *mr = &mr_;
         const bool can_l = !(flags & 2), can_r = !(flags & 1);
         const u32 end = addr + size;
         // at most one block ends where this one starts and at most one starts where it ends: every
@@ -515,11 +526,13 @@ struct SplitRegs {
         } else {
             if (n == cap) {
                 A.overflow(ev, VMS_ST_OVF_FREE_BLOCKS);
+                ovf();
                 return;
             }
             insert(key);
             A.peak(SC_HW_FREE, n);
         }
+        done(ml_, mr_);
     }
 };
 
@@ -1746,59 +1759,69 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
             ev_next = nx < n_ev ? x : 0;
         }
         u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
-        u32 done = tile;
+        u32 done = tile, todo = tile;       // todo drops to 0 when the free list overflows: the trace ends there
         u32 w_next = from_lane(ev_lo, 0), slot_next = from_lane(ev_hi, 0);     // one event ahead
-        for (u32 j = 0; j < tile; j++) {
+        for (u32 j = 0; j < todo; j++) {
             const u32 w = w_next, slot = slot_next;
             w_next = from_lane(ev_lo, (j + 1) & 63);
             slot_next = from_lane(ev_hi, (j + 1) & 63);
-            u32 dlo = C_INVALID, dhi = 0;
-            do {
-                if (UNLIKELY(slot >= P.max_slots)) break;
-                const u32 req = S.get_req(slot);
-                if ((int)w < 0) {
-                    if (UNLIKELY(req + 1u <= 1u)) {         // unbound, or bound to a request that failed
-                        if (req == SLOT_OOM) {
-                            S.set_req(slot, (u32)SLOT_UNBOUND);
-                            dlo = C_FREE_NOOP;
-                        }
-                        break;
-                    }
-                    const u32 a = S.get_a(slot);
-                    S.set_req(slot, (u32)SLOT_UNBOUND);
-                    bool ml, mr;
-                    sp.release(a >> 2, req, a & 3, &ml, &mr, A, base + j);
-                    requested -= req;
-                    dlo = C_FREE | (ml ? B_6 : 0u) | (mr ? B_7 : 0u);
-                    dhi = a >> 2;
-                    break;
-                }
-                const u32 size = w;
-                if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) break;
-                const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
-                SplitRes r;
-                sp.alloc(size, seg, sp.reserved() + seg <= P.capacity_units, A, base + j, r);
-                if (UNLIKELY(A.stop)) break;
-                if (UNLIKELY(r.code == C_OOM)) {
-                    S.set_req(slot, (u32)SLOT_OOM);
-                    if (A.f[SC_FIRST_OOM] == NONE32) A.f[SC_FIRST_OOM] = base + j;
-                    dlo = C_OOM;
-                    break;
-                }
-                S.set_a(slot, (r.addr << 2) | r.flags);
-                S.set_req(slot, size);
-                dlo = r.code | (r.split ? B_6 : 0u) | ((r.code == C_GROW ? 0u : 1u) << 8);
-                dhi = r.addr;
-                // blocks are cut to the request: active bytes are the requested bytes
-                requested += size;
-                peak_requested = max(peak_requested, requested);
-            } while (0);
-            wave_sync();
-            if (UNLIKELY(A.stop)) {                         // the free list overflowed: the trace ends here
+            // every path of an event ends by parking its results in lane j; none hands a result to
+            // a common tail (that would cost flags to test)
+            auto emit = [&](u32 dlo, u32 dhi) {
+                write_lane4(v_dlo, v_dhi, v_act, v_res, dlo, dhi, requested, sp.reserved(), j);
+                wave_sync();
+            };
+            auto overflow = [&]() {
                 done = j;
-                break;
+                todo = 0;
+            };
+            if (UNLIKELY(slot >= P.max_slots)) {
+                emit((u32)C_INVALID, 0u);
+                continue;
             }
-            write_lane4(v_dlo, v_dhi, v_act, v_res, dlo, dhi, requested, sp.reserved(), j);
+            const u32 req = S.get_req(slot);
+            if ((int)w < 0) {
+                if (UNLIKELY(req + 1u <= 1u)) {             // unbound, or bound to a request that failed
+                    if (req == SLOT_OOM) {
+                        S.set_req(slot, (u32)SLOT_UNBOUND);
+                        emit((u32)C_FREE_NOOP, 0u);
+                        continue;
+                    }
+                    emit((u32)C_INVALID, 0u);
+                    continue;
+                }
+                const u32 a = S.get_a(slot);
+                S.set_req(slot, (u32)SLOT_UNBOUND);
+                sp.release(a >> 2, req, a & 3, A, base + j,
+                           [&](bool ml, bool mr) {
+                               requested -= req;
+                               emit(C_FREE | (ml ? B_6 : 0u) | (mr ? B_7 : 0u), a >> 2);
+                           },
+                           overflow);
+                continue;
+            }
+            const u32 size = w;
+            if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) {
+                emit((u32)C_INVALID, 0u);
+                continue;
+            }
+            const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
+            sp.alloc(size, seg, sp.reserved() + seg <= P.capacity_units, A, base + j,
+                     [&](u32 code, u32 addr, u32 flags, bool split) {
+                         if (code == C_OOM) {
+                             S.set_req(slot, (u32)SLOT_OOM);
+                             if (A.f[SC_FIRST_OOM] == NONE32) A.f[SC_FIRST_OOM] = base + j;
+                             emit((u32)C_OOM, 0u);
+                             return;
+                         }
+                         S.set_a(slot, (addr << 2) | flags);
+                         S.set_req(slot, size);
+                         // blocks are cut to the request: active bytes are the requested bytes
+                         requested += size;
+                         peak_requested = max(peak_requested, requested);
+                         emit(code | (split ? B_6 : 0u) | ((code == C_GROW ? 0u : 1u) << 8), addr);
+                     },
+                     overflow);
         }
         tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
         if (A.stop) break;
