@@ -1059,7 +1059,7 @@ DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
         base = rank_fast<BIG>(V.pp, V.pool, V.np, q);
     } else {
         const u32 c = popc64(ballot(V.pp.v > q));
-        base = (c ? c - 1 : 0u) * V.pp.stride;  // the first pBlock of bsize chunks lies inside this tile
+        base = dec_sat(c) * V.pp.stride;  // the first pBlock of bsize chunks lies inside this tile
     }
     for (;;) {
         const u32 i = base + lane;
@@ -1105,7 +1105,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
         if (LIKELY(V.pp.stride <= 64)) {
             // the first search level is in registers and still describes the pool: one LDS round trip
             const u32 c1 = popc64(ballot(V.pp.v > k1)), c2 = popc64(ballot(V.pp.v > k2));
-            const u32 b1 = (c1 ? c1 - 1 : 0u) * V.pp.stride, b2 = (c2 ? c2 - 1 : 0u) * V.pp.stride;
+            const u32 b1 = dec_sat(c1) * V.pp.stride, b2 = dec_sat(c2) * V.pp.stride;
             const u64 v1 = V.pool[b1 + lane], v2 = V.pool[b2 + lane];
             lo_p = b1 + popc64(ballot(v1 > k1));
             hi_p = b2 + popc64(ballot(v2 > k2));
@@ -1476,6 +1476,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     const u64 *ev_row = events + (size_t)trace * P.max_events;
     u64 *dec_row = decisions ? decisions + (size_t)trace * P.max_events : nullptr;
 
+    u32 fast_limit = P.small_limit_units;   // requests from this size on take the usual S1 route (renewed with the probe)
     u64 ev_next = lane < n_ev ? ev_row[lane] : 0;
     for (u32 base = 0; base < n_ev; base += 64) {
         const u32 tile = min(64u, n_ev - base);
@@ -1543,7 +1544,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
             // ---- ALLOC
             const u32 size = w;
             if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) EMIT((u32)C_INVALID, 0u)
-            if (LIKELY(size >= P.small_limit_units)) {
+            if (LIKELY(size >= fast_limit)) {
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
                 // Sec. 5.1: active memory is recorded at its peak; the totals only rise on an allocation
@@ -1564,14 +1565,10 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 switch (0) {
                 default:
                     const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
-                    if (UNLIKELY(V.sp.stride >= 64)) {
-                        from = rank_fast<BIG>(V.sp, V.skey, V.ns, q);
-                        break;
-                    }
                     // keys greater than q end at most `stride` < 64 places into the block: the first
                     // sBlock of bsize chunks, if there is one, lies inside the tile
                     const u32 c = popc64(ballot(V.sp.v > q));
-                    const u32 b0 = (c ? c - 1 : 0u) * V.sp.stride;
+                    const u32 b0 = dec_sat(c) * V.sp.stride;
                     const u32 i = b0 + lane;
                     // (pinned, after all three loads are on their way: one round trip, not the last two
                     // behind the branch)
@@ -1606,19 +1603,30 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 }
                 if (UNLIKELY(from != NONE32))
                     if (s1_sblock_from(V, bsize, from, ref, list)) S1_SBLOCK_HIT
-#undef S1_SBLOCK_HIT
-                if (s1_pblock(V, bsize, ref)) {
-                    bmp_fill(V.bmp, ENT_WORD(V.e_skip), ref, bsize, true);
-                    S.set_a(slot, ref);
-                    S.set_b(slot, KIND_PBLOCK | (bsize << 2));
-                    S.set_req(slot, size);
-                    requested += size;
-                    active += bsize << P.chunk_shift;
-                    peak_requested = max(peak_requested, requested);
-                    peak_active = max(peak_active, active);
-                    EMIT(C_EXACT | (1u << 8), ref)
-                }
+#define S1_PBLOCK_TRY                                                      \
+    if (s1_pblock(V, bsize, ref)) {                                        \
+        bmp_fill(V.bmp, ENT_WORD(V.e_skip), ref, bsize, true);             \
+        S.set_a(slot, ref);                                                \
+        S.set_b(slot, KIND_PBLOCK | (bsize << 2));                         \
+        S.set_req(slot, size);                                             \
+        requested += size;                                                 \
+        active += bsize << P.chunk_shift;                                  \
+        peak_requested = max(peak_requested, requested);                   \
+        peak_active = max(peak_active, active);                            \
+        EMIT(C_EXACT | (1u << 8), ref)                                     \
+    }
+                S1_PBLOCK_TRY
+            } else if (UNLIKELY(size >= P.small_limit_units)) {
+                // more than 4,032 sBlocks cached: their first search level no longer selects a single
+                // tile (fast_limit keeps such a trace off the route above, at no cost to the others)
+                const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
+                u32 ref, list = 0;
+                const u32 from = rank_fast<BIG>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
+                if (s1_sblock_from(V, bsize, from, ref, list)) S1_SBLOCK_HIT
+                S1_PBLOCK_TRY
             }
+#undef S1_PBLOCK_TRY
+#undef S1_SBLOCK_HIT
             // ---- the rare cases: no exact fit (states S2 to S5), or a request below one chunk
             u32 dlo, dhi = 0, held_units = size;
             wave_sync();
@@ -1631,6 +1639,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 // the pools may have changed: renew the first search level of both
                 probe_refresh(V.sp, V.skey, V.ns);
                 probe_refresh(V.pp, V.pool, V.np);
+                fast_limit = V.sp.stride >= 64 ? NONE32 : P.small_limit_units;
                 // lists have moved: every slot holding an sBlock looks its list up again
                 if (USE_LIST && UNLIKELY(compacted)) S.relist(V.skey, (const u32 *)V.smeta, V.ns);
                 if (UNLIKELY(!went)) {                                // an engine table overflowed: the trace ends here

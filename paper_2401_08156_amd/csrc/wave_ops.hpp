@@ -21,6 +21,10 @@ DI void wave_sync()
     __builtin_amdgcn_wave_barrier();
 }
 
+// c - 1, or 0 for 0, on a wave-uniform count: two scalar instructions (the conditional form is
+// compiled into a clamped vector subtract and a v_readfirstlane)
+DI u32 dec_sat(u32 c) { return c - min(c, 1u); }
+
 DI u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 DI u32 first_lane(u64 mask) { return (u32)__builtin_ctzll(mask); }
 DI u32 popc64(u64 m) { return (u32)__builtin_popcountll(m); }
@@ -141,7 +145,7 @@ DI u32 rank_desc(const u64 *a, u32 n, u64 key)
     if (n > 4096) return count_gt(a, n, key);
     const u32 stride = (n + 63) >> 6;
     const u32 c = popc64(ballot(a[lane * stride] > key));    // probes above key form a prefix
-    const u32 b0 = (c ? c - 1 : 0u) * stride;                // a[b0] > key >= a[b0 + stride] (if c)
+    const u32 b0 = dec_sat(c) * stride;                // a[b0] > key >= a[b0 + stride] (if c)
     return b0 + popc64(ballot(a[b0 + lane] > key));          // keys from b0 + stride on are not greater
 }
 
@@ -162,7 +166,7 @@ DI void rank_desc2(const u64 *a, u32 n, u64 k1, u64 k2, u32 *r1, u32 *r2)
     const u32 stride = (n + 63) >> 6;
     const u64 pv = a[lane * stride];
     const u32 c1 = popc64(ballot(pv > k1)), c2 = popc64(ballot(pv > k2));
-    const u32 b1 = (c1 ? c1 - 1 : 0u) * stride, b2 = (c2 ? c2 - 1 : 0u) * stride;
+    const u32 b1 = dec_sat(c1) * stride, b2 = dec_sat(c2) * stride;
     const u64 v1 = a[b1 + lane], v2 = a[b2 + lane];
     *r1 = b1 + popc64(ballot(v1 > k1));
     *r2 = b2 + popc64(ballot(v2 > k2));
@@ -279,7 +283,7 @@ DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
 {
     if (WIDE && p.stride > 64) return rank_probe(p, a, n, key);
     const u32 c = popc64(ballot(p.v > key));
-    const u32 b0 = (c ? c - 1 : 0u) * p.stride;
+    const u32 b0 = dec_sat(c) * p.stride;
     return b0 + popc64(ballot(a[b0 + lane_id()] > key));
 }
 
