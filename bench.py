@@ -167,6 +167,9 @@ def main():
                    "batches": len(batches), "lds_bytes_per_wave": {"split": lds[0], "vms": lds[1]}},
         "policy_events_per_s": 2 * total_events / (dt / args.steps),     # every event is decided under both policies
         "kernel_ms": kernel_ms,
+        # one wavefront per (trace, policy); how many fit a compute unit at once is set by their LDS (160 KB per CU)
+        "resident_waves_per_cu": {k: min(-(-n_traces // 256), (160 * 1024) // max(b, 1) if b else 32)
+                                  for k, b in (("split", lds[0]), ("vms", lds[1]))},
         # a single trace is a single wavefront per policy: a latency figure, not a throughput
         "ns_per_event": ms_per_step * 1e6 / n_events if n_traces == 1 else None,
         "roofline": {"bound": "hbm", "kernel": "replay_vms_kernel (stitching policy)" if dom == "vms" else "replay_split_kernel (splitting policy)",
