@@ -178,3 +178,31 @@ def test_randomised_workloads_and_parameters():
             if "table overflow" not in str(e):
                 raise
     assert ran >= 48                                      # a few draws outgrow the small arena: reported, not replayed
+
+
+def test_run_time_argument_errors_are_codes_and_launch_nothing():
+    # every call below is refused on the host, before any kernel could see a bad pointer
+    import ctypes
+    import torch
+    L = binding.lib()
+    ev, ms = tg.generate(1, n_traces=4, n_events=200, seed=3)
+    d_ev = torch.from_numpy(ev.view(np.int64)).cuda()
+    r = binding.Replay(gpu_util.make_cfg(4, 200, ms, max_runs=20000))        # lists in the workspace: one is needed
+    stats = np.zeros((2, 4), dtype=binding.STATS_DTYPE)
+    assert L.vms_replay_stats(r._h, stats.ctypes.data, stats.size) == -7      # nothing has run yet
+    summ = binding.vms_summary()
+    assert L.vms_replay_summary(r._h, ctypes.byref(summ)) == -7
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ev_ptr = ctypes.c_void_p(d_ev.data_ptr())
+    assert L.vms_replay_run(r._h, None, None, None, None, None, stream) == -1                 # no events
+    assert L.vms_replay_run(None, ev_ptr, None, None, None, None, stream) == -1               # no handle
+    assert r.workspace_bytes() > 0
+    assert L.vms_replay_run(r._h, ev_ptr, None, None, None, None, stream) == -4               # workspace missing
+    ws = torch.empty(r.workspace_bytes() + 512, dtype=torch.uint8, device="cuda")
+    odd = ((ws.data_ptr() + 255) & ~255) + 8
+    assert L.vms_replay_run(r._h, ev_ptr, None, None, None, ctypes.c_void_p(odd), stream) == -4   # misaligned
+    r.run(d_ev)                                                                # the binding brings its own
+    assert L.vms_replay_stats(r._h, stats.ctypes.data, 3) == -1               # wrong record count
+    st = r.stats()
+    assert (st["status"] & binding.VMS_ST_TABLE_OVERFLOW).sum() == 0 and (st["peak_reserved"] > 0).all()
+    r.close()
