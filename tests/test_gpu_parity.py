@@ -206,3 +206,18 @@ def test_run_time_argument_errors_are_codes_and_launch_nothing():
     st = r.stats()
     assert (st["status"] & binding.VMS_ST_TABLE_OVERFLOW).sum() == 0 and (st["peak_reserved"] > 0).all()
     r.close()
+
+
+def test_largest_requests_and_full_capacity():
+    # the engine models at most 512 GiB (2^30 units of 512 B): requests of the largest encodable size
+    # fail, two of 256 GiB fill the capacity exactly, nothing more fits, and a cached 256 GiB block is cut
+    GiB = 1 << 30
+    ev = tg.make_events([("A", 0, ((1 << 31) - 1) * 512), ("F", 0), ("A", 1, 256 * GiB), ("A", 2, 256 * GiB),
+                         ("A", 3, 2 * MiB), ("F", 3), ("F", 1), ("A", 3, 128 * GiB), ("A", 4, 128 * GiB),
+                         ("A", 5, 512), ("F", 2), ("F", 3), ("F", 4), ("A", 6, 512 * GiB - 2 * MiB), ("A", 7, 2 * MiB)])[None, :]
+    for cap in (0, 512 * GiB):
+        # (a block of 131,072 chunks may need 12,294 list entries: lists in the workspace)
+        cfg = gpu_util.make_cfg(1, ev.shape[1], 8, capacity_bytes=cap, max_chunks=1 << 18, max_runs=1 << 16)
+        st = gpu_util.assert_parity(ev, cfg, label="largest requests, capacity %d" % cap)
+        assert st["n_code"][:, 0, 5].min() >= 2                     # the 1 TiB request and the 2 MiB one fail under both policies
+        assert (st["peak_reserved"] == 512 * GiB).all()
