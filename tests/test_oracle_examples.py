@@ -119,3 +119,25 @@ def test_fragmentation_limit_hands_out_whole_block():
     assert codes == [4, 0, 2, 0, 2, 4] and cut[2] == 0 and cut[4] == 0
     assert st["peak_active"][0] == 10 * MiB and st["peak_reserved"][0] == 10 * MiB
     assert st["n_sblock_created"][0] == 0
+
+
+def test_full_device_is_reusable_only_by_stitching():
+    # Derived by hand (Sec. 2.2 against Sec. 3.3.1, Sec. 4.1): a 512 GiB device filled by two 256 GiB
+    # blocks, the first later reused as 128 + 128 GiB, everything freed.  The splitting allocator holds
+    # two inactive segments that cannot merge (different native allocations) and has no memory left
+    # to grow: a request of 512 GiB - 2 MiB fails.  The stitching allocator takes its inactive blocks
+    # largest first (256, 128, 128 GiB: state S3 with three candidates), cuts 2 MiB off the last and
+    # serves the request from memory it already has; the 2 MiB left over then serves an exact request.
+    GiB = 1 << 30
+    ev = tg.make_events([("A", 1, 256 * GiB), ("A", 2, 256 * GiB), ("F", 1), ("A", 3, 128 * GiB), ("A", 4, 128 * GiB),
+                         ("F", 2), ("F", 3), ("F", 4), ("A", 6, 512 * GiB - 2 * MiB), ("A", 7, 2 * MiB)])[None, :]
+    P = oracle.make_params(8, capacity_bytes=512 * GiB)
+    dec, st = oracle.replay(ev, P, oracle.SPLIT)
+    assert [int(d) & 15 for d in dec[0]] == [4, 4, 0, 2, 1, 0, 0, 0, 5, 2]      # ..., merge-left on the last free, OOM, split
+    assert st["peak_reserved"][0] == 512 * GiB and st["first_oom_event"][0] == 8
+    dec, st = oracle.replay(ev, P, oracle.VMS)
+    codes = [int(d) & 15 for d in dec[0]]
+    assert codes == [4, 4, 0, 2, 1, 0, 0, 0, 3, 1]
+    assert (int(dec[0][8]) >> 8) & 0xFFFFFF == 3 and int(dec[0][8]) & 0x40       # three candidates, the last one cut
+    assert st["peak_reserved"][0] == 512 * GiB and st["n_code"][0][5] == 0
+    assert st["peak_active"][0] == 512 * GiB and st["fragmentation"][0] == 0.0
