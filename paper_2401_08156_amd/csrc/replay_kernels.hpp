@@ -1193,21 +1193,26 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
             return;
         }
     }
-    // list entries created below: a run of L chunks touches at most L / 32 + 2 bitmap words
-    const u32 need = 2u * k + 3u * (((sum > bsize ? sum : bsize) >> 5) + 2u);
-    if (UNLIKELY(V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev))) {
-        A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
-        R.dec_lo = C_INVALID;
-        return;
-    }
     if (!s3 && k == 0) {
-        // nothing cached is usable: the new pBlock serves the request directly
+        // nothing cached is usable: the new pBlock serves the request directly (no list, no sBlock)
+        if (UNLIKELY(V.np + 1 > P.cap_pblocks)) {
+            A.overflow(ev, VMS_ST_OVF_PBLOCKS);
+            R.dec_lo = C_INVALID;
+            return;
+        }
         u32 start = V.n_chunks;
         pool_insert(V, deficit, start, A);
         V.n_chunks += deficit;
         bmp_fill(V.bmp, ENT_WORD(V.e_skip), start, deficit, true);
         R.ref = start;
         R.dec_lo = C_GROW;
+        return;
+    }
+    // list entries created below: a run of L chunks touches at most L / 32 + 2 bitmap words
+    const u32 need = 2u * k + 3u * (((sum > bsize ? sum : bsize) >> 5) + 2u);
+    if (UNLIKELY(V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks || !arena_reserve(V, S, need, P, A, ev))) {
+        A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
+        R.dec_lo = C_INVALID;
         return;
     }
     // second pass: the candidates' chunk runs (and the new pBlock's) are collected in tmp[] and
