@@ -104,7 +104,9 @@ typedef struct vms_config {
     uint32_t max_sblocks;        /* cached sBlocks; must exceed spool_threshold + 2          */
     uint32_t max_runs;           /* chunk runs summed over all cached sBlocks                */
     uint32_t max_chunks;         /* physical chunks of the VMS large path                    */
-    uint32_t reserved0;
+    uint32_t max_small_blocks;   /* VMS: inactive blocks of its pool for requests below
+                                    small_limit_bytes; 0 = max_free_blocks.  At most 192:
+                                    that pool is held in registers                           */
 } vms_config;
 
 typedef struct vms_trace_stats {        /* one per (policy, trace) */

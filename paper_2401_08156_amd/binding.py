@@ -25,7 +25,7 @@ class vms_config(ctypes.Structure):
                 ("spool_threshold", ctypes.c_uint32), ("max_slots", ctypes.c_uint32),
                 ("max_free_blocks", ctypes.c_uint32), ("max_pblocks", ctypes.c_uint32),
                 ("max_sblocks", ctypes.c_uint32), ("max_runs", ctypes.c_uint32),
-                ("max_chunks", ctypes.c_uint32), ("reserved0", ctypes.c_uint32)]
+                ("max_chunks", ctypes.c_uint32), ("max_small_blocks", ctypes.c_uint32)]
 
 
 class vms_summary(ctypes.Structure):

@@ -40,6 +40,7 @@ struct KParams {
     u32 off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
         off_sstamp, off_swit, off_tmp, off_arena;
     u32 lds_bytes;
+    u32 small_regs;             // stitching kernel: its pool for small requests is held in registers (cap_free <= 192)
     u32 ws_stamp_off;           // BIG only: not 0 = sstamp[] lives at this byte offset of the trace's workspace slice
     u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
 };
@@ -1459,7 +1460,10 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     V.tmp[(P.cap_chunks + 31) / 32 + lane] = 0;             // 64 spare words: where idle lanes OR their zeros
     // the searches read up to 64 places past the live part of pool[], skey[], swit[] and arena[]
     // without clamping: zero keys there, and witnesses / entries on words that exist
-    for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;
+    if (!P.small_regs)
+        for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;
+    SplitRegs<3> Q;                                         // the pool for small requests, if it fits registers
+    Q.init(lds, P);
     for (u32 i = lane; i < P.cap_pblocks + 64; i += 64) V.pool[i] = 0;
     for (u32 i = lane; i < P.cap_sblocks + 64; i += 64) {
         V.skey[i] = 0;
@@ -1534,6 +1538,24 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                     bmp_fill(V.bmp, ENT_WORD(V.e_skip), a, b >> 2, false);
                     active -= (b >> 2) << P.chunk_shift;
                     EMIT((u32)C_FREE, a)
+                }
+                if (LIKELY(P.small_regs)) {
+                    AcctLds A;
+                    A.sc = (u32 *)(lds + LDS_SCALARS);
+                    A.idle = V.idle;
+                    Q.release(a >> 2, req, a & 3, A, base + j,
+                              [&](bool ml, bool mr) {
+                                  active -= req;
+                                  write_lane4(v_dlo, v_dhi, v_act, v_res, C_FREE | B_SMALL | (ml ? B_6 : 0u) | (mr ? B_7 : 0u),
+                                              a >> 2, active, sp_reserved + (V.n_chunks << P.chunk_shift), j);
+                                  wave_sync();
+                              },
+                              [&]() {
+                                  stop = true;
+                                  done = j;
+                                  todo = 0;
+                              });
+                    continue;
                 }
                 bool ml, mr;
                 small_free(lds, P, V.idle, a >> 2, req, a & 3, base + j, &ml, &mr);
@@ -1664,6 +1686,42 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
             } else {
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
                 const u32 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
+                if (LIKELY(P.small_regs)) {
+                    AcctLds A;
+                    A.sc = (u32 *)(lds + LDS_SCALARS);
+                    A.idle = V.idle;
+                    Q.alloc(size, seg, reserved + seg <= P.capacity_units, A, base + j,
+                            [&](u32 code, u32 addr, u32 flags, bool split) {
+                                sp_reserved = Q.reserved();
+                                u32 d_lo = C_OOM, d_hi = 0;
+                                if (code == C_OOM) {
+                                    S.set_req(slot, (u32)SLOT_OOM);
+                                    ColdState C;            // rare: note the first failed request
+                                    C.load(lds);
+                                    if (C.get(SC_FIRST_OOM) == NONE32)
+                                        st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_FIRST_OOM, base + j);
+                                } else {
+                                    S.set_a(slot, (addr << 2) | flags);
+                                    S.set_b(slot, (u32)KIND_SMALL);
+                                    S.set_req(slot, size);
+                                    requested += size;
+                                    active += size;
+                                    peak_requested = max(peak_requested, requested);
+                                    peak_active = max(peak_active, active);
+                                    d_lo = code | B_SMALL | (split ? B_6 : 0u) | ((code == C_GROW ? 0u : 1u) << 8);
+                                    d_hi = addr;
+                                }
+                                write_lane4(v_dlo, v_dhi, v_act, v_res, d_lo, d_hi, active,
+                                            sp_reserved + (V.n_chunks << P.chunk_shift), j);
+                                wave_sync();
+                            },
+                            [&]() {
+                                stop = true;
+                                done = j;
+                                todo = 0;
+                            });
+                    continue;
+                }
                 SplitRes r;
                 small_alloc(lds, P, V.idle, size, seg, reserved + seg <= P.capacity_units, base + j, r, sp_reserved);
                 if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {

@@ -71,7 +71,7 @@ void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_reg
         k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
     }
     // the splitting policy keeps small pools in registers: no LDS array then
-    k.off_fl = (!policy && c.max_free_blocks <= 192) ? 0 : take((c.max_free_blocks + 128) * 8);   // 128 spare places: scans read whole tiles
+    k.off_fl = k.cap_free <= 192 ? 0 : take((k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
     if (policy) {
         // 64 spare places behind each searched array: reads there need no bounds check
         k.off_pool = take((c.max_pblocks + 64) * 8);
@@ -171,7 +171,9 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
         k.spool_threshold = c.spool_threshold;
         k.capacity_units = (uint32_t)(cap / UNIT);
         k.max_slots = c.max_slots;
-        k.cap_free = c.max_free_blocks;
+        // the stitching policy's pool for small requests may be given a size of its own
+        k.cap_free = p && c.max_small_blocks ? c.max_small_blocks : c.max_free_blocks;
+        k.small_regs = p && k.cap_free <= 192;
         k.cap_pblocks = c.max_pblocks;
         k.cap_sblocks = c.max_sblocks;
         k.cap_runs = c.max_runs;

@@ -11,12 +11,13 @@ NAMES = {1: "config1-random", 2: "config2-recompute", 3: "config3-offload", 4: "
          5: "config5-mixture", 6: "config6-zero3-scaleout"}
 
 TABLES = {
-    # config: splitting free list, pBlocks, sBlocks, chunk-run list entries, chunks (x 2 MiB)
+    # config: splitting free list (max_small_blocks: the stitching policy's own, smaller one), pBlocks, sBlocks,
+    # chunk-run list entries, chunks (x 2 MiB)
     1: dict(max_free_blocks=512, max_pblocks=1024, max_sblocks=640, max_runs=4096, max_chunks=8192),
     2: dict(max_free_blocks=192, max_pblocks=544, max_sblocks=576, max_runs=3840, max_chunks=4096),
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks, runs kept in HBM
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=3584, max_runs=1 << 20, max_chunks=16384),
-    4: dict(max_free_blocks=320, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576),
+    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576),
     6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
 }
 # config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
@@ -24,7 +25,7 @@ TABLES = {
 TABLES_5 = {
     2: dict(max_free_blocks=192, max_pblocks=640, max_sblocks=640, max_runs=5120, max_chunks=4096),
     3: dict(max_free_blocks=64, max_pblocks=8192, max_sblocks=4352, max_runs=1 << 21, max_chunks=16384),
-    4: dict(max_free_blocks=320, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576),
+    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576),
 }
 
 

@@ -40,6 +40,13 @@ def test_splitting_pool_in_registers():
     cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=6)
     _, _, st = gpu_util.gpu_replay(ev, cfg)
     assert (st["status"][0] & binding.VMS_ST_TABLE_OVERFLOW).all()
+    # the stitching policy's pool for requests below one chunk may have a size of its own: in registers
+    # beside a splitting pool in LDS, and too small (reported for that policy only)
+    cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=512, max_small_blocks=192)
+    gpu_util.assert_parity(ev, cfg, label="config 1, small pool of the stitching policy in registers")
+    cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=512, max_small_blocks=3)
+    _, _, st = gpu_util.gpu_replay(ev, cfg)
+    assert (st["status"][1] & binding.VMS_ST_OVF_FREE_BLOCKS).all() and (st["status"][0] == 0).all()
 
 
 def test_worked_examples_on_gpu():
