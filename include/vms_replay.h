@@ -107,6 +107,11 @@ typedef struct vms_config {
     uint32_t max_small_blocks;   /* VMS: inactive blocks of its pool for requests below
                                     small_limit_bytes; 0 = max_free_blocks.  At most 192:
                                     that pool is held in registers                           */
+    uint32_t max_multi_pblocks;  /* VMS, tables of the fine-grained variant (more than 16384
+                                    runs, or more than 4096 pBlocks or sBlocks): pBlocks of
+                                    two or more chunks, at most 4096; 0 = min(max_pblocks,
+                                    4096).  pBlocks of one chunk take no table space there   */
+    uint32_t reserved0;          /* 0                                                        */
 } vms_config;
 
 typedef struct vms_trace_stats {        /* one per (policy, trace) */
@@ -129,6 +134,9 @@ typedef struct vms_trace_stats {        /* one per (policy, trace) */
                                     max_members = most blocks stitched into one sBlock       */
     uint32_t max_runs;           /* high-water mark of chunk runs held by cached sBlocks     */
     uint32_t overflow_event;     /* event at which a table overflowed, else 0xFFFFFFFF       */
+    uint32_t max_multi_pblocks;  /* fine-grained variant: high-water mark of its table of
+                                    pBlocks of two or more chunks; 0 from the other kernels  */
+    uint32_t reserved1;          /* 0                                                        */
     double   fragmentation;      /* 1.0 - (double)peak_active / (double)peak_reserved;
                                     0.0 when nothing was reserved                            */
 } vms_trace_stats;

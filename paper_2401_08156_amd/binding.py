@@ -25,7 +25,8 @@ class vms_config(ctypes.Structure):
                 ("spool_threshold", ctypes.c_uint32), ("max_slots", ctypes.c_uint32),
                 ("max_free_blocks", ctypes.c_uint32), ("max_pblocks", ctypes.c_uint32),
                 ("max_sblocks", ctypes.c_uint32), ("max_runs", ctypes.c_uint32),
-                ("max_chunks", ctypes.c_uint32), ("max_small_blocks", ctypes.c_uint32)]
+                ("max_chunks", ctypes.c_uint32), ("max_small_blocks", ctypes.c_uint32),
+                ("max_multi_pblocks", ctypes.c_uint32), ("reserved0", ctypes.c_uint32)]
 
 
 class vms_summary(ctypes.Structure):
@@ -98,6 +99,7 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
                         ("max_pblocks", "<u4"), ("max_sblocks", "<u4"),
                         ("max_free_blocks", "<u4"), ("max_members", "<u4"),
                         ("max_runs", "<u4"), ("overflow_event", "<u4"),
+                        ("max_multi_pblocks", "<u4"), ("reserved1", "<u4"),
                         ("fragmentation", "<f8")])
 
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",

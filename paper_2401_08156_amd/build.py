@@ -6,7 +6,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libvmsreplay.so")
 SOURCES = ["vms_replay.hip", "vms_demo.hip", "vms_live.hip", "vms_peaks.hip"]
-HEADERS = ["wave_ops.hpp", "replay_kernels.hpp", "selftest.hpp", "../../include/vms_replay.h", "../../include/vms_live.h"]
+HEADERS = ["wave_hw.hpp", "wave_ops.hpp", "replay_plan.hpp", "replay_kernels.hpp", "replay_fine.hpp", "selftest.hpp", "../../include/vms_replay.h", "../../include/vms_live.h"]
 
 # The replay loops branch on wave-uniform conditions only (whatever would switch lanes off is written
 # with selects or kept in non-inlined functions).  With the option below LLVM leaves such regions as

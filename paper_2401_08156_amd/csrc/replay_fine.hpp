@@ -1,0 +1,994 @@
+// Replay under the stitching policy (Sec. 3, Sec. 4.1), fine-grained variant: for traces whose
+// pools grow to thousands of blocks.  Offloading streams grind the pBlocks down until nearly every
+// one is a single chunk, cache thousands of sBlocks, and stitch a new sBlock from a hundred
+// candidates for every other request.  One wavefront still replays one trace, but its tables are
+// laid out for that regime, in a quarter of the LDS the flat sorted arrays of replay_kernels.hpp
+// would need, so that four such wavefronts share a compute unit:
+//
+//   bnd[]   one bit per physical chunk: set where a pBlock starts (and at the end of the last one).
+//           pBlocks are only ever created behind the last chunk (Alloc) or cut in two (Split), so
+//           the set bits are exactly the pBlock boundaries.
+//   bmp[]   one bit per chunk: set while the pBlock that owns it is active.
+//   A pBlock of ONE chunk is nothing but its two boundary bits: chunk c is one iff bnd has bits c
+//           and c + 1.  In pool order (size descending, then first chunk ascending) these blocks
+//           come last, in chunk order: Algorithm 1's scan over them is a scan over the words of
+//           (singles & ~bmp), 2048 chunks per step of the wavefront.
+//   pool[]  the pBlocks of two or more chunks, as in replay_kernels.hpp but with keys of twice the
+//           width of a chunk number:  size << W | ~first_chunk, sorted descending.
+//   ssz[] / swit[] / soff[]  the sBlocks in pool order (size descending, then creation order):
+//           size in chunks, a witness chunk (one that was last seen active: while it still is, the
+//           sBlock is known active after one bitmap read) and the place of its list, 6 bytes per
+//           sBlock.  A new sBlock is the youngest of its size, so it enters behind the sBlocks of
+//           that size and the order needs no creation number in the key.  Inserts and removals move
+//           16 bytes per lane and step.
+//   lists   in the trace's slice of the workspace (global memory): per sBlock two header words
+//           (creation number | entries << 32,  last-use stamp) and one word per bitmap word it
+//           touches (word index << 32 | chunk mask).  A list is read by an S1 test, by the FREE of
+//           its sBlock (whose slot remembers the place) and by StitchFree; testing, setting and
+//           clearing an sBlock is one bitmap word per lane.  Lists are bump-allocated in granules
+//           and squeezed into the other half of the slice when the half in use is full.
+//
+// StitchFree (Sec. 3.3.2, Sec. 4.2.3) here takes one pass over the witnesses per call: every
+// sBlock whose witness is no longer active is tested in full, the inactive ones are collected with
+// their stamps (the 64 least recently used at most), and as many of them as the threshold asks for
+// are released, least recently used first.
+#ifndef VMS_REPLAY_FINE_HPP
+#define VMS_REPLAY_FINE_HPP
+#include "replay_kernels.hpp"
+
+typedef uint16_t u16;
+
+template <class IDX>
+struct FineT {
+    typedef typename std::conditional<sizeof(IDX) == 2, u32, u64>::type pkey_t;
+    static constexpr u32 W = sizeof(IDX) * 8;
+    pkey_t *pool;
+    u32 *bmp, *bnd, *tmp;
+    u32 *idle;                  // 64 spare words behind tmp[]: targets of lanes that have nothing to update
+    IDX *ssz, *swit;
+    u16 *soff;
+    u64 *arena, *bounce;        // the two halves of the workspace slice
+    u32 np, ns, n_chunks;       // multi-chunk pBlocks in pool[], cached sBlocks, chunks created
+    u32 np_all;                 // all pBlocks
+    u32 top, live;              // granules used / still referenced in the arena
+    u32 next_sid, clock;
+    u32 w_spare;                // a bitmap word no chunk lives in
+    u32 gs, cap_grans;
+    Probe2<IDX> sp;             // first level of the rank search over ssz[]
+    static DI pkey_t key(u32 size, u32 start) { return ((pkey_t)size << W) | (pkey_t)(IDX)~start; }
+    static DI u32 ksize(pkey_t k) { return (u32)(k >> W); }
+    static DI u32 kstart(pkey_t k) { return (u32)(IDX) ~(IDX)k; }
+    DI u64 *list_at(u32 place) const { return arena + ((size_t)place << gs); }
+    DI u32 grans(u32 entries) const { return (entries + 2 + (1u << gs) - 1) >> gs; }
+};
+
+template <class K>
+DI K from_lane_k(K v, u32 l)
+{
+    if constexpr (sizeof(K) == 8) return from_lane64(v, l);
+    else return (K)from_lane((u32)v, l);
+}
+
+// ---- single-chunk pBlocks --------------------------------------------------------------------
+// the chunks of bitmap word w that are inactive pBlocks of one chunk (one lane per word)
+template <class IDX>
+DI u32 singles_free(const FineT<IDX> &V, u32 w)
+{
+    const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
+    return b & ((b >> 1) | (bn << 31)) & ~a;
+}
+
+// S1 for a request of one chunk: the first inactive pBlock of one chunk
+template <class IDX>
+DI bool s1_single(const FineT<IDX> &V, u32 &start)
+{
+    for (u32 wb = 0; wb * 32 < V.n_chunks; wb += 64) {
+        const u32 m = singles_free(V, wb + lane_id());
+        const u64 bm = ballot(m != 0);
+        if (bm) {
+            const u32 l = first_lane(bm);
+            start = (wb + l) * 32 + (u32)__builtin_ctz(from_lane(m, l));
+            return true;
+        }
+    }
+    return false;
+}
+
+// ---- pool[] of multi-chunk pBlocks --------------------------------------------------------------
+template <class IDX, class AcctT>
+DI void fine_pool_insert(FineT<IDX> &V, u32 size, u32 start, AcctT &A)
+{
+    const auto k = V.key(size, start);
+    const u32 pos = rank_desc_k(V.pool, V.np, k);
+    shift_up(V.pool, pos, V.np);
+    st_one(V.pool, pos, k);
+    V.np++;
+    A.peak(SC_HW_MULTI, V.np);
+    wave_sync();
+}
+
+template <class IDX>
+DI void fine_pool_remove(FineT<IDX> &V, u32 idx)
+{
+    shift_down(V.pool, idx, V.np);
+    V.np--;
+    st_one(V.pool, V.np, (typename FineT<IDX>::pkey_t)0);
+    wave_sync();
+}
+
+// Split (Sec. 3.3.1): the pBlock at pool[idx] = [start, start + size) becomes [start, start + keep)
+// and the rest.  A piece of one chunk leaves the array: its boundary bits say all there is to say.
+template <class IDX, class AcctT>
+DI void fine_cut(FineT<IDX> &V, u32 idx, u32 start, u32 size, u32 keep, AcctT &A)
+{
+    fine_pool_remove(V, idx);
+    const u32 cut = start + keep;
+    atomicOr(lane_id() == 0 ? &V.bnd[cut >> 5] : &V.idle[lane_id()], lane_id() == 0 ? 1u << (cut & 31) : 0u);
+    wave_sync();
+    if (keep > 1) fine_pool_insert(V, keep, start, A);
+    if (size - keep > 1) fine_pool_insert(V, size - keep, cut, A);
+    V.np_all++;
+    A.add(SC_N_SPLIT, 1);
+    A.peak(SC_HW_PBLOCKS, V.np_all);
+}
+
+// Alloc (Sec. 3.3.1): `len` new chunks behind the last one
+template <class IDX, class AcctT>
+DI u32 fine_grow(FineT<IDX> &V, u32 len, AcctT &A)
+{
+    const u32 start = V.n_chunks, end = start + len;
+    atomicOr(lane_id() == 0 ? &V.bnd[end >> 5] : &V.idle[lane_id()], lane_id() == 0 ? 1u << (end & 31) : 0u);
+    wave_sync();
+    V.n_chunks = end;
+    if (len > 1) fine_pool_insert(V, len, start, A);
+    V.np_all++;
+    A.peak(SC_HW_PBLOCKS, V.np_all);
+    return start;
+}
+
+// S1, primitive blocks of two or more chunks: the first inactive one of exactly bsize chunks
+template <class IDX>
+DI bool fine_s1_pblock(const FineT<IDX> &V, u32 bsize, u32 &start)
+{
+    const u32 lane = lane_id();
+    u32 base = rank_desc_k(V.pool, V.np, V.key(bsize, 0));     // keys of bsize chunks start here
+    for (;;) {
+        const auto k = V.pool[base + lane];                     // zero keys follow the pool
+        const bool eq = V.ksize(k) == bsize;
+        const u64 vm = ballot(eq);
+        if (!vm) return false;
+        const u32 st = V.kstart(k);
+        const u32 word = V.bmp[eq ? st >> 5 : V.w_spare];
+        const u64 m = ballot(eq && !((word >> (st & 31)) & 1u));
+        if (m) {
+            start = from_lane(st, first_lane(m));
+            return true;
+        }
+        if (~vm >> 63) return false;                            // the run ended inside the tile
+        base += 64;
+    }
+}
+
+// ---- lists ------------------------------------------------------------------------------------
+// One tile of list words (e, if live): their chunks are tested, set or cleared, one bitmap word per
+// lane.  Set and clear are LDS atomics without a result; idle lanes aim at a spare word of their own.
+template <class IDX>
+DI u64 tile_busy(const FineT<IDX> &V, u64 e, bool live, u32 &seen)
+{
+    const u32 word = V.bmp[live ? (u32)(e >> 32) : V.w_spare];
+    seen = live ? word & (u32)e : 0u;
+    return ballot(seen != 0);
+}
+
+template <class IDX>
+DI void tile_apply(const FineT<IDX> &V, u64 e, bool live, bool set)
+{
+    u32 *t = live ? &V.bmp[(u32)(e >> 32)] : &V.idle[lane_id()];
+    const u32 m = live ? (u32)e : 0u;
+    if (set) atomicOr(t, m);
+    else atomicAnd(t, ~m);
+}
+
+// all chunks of the list at `list` (header word 0 already read: cnt entries)
+template <class IDX>
+DI void list_apply(const FineT<IDX> &V, const u64 *list, u32 cnt, bool set)
+{
+    for (u32 eb = 0; eb < cnt; eb += 64) {
+        const u32 k = eb + lane_id();
+        const u64 e = ld_list(list + 2 + (k < cnt ? k : 0u));
+        tile_apply(V, e, k < cnt, set);
+    }
+    wave_sync();
+}
+
+// Is any chunk of the list active?  If so *witness receives such a chunk.
+template <class IDX>
+DI bool list_busy(const FineT<IDX> &V, const u64 *list, u32 cnt, u32 &witness)
+{
+    for (u32 eb = 0; eb < cnt; eb += 64) {
+        const u32 k = eb + lane_id();
+        const u64 e = ld_list(list + 2 + (k < cnt ? k : 0u));
+        u32 seen;
+        const u64 bm = tile_busy(V, e, k < cnt, seen);
+        if (bm) {
+            const u32 l = first_lane(bm);
+            witness = (u32)(from_lane64(e, l) >> 32) * 32 + (u32)__builtin_ctz(from_lane(seen, l));
+            return true;
+        }
+    }
+    return false;
+}
+
+// ---- sBlock table -------------------------------------------------------------------------------
+// Stitch (Sec. 3.3.1): the new sBlock enters behind the cached ones of its size
+template <class IDX, class AcctT>
+DI void fine_spool_insert(FineT<IDX> &V, u32 size, u32 place, u32 witness, AcctT &A)
+{
+    V.sp.refresh(V.ssz, V.ns);
+    const u32 pos = V.sp.rank(V.ssz, (IDX)(size - 1));          // sizes >= size come before it
+    blk_shift_up(V.ssz, pos, V.ns);
+    blk_shift_up(V.swit, pos, V.ns);
+    blk_shift_up(V.soff, pos, V.ns);
+    st_one(V.ssz, pos, (IDX)size);
+    st_one(V.swit, pos, (IDX)witness);
+    st_one(V.soff, pos, (u16)place);
+    V.ns++;
+    A.add(SC_N_CREATED, 1);
+    wave_sync();
+}
+
+template <class IDX>
+DI void fine_spool_remove(FineT<IDX> &V, u32 idx)
+{
+    blk_shift_down(V.ssz, idx, V.ns);
+    blk_shift_down(V.swit, idx, V.ns);
+    blk_shift_down(V.soff, idx, V.ns);
+    V.ns--;
+}
+
+// the two header words of a new list; its entries follow
+template <class IDX>
+DI void list_head(const FineT<IDX> &V, u32 place, u32 id, u32 cnt, u32 stamp)
+{
+    u64 *l = V.list_at(place);
+    const u32 lane = lane_id() & 1;                             // every lane stores one of the two words
+    l[lane] = lane ? (u64)stamp : ((u64)cnt << 32) | id;
+}
+
+// the list of one run of chunks [start, start + len) at `place`; returns its entries
+template <class IDX>
+DI u32 list_put_run(const FineT<IDX> &V, u32 place, u32 start, u32 len)
+{
+    const u32 n = run_words(start, len), w0 = start >> 5;
+    u64 *l = V.list_at(place) + 2;
+    for (u32 qb = 0; qb < n; qb += 64) {
+        const u32 q = min(qb + lane_id(), n - 1);               // lanes past the run write its last word again
+        l[q] = ((u64)(w0 + q) << 32) | word_mask(w0 + q, start, start + len);
+    }
+    return n;
+}
+
+// Squeeze the lists of released sBlocks out: copy the live lists, in table order, to the other
+// half of the slice, which becomes the arena.  Slots that hold an sBlock learn its new place.
+template <class IDX, class Slots>
+DI void fine_compact(FineT<IDX> &V, Slots &S)
+{
+    u32 top = 0;
+    for (u32 s = 0; s < V.ns; s++) {
+        const u32 from = ld_uni(V.soff, s);
+        const u64 *src = V.list_at(from);
+        const u32 cnt = (u32)(uni64(ld_list(src)) >> 32), words = cnt + 2;
+        u64 *dst = V.bounce + ((size_t)top << V.gs);
+        for (u32 rb = 0; rb < words; rb += 64) {                // lanes past the end copy the last word again
+            const u32 r = min(rb + lane_id(), words - 1);
+            dst[r] = ld_list(src + r);
+        }
+        st_one(V.soff, s, (u16)top);
+        S.relocate(from, top);
+        top += V.grans(cnt);
+    }
+    S.relocate_done();
+    __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");      // later reads are of other lanes' global writes
+    wave_sync();
+    u64 *t = V.arena;
+    V.arena = V.bounce;
+    V.bounce = t;
+    V.top = V.live = top;
+}
+
+template <class IDX, class Slots, class AcctT>
+DI bool fine_reserve(FineT<IDX> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
+{
+    if (UNLIKELY(V.top + need_grans > V.cap_grans && V.live < V.top)) fine_compact(V, S);
+    if (UNLIKELY(V.top + need_grans > V.cap_grans)) {
+        A.overflow(ev, VMS_ST_OVF_RUNS);
+        return false;
+    }
+    return true;
+}
+
+// ---- StitchFree (Sec. 3.3.2, Sec. 4.2.3) ----------------------------------------------------------
+// While more sBlocks than the threshold are cached, the least recently used inactive one is
+// released.  Releasing one changes nothing about the others, so the sBlocks released by one call
+// are the inactive ones with the oldest stamps, as many as the excess over the threshold: one pass
+// finds the inactive ones (witness first, whole list if the witness is idle), the 64 oldest of
+// them wait in registers (lane v: stamp, table index, granules), the ones that must go are
+// removed from the highest index down.  A call that leaves more than 64 to release goes round again.
+template <class IDX, class AcctT>
+DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
+{
+    const u32 lane = lane_id();
+    bool any = false;
+    while (V.ns > P.spool_threshold) {
+        u32 v_stamp = NONE32, v_idx = 0, v_gr = 0;              // empty places hold the youngest possible stamp
+        u32 n_found = 0;
+        for (u32 base = 0; base < V.ns; base += 64) {
+            const u32 i = base + lane;
+            const u32 wit = V.swit[i];                           // (spare places behind the table: witness 0)
+            const u32 word = V.bmp[wit >> 5];
+            u64 unknown = ballot(i < V.ns && !((word >> (wit & 31)) & 1u));
+            while (unknown) {
+                const u32 l = first_lane(unknown);
+                unknown &= unknown - 1;
+                const u32 place = ld_uni(V.soff, base + l);
+                const u64 *list = V.list_at(place);
+                const u64 h = ld_list(list + (lane & 1));
+                const u32 cnt = (u32)(from_lane64(h, 0) >> 32), stamp = (u32)from_lane64(h, 1);
+                u32 witness;
+                if (list_busy(V, list, cnt, witness)) {
+                    st_one(V.swit, base + l, (IDX)witness);     // active after all: remember where
+                    continue;
+                }
+                // inactive: it takes an empty place, or the place of the youngest one waiting if it is older
+                const u32 worst = ~wave_min_u32(~v_stamp);
+                if (stamp < worst) {
+                    const u32 at = first_lane(ballot(v_stamp == worst));
+                    v_stamp = write_lane(v_stamp, stamp, at);
+                    v_idx = write_lane(v_idx, base + l, at);
+                    v_gr = write_lane(v_gr, V.grans(cnt), at);
+                }
+                n_found++;
+            }
+            wave_sync();
+        }
+        if (!n_found) break;                                    // everything cached is in use: the threshold stays exceeded
+        const u32 excess = V.ns - P.spool_threshold, have = min(n_found, 64u);
+        u32 go = min(excess, have);
+        // the `go` oldest of the waiting ones: a place goes if fewer than `go` places hold an older stamp
+        u32 older = 0;
+        for (u32 l = 0; l < 64; l++) older += from_lane(v_stamp, l) < v_stamp ? 1u : 0u;
+        bool sel = v_stamp != NONE32 && older < go;
+        for (; go; go--) {
+            // highest table index first: the places of the others stay valid
+            const u32 hi = ~wave_min_u32(sel ? ~v_idx : NONE32);
+            const u32 at = first_lane(ballot(sel && v_idx == hi));
+            fine_spool_remove(V, hi);
+            V.live -= from_lane(v_gr, at);
+            sel = sel && lane != at;
+            A.add(SC_N_EVICTED, 1);
+        }
+        any = true;
+        if (n_found <= 64) break;                               // no inactive sBlock is left unseen
+    }
+    A.peak(SC_HW_SBLOCKS, V.ns);     // high-water marks as seen between events
+    A.peak(SC_HW_RUNS, V.live);
+    return any;
+}
+
+// ---- S1 (Algorithm 1, first loop; Sec. 4.1 state S1) on stitched blocks, oldest first ------------
+// The block of 64 sizes that the rank search reads holds the first sBlock of bsize chunks, if there
+// is one: it doubles as the first tile of candidates.  One lane per candidate reads its witness;
+// the others are tested in pool order with all lanes over the words of one list.
+template <class IDX>
+DI bool fine_s1_sblock(FineT<IDX> &V, u32 bsize, u32 &ref, u32 &place_out)
+{
+    const u32 lane = lane_id();
+    u32 base = V.sp.block((IDX)bsize);
+    for (;;) {
+        const u32 i = base + lane;
+        const u32 sz = V.ssz[i], wit = V.swit[i], so = V.soff[i];   // zero sizes follow the table
+        const u64 vm = ballot(sz == bsize);
+        if (!vm) return false;
+        const u32 word = V.bmp[wit >> 5];
+        u64 unknown = vm & ~ballot((word >> (wit & 31)) & 1u);
+        while (unknown) {
+            const u32 l = first_lane(unknown);
+            unknown &= unknown - 1;
+            const u32 place = from_lane(so, l);
+            u64 *list = V.list_at(place);
+            // header and first 62 entries in one read
+            const u64 e = ld_list(list + lane);
+            const u32 cnt = (u32)(from_lane64(e, 0) >> 32);
+            u32 seen;
+            u64 bm = tile_busy(V, e, lane >= 2 && lane - 2 < cnt, seen);
+            u32 witness = 0;
+            bool busy = bm != 0;
+            if (busy) {
+                const u32 b = first_lane(bm);
+                witness = (u32)(from_lane64(e, b) >> 32) * 32 + (u32)__builtin_ctz(from_lane(seen, b));
+            } else if (UNLIKELY(cnt > 62)) {
+                busy = list_busy(V, list + 62, cnt - 62, witness);
+            }
+            if (!busy) {
+                // inactive: hand it out
+                tile_apply(V, e, lane >= 2 && lane - 2 < cnt, true);
+                if (UNLIKELY(cnt > 62)) list_apply(V, list + 62, cnt - 62, true);
+                list[1] = (u64)++V.clock;                       // last use (every lane stores the same word)
+                ref = (u32)from_lane64(e, 0);
+                place_out = place;
+                return true;
+            }
+            st_one(V.swit, base + l, (IDX)witness);
+        }
+        if (~vm >> 63) return false;                            // the run of equal sizes ended inside this tile
+        base += 64;
+    }
+}
+
+// Update (Sec. 3.3.2) of the sBlock whose list is at `place`
+template <class IDX>
+DI void fine_free_sblock(const FineT<IDX> &V, u32 place)
+{
+    const u64 *list = V.list_at(place);
+    const u32 lane = lane_id();
+    const u64 e = ld_list(list + lane);
+    const u32 cnt = (u32)(from_lane64(e, 0) >> 32);
+    tile_apply(V, e, lane >= 2 && lane - 2 < cnt, false);
+    if (UNLIKELY(cnt > 62)) list_apply(V, list + 62, cnt - 62, false);
+}
+
+// a new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing)
+template <class IDX>
+DI void fine_mark(const FineT<IDX> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
+{
+    const u32 end = start + len;
+    const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
+    for (u32 q = 0; ballot(len && w0 + q <= w1); q++) {
+        const bool in = len && w0 + q <= w1;
+        const u32 mw = word_mask(in ? w0 + q : 0u, start, end);
+        atomicOr(in ? &V.tmp[w0 + q] : &V.idle[lane_id()], in ? mw : 0u);
+    }
+    wmin = min(wmin, w0);
+    wmax = max(wmax, w1);
+}
+
+// No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of its
+// state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).
+template <class IDX, class Slots, class AcctT>
+DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, AcctT &A, u32 ev,
+                        VmsRes &R)
+{
+    typedef typename FineT<IDX>::pkey_t pkey_t;
+    const u32 lane = lane_id();
+    R.kind = KIND_PBLOCK;
+    R.held = bsize;
+    R.ref = 0;
+    R.list = 0;
+    // pool[lo_p, hi_p) are the multi-chunk pBlocks of exactly bsize chunks (all active, or S1 had taken one)
+    const u32 lo_p = rank_desc_k(V.pool, V.np, V.key(bsize, 0));
+    const u32 hi_p = rank_desc_k(V.pool, V.np, (pkey_t)(((pkey_t)bsize << V.W) - 1));
+
+    // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
+    // pool order is the single-block candidate (state 2).
+    for (u32 hi = lo_p; hi > 0;) {
+        const u32 lo = hi > 64 ? hi - 64 : 0;
+        const bool v = lane < hi - lo;
+        const pkey_t k = V.pool[v ? hi - 1 - lane : 0u];
+        const u32 fc = V.kstart(k);
+        const u32 kw = V.bmp[v ? fc >> 5 : V.w_spare];
+        const u64 m = ballot(v && !((kw >> (fc & 31)) & 1u));
+        if (m) {
+            const u32 l = first_lane(m), idx = hi - 1 - l;
+            const pkey_t pk = from_lane_k(k, l);
+            const u32 psize = V.ksize(pk), pstart = V.kstart(pk);
+            if (UNLIKELY(psize < P.frag_limit_chunks)) {
+                // below the fragmentation limit: not worth cutting, hand it out whole (Sec. 4.2.3)
+                bmp_fill(V.bmp, V.w_spare, pstart, psize, true);
+                R.ref = pstart;
+                R.held = psize;
+                R.dec_lo = C_SPLIT | (1u << 8);
+                return;
+            }
+            const u32 gr = V.grans(run_words(pstart, psize));
+            if (UNLIKELY(V.np + 1 > P.cap_pblocks || V.ns + 1 > P.cap_sblocks || !fine_reserve(V, S, gr, A, ev))) {
+                A.overflow(ev, (V.np + 1 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 1 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
+                R.dec_lo = C_INVALID;
+                return;
+            }
+            // S2: Split into the request and the rest; a stitched block keeps the uncut size on record
+            fine_cut(V, idx, pstart, psize, bsize, A);
+            const u32 n = list_put_run(V, V.top, pstart, psize);
+            list_head(V, V.top, V.next_sid++, n, ++V.clock);
+            fine_spool_insert(V, psize, V.top, pstart, A);      // its first chunk is handed out: a witness
+            V.top += gr;
+            V.live += gr;
+            bmp_fill(V.bmp, V.w_spare, pstart, bsize, true);
+            R.ref = pstart;
+            R.dec_lo = C_SPLIT | B_6 | (1u << 8);
+            if (fine_stitch_free(V, P, A)) R.dec_lo |= B_7;
+            return;
+        }
+        hi = lo;
+    }
+
+    // Smaller blocks, largest first, until the request is covered (states 3 and 4): first the
+    // multi-chunk ones in pool[hi_p, lim), then the single chunks in chunk order.  Blocks below the
+    // fragmentation limit sit at the tail of the pool and are never stitched.
+    u32 lim = V.np;
+    const bool singles_ok = P.frag_limit_chunks <= 1;
+    if (UNLIKELY(!singles_ok)) lim = rank_desc_k(V.pool, V.np, (pkey_t)(((pkey_t)P.frag_limit_chunks << V.W) - 1));
+    u32 sum = 0, k = 0, pos = NONE32;
+    for (u32 base = hi_p; base < lim; base += 64) {
+        const u32 i = base + lane;
+        const pkey_t key = V.pool[i < lim ? i : 0u];
+        const u32 fc = V.kstart(key);
+        const u32 kw = V.bmp[i < lim ? fc >> 5 : V.w_spare];
+        const bool inact = i < lim && !((kw >> (fc & 31)) & 1u);
+        u32 tot;
+        const u32 incl = wave_scan_add(inact ? V.ksize(key) : 0u, &tot);
+        const u64 im = ballot(inact);
+        if (sum + tot >= bsize) {
+            const u32 l = first_lane(ballot(inact && sum + incl >= bsize));
+            pos = base + l;
+            k += popc64(im & ((2ull << l) - 1));
+            sum += from_lane(incl, l);
+            break;
+        }
+        k += popc64(im);
+        sum += tot;
+    }
+    // single chunks: all free ones before word s_last, and the lowest s_take of that word
+    u32 s_last = NONE32, s_take = 0, n_single = 0;
+    if (pos == NONE32 && singles_ok) {
+        const u32 want = bsize - sum;
+        for (u32 wb = 0; wb * 32 < V.n_chunks; wb += 64) {
+            const u32 m = singles_free(V, wb + lane);
+            const u32 pc = (u32)__builtin_popcount(m);
+            u32 tot;
+            const u32 incl = wave_scan_add(pc, &tot);
+            if (n_single + tot >= want) {
+                const u32 l = first_lane(ballot(n_single + incl >= want));
+                s_last = wb + l;
+                s_take = want - (n_single + from_lane(incl - pc, l));
+                n_single = want;
+                break;
+            }
+            n_single += tot;
+        }
+        k += n_single;
+        sum += n_single;
+    }
+    const bool s3 = sum >= bsize;
+    const u32 excess = s3 ? sum - bsize : 0, deficit = s3 ? 0 : bsize - sum;
+    if (!s3) {
+        // S4 needs new physical chunks; S5 if the device cannot provide them
+        if (UNLIKELY(reserved_units + (deficit << P.chunk_shift) > P.capacity_units)) {
+            R.dec_lo = C_OOM;
+            return;
+        }
+        if (UNLIKELY(V.n_chunks + deficit > P.cap_chunks)) {
+            A.overflow(ev, VMS_ST_OVF_CHUNKS);
+            R.dec_lo = C_INVALID;
+            return;
+        }
+    }
+    if (!s3 && k == 0) {
+        // nothing cached is usable: the new pBlock serves the request directly (no list, no sBlock)
+        if (UNLIKELY(V.np + 1 > P.cap_pblocks)) {
+            A.overflow(ev, VMS_ST_OVF_PBLOCKS);
+            R.dec_lo = C_INVALID;
+            return;
+        }
+        const u32 start = fine_grow(V, deficit, A);
+        bmp_fill(V.bmp, V.w_spare, start, deficit, true);
+        R.ref = start;
+        R.dec_lo = C_GROW;
+        return;
+    }
+    if (UNLIKELY(V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks)) {
+        A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
+        R.dec_lo = C_INVALID;
+        return;
+    }
+    // second pass: the candidates' chunks (and the new pBlock's) are collected in tmp[]
+    u32 wmin = NONE32, wmax = 0;
+    {
+        const u32 endi = pos != NONE32 ? pos + 1 : lim;
+        for (u32 base = hi_p; base < endi; base += 64) {
+            const u32 i = base + lane;
+            const pkey_t key = V.pool[i < endi ? i : 0u];
+            const u32 fc = V.kstart(key);
+            const u32 kw = V.bmp[i < endi ? fc >> 5 : V.w_spare];
+            const bool inact = i < endi && !((kw >> (fc & 31)) & 1u);
+            u32 len = V.ksize(key);
+            if (i == pos) len -= excess;
+            fine_mark(V, fc, inact ? len : 0u, wmin, wmax);
+        }
+        if (n_single) {
+            // (the last word's share: its lowest s_take free chunks)
+            for (u32 wb = 0; wb * 32 < V.n_chunks && (s_last == NONE32 || wb <= s_last); wb += 64) {
+                const u32 w = wb + lane;
+                u32 m = singles_free(V, w);
+                if (s_last != NONE32) {
+                    u32 rest = m;
+                    for (u32 t = 0; t < s_take; t++) rest &= rest - 1;      // m without its lowest s_take bits
+                    m = w < s_last ? m : (w == s_last ? m & ~rest : 0u);
+                }
+                atomicOr(m ? &V.tmp[w] : &V.idle[lane], m);
+                wmin = min(wmin, m ? w : NONE32);
+                wmax = max(wmax, m ? w : 0u);
+            }
+        }
+        if (!s3) fine_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
+        wave_sync();
+        wmin = wave_min_u32(wmin);
+        wmax = wave_max_u32(wmax);
+    }
+    // room for the list (at most one word per bitmap word in range) and for the record of a cut candidate
+    u64 qk = 0;
+    u32 q_gr = 0;
+    if (excess) {
+        qk = (u64)ld_uni(V.pool, pos);
+        q_gr = V.grans(run_words(V.kstart((pkey_t)qk), V.ksize((pkey_t)qk)));
+    }
+    if (UNLIKELY(!fine_reserve(V, S, V.grans(wmax - wmin + 1) + q_gr, A, ev))) {
+        R.dec_lo = C_INVALID;
+        return;
+    }
+    // the list: one word per bitmap word touched; its chunks become active on the way
+    const u32 place = V.top;
+    u32 cnt = 0, witness = 0;
+    {
+        u64 *l = V.list_at(place) + 2;
+        u64 *spare = V.arena + ((size_t)V.cap_grans << V.gs);
+        for (u32 wb = wmin; wb <= wmax; wb += 64) {
+            const u32 w = min(wb + lane, wmax);
+            const u32 mw = V.tmp[w];
+            const u32 m = wb + lane <= wmax ? mw : 0u;
+            wave_lockstep();
+            const u64 has = ballot(m != 0);
+            if (!cnt && has) {
+                const u32 f = first_lane(has);
+                witness = (wb + f) * 32 + (u32)__builtin_ctz(from_lane(m, f));
+            }
+            // a lane without chunks writes into the spare words behind the arena
+            (m ? l + cnt + rank_in(has) : spare + lane)[0] = ((u64)w << 32) | m;
+            atomicOr(m ? &V.bmp[w] : &V.idle[lane], m);
+            if (wb + lane <= wmax) V.tmp[w] = 0;
+            cnt += popc64(has);
+        }
+        wave_sync();
+    }
+    u32 used = V.grans(cnt);
+    R.dec_lo = 0;
+    // the record of a cut candidate is created first and is therefore the older of the two sBlocks
+    u32 rid = 0, rstamp = 0;
+    if (excess) {
+        rid = V.next_sid++;
+        rstamp = ++V.clock;
+    }
+    const u32 sid = V.next_sid++;
+    list_head(V, place, sid, cnt, ++V.clock);
+    if (s3) {
+        if (excess) {
+            // cut the last candidate so the sum is exact; remember its uncut size (Fig. 9, sBlock 2)
+            const u32 qsize = V.ksize((pkey_t)qk), qstart = V.kstart((pkey_t)qk);
+            fine_cut(V, pos, qstart, qsize, qsize - excess, A);
+            const u32 n = list_put_run(V, place + used, qstart, qsize);
+            list_head(V, place + used, rid, n, rstamp);
+            fine_spool_insert(V, qsize, place + used, qstart, A);
+            used += q_gr;
+            R.dec_lo |= B_6;
+        }
+        R.dec_lo |= C_STITCH;
+    } else {
+        fine_grow(V, deficit, A);               // Alloc: exactly the missing chunks
+        R.dec_lo |= C_GROW;
+    }
+    fine_spool_insert(V, bsize, place, witness, A);
+    V.top += used;
+    V.live += used;
+    A.peak(SC_HW_MEMBERS, k + (s3 ? 0u : 1u));
+    R.ref = sid;
+    R.list = place;
+    R.kind = KIND_SBLOCK;
+    R.dec_lo |= B_SBLOCK | (k << 8);
+    if (fine_stitch_free(V, P, A)) R.dec_lo |= B_7;
+}
+
+// The rare path of the replay loop (see vms_alloc_cold): its scalars wait in the LDS header.
+template <class IDX, class Slots>
+DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u32 bsize, u32 reserved_units, u32 ev,
+                        VmsRes &R)
+{
+    u32 *sc = (u32 *)(lds + LDS_SCALARS);
+    ColdState C;
+    C.load(lds);
+    V.top = C.get(SC_TOP);
+    V.live = C.get(SC_LIVE);
+    V.next_sid = C.get(SC_NEXT_SID);
+    V.np_all = C.get(SC_NP_ALL);
+    AcctLds A;
+    A.sc = sc;
+    A.idle = V.idle;
+    fine_alloc_rest(V, S, bsize, reserved_units, P, A, ev, R);
+    st_one(sc, (u32)SC_TOP, V.top);
+    st_one(sc, (u32)SC_LIVE, V.live);
+    st_one(sc, (u32)SC_NEXT_SID, V.next_sid);
+    st_one(sc, (u32)SC_NP_ALL, V.np_all);
+    wave_sync();
+    return ld_uni(sc, (u32)SC_STOP) == 0;
+}
+
+// ---------------------------------------------------------------------------
+// The kernel: same event loop, slot table, small-request pool and per-tile accounting as
+// replay_vms_kernel; the pools are the ones above.  IDX: the type of a chunk number.
+// ---------------------------------------------------------------------------
+template <bool SLOT_REGS, class IDX>
+__global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u64 *__restrict__ events,
+                                                             const u32 *__restrict__ n_events,
+                                                             u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
+                                                             char *__restrict__ workspace)
+{
+    WAVE_DYNAMIC_LDS(lds);
+    typedef typename FineT<IDX>::pkey_t pkey_t;
+    const u32 lane = lane_id();
+    const u32 trace = blockIdx.x;
+    char *ws_slice = workspace + (size_t)trace * P.ws_stride;
+
+    SlotsT<SLOT_REGS> S;
+    S.init(lds, P);
+    ((u32 *)(lds + LDS_SCALARS))[lane] = lane == SC_FIRST_OOM || lane == SC_OVF_EVENT ? NONE32 : 0u;     // LDS header
+    FineT<IDX> V;
+    V.pool = (pkey_t *)(lds + P.off_pool);
+    V.bmp = (u32 *)(lds + P.off_bmp);
+    V.bnd = (u32 *)(lds + P.off_bnd);
+    V.tmp = (u32 *)(lds + P.off_tmp);
+    V.idle = V.tmp + P.bmp_words;
+    V.ssz = (IDX *)(lds + P.off_skey);
+    V.swit = (IDX *)(lds + P.off_swit);
+    V.soff = (u16 *)(lds + P.off_soff);
+    V.gs = P.gran_shift;
+    V.cap_grans = P.cap_grans;
+    V.arena = (u64 *)ws_slice;
+    V.bounce = (u64 *)(ws_slice + P.ws_stride / 2);
+    V.w_spare = P.bmp_words;
+    V.np = V.ns = V.n_chunks = V.np_all = V.top = V.live = V.next_sid = V.clock = 0;
+    for (u32 i = lane; i < P.bmp_words + 1; i += 64) V.bmp[i] = V.bnd[i] = 0;
+    for (u32 i = lane; i < P.bmp_words + 64; i += 64) V.tmp[i] = 0;
+    if (!P.small_regs)
+        for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;
+    SplitRegs<3> Q;                                         // the pool for small requests, if it fits registers
+    Q.init(lds, P);
+    for (u32 i = lane; i < P.cap_pblocks + 64; i += 64) V.pool[i] = 0;
+    for (u32 i = lane; i < P.cap_sblocks + 80; i += 64) {
+        V.ssz[i] = 0;
+        V.swit[i] = 0;
+        V.soff[i] = 0;
+    }
+    wave_sync();
+    st_one(V.bnd, 0u, 1u);                                  // no chunk yet: the end of the last pBlock is chunk 0
+    V.sp.refresh(V.ssz, 0u);
+    wave_sync();
+
+    u32 requested = 0, active = 0, peak_requested = 0, peak_active = 0;
+    u32 sp_reserved = 0;        // small-request pool: units reserved so far
+    bool stop = false;
+    TileOut T;
+    T.init();
+    const u32 chunk_units = 1u << P.chunk_shift;
+    const u32 n_ev = n_events ? min(uni(n_events[trace]), P.max_events) : P.max_events;
+    const u64 *ev_row = events + (size_t)trace * P.max_events;
+    u64 *dec_row = decisions ? decisions + (size_t)trace * P.max_events : nullptr;
+
+    u64 ev_next = lane < n_ev ? ev_row[lane] : 0;
+    for (u32 base = 0; base < n_ev; base += 64) {
+        const u32 tile = min(64u, n_ev - base);
+        const u32 ev_lo = (u32)ev_next, ev_hi = (u32)(ev_next >> 32);
+        if (base + 64 < n_ev) {                             // prefetch; lanes past the end re-read the last event
+            const u32 nx = base + 64 + lane;
+            const u64 x = pin64(ev_row[min(nx, n_ev - 1)]);
+            ev_next = nx < n_ev ? x : 0;
+        }
+        u32 v_dlo = 0, v_dhi = 0, v_act = 0, v_res = 0;
+        u32 done = tile, todo = tile;       // todo drops to 0 when an engine table overflows: the trace ends there
+        // every path of an event ends by parking its results in lane j and going on to the next event
+#define EMIT(DLO, DHI)                                                     \
+    {                                                                      \
+        write_lane4(v_dlo, v_dhi, v_act, v_res, (DLO), (DHI), active,      \
+                    sp_reserved + (V.n_chunks << P.chunk_shift), j);       \
+        wave_sync();                                                       \
+        continue;                                                          \
+    }
+        for (u32 j = 0; j < todo; j++) {
+            const u32 w = from_lane(ev_lo, j), slot = from_lane(ev_hi, j);
+            if (UNLIKELY(slot >= P.max_slots)) EMIT((u32)C_INVALID, 0u)
+            const u32 req = S.get_req(slot);
+            if ((int)w < 0) {
+                // ---- FREE.  Update (Sec. 3.3.2): only activity flips; memory stays with its pBlocks
+                if (UNLIKELY(req + 1u <= 1u)) {             // unbound, or bound to a request that failed
+                    if (req == SLOT_OOM) {
+                        S.set_req(slot, (u32)SLOT_UNBOUND);
+                        EMIT((u32)C_FREE_NOOP, 0u)
+                    }
+                    EMIT((u32)C_INVALID, 0u)
+                }
+                const u32 a = S.get_a(slot), b = S.get_b(slot);
+                const u32 kind = b & 3;
+                S.set_req(slot, (u32)SLOT_UNBOUND);
+                requested -= req;
+                if (LIKELY((kind & KIND_SBLOCK) != 0)) {
+                    fine_free_sblock(V, S.get_c(slot));
+                    active -= (b >> 2) << P.chunk_shift;
+                    EMIT(C_FREE | B_SBLOCK, a)
+                }
+                if (kind == KIND_PBLOCK) {
+                    bmp_fill(V.bmp, V.w_spare, a, b >> 2, false);
+                    active -= (b >> 2) << P.chunk_shift;
+                    EMIT((u32)C_FREE, a)
+                }
+                bool ml = false, mr = false;
+                if (LIKELY(P.small_regs)) {
+                    AcctLds A;
+                    A.sc = (u32 *)(lds + LDS_SCALARS);
+                    A.idle = V.idle;
+                    Q.release(a >> 2, req, a & 3, A, base + j,
+                              [&](bool l, bool r) {
+                                  ml = l;
+                                  mr = r;
+                              },
+                              [&]() {});
+                } else {
+                    small_free(lds, P, V.idle, a >> 2, req, a & 3, base + j, &ml, &mr);
+                }
+                if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
+                    stop = true;
+                    done = j;
+                    todo = 0;
+                    continue;
+                }
+                active -= req;
+                EMIT(C_FREE | B_SMALL | (ml ? B_6 : 0u) | (mr ? B_7 : 0u), a >> 2)
+            }
+            // ---- ALLOC
+            const u32 size = w;
+            if (UNLIKELY(size == 0 || req != SLOT_UNBOUND)) EMIT((u32)C_INVALID, 0u)
+            u32 dlo, dhi = 0, held_units = size;
+            if (LIKELY(size >= P.small_limit_units)) {
+                const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
+                u32 ref, place;
+                // S1: stitched blocks first, then primitive blocks (Algorithm 1, first loop)
+                if (fine_s1_sblock(V, bsize, ref, place)) {
+                    S.bind(slot, size, ref, KIND_SBLOCK | (bsize << 2), place);
+                    if (!SLOT_REGS) S.set_c(slot, place);
+                    requested += size;
+                    active += bsize << P.chunk_shift;
+                    peak_requested = max(peak_requested, requested);
+                    peak_active = max(peak_active, active);
+                    EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)
+                }
+                if (bsize > 1 ? fine_s1_pblock(V, bsize, ref) : s1_single(V, ref)) {
+                    bmp_fill(V.bmp, V.w_spare, ref, bsize, true);
+                    S.bind(slot, size, ref, KIND_PBLOCK | (bsize << 2), 0u);
+                    requested += size;
+                    active += bsize << P.chunk_shift;
+                    peak_requested = max(peak_requested, requested);
+                    peak_active = max(peak_active, active);
+                    EMIT(C_EXACT | (1u << 8), ref)
+                }
+                // ---- no exact fit: states S2 to S5
+                VmsRes R;
+                const bool went = fine_alloc_cold(lds, V, S, P, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), base + j, R);
+                V.sp.refresh(V.ssz, V.ns);                  // the sBlock table may have changed
+                if (UNLIKELY(!went)) {                      // an engine table overflowed: the trace ends here
+                    stop = true;
+                    done = j;
+                    todo = 0;
+                    continue;
+                }
+                dlo = R.dec_lo;
+                if (LIKELY((dlo & 15) != C_OOM)) {
+                    dhi = R.ref;
+                    S.set_a(slot, dhi);
+                    S.set_b(slot, R.kind | (R.held << 2));
+                    S.set_c(slot, R.list);
+                    held_units = R.held << P.chunk_shift;
+                }
+            } else {
+                // ---- a request below one chunk: the policy's own splitting pool (Sec. 3.1)
+                const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
+                const u32 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
+                SplitRes r;
+                r.code = C_OOM;
+                r.addr = r.flags = 0;
+                r.split = false;
+                if (LIKELY(P.small_regs)) {
+                    AcctLds A;
+                    A.sc = (u32 *)(lds + LDS_SCALARS);
+                    A.idle = V.idle;
+                    Q.alloc(size, seg, reserved + seg <= P.capacity_units, A, base + j,
+                            [&](u32 code, u32 addr, u32 flags, bool split) {
+                                r.code = code;
+                                r.addr = addr;
+                                r.flags = flags;
+                                r.split = split;
+                            },
+                            [&]() {});
+                    sp_reserved = Q.reserved();
+                } else {
+                    small_alloc(lds, P, V.idle, size, seg, reserved + seg <= P.capacity_units, base + j, r, sp_reserved);
+                }
+                if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
+                    stop = true;
+                    done = j;
+                    todo = 0;
+                    continue;
+                }
+                dlo = C_OOM;
+                if (r.code != C_OOM) {
+                    S.set_a(slot, (r.addr << 2) | r.flags);
+                    S.set_b(slot, (u32)KIND_SMALL);
+                    dlo = r.code | B_SMALL | (r.split ? B_6 : 0u) | ((r.code == C_GROW ? 0u : 1u) << 8);
+                    dhi = r.addr;
+                }
+            }
+            if (UNLIKELY((dlo & 15) == C_OOM)) {
+                S.set_req(slot, (u32)SLOT_OOM);
+                ColdState C;                                // rare: note the first failed request
+                C.load(lds);
+                if (C.get(SC_FIRST_OOM) == NONE32) st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_FIRST_OOM, base + j);
+                EMIT((u32)C_OOM, 0u)
+            }
+            S.set_req(slot, size);
+            requested += size;
+            active += held_units;
+            peak_requested = max(peak_requested, requested);
+            peak_active = max(peak_active, active);
+            EMIT(dlo, dhi)
+        }
+#undef EMIT
+        tile_emit(T, dec_row, base, done, v_dlo, v_dhi, v_act, v_res);
+        if (stop) break;
+    }
+
+    wave_sync();
+    u32 n_code[8];
+    const u64 digest = tile_totals(T, n_code);
+    ColdState C;
+    C.load(lds);
+    // (lane reads stay outside the one-lane block below: they are wave-wide operations)
+    u32 sc[SC_COUNT];
+#pragma unroll
+    for (u32 k = 0; k < SC_COUNT; k++) sc[k] = C.get(k);
+    if (lane == 0) {
+        vms_trace_stats &s = stats[(size_t)P.n_traces + trace];
+#pragma unroll
+        for (u32 c = 0; c < 8; c++) s.n_code[c] = n_code[c];
+        const u64 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
+        s.peak_requested = (u64)peak_requested * 512;
+        s.peak_active = (u64)peak_active * 512;
+        s.peak_reserved = reserved * 512;           // reserved memory never shrinks: its peak is its final value
+        s.final_requested = (u64)requested * 512;
+        s.final_active = (u64)active * 512;
+        s.final_reserved = reserved * 512;
+        s.digest = digest;
+        s.n_split = sc[SC_N_SPLIT];
+        s.n_merge = sc[SC_N_MERGE];
+        s.n_sblock_created = sc[SC_N_CREATED];
+        s.n_sblock_evicted = sc[SC_N_EVICTED];
+        s.first_oom_event = sc[SC_FIRST_OOM];
+        s.status = sc[SC_STATUS] | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
+        s.max_pblocks = sc[SC_HW_PBLOCKS];
+        s.max_sblocks = sc[SC_HW_SBLOCKS];
+        s.max_free_blocks = sc[SC_HW_FREE];
+        s.max_members = sc[SC_HW_MEMBERS];
+        s.max_runs = sc[SC_HW_RUNS];
+        s.overflow_event = sc[SC_OVF_EVENT];
+        s.max_multi_pblocks = sc[SC_HW_MULTI];
+        s.reserved1 = 0;
+        // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
+        s.fragmentation = reserved ? 1.0 - (double)peak_active / (double)reserved : 0.0;
+    }
+}
+
+#endif

@@ -16,7 +16,7 @@
 #pragma once
 #include <type_traits>
 #include "wave_ops.hpp"
-#include "../../include/vms_replay.h"
+#include "replay_plan.hpp"
 
 enum { C_FREE = 0, C_EXACT = 1, C_SPLIT = 2, C_STITCH = 3, C_GROW = 4, C_OOM = 5, C_FREE_NOOP = 6, C_INVALID = 15 };
 enum : u32 { B_SMALL = 1u << 4, B_SBLOCK = 1u << 5, B_6 = 1u << 6, B_7 = 1u << 7 };
@@ -26,34 +26,16 @@ enum { KIND_SMALL = 0u, KIND_PBLOCK = 1u, KIND_SBLOCK = 2u };
 #define WIT_NONE 32u            // a list entry with an empty mask (first bit 1, last bit 0 of word 0): "no witness"
 #define ENT_WORD(e) ((e) >> 12)
 
-// Launch-constant parameters (passed by value as a kernel argument).
-struct KParams {
-    u32 n_traces, max_events;
-    u32 chunk_shift;            // log2(chunk in 512-byte units)
-    u32 small_limit_units;
-    u32 frag_limit_chunks;
-    u32 spool_threshold;
-    u32 capacity_units;         // at most 2^30 (512 GiB)
-    u32 max_slots;
-    u32 cap_free, cap_pblocks, cap_sblocks, cap_runs, cap_chunks;
-    // byte offsets of the per-wave arrays inside dynamic LDS
-    u32 off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
-        off_sstamp, off_swit, off_tmp, off_arena;
-    u32 lds_bytes;
-    u32 small_regs;             // stitching kernel: its pool for small requests is held in registers (cap_free <= 192)
-    u32 ws_stamp_off;           // BIG only: not 0 = sstamp[] lives at this byte offset of the trace's workspace slice
-    u64 ws_stride;              // workspace bytes per trace (chunk-run arena / compaction buffer)
-};
-
 // Scalars of one trace that live in LDS (stitching kernel): index k is the u32 at lds[4 k].  The
 // first SC_STATE_COUNT are state that only the rare paths need (read when they start, written back
 // when they end); the counters after them are only ever updated in place.
 enum {
     SC_TOP, SC_LIVE, SC_NEXT_SID,                       // arena top, live list entries, next creation number
     SC_SP_N,                                            // blocks in the splitting pool for requests below one chunk
+    SC_NP_ALL,                                          // fine-grained variant: pBlocks of any size
     SC_STATE_COUNT,
     SC_N_SPLIT = SC_STATE_COUNT, SC_N_MERGE, SC_N_CREATED, SC_N_EVICTED, SC_FIRST_OOM, SC_STATUS, SC_OVF_EVENT, SC_STOP,
-    SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS,
+    SC_HW_PBLOCKS, SC_HW_SBLOCKS, SC_HW_FREE, SC_HW_MEMBERS, SC_HW_RUNS, SC_HW_MULTI,
     SC_COUNT
 };
 
@@ -143,6 +125,14 @@ struct SlotsT<true> {
         c = holds ? found : c;
         wave_sync();
     }
+    // fine-grained variant: c is the place of the held sBlock's list.  The list at `from` has moved
+    // to `to`; bit 31 marks a slot that has its new place already (places are reused as lists move)
+    DI void relocate(u32 from, u32 to)
+    {
+        const bool hit = req + 1u > 1u && (b & 3) == KIND_SBLOCK && c == from;
+        c = hit ? (to | 0x80000000u) : c;
+    }
+    DI void relocate_done() { c &= 0x7FFFFFFFu; }
 };
 
 template <>
@@ -154,6 +144,7 @@ struct SlotsT<false> {
         a = (u32 *)(lds + P.off_slot_a);
         b = (u32 *)(lds + P.off_slot_b);
         c = (u32 *)(lds + P.off_slot_c);
+        n_slots = P.max_slots;
         for (u32 i = lane_id(); i < P.max_slots; i += 64) req[i] = SLOT_UNBOUND;
     }
     DI u32 get_req(u32 s) const { return ld_uni(req, s); }
@@ -171,6 +162,21 @@ struct SlotsT<false> {
         st_one(b, s, vb);           // c is not used with the table in LDS
     }
     DI void relist(const u64 *, const u32 *, u32) {}  // c is not used with the table in LDS
+    // fine-grained variant (c is used): see SlotsT<true>
+    u32 n_slots;
+    DI void relocate(u32 from, u32 to)
+    {
+        for (u32 i = lane_id(); i < n_slots; i += 64) {
+            const bool hit = req[i] + 1u > 1u && (b[i] & 3) == KIND_SBLOCK && c[i] == from;
+            if (hit) c[i] = to | 0x80000000u;
+        }
+        wave_sync();
+    }
+    DI void relocate_done()
+    {
+        for (u32 i = lane_id(); i < n_slots; i += 64) c[i] &= 0x7FFFFFFFu;
+        wave_sync();
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -1442,7 +1448,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                                                         u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
                                                         char *__restrict__ workspace)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    WAVE_DYNAMIC_LDS(lds);
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
     constexpr bool USE_LIST = SLOT_REGS && !BIG;
@@ -1763,6 +1769,10 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     const u64 digest = tile_totals(T, n_code);
     ColdState C;
     C.load(lds);
+    // (lane reads stay outside the one-lane block below: they are wave-wide operations)
+    u32 sc[SC_COUNT];
+#pragma unroll
+    for (u32 k = 0; k < SC_COUNT; k++) sc[k] = C.get(k);
     if (lane == 0) {
         vms_trace_stats &s = stats[(size_t)P.n_traces + trace];
 #pragma unroll
@@ -1775,18 +1785,20 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
         s.final_active = (u64)active * 512;
         s.final_reserved = reserved * 512;
         s.digest = digest;
-        s.n_split = C.get(SC_N_SPLIT);
-        s.n_merge = C.get(SC_N_MERGE);
-        s.n_sblock_created = C.get(SC_N_CREATED);
-        s.n_sblock_evicted = C.get(SC_N_EVICTED);
-        s.first_oom_event = C.get(SC_FIRST_OOM);
-        s.status = C.get(SC_STATUS) | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
-        s.max_pblocks = C.get(SC_HW_PBLOCKS);
-        s.max_sblocks = C.get(SC_HW_SBLOCKS);
-        s.max_free_blocks = C.get(SC_HW_FREE);
-        s.max_members = C.get(SC_HW_MEMBERS);
-        s.max_runs = C.get(SC_HW_RUNS);
-        s.overflow_event = C.get(SC_OVF_EVENT);
+        s.n_split = sc[SC_N_SPLIT];
+        s.n_merge = sc[SC_N_MERGE];
+        s.n_sblock_created = sc[SC_N_CREATED];
+        s.n_sblock_evicted = sc[SC_N_EVICTED];
+        s.first_oom_event = sc[SC_FIRST_OOM];
+        s.status = sc[SC_STATUS] | (n_code[7] ? VMS_ST_INVALID_EVENT : 0u);
+        s.max_pblocks = sc[SC_HW_PBLOCKS];
+        s.max_sblocks = sc[SC_HW_SBLOCKS];
+        s.max_free_blocks = sc[SC_HW_FREE];
+        s.max_members = sc[SC_HW_MEMBERS];
+        s.max_runs = sc[SC_HW_RUNS];
+        s.overflow_event = sc[SC_OVF_EVENT];
+        s.max_multi_pblocks = sc[SC_HW_MULTI];
+        s.reserved1 = 0;
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
         s.fragmentation = reserved ? 1.0 - (double)peak_active / (double)reserved : 0.0;
     }
@@ -1801,7 +1813,7 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
                                                           const u32 *__restrict__ n_events, u64 *__restrict__ decisions,
                                                           vms_trace_stats *__restrict__ stats)
 {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    WAVE_DYNAMIC_LDS(lds);
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
 
@@ -1926,61 +1938,9 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
         s.max_members = 0;
         s.max_runs = 0;
         s.overflow_event = A.f[SC_OVF_EVENT];
+        s.max_multi_pblocks = 0;
+        s.reserved1 = 0;
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
         s.fragmentation = reserved ? 1.0 - (double)peak_requested / (double)reserved : 0.0;
-    }
-}
-
-// Batch summary (Sec. 5.1, memory reduction ratio): one wavefront reduces the statistics.
-__global__ __launch_bounds__(64) void summary_kernel(const vms_trace_stats *__restrict__ stats, u32 n_traces,
-                                                     u32 policy_mask, vms_summary *__restrict__ out)
-{
-    __shared__ u64 acc[64 * 3];
-    __shared__ double facc[64 * 2];
-    const u32 lane = lane_id();
-    vms_summary r;
-    for (int p = 0; p < 2; p++) {
-        u64 res = 0, act = 0, flagged = 0;
-        double fmax = 0.0, fsum = 0.0;
-        if (policy_mask & (1u << p)) {
-            for (u32 t = lane; t < n_traces; t += 64) {
-                const vms_trace_stats &s = stats[(size_t)p * n_traces + t];
-                res += s.peak_reserved;
-                act += s.peak_active;
-                flagged += s.status != 0;
-                fmax = fmax > s.fragmentation ? fmax : s.fragmentation;
-            }
-        }
-        acc[lane] = res;
-        acc[64 + lane] = act;
-        acc[128 + lane] = flagged;
-        facc[lane] = fmax;
-        __syncthreads();
-        if (lane == 0) {
-            res = act = flagged = 0;
-            fmax = 0.0;
-            for (int i = 0; i < 64; i++) {
-                res += acc[i];
-                act += acc[64 + i];
-                flagged += acc[128 + i];
-                fmax = fmax > facc[i] ? fmax : facc[i];
-            }
-            // the mean is summed in trace order so that it does not depend on the lane split
-            if (policy_mask & (1u << p))
-                for (u32 t = 0; t < n_traces; t++) fsum += stats[(size_t)p * n_traces + t].fragmentation;
-            r.sum_peak_reserved[p] = res;
-            r.sum_peak_active[p] = act;
-            r.n_flagged[p] = flagged;
-            r.max_fragmentation[p] = fmax;
-            r.mean_fragmentation[p] = n_traces ? fsum / (double)n_traces : 0.0;
-        }
-        __syncthreads();
-    }
-    if (lane == 0) {
-        r.mem_reduction_ratio = 0.0;
-        if (policy_mask == 3u && r.sum_peak_reserved[0])
-            r.mem_reduction_ratio = (double)((long long)r.sum_peak_reserved[0] - (long long)r.sum_peak_reserved[1]) /
-                                    (double)r.sum_peak_reserved[0];
-        *out = r;
     }
 }

@@ -1,0 +1,179 @@
+// Host-side planning of a replay: checks a vms_config, chooses the kernel variants and lays out
+// the per-wavefront LDS arrays and the per-trace workspace slice.  Plain C++ with no device or
+// runtime calls, so that the same code serves the library and host-only checks of the kernels.
+#ifndef VMS_REPLAY_PLAN_HPP
+#define VMS_REPLAY_PLAN_HPP
+#include <stdint.h>
+#include <string.h>
+
+#include "../../include/vms_replay.h"
+
+// Launch-constant parameters (passed by value as a kernel argument).
+struct KParams {
+    uint32_t n_traces, max_events;
+    uint32_t chunk_shift;            // log2(chunk in 512-byte units)
+    uint32_t small_limit_units;
+    uint32_t frag_limit_chunks;
+    uint32_t spool_threshold;
+    uint32_t capacity_units;         // at most 2^30 (512 GiB)
+    uint32_t max_slots;
+    uint32_t cap_free, cap_pblocks, cap_sblocks, cap_runs, cap_chunks;
+    // byte offsets of the per-wave arrays inside dynamic LDS
+    uint32_t off_slot_req, off_slot_a, off_slot_b, off_slot_c, off_fl, off_pool, off_bmp, off_skey, off_smeta,
+        off_sstamp, off_swit, off_tmp, off_arena;
+    uint32_t lds_bytes;
+    uint32_t small_regs;             // stitching kernel: its pool for small requests is held in registers (cap_free <= 192)
+    uint32_t ws_stamp_off;           // unused by the current variants (kept zero)
+    uint64_t ws_stride;              // workspace bytes per trace
+    // fine-grained variant only (see replay_fine.hpp)
+    uint32_t off_bnd, off_soff;      // block-start bitmap; list places of the sBlocks
+    uint32_t bmp_words;              // words per bitmap that scans may read (a multiple of 64)
+    uint32_t gran_shift;             // a list starts on a multiple of 2^gran_shift 8-byte words of the arena
+    uint32_t cap_grans;              // granules per arena half
+};
+
+struct ReplayPlan {
+    KParams kp[2];                   // [0] splitting kernel, [1] stitching kernel
+    bool fine;                       // stitching kernel: the fine-grained variant (lists in the workspace)
+    bool wide;                       // fine-grained variant with 32-bit chunk numbers (more than 65,000 chunks)
+    bool slot_regs;                  // slot table in registers (at most 64 slots)
+    bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 192)
+    size_t ws_bytes;
+};
+
+namespace plan_detail {
+
+const uint64_t UNIT = 512;
+const uint64_t ENGINE_MAX_BYTES = 1ull << 39;       // 30-bit block addresses in 512-byte units
+const uint64_t LDS_PER_CU = 160 * 1024;
+const uint32_t TABLE_MAX = 1u << 24;                // upper bound of every per-trace table size
+
+inline uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+inline bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
+
+// Per-wave LDS layout, in 64-bit arithmetic (a table size that would wrap a 32-bit offset must end
+// as "too big", not as a small layout).  Returns the bytes needed.
+inline uint64_t layout(KParams &k, int policy, const vms_config &c, const ReplayPlan &p)
+{
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) {
+        uint64_t at = off;
+        off = align_up(off + bytes, 16);
+        return (uint32_t)(at <= 0xFFFFFFFFu ? at : 0xFFFFFFFFu);
+    };
+    k.off_slot_req = k.off_slot_a = k.off_slot_b = k.off_slot_c = 0;
+    k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_swit = k.off_tmp = k.off_arena = 0;
+    k.off_bnd = k.off_soff = 0;
+    if (policy) take(256);      // scalars of the trace (see replay_kernels.hpp)
+    if (!p.slot_regs) {
+        k.off_slot_req = take((uint64_t)c.max_slots * 4);
+        k.off_slot_a = take((uint64_t)c.max_slots * 4);
+        k.off_slot_b = policy ? take((uint64_t)c.max_slots * 4) : 0;
+        k.off_slot_c = policy && p.fine ? take((uint64_t)c.max_slots * 4) : 0;
+    }
+    // the splitting policy keeps small pools in registers: no LDS array then
+    k.off_fl = k.cap_free <= 192 ? 0 : take(((uint64_t)k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
+    if (policy && p.fine) {
+        const uint64_t idx = p.wide ? 4 : 2;                    // bytes of a chunk number
+        k.off_pool = take(((uint64_t)k.cap_pblocks + 64) * 2 * idx);
+        k.off_bmp = take(((uint64_t)k.bmp_words + 1) * 4);      // and one spare word
+        k.off_bnd = take(((uint64_t)k.bmp_words + 1) * 4);      // scans read one word ahead
+        k.off_tmp = take(((uint64_t)k.bmp_words + 64) * 4);     // and 64 spare words
+        k.off_skey = take(((uint64_t)c.max_sblocks + 80) * idx);    // 64 spare places, and shifts move whole 16-byte blocks
+        k.off_swit = take(((uint64_t)c.max_sblocks + 80) * idx);
+        k.off_soff = take(((uint64_t)c.max_sblocks + 80) * 2);
+    } else if (policy) {
+        // 64 spare places behind each searched array: reads there need no bounds check
+        k.off_pool = take(((uint64_t)c.max_pblocks + 64) * 8);
+        k.off_bmp = take(((uint64_t)c.max_chunks + 31) / 32 * 4 + 4);     // and one spare bitmap word
+        k.off_skey = take(((uint64_t)c.max_sblocks + 64) * 8);
+        k.off_smeta = take(((uint64_t)c.max_sblocks + 64) * 4);
+        k.off_sstamp = take(((uint64_t)c.max_sblocks + 64) * 4);
+        k.off_swit = take(((uint64_t)c.max_sblocks + 64) * 4);
+        k.off_tmp = take(((uint64_t)c.max_chunks + 31) / 32 * 4 + 256);   // and 64 spare words
+        k.off_arena = take(((uint64_t)c.max_runs + 64) * 4);
+    }
+    k.lds_bytes = (uint32_t)(off <= 0xFFFFFFFFu ? off : 0xFFFFFFFFu);
+    return off;
+}
+
+}  // namespace plan_detail
+
+// VMS_OK, VMS_EINVAL / VMS_ESTRUCT for a configuration that makes no sense, VMS_ETOOBIG for tables
+// that do not fit a compute unit's LDS.  Touches no device.
+inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
+{
+    using namespace plan_detail;
+    if (!cfg) return VMS_EINVAL;
+    if (cfg->struct_size != sizeof(vms_config)) return VMS_ESTRUCT;
+    const vms_config &c = *cfg;
+    if (c.n_traces == 0 || c.max_events == 0 || c.max_slots == 0) return VMS_EINVAL;
+    if ((c.policy_mask & ~3u) || c.policy_mask == 0) return VMS_EINVAL;
+    if (!is_pow2(c.chunk_bytes) || c.chunk_bytes < UNIT || c.chunk_bytes > (1ull << 30)) return VMS_EINVAL;
+    if (c.small_limit_bytes > c.chunk_bytes || c.small_limit_bytes % UNIT) return VMS_EINVAL;
+    if (c.frag_limit_bytes % c.chunk_bytes) return VMS_EINVAL;
+    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_runs > TABLE_MAX || c.max_chunks == 0)
+        return VMS_EINVAL;
+    if (c.max_chunks > TABLE_MAX) return VMS_EINVAL;
+    if (c.max_sblocks < c.spool_threshold + 3) return VMS_EINVAL;
+    if ((uint64_t)c.max_chunks * c.chunk_bytes > ENGINE_MAX_BYTES) return VMS_EINVAL;
+    if ((uint64_t)c.n_traces * c.max_events > (1ull << 40)) return VMS_EINVAL;
+    if (c.max_small_blocks > 192) return VMS_EINVAL;            // that pool is held in registers
+    // table sizes no LDS could hold: too big, whatever a 32-bit layout would make of them
+    if (c.max_slots > TABLE_MAX || c.max_free_blocks > TABLE_MAX || c.max_pblocks > TABLE_MAX || c.max_sblocks > TABLE_MAX ||
+        c.max_multi_pblocks > TABLE_MAX)
+        return VMS_ETOOBIG;
+
+    memset(&p, 0, sizeof p);
+    // tables beyond what flat sorted LDS arrays serve well (lists of more than 64 KB, thousands of
+    // blocks): the fine-grained variant with its lists in the workspace
+    p.fine = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
+    p.wide = c.max_chunks > 65000;
+    p.slot_regs = c.max_slots <= 64;
+    p.fl_regs = c.max_free_blocks <= 192;
+    uint32_t shift = 0;
+    while ((UNIT << shift) < c.chunk_bytes) shift++;
+    const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)
+                                          : ENGINE_MAX_BYTES;
+    for (int pol = 0; pol < 2; pol++) {
+        KParams &k = p.kp[pol];
+        k.n_traces = c.n_traces;
+        k.max_events = c.max_events;
+        k.chunk_shift = shift;
+        k.small_limit_units = (uint32_t)(c.small_limit_bytes / UNIT);
+        k.frag_limit_chunks = (uint32_t)(c.frag_limit_bytes / c.chunk_bytes);
+        k.spool_threshold = c.spool_threshold;
+        k.capacity_units = (uint32_t)(cap / UNIT);
+        k.max_slots = c.max_slots;
+        // the stitching policy's pool for small requests may be given a size of its own
+        k.cap_free = pol && c.max_small_blocks ? c.max_small_blocks : c.max_free_blocks;
+        k.small_regs = pol && k.cap_free <= 192;
+        k.cap_pblocks = c.max_pblocks;
+        k.cap_sblocks = c.max_sblocks;
+        k.cap_runs = c.max_runs;
+        k.cap_chunks = c.max_chunks;
+        k.ws_stride = 0;
+        if (pol && p.fine) {
+            // pool[] holds the pBlocks of two or more chunks only; its rank search covers 4096 keys,
+            // the one over the sBlocks 8064
+            k.cap_pblocks = c.max_multi_pblocks ? c.max_multi_pblocks : (c.max_pblocks < 4096 ? c.max_pblocks : 4096);
+            if (k.cap_pblocks > 4096 || c.max_sblocks > 8000) return VMS_ETOOBIG;
+            k.bmp_words = (uint32_t)align_up((uint64_t)c.max_chunks / 32 + 1, 64);
+            // list places are 16-bit granule numbers
+            k.gran_shift = 2;
+            while (((uint64_t)c.max_runs >> k.gran_shift) > 65535) k.gran_shift++;
+            k.cap_grans = (uint32_t)((uint64_t)c.max_runs >> k.gran_shift);
+            if (k.cap_grans < 4) return VMS_EINVAL;
+            // two halves (the lists, and where compaction copies them), each followed by 64 spare words
+            k.ws_stride = align_up((((uint64_t)k.cap_grans << k.gran_shift) + 64) * 8, 256) * 2;
+        } else if (pol) {
+            k.ws_stride = align_up(((uint64_t)c.max_runs + 64) * 4, 256);     // where compaction copies the lists
+        }
+        const uint64_t need = layout(k, pol, c, p);
+        if ((c.policy_mask & (1u << pol)) && need > LDS_PER_CU) return VMS_ETOOBIG;
+    }
+    p.ws_bytes = (c.policy_mask & VMS_POLICY_VMS) ? (size_t)p.kp[1].ws_stride * c.n_traces : 0;
+    return VMS_OK;
+}
+
+#endif

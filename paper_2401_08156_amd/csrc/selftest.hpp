@@ -100,15 +100,3 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
     if (lane == 0) *fail = any ? (bad | 0x80000000u) : 0;
     if (any && bad) atomicOr(fail, bad);
 }
-
-static int selftest_run()
-{
-    u32 *d = nullptr, h = 0xFFFFFFFFu;
-    if (hipMalloc((void **)&d, sizeof(u32)) != hipSuccess) return VMS_EHIP;
-    hipLaunchKernelGGL(selftest_kernel, dim3(1), dim3(64), 0, 0, d);
-    hipError_t e = hipGetLastError();
-    if (e == hipSuccess) e = hipMemcpy(&h, d, sizeof h, hipMemcpyDeviceToHost);
-    (void)hipFree(d);
-    if (e != hipSuccess) return VMS_EHIP;
-    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFFF));
-}

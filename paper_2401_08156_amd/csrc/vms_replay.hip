@@ -6,26 +6,18 @@
 #include <string.h>
 
 #include "replay_kernels.hpp"
+#include "replay_fine.hpp"
 #include "selftest.hpp"
 
 namespace {
 
-const uint64_t UNIT = 512;
-const uint64_t ENGINE_MAX_BYTES = 1ull << 39;       // 30-bit block addresses in 512-byte units
 const uint32_t LDS_PER_CU = 160 * 1024;
-
-uint32_t align_up(uint32_t x, uint32_t a) { return (x + a - 1) / a * a; }
-
-bool is_pow2(uint64_t x) { return x && !(x & (x - 1)); }
 
 }  // namespace
 
 struct vms_replay {
     vms_config cfg;
-    KParams kp[2];              // [0] splitting kernel, [1] stitching kernel
-    bool big;                   // sBlock chunk runs in global memory (see VmsT)
-    bool slot_regs;             // slot table in registers (see SlotsT)
-    bool fl_regs;               // splitting policy: inactive blocks in registers (see SplitRegs)
+    ReplayPlan plan;            // kernel variants, LDS layouts, workspace slice (replay_plan.hpp)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
     hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
@@ -51,51 +43,84 @@ int hip_fail(vms_replay *h, hipError_t e)
         if (e_ != hipSuccess) return hip_fail(h, e_); \
     } while (0)
 
-// Per-wave LDS layout.  The splitting kernel only needs the slot table and its free list; with at
-// most 64 slots the slot table lives in registers and takes no LDS at all.
-// stamps_ws: the last-use stamps of the sBlocks move to the trace's slice of the global workspace
-// (tables that would not fit the LDS otherwise; the hot path only ever stores to them).
-void layout(KParams &k, int policy, const vms_config &c, bool big, bool slot_regs, bool stamps_ws)
+// Batch summary (Sec. 5.1, memory reduction ratio): one wavefront reduces the statistics.
+__global__ __launch_bounds__(64) void summary_kernel(const vms_trace_stats *__restrict__ stats, u32 n_traces,
+                                                     u32 policy_mask, vms_summary *__restrict__ out)
 {
-    uint32_t off = 0;
-    auto take = [&](uint32_t bytes) {
-        uint32_t at = off;
-        off = align_up(off + bytes, 16);
-        return at;
-    };
-    k.off_slot_req = k.off_slot_a = k.off_slot_b = k.off_slot_c = 0;
-    if (policy) take(256);      // scalars of the trace (see replay_kernels.hpp)
-    if (!slot_regs) {
-        k.off_slot_req = take(c.max_slots * 4);
-        k.off_slot_a = take(c.max_slots * 4);
-        k.off_slot_b = policy ? take(c.max_slots * 4) : 0;
+    __shared__ u64 acc[64 * 3];
+    __shared__ double facc[64 * 2];
+    const u32 lane = lane_id();
+    vms_summary r;
+    for (int p = 0; p < 2; p++) {
+        u64 res = 0, act = 0, flagged = 0;
+        double fmax = 0.0, fsum = 0.0;
+        if (policy_mask & (1u << p)) {
+            for (u32 t = lane; t < n_traces; t += 64) {
+                const vms_trace_stats &s = stats[(size_t)p * n_traces + t];
+                res += s.peak_reserved;
+                act += s.peak_active;
+                flagged += s.status != 0;
+                fmax = fmax > s.fragmentation ? fmax : s.fragmentation;
+            }
+        }
+        acc[lane] = res;
+        acc[64 + lane] = act;
+        acc[128 + lane] = flagged;
+        facc[lane] = fmax;
+        __syncthreads();
+        if (lane == 0) {
+            res = act = flagged = 0;
+            fmax = 0.0;
+            for (int i = 0; i < 64; i++) {
+                res += acc[i];
+                act += acc[64 + i];
+                flagged += acc[128 + i];
+                fmax = fmax > facc[i] ? fmax : facc[i];
+            }
+            // the mean is summed in trace order so that it does not depend on the lane split
+            if (policy_mask & (1u << p))
+                for (u32 t = 0; t < n_traces; t++) fsum += stats[(size_t)p * n_traces + t].fragmentation;
+            r.sum_peak_reserved[p] = res;
+            r.sum_peak_active[p] = act;
+            r.n_flagged[p] = flagged;
+            r.max_fragmentation[p] = fmax;
+            r.mean_fragmentation[p] = n_traces ? fsum / (double)n_traces : 0.0;
+        }
+        __syncthreads();
     }
-    // the splitting policy keeps small pools in registers: no LDS array then
-    k.off_fl = k.cap_free <= 192 ? 0 : take((k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
-    if (policy) {
-        // 64 spare places behind each searched array: reads there need no bounds check
-        k.off_pool = take((c.max_pblocks + 64) * 8);
-        k.off_bmp = take((c.max_chunks + 31) / 32 * 4 + 4);     // and one spare bitmap word
-        k.off_skey = take((c.max_sblocks + 64) * 8);
-        k.off_smeta = take((c.max_sblocks + 64) * (big ? 8 : 4));
-        k.off_sstamp = stamps_ws ? 0 : take((c.max_sblocks + 64) * 4);
-        k.off_swit = take((c.max_sblocks + 64) * 4);
-        k.off_tmp = take((c.max_chunks + 31) / 32 * 4 + 256);   // and 64 spare words
-        k.off_arena = big ? 0 : take((c.max_runs + 64) * 4);
-    } else {
-        k.off_pool = k.off_bmp = k.off_skey = k.off_smeta = k.off_sstamp = k.off_swit = k.off_tmp = k.off_arena = 0;
+    if (lane == 0) {
+        r.mem_reduction_ratio = 0.0;
+        if (policy_mask == 3u && r.sum_peak_reserved[0])
+            r.mem_reduction_ratio = (double)((long long)r.sum_peak_reserved[0] - (long long)r.sum_peak_reserved[1]) /
+                                    (double)r.sum_peak_reserved[0];
+        *out = r;
     }
-    k.lds_bytes = off;
+}
+
+static int selftest_run()
+{
+    u32 *d = nullptr, h = 0xFFFFFFFFu;
+    if (hipMalloc((void **)&d, sizeof(u32)) != hipSuccess) return VMS_EHIP;
+    hipLaunchKernelGGL(selftest_kernel, dim3(1), dim3(64), 0, 0, d);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipMemcpy(&h, d, sizeof h, hipMemcpyDeviceToHost);
+    (void)hipFree(d);
+    if (e != hipSuccess) return VMS_EHIP;
+    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFFF));
 }
 
 typedef void (*vms_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);
 typedef void (*split_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *);
 
-// the kernel variants: chunk-run lists in HBM or LDS, slot table in LDS or registers
-vms_fn pick_vms(bool big, bool slot_regs)
+// the kernel variants: flat sorted tables in LDS or the fine-grained layout (16- or 32-bit chunk
+// numbers), slot table in LDS or registers
+vms_fn pick_vms(const ReplayPlan &p)
 {
-    if (big) return slot_regs ? replay_vms_kernel<true, true> : replay_vms_kernel<true, false>;
-    return slot_regs ? replay_vms_kernel<false, true> : replay_vms_kernel<false, false>;
+    if (p.fine) {
+        if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32> : replay_vms_fine_kernel<false, u32>;
+        return p.slot_regs ? replay_vms_fine_kernel<true, u16> : replay_vms_fine_kernel<false, u16>;
+    }
+    return p.slot_regs ? replay_vms_kernel<false, true> : replay_vms_kernel<false, false>;
 }
 // fl_regs: the splitting pool's inactive blocks fit three registers per lane (at most 192 blocks)
 split_fn pick_split(bool slot_regs, bool fl_regs)
@@ -133,66 +158,17 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
 {
     if (!cfg || !out) return VMS_EINVAL;
     *out = nullptr;
-    if (cfg->struct_size != sizeof(vms_config)) return VMS_ESTRUCT;
+    ReplayPlan plan;
+    const int prc = replay_plan_make(cfg, plan);      // refuses bad or oversized tables before any device call
+    if (prc != VMS_OK) return prc;
     const vms_config &c = *cfg;
-    if (c.n_traces == 0 || c.max_events == 0 || c.max_slots == 0) return VMS_EINVAL;
-    if ((c.policy_mask & ~3u) || c.policy_mask == 0) return VMS_EINVAL;
-    if (!is_pow2(c.chunk_bytes) || c.chunk_bytes < UNIT || c.chunk_bytes > (1ull << 30)) return VMS_EINVAL;
-    if (c.small_limit_bytes > c.chunk_bytes || c.small_limit_bytes % UNIT) return VMS_EINVAL;
-    if (c.frag_limit_bytes % c.chunk_bytes) return VMS_EINVAL;
-    if (c.max_free_blocks == 0 || c.max_pblocks < 4 || c.max_runs < 4 || c.max_runs > (1u << 24) || c.max_chunks == 0)
-        return VMS_EINVAL;
-    if (c.max_chunks > (1u << 24)) return VMS_EINVAL;
-    if (c.max_sblocks < c.spool_threshold + 3) return VMS_EINVAL;
-    if ((uint64_t)c.max_chunks * c.chunk_bytes > ENGINE_MAX_BYTES) return VMS_EINVAL;
-    if ((uint64_t)c.n_traces * c.max_events > (1ull << 40)) return VMS_EINVAL;
 
     vms_replay *h = new (std::nothrow) vms_replay;
     if (!h) return VMS_ENOMEM;
     memset(h, 0, sizeof *h);
     h->cfg = c;
-    // more than 64 KB of chunk-run lists per trace: keep them in HBM; that kernel variant is also
-    // the one whose rank searches cope with pools beyond 4096 blocks
-    h->big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
-    h->slot_regs = c.max_slots <= 64;
-    h->fl_regs = c.max_free_blocks <= 192;
-    uint32_t shift = 0;
-    while ((UNIT << shift) < c.chunk_bytes) shift++;
-    const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)
-                                          : ENGINE_MAX_BYTES;
-    for (int p = 0; p < 2; p++) {
-        KParams &k = h->kp[p];
-        memset(&k, 0, sizeof k);
-        k.n_traces = c.n_traces;
-        k.max_events = c.max_events;
-        k.chunk_shift = shift;
-        k.small_limit_units = (uint32_t)(c.small_limit_bytes / UNIT);
-        k.frag_limit_chunks = (uint32_t)(c.frag_limit_bytes / c.chunk_bytes);
-        k.spool_threshold = c.spool_threshold;
-        k.capacity_units = (uint32_t)(cap / UNIT);
-        k.max_slots = c.max_slots;
-        // the stitching policy's pool for small requests may be given a size of its own
-        k.cap_free = p && c.max_small_blocks ? c.max_small_blocks : c.max_free_blocks;
-        k.small_regs = p && k.cap_free <= 192;
-        k.cap_pblocks = c.max_pblocks;
-        k.cap_sblocks = c.max_sblocks;
-        k.cap_runs = c.max_runs;
-        k.cap_chunks = c.max_chunks;
-        layout(k, p, c, h->big, h->slot_regs, false);
-        // compaction buffer, and for the big variant the lists themselves (each with 64 spare entries)
-        k.ws_stride = p ? (uint64_t)align_up((c.max_runs + 64) * 4 * (h->big ? 2 : 1), 256) : 0;
-        k.ws_stamp_off = 0;
-        if (p && h->big && k.lds_bytes > LDS_PER_CU) {
-            layout(k, p, c, h->big, h->slot_regs, true);
-            k.ws_stamp_off = (uint32_t)k.ws_stride;     // behind the lists: never 0
-            k.ws_stride += align_up((c.max_sblocks + 64) * 4, 256);
-        }
-        if ((c.policy_mask & (1u << p)) && k.lds_bytes > LDS_PER_CU) {
-            delete h;
-            return VMS_ETOOBIG;
-        }
-    }
-    h->ws_bytes = (c.policy_mask & VMS_POLICY_VMS) ? (size_t)h->kp[1].ws_stride * c.n_traces : 0;
+    h->plan = plan;
+    h->ws_bytes = plan.ws_bytes;
 
     if (hipGetDevice(&h->device) != hipSuccess) {
         delete h;
@@ -206,10 +182,10 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)pick_split(h->slot_regs, h->fl_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)pick_split(h->plan.slot_regs, h->plan.fl_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)pick_vms(h->big, h->slot_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)pick_vms(h->plan), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e != hipSuccess) {
         int rc = e == hipErrorOutOfMemory ? VMS_ENOMEM : VMS_EHIP;
@@ -225,8 +201,8 @@ size_t vms_replay_workspace_bytes(const vms_replay *h) { return h ? h->ws_bytes 
 int vms_replay_lds_bytes(const vms_replay *h, uint32_t out[2])
 {
     if (!h || !out) return VMS_EINVAL;
-    out[0] = h->kp[0].lds_bytes;
-    out[1] = h->kp[1].lds_bytes;
+    out[0] = h->plan.kp[0].lds_bytes;
+    out[1] = h->plan.kp[1].lds_bytes;
     return VMS_OK;
 }
 
@@ -245,14 +221,14 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     hipStream_t sst = both ? h->side : st;
     if (both) HIP_TRY(h, hipStreamWaitEvent(sst, h->ev[0], 0));
     if (c.policy_mask & VMS_POLICY_VMS) {
-        hipLaunchKernelGGL(pick_vms(h->big, h->slot_regs), dim3(c.n_traces), dim3(64), h->kp[1].lds_bytes, st, h->kp[1],
+        hipLaunchKernelGGL(pick_vms(h->plan), dim3(c.n_traces), dim3(64), h->plan.kp[1].lds_bytes, st, h->plan.kp[1],
                            d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL(pick_split(h->slot_regs, h->fl_regs), dim3(c.n_traces), dim3(64), h->kp[0].lds_bytes, sst, h->kp[0],
+        hipLaunchKernelGGL(pick_split(h->plan.slot_regs, h->plan.fl_regs), dim3(c.n_traces), dim3(64), h->plan.kp[0].lds_bytes, sst, h->plan.kp[0],
                            d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }

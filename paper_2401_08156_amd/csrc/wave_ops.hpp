@@ -1,105 +1,15 @@
-// Wavefront-wide primitives for gfx950 (wave64).  Every workgroup of the replay
-// kernels is exactly one wavefront, so "the wave" and "the workgroup" coincide
-// and all of these must be called from wave-uniform control flow (EXEC full).
-#pragma once
-#include <hip/hip_runtime.h>
-#include <stdint.h>
-
-typedef uint32_t u32;
-typedef uint64_t u64;
-
-#define DI __device__ __forceinline__
-
-DI u32 lane_id() { return threadIdx.x; }
-
-// Other lanes' LDS/global writes become visible to this lane's later reads.
-// LDS operations of one wavefront execute in order, so no hardware wait is
-// needed; the fence only stops the compiler from caching values across it.
-DI void wave_sync()
-{
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-// c - 1, or 0 for 0, on a wave-uniform count: two scalar instructions (the conditional form is
-// compiled into a clamped vector subtract and a v_readfirstlane)
-DI u32 dec_sat(u32 c) { return c - min(c, 1u); }
-
-DI u64 ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
-DI u32 first_lane(u64 mask) { return (u32)__builtin_ctzll(mask); }
-DI u32 popc64(u64 m) { return (u32)__builtin_popcountll(m); }
-
-// number of set bits of mask below this lane
-DI u32 rank_in(u64 mask)
-{
-    return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
-}
-
-DI u32 uni(u32 v) { return __builtin_amdgcn_readfirstlane(v); }
-DI u64 uni64(u64 v)
-{
-    u32 lo = __builtin_amdgcn_readfirstlane((u32)v);
-    u32 hi = __builtin_amdgcn_readfirstlane((u32)(v >> 32));
-    return ((u64)hi << 32) | lo;
-}
-DI u32 from_lane(u32 v, u32 lane) { return __builtin_amdgcn_readlane(v, lane); }
-DI u64 from_lane64(u64 v, u32 lane)
-{
-    u32 lo = __builtin_amdgcn_readlane((u32)v, lane);
-    u32 hi = __builtin_amdgcn_readlane((u32)(v >> 32), lane);
-    return ((u64)hi << 32) | lo;
-}
-
-// DPP lane permutations (all rows / banks enabled, out-of-range source reads 0)
-template <int CTRL>
-DI u32 dpp_zero(u32 v)
-{
-    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
-}
-template <int CTRL>
-DI u32 dpp_perm(u32 v)
-{
-    return (u32)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, true);
-}
-
-enum {
-    DPP_QUAD_XOR1 = 0xB1,       // quad_perm [1,0,3,2]
-    DPP_QUAD_XOR2 = 0x4E,       // quad_perm [2,3,0,1]
-    DPP_ROW_HALF_MIRROR = 0x141,
-    DPP_ROW_MIRROR = 0x140,
-    DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118
-};
-
-// minimum over the 64 lanes, returned wave-uniform
-DI u32 wave_min_u32(u32 v)
-{
-    v = min(v, dpp_perm<DPP_QUAD_XOR1>(v));
-    v = min(v, dpp_perm<DPP_QUAD_XOR2>(v));
-    v = min(v, dpp_perm<DPP_ROW_HALF_MIRROR>(v));
-    v = min(v, dpp_perm<DPP_ROW_MIRROR>(v));          // every lane: minimum of its row of 16
-    u32 a = from_lane(v, 0), b = from_lane(v, 16), c = from_lane(v, 32), d = from_lane(v, 48);
-    return min(min(a, b), min(c, d));
-}
-
-// inclusive prefix sum over the 64 lanes; *total receives the wave sum (uniform)
-DI u32 wave_scan_add(u32 v, u32 *total)
-{
-    v += dpp_zero<DPP_ROW_SHR1>(v);
-    v += dpp_zero<DPP_ROW_SHR2>(v);
-    v += dpp_zero<DPP_ROW_SHR4>(v);
-    v += dpp_zero<DPP_ROW_SHR8>(v);                    // inclusive scan inside each row of 16
-    u32 t0 = from_lane(v, 15), t1 = from_lane(v, 31), t2 = from_lane(v, 47), t3 = from_lane(v, 63);
-    u32 row = lane_id() >> 4;
-    u32 add = (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);     // three selects, no branch
-    *total = t0 + t1 + t2 + t3;
-    return v + add;
-}
+// Wavefront-wide searches, shifts and reductions over the arrays of one trace, built on the
+// hardware primitives of wave_hw.hpp.
+#ifndef VMS_WAVE_OPS_HPP
+#define VMS_WAVE_OPS_HPP
+#include "wave_hw.hpp"
 
 // ---- arrays of one trace, shared by the 64 lanes ---------------------------
 
 // read one element at a wave-uniform index; result is wave-uniform
 DI u32 ld_uni(const u32 *a, u32 i) { return uni(a[i]); }
 DI u64 ld_uni(const u64 *a, u32 i) { return uni64(a[i]); }
+DI u32 ld_uni(const uint16_t *a, u32 i) { return uni(a[i]); }
 
 // store of a wave-uniform value at a wave-uniform place: every lane writes it (one address, one
 // value: no bank conflict, measured cheaper than a store under a one-lane mask, and no
@@ -181,7 +91,9 @@ DI void shift_up(T *a, u32 pos, u32 n)
         const u32 lo = hi - pos > 64 ? hi - 64 : pos;
         const u32 i = lo + lane_id();
         const T x = a[i < hi ? i : i + 1];
+        wave_lockstep();
         a[i + 1] = x;
+        wave_lockstep();
         hi = lo;
     }
     wave_sync();
@@ -195,7 +107,9 @@ DI void shift_down(T *a, u32 pos, u32 n)
     for (u32 lo = pos + 1; lo < n; lo += 64) {
         const u32 i = lo + lane_id();
         const T x = a[i];
+        wave_lockstep();
         a[i < n ? i - 1 : i] = x;
+        wave_lockstep();
     }
     wave_sync();
 }
@@ -287,37 +201,108 @@ DI u32 rank_fast(const Probe &p, const u64 *a, u32 n, u64 key)
     return b0 + popc64(ballot(a[b0 + lane_id()] > key));
 }
 
-// vec with lane `lane` replaced by val (both wave-uniform): one v_writelane instead of a compare and a
-// select.  On this target the lane select of v_writelane travels in m0 when the value is in a scalar
-// register too (one scalar register operand per vector instruction).
-DI u32 write_lane(u32 vec, u32 val, u32 lane)
+// ---- sorted arrays of narrow keys (K = uint16_t, u32 or u64) ------------------------------------
+// Same conventions: descending order, at least 64 zero keys behind the live ones, live keys never 0.
+
+// number of elements of a[0..n) that are greater than key, by a two-level search whose first level
+// is read on the spot (two dependent LDS reads; every n up to 64 * 64)
+template <class K>
+DI u32 rank_desc_k(const K *a, u32 n, K key)
 {
-    // (uni(): a value the compiler cannot prove wave-uniform would arrive in a vector register)
-    asm("s_mov_b32 m0, %2\n\ts_nop 0\n\tv_writelane_b32 %0, %1, m0" : "+v"(vec) : "s"(uni(val)), "s"(uni(lane)) : "m0");
-    return vec;
-}
-// four vectors, the same lane
-DI void write_lane4(u32 &a, u32 &b, u32 &c, u32 &d, u32 va, u32 vb, u32 vc, u32 vd, u32 lane)
-{
-    asm("s_mov_b32 m0, %8\n\ts_nop 0\n\tv_writelane_b32 %0, %4, m0\n\tv_writelane_b32 %1, %5, m0\n\t"
-        "v_writelane_b32 %2, %6, m0\n\tv_writelane_b32 %3, %7, m0"
-        : "+v"(a), "+v"(b), "+v"(c), "+v"(d)
-        : "s"(uni(va)), "s"(uni(vb)), "s"(uni(vc)), "s"(uni(vd)), "s"(uni(lane))
-        : "m0");
+    const u32 lane = lane_id();
+    if (n <= 64) return popc64(ballot(a[lane] > key));
+    const u32 stride = (n + 63) >> 6;               // at most 64 for n <= 4096
+    const u32 pi = lane * stride;
+    const K pv = a[pi < n ? pi : n];                // a[n] is a spare zero key
+    const u32 c = popc64(ballot(pv > key));
+    const u32 b0 = dec_sat(c) * stride;             // a[b0] > key >= a[b0 + stride] (if c)
+    return b0 + popc64(ballot(a[b0 + lane] > key));
 }
 
-// which way a wave-uniform branch usually goes: the usual way becomes the fall-through
-#define LIKELY(x) __builtin_expect(!!(x), 1)
-#define UNLIKELY(x) __builtin_expect(!!(x), 0)
+// 128 probes held in registers: lane l holds a[l * stride] and a[(64 + l) * stride] (0 past the
+// end).  With stride < 64 (n <= 8064) the block of 64 keys from block() on holds every key greater
+// than `key` that lies behind its start, and the first key not greater than `key`.
+template <class K>
+struct Probe2 {
+    K v0, v1;       // per lane
+    u32 stride;     // wave-uniform
+    DI void refresh(const K *a, u32 n)
+    {
+        stride = n > 128 ? (n + 127) >> 7 : 1;
+        const u32 p0 = lane_id() * stride, p1 = (64 + lane_id()) * stride;
+        const K x0 = a[p0 < n ? p0 : n], x1 = a[p1 < n ? p1 : n];   // a[n] is a spare zero key
+        v0 = x0;
+        v1 = x1;
+    }
+    DI u32 block(K key) const
+    {
+        const u32 c = popc64(ballot(v0 > key)) + popc64(ballot(v1 > key));
+        return dec_sat(c) * stride;
+    }
+    DI u32 rank(const K *a, K key) const
+    {
+        const u32 b0 = block(key);
+        return b0 + popc64(ballot(a[b0 + lane_id()] > key));
+    }
+};
 
-// keeps a loaded value where it is: the compiler may not sink the load into a later branch
-DI u32 pin(u32 x)
+// a[pos..n) -> a[pos+1..n+1) for an array of 2- or 4-byte elements, sixteen bytes per lane and
+// step (highest blocks first).  The array starts on a 16-byte boundary and is allocated up to the
+// end of the block that holds place n.  a[pos] keeps its old value (the caller overwrites it).
+template <class T>
+DI void blk_shift_up(T *a, u32 pos, u32 n)
 {
-    asm volatile("" : "+v"(x));
-    return x;
+    constexpr u32 E = 16 / sizeof(T);
+    struct alignas(16) Blk { T e[E]; };
+    Blk *b = (Blk *)a;
+    const u32 bf = (pos + 1) / E, bl = n / E;       // first and last block that receive an element
+    for (u32 hi = bl + 1; hi > bf;) {
+        const u32 lo = hi - bf > 64 ? hi - 64 : bf;
+        const u32 B = lo + lane_id();
+        const bool mine = B < hi;
+        const Blk old = b[mine ? B : lo];
+        const T prev = a[(mine && B ? B : 1u) * E - 1];     // last element of the block below
+        wave_lockstep();
+        Blk out;
+#pragma unroll
+        for (u32 j = 0; j < E; j++) {
+            const u32 at = B * E + j;
+            const T from = j ? old.e[j - 1] : prev;
+            out.e[j] = (at > pos && at <= n) ? from : old.e[j];
+        }
+        if (mine) b[B] = out;
+        wave_lockstep();
+        hi = lo;
+    }
+    wave_sync();
 }
-DI u64 pin64(u64 x)
+
+// a[pos+1..n) -> a[pos..n-1) and a[n-1] = 0, lowest blocks first; same layout as above, and the
+// block behind the one that holds place n-1 exists
+template <class T>
+DI void blk_shift_down(T *a, u32 pos, u32 n)
 {
-    asm volatile("" : "+v"(x));
-    return x;
+    constexpr u32 E = 16 / sizeof(T);
+    struct alignas(16) Blk { T e[E]; };
+    Blk *b = (Blk *)a;
+    const u32 bf = pos / E, bl = (n - 1) / E;
+    for (u32 lo = bf; lo <= bl; lo += 64) {
+        const u32 B = lo + lane_id();
+        const bool mine = B <= bl;
+        const Blk old = b[mine ? B : bl];
+        const T next = a[(mine ? B : bl) * E + E];          // first element of the block above
+        wave_lockstep();
+        Blk out;
+#pragma unroll
+        for (u32 j = 0; j < E; j++) {
+            const u32 at = B * E + j;
+            const T from = j + 1 < E ? old.e[j + 1] : next;
+            out.e[j] = at >= pos && at + 1 < n ? from : (at + 1 == n ? (T)0 : old.e[j]);
+        }
+        if (mine) b[B] = out;
+        wave_lockstep();
+    }
+    wave_sync();
 }
+
+#endif

@@ -27,8 +27,8 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(binding.vms_config) == 80
-    assert binding.STATS_DTYPE.itemsize == 144
+    assert ctypes.sizeof(binding.vms_config) == 88
+    assert binding.STATS_DTYPE.itemsize == 152
     assert ctypes.sizeof(binding.vms_summary) == 88
     assert ctypes.sizeof(binding.vms_demo_report) == 224
     assert ctypes.sizeof(binding.vms_vmm_latency_report) == 104
@@ -39,7 +39,7 @@ def test_struct_layouts_match_the_header():
 
 def test_config_default_and_argument_errors_need_no_gpu():
     cfg = binding.vms_config_default(7, 100, 9)
-    assert (cfg.struct_size, cfg.n_traces, cfg.max_events, cfg.max_slots) == (80, 7, 100, 9)
+    assert (cfg.struct_size, cfg.n_traces, cfg.max_events, cfg.max_slots) == (88, 7, 100, 9)
     assert cfg.chunk_bytes == 2 << 20 and cfg.policy_mask == 3 and cfg.spool_threshold == 512
     L = binding.lib()
     h = ctypes.c_void_p()
@@ -66,14 +66,38 @@ def test_tables_that_exceed_the_lds_are_refused_before_any_device_call():
     assert rc in (0, -5)                        # -5: no device here; the layout itself was accepted
     if rc == 0:
         L.vms_replay_destroy(h)
-    # lists in the workspace: the tables of the largest offloading traces fit once the last-use stamps
-    # go to the workspace too ...
+    # tables beyond those go to the fine-grained variant (lists in the workspace, 6 bytes of LDS per
+    # sBlock, single-chunk pBlocks in bitmaps): the largest offloading traces take about 50 KB there ...
     cfg = binding.vms_config_default(4, 100, 9)
     cfg.max_free_blocks, cfg.max_pblocks, cfg.max_sblocks, cfg.max_runs, cfg.max_chunks = 64, 8192, 4352, 1 << 21, 16384
     rc = L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h))
     assert rc in (0, -5)
     if rc == 0:
         L.vms_replay_destroy(h)
-    # ... and beyond that nothing helps
-    cfg.max_sblocks = 6000
+    # ... its rank search covers 8,000 sBlocks and 4,096 multi-chunk pBlocks, not more
+    cfg.max_sblocks = 9000
     assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6
+    cfg.max_sblocks, cfg.max_multi_pblocks = 4352, 5000
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6
+    # a chunk bitmap that alone exceeds the LDS
+    cfg = binding.vms_config_default(4, 100, 9)
+    cfg.chunk_bytes, cfg.small_limit_bytes, cfg.frag_limit_bytes, cfg.max_chunks = 1 << 15, 1 << 15, 1 << 15, 1 << 22
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6
+
+
+def test_table_sizes_that_would_wrap_a_32_bit_layout_are_refused():
+    # the LDS layout is computed in 64 bits and every table size is bounded: a huge value must end as
+    # "too big" (or invalid), never as a small layout that a kernel would then overrun
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    for field, value in (("max_slots", 0x40000010), ("max_pblocks", 0x20000000), ("max_sblocks", 0x20000000),
+                         ("max_free_blocks", 0x20000000), ("max_multi_pblocks", 0x20000000),
+                         ("max_slots", 100000), ("max_free_blocks", 30000), ("max_slots", 0xFFFFFFFF)):
+        cfg = binding.vms_config_default(4, 100, 9)
+        setattr(cfg, field, value)
+        assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6, (field, value)
+        assert not h.value
+    for field, value in (("max_runs", 0x40000000), ("max_chunks", 0x08000000), ("max_small_blocks", 193)):
+        cfg = binding.vms_config_default(4, 100, 9)
+        setattr(cfg, field, value)
+        assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -1, (field, value)
