@@ -66,6 +66,10 @@ extern "C" {
 #define VMS_ETOOBIG    (-6)   /* per-trace tables do not fit the 160 KB of LDS per CU  */
 #define VMS_ESTATE     (-7)   /* call out of order (stats before run, ...)             */
 
+#define VMS_VARIANT_AUTO 0u
+#define VMS_VARIANT_FLAT 1u
+#define VMS_VARIANT_FINE 2u
+
 #define VMS_POLICY_SPLIT 1u
 #define VMS_POLICY_VMS   2u
 
@@ -111,7 +115,12 @@ typedef struct vms_config {
                                     runs, or more than 4096 pBlocks or sBlocks): pBlocks of
                                     two or more chunks, at most 4096; 0 = min(max_pblocks,
                                     4096).  pBlocks of one chunk take no table space there   */
-    uint32_t reserved0;          /* 0                                                        */
+    uint32_t variant;            /* VMS kernel: 0 = chosen by the library (VMS_VARIANT_AUTO),
+                                    VMS_VARIANT_FLAT = flat sorted tables and lists in LDS
+                                    (lowest latency per trace; up to 16384 runs and 4096
+                                    pBlocks / sBlocks), VMS_VARIANT_FINE = the fine-grained
+                                    variant (a fraction of the LDS, lists in the workspace:
+                                    more traces resident per compute unit)                   */
 } vms_config;
 
 typedef struct vms_trace_stats {        /* one per (policy, trace) */

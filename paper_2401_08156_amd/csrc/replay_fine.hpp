@@ -78,6 +78,42 @@ DI u32 singles_free(const FineT<IDX> &V, u32 w)
     return b & ((b >> 1) | (bn << 31)) & ~a;
 }
 
+// the chunks of bitmap word w that belong to inactive pBlocks of two or more chunks: the inactive
+// chunks that exist and are not single-chunk pBlocks (an inactive pBlock has none of its bits set)
+template <class IDX>
+DI u32 multi_free(const FineT<IDX> &V, u32 w)
+{
+    const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
+    const u32 single = b & ((b >> 1) | (bn << 31));
+    const u32 n = V.n_chunks, exist = w * 32 + 32 <= n ? 0xFFFFFFFFu : (w * 32 >= n ? 0u : (1u << (n & 31)) - 1u);
+    return ~a & ~single & exist;
+}
+
+// The same for four consecutive bitmap words per lane (words 4 q .. 4 q + 3, sixteen-byte loads): the
+// free single-chunk pBlocks, the chunks of free multi-chunk pBlocks and the block starts.  One step
+// of the wavefront covers 8192 chunks.
+struct Quad {
+    u32 single[4], multi[4], start[4];
+};
+
+template <class IDX>
+DI Quad quad_load(const FineT<IDX> &V, u32 q)
+{
+    const Blk16 b = ((const Blk16 *)V.bnd)[q], a = ((const Blk16 *)V.bmp)[q];
+    const u32 bn = V.bnd[4 * q + 4], n = V.n_chunks;
+    Quad r;
+#pragma unroll
+    for (u32 k = 0; k < 4; k++) {
+        const u32 w = 4 * q + k, nb = k < 3 ? b.w[k < 3 ? k + 1 : 3] : bn;
+        const u32 sg = b.w[k] & ((b.w[k] >> 1) | (nb << 31));
+        const u32 exist = w * 32 + 32 <= n ? 0xFFFFFFFFu : (w * 32 >= n ? 0u : (1u << (n & 31)) - 1u);
+        r.single[k] = sg & ~a.w[k];
+        r.multi[k] = ~a.w[k] & ~sg & exist;
+        r.start[k] = b.w[k];
+    }
+    return r;
+}
+
 // S1 for a request of one chunk: the first inactive pBlock of one chunk
 template <class IDX>
 DI bool s1_single(const FineT<IDX> &V, u32 &start)
@@ -146,27 +182,24 @@ DI u32 fine_grow(FineT<IDX> &V, u32 len, AcctT &A)
     return start;
 }
 
-// S1, primitive blocks of two or more chunks: the first inactive one of exactly bsize chunks
+// S1, primitive blocks of two or more chunks: the first inactive one among pool[lo_p, hi_p), the
+// pBlocks of exactly the requested number of chunks
 template <class IDX>
-DI bool fine_s1_pblock(const FineT<IDX> &V, u32 bsize, u32 &start)
+DI bool fine_s1_pblock(const FineT<IDX> &V, u32 lo_p, u32 hi_p, u32 &start)
 {
     const u32 lane = lane_id();
-    u32 base = rank_desc_k(V.pool, V.np, V.key(bsize, 0));     // keys of bsize chunks start here
-    for (;;) {
-        const auto k = V.pool[base + lane];                     // zero keys follow the pool
-        const bool eq = V.ksize(k) == bsize;
-        const u64 vm = ballot(eq);
-        if (!vm) return false;
+    for (u32 base = lo_p; base < hi_p; base += 64) {
+        const u32 i = base + lane;
+        const auto k = V.pool[i];                               // zero keys follow the pool
         const u32 st = V.kstart(k);
-        const u32 word = V.bmp[eq ? st >> 5 : V.w_spare];
-        const u64 m = ballot(eq && !((word >> (st & 31)) & 1u));
+        const u32 word = V.bmp[i < hi_p ? st >> 5 : V.w_spare];
+        const u64 m = ballot(i < hi_p && !((word >> (st & 31)) & 1u));
         if (m) {
             start = from_lane(st, first_lane(m));
             return true;
         }
-        if (~vm >> 63) return false;                            // the run ended inside the tile
-        base += 64;
     }
+    return false;
 }
 
 // ---- lists ------------------------------------------------------------------------------------
@@ -220,15 +253,33 @@ DI bool list_busy(const FineT<IDX> &V, const u64 *list, u32 cnt, u32 &witness)
 }
 
 // ---- sBlock table -------------------------------------------------------------------------------
+// the three fields of the records [pos, ns) move one place up / of (idx, ns) one place down
+template <class IDX>
+DI void fine_spool_shift(FineT<IDX> &V, u32 pos, bool up)
+{
+    if constexpr (sizeof(IDX) == 2) {
+        u16 *const f[3] = { V.ssz, V.swit, V.soff };
+        if (up) blk_shift_up<u16, 3>(f, pos, V.ns);
+        else blk_shift_down<u16, 3>(f, pos, V.ns);
+    } else {
+        IDX *const f[2] = { V.ssz, V.swit };
+        if (up) {
+            blk_shift_up<IDX, 2>(f, pos, V.ns);
+            blk_shift_up(V.soff, pos, V.ns);
+        } else {
+            blk_shift_down<IDX, 2>(f, pos, V.ns);
+            blk_shift_down(V.soff, pos, V.ns);
+        }
+    }
+}
+
 // Stitch (Sec. 3.3.1): the new sBlock enters behind the cached ones of its size
 template <class IDX, class AcctT>
 DI void fine_spool_insert(FineT<IDX> &V, u32 size, u32 place, u32 witness, AcctT &A)
 {
     V.sp.refresh(V.ssz, V.ns);
     const u32 pos = V.sp.rank(V.ssz, (IDX)(size - 1));          // sizes >= size come before it
-    blk_shift_up(V.ssz, pos, V.ns);
-    blk_shift_up(V.swit, pos, V.ns);
-    blk_shift_up(V.soff, pos, V.ns);
+    fine_spool_shift(V, pos, true);
     st_one(V.ssz, pos, (IDX)size);
     st_one(V.swit, pos, (IDX)witness);
     st_one(V.soff, pos, (u16)place);
@@ -240,9 +291,7 @@ DI void fine_spool_insert(FineT<IDX> &V, u32 size, u32 place, u32 witness, AcctT
 template <class IDX>
 DI void fine_spool_remove(FineT<IDX> &V, u32 idx)
 {
-    blk_shift_down(V.ssz, idx, V.ns);
-    blk_shift_down(V.swit, idx, V.ns);
-    blk_shift_down(V.soff, idx, V.ns);
+    fine_spool_shift(V, idx, false);
     V.ns--;
 }
 
@@ -317,47 +366,115 @@ DI bool fine_reserve(FineT<IDX> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
 template <class IDX, class AcctT>
 DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
 {
+    constexpr u32 E = 16 / sizeof(IDX);                         // witnesses per lane and step
     const u32 lane = lane_id();
     bool any = false;
     while (V.ns > P.spool_threshold) {
         u32 v_stamp = NONE32, v_idx = 0, v_gr = 0;              // empty places hold the youngest possible stamp
         u32 n_found = 0;
-        for (u32 base = 0; base < V.ns; base += 64) {
-            const u32 i = base + lane;
-            const u32 wit = V.swit[i];                           // (spare places behind the table: witness 0)
-            const u32 word = V.bmp[wit >> 5];
-            u64 unknown = ballot(i < V.ns && !((word >> (wit & 31)) & 1u));
-            while (unknown) {
-                const u32 l = first_lane(unknown);
-                unknown &= unknown - 1;
-                const u32 place = ld_uni(V.soff, base + l);
-                const u64 *list = V.list_at(place);
-                const u64 h = ld_list(list + (lane & 1));
-                const u32 cnt = (u32)(from_lane64(h, 0) >> 32), stamp = (u32)from_lane64(h, 1);
-                u32 witness;
-                if (list_busy(V, list, cnt, witness)) {
-                    st_one(V.swit, base + l, (IDX)witness);     // active after all: remember where
-                    continue;
-                }
-                // inactive: it takes an empty place, or the place of the youngest one waiting if it is older
-                const u32 worst = ~wave_min_u32(~v_stamp);
-                if (stamp < worst) {
-                    const u32 at = first_lane(ballot(v_stamp == worst));
-                    v_stamp = write_lane(v_stamp, stamp, at);
-                    v_idx = write_lane(v_idx, base + l, at);
-                    v_gr = write_lane(v_gr, V.grans(cnt), at);
-                }
-                n_found++;
+        u32 u_idx = 0, n_unk = 0;                               // lane v: table index of the v-th sBlock to test in full
+        // an inactive sBlock takes an empty place, or the place of the youngest one waiting if it is older
+        auto found = [&](u32 stamp, u32 idx, u32 cnt) {
+            const u32 worst = ~wave_min_u32(~v_stamp);
+            if (stamp < worst) {
+                const u32 at = first_lane(ballot(v_stamp == worst));
+                v_stamp = write_lane(v_stamp, stamp, at);
+                v_idx = write_lane(v_idx, idx, at);
+                v_gr = write_lane(v_gr, V.grans(cnt), at);
             }
+            n_found++;
+        };
+        // The tests of the sBlocks noted so far.  Most of them are active through another chunk:
+        // first every lane looks at the first four words of the list of one noted sBlock (all lists
+        // in flight at once), which settles most; the rest are tested with all lanes on one list,
+        // four lists in flight at a time.
+        auto test_noted = [&]() {
+            const bool mine = lane < n_unk;
+            const u32 my_place = V.soff[mine ? u_idx : 0u];
+            const u64 *ml = V.list_at(my_place);
+            u64 h[6];
+#pragma unroll
+            for (u32 q = 0; q < 6; q++) h[q] = ld_list(ml + q);
+            const u32 my_cnt = (u32)(h[0] >> 32);
+            u32 wit = NONE32;                                   // an active chunk among the first four words
+#pragma unroll
+            for (u32 q = 0; q < 4; q++) {
+                const bool live = q < my_cnt;
+                const u32 word = V.bmp[live ? (u32)(h[2 + q] >> 32) : V.w_spare];
+                const u32 seen = live ? word & (u32)h[2 + q] : 0u;
+                wit = seen && wit == NONE32 ? (u32)(h[2 + q] >> 32) * 32 + (u32)__builtin_ctz(seen) : wit;
+            }
+            if (mine && wit != NONE32) V.swit[u_idx] = (IDX)wit;        // active after all: remember where
+            const u64 idle_short = ballot(mine && wit == NONE32 && my_cnt <= 4);
+            u64 unsettled = ballot(mine && wit == NONE32 && my_cnt > 4);
             wave_sync();
+            for (u64 t = idle_short; t; t &= t - 1) {
+                const u32 l = first_lane(t);
+                found(from_lane((u32)h[1], l), from_lane(u_idx, l), from_lane(my_cnt, l));
+            }
+            while (unsettled) {
+                u64 e[4];
+                u32 from[4];
+#pragma unroll
+                for (u32 q = 0; q < 4; q++) {
+                    from[q] = unsettled ? first_lane(unsettled) : NONE32;
+                    unsettled &= unsettled - 1;
+                    e[q] = ld_list(V.list_at(from_lane(my_place, from[q] & 63)) + lane);    // header and first 62 entries
+                }
+#pragma unroll
+                for (u32 q = 0; q < 4; q++) {
+                    if (from[q] == NONE32) break;
+                    const u32 cnt = (u32)(from_lane64(e[q], 0) >> 32), stamp = (u32)from_lane64(e[q], 1);
+                    const u32 idx = from_lane(u_idx, from[q]);
+                    u32 seen, witness = 0;
+                    const u64 bm = tile_busy(V, e[q], lane >= 2 && lane - 2 < cnt, seen);
+                    bool busy = bm != 0;
+                    if (busy) {
+                        const u32 f = first_lane(bm);
+                        witness = (u32)(from_lane64(e[q], f) >> 32) * 32 + (u32)__builtin_ctz(from_lane(seen, f));
+                    } else if (UNLIKELY(cnt > 62)) {
+                        busy = list_busy(V, V.list_at(from_lane(my_place, from[q])) + 62, cnt - 62, witness);
+                    }
+                    if (busy) st_one(V.swit, idx, (IDX)witness);
+                    else found(stamp, idx, cnt);
+                }
+            }
+            n_unk = 0;
+            wave_sync();
+        };
+        for (u32 base = 0; base < V.ns; base += 64 * E) {
+            // E witnesses per lane: sBlocks base + lane * E + j; all their bitmap words are on their way
+            // before the first is looked at
+            const Blk16 wb = ((const Blk16 *)V.swit)[min(base / E + lane, (V.ns - 1) / E)];    // (lanes past the table: its last block again)
+            u32 word[E], wit[E];
+#pragma unroll
+            for (u32 j = 0; j < E; j++) {
+                wit[j] = sizeof(IDX) == 2 ? (wb.w[j >> 1] >> (16 * (j & 1))) & 0xFFFFu : wb.w[j];
+                word[j] = V.bmp[wit[j] >> 5];
+            }
+            u32 idle = 0;                                       // bit j: the witness of sBlock j of this lane is inactive
+#pragma unroll
+            for (u32 j = 0; j < E; j++)
+                idle |= (base + lane * E + j < V.ns && !((word[j] >> (wit[j] & 31)) & 1u) ? 1u : 0u) << j;
+            for (u64 todo = ballot(idle != 0); todo; todo &= todo - 1) {
+                const u32 l = first_lane(todo);
+                for (u32 bits = from_lane(idle, l); bits; bits &= bits - 1) {
+                    u_idx = write_lane(u_idx, base + l * E + (u32)__builtin_ctz(bits), n_unk);
+                    if (++n_unk == 64) test_noted();
+                }
+            }
         }
+        if (n_unk) test_noted();
         if (!n_found) break;                                    // everything cached is in use: the threshold stays exceeded
         const u32 excess = V.ns - P.spool_threshold, have = min(n_found, 64u);
         u32 go = min(excess, have);
         // the `go` oldest of the waiting ones: a place goes if fewer than `go` places hold an older stamp
-        u32 older = 0;
-        for (u32 l = 0; l < 64; l++) older += from_lane(v_stamp, l) < v_stamp ? 1u : 0u;
-        bool sel = v_stamp != NONE32 && older < go;
+        bool sel = v_stamp != NONE32;
+        if (UNLIKELY(go < have)) {
+            u32 older = 0;
+            for (u32 l = 0; l < 64; l++) older += from_lane(v_stamp, l) < v_stamp ? 1u : 0u;
+            sel = sel && older < go;
+        }
         for (; go; go--) {
             // highest table index first: the places of the others stay valid
             const u32 hi = ~wave_min_u32(sel ? ~v_idx : NONE32);
@@ -376,9 +493,40 @@ DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
 }
 
 // ---- S1 (Algorithm 1, first loop; Sec. 4.1 state S1) on stitched blocks, oldest first ------------
+// Is the sBlock whose list is at `place` active?  One read of the list (header and first 62 entries,
+// returned in e), more only for longer lists.  If active, *witness receives an active chunk.
+template <class IDX>
+DI bool sblock_busy(const FineT<IDX> &V, u32 place, u64 &e, u32 &cnt, u32 &witness)
+{
+    const u32 lane = lane_id();
+    const u64 *list = V.list_at(place);
+    e = ld_list(list + lane);
+    cnt = (u32)(from_lane64(e, 0) >> 32);
+    u32 seen;
+    const u64 bm = tile_busy(V, e, lane >= 2 && lane - 2 < cnt, seen);
+    if (bm) {
+        const u32 b = first_lane(bm);
+        witness = (u32)(from_lane64(e, b) >> 32) * 32 + (u32)__builtin_ctz(from_lane(seen, b));
+        return true;
+    }
+    if (UNLIKELY(cnt > 62)) return list_busy(V, list + 62, cnt - 62, witness);
+    return false;
+}
+
+// hand out the (inactive) sBlock whose first list tile is e
+template <class IDX>
+DI void sblock_take(FineT<IDX> &V, u32 place, u64 e, u32 cnt)
+{
+    const u32 lane = lane_id();
+    u64 *list = V.list_at(place);
+    tile_apply(V, e, lane >= 2 && lane - 2 < cnt, true);
+    if (UNLIKELY(cnt > 62)) list_apply(V, list + 62, cnt - 62, true);
+    list[1] = (u64)++V.clock;                                   // last use (every lane stores the same word)
+}
+
 // The block of 64 sizes that the rank search reads holds the first sBlock of bsize chunks, if there
 // is one: it doubles as the first tile of candidates.  One lane per candidate reads its witness;
-// the others are tested in pool order with all lanes over the words of one list.
+// the others are tested oldest first (table order) with all lanes over the words of one list.
 template <class IDX>
 DI bool fine_s1_sblock(FineT<IDX> &V, u32 bsize, u32 &ref, u32 &place_out)
 {
@@ -395,25 +543,10 @@ DI bool fine_s1_sblock(FineT<IDX> &V, u32 bsize, u32 &ref, u32 &place_out)
             const u32 l = first_lane(unknown);
             unknown &= unknown - 1;
             const u32 place = from_lane(so, l);
-            u64 *list = V.list_at(place);
-            // header and first 62 entries in one read
-            const u64 e = ld_list(list + lane);
-            const u32 cnt = (u32)(from_lane64(e, 0) >> 32);
-            u32 seen;
-            u64 bm = tile_busy(V, e, lane >= 2 && lane - 2 < cnt, seen);
-            u32 witness = 0;
-            bool busy = bm != 0;
-            if (busy) {
-                const u32 b = first_lane(bm);
-                witness = (u32)(from_lane64(e, b) >> 32) * 32 + (u32)__builtin_ctz(from_lane(seen, b));
-            } else if (UNLIKELY(cnt > 62)) {
-                busy = list_busy(V, list + 62, cnt - 62, witness);
-            }
-            if (!busy) {
-                // inactive: hand it out
-                tile_apply(V, e, lane >= 2 && lane - 2 < cnt, true);
-                if (UNLIKELY(cnt > 62)) list_apply(V, list + 62, cnt - 62, true);
-                list[1] = (u64)++V.clock;                       // last use (every lane stores the same word)
+            u64 e;
+            u32 cnt, witness;
+            if (!sblock_busy(V, place, e, cnt, witness)) {
+                sblock_take(V, place, e, cnt);                  // inactive: hand it out
                 ref = (u32)from_lane64(e, 0);
                 place_out = place;
                 return true;
@@ -455,8 +588,8 @@ DI void fine_mark(const FineT<IDX> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of its
 // state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).
 template <class IDX, class Slots, class AcctT>
-DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, AcctT &A, u32 ev,
-                        VmsRes &R)
+DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, u32 reserved_units, const KParams &P,
+                        AcctT &A, u32 ev, VmsRes &R)
 {
     typedef typename FineT<IDX>::pkey_t pkey_t;
     const u32 lane = lane_id();
@@ -465,8 +598,6 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, 
     R.ref = 0;
     R.list = 0;
     // pool[lo_p, hi_p) are the multi-chunk pBlocks of exactly bsize chunks (all active, or S1 had taken one)
-    const u32 lo_p = rank_desc_k(V.pool, V.np, V.key(bsize, 0));
-    const u32 hi_p = rank_desc_k(V.pool, V.np, (pkey_t)(((pkey_t)bsize << V.W) - 1));
 
     // ---- Algorithm 1, second loop.  Larger blocks are pool[0, lo_p): the last inactive one in
     // pool order is the single-block candidate (state 2).
@@ -518,38 +649,107 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, 
     const bool singles_ok = P.frag_limit_chunks <= 1;
     if (UNLIKELY(!singles_ok)) lim = rank_desc_k(V.pool, V.np, (pkey_t)(((pkey_t)P.frag_limit_chunks << V.W) - 1));
     u32 sum = 0, k = 0, pos = NONE32;
-    for (u32 base = hi_p; base < lim; base += 64) {
-        const u32 i = base + lane;
-        const pkey_t key = V.pool[i < lim ? i : 0u];
-        const u32 fc = V.kstart(key);
-        const u32 kw = V.bmp[i < lim ? fc >> 5 : V.w_spare];
-        const bool inact = i < lim && !((kw >> (fc & 31)) & 1u);
-        u32 tot;
-        const u32 incl = wave_scan_add(inact ? V.ksize(key) : 0u, &tot);
-        const u64 im = ballot(inact);
-        if (sum + tot >= bsize) {
-            const u32 l = first_lane(ballot(inact && sum + incl >= bsize));
-            pos = base + l;
-            k += popc64(im & ((2ull << l) - 1));
-            sum += from_lane(incl, l);
-            break;
+    // No inactive pBlock of bsize chunks or more exists at this point, so every inactive chunk that is
+    // not a single-chunk pBlock belongs to a candidate.  If all of those together do not cover the
+    // request, every inactive multi-chunk pBlock is taken and the order among them does not matter:
+    // their chunks and their number come from the bitmaps alone, 2048 chunks per step, and pool[]
+    // is not read at all.
+    bool all_multi = false;
+    const u32 n_quads = (V.n_chunks + 127) >> 7;                // lanes that hold chunks, four bitmap words each
+    if (LIKELY(singles_ok)) {
+        u32 mine = 0;                                           // chunks | blocks << 16 of this lane's words
+        for (u32 qb = 0; qb < n_quads; qb += 64) {
+            const u32 q = qb + lane;
+            const Quad Q = quad_load(V, q < n_quads ? q : 0u);
+#pragma unroll
+            for (u32 t = 0; t < 4; t++)
+                mine += q < n_quads ? (u32)__builtin_popcount(Q.multi[t]) | ((u32)__builtin_popcount(Q.multi[t] & Q.start[t]) << 16) : 0u;
         }
-        k += popc64(im);
-        sum += tot;
+        // (at most 4096 blocks and 8192 chunks per step; larger bitmaps: the sums are taken in two halves)
+        u32 t_lo, t_hi;
+        wave_scan_add(mine & 0xFFFFu, &t_lo);
+        wave_scan_add(mine >> 16, &t_hi);
+        if (t_lo < bsize) {
+            all_multi = true;
+            sum = t_lo;
+            k = t_hi;
+        }
     }
-    // single chunks: all free ones before word s_last, and the lowest s_take of that word
+    // (the pool scans below take sixteen bytes of keys per lane and step: KE keys, all their bitmap
+    // words on their way before the first is looked at)
+    constexpr u32 KE = 16 / sizeof(pkey_t);
+    struct alignas(16) Keys {
+        pkey_t k[KE];
+    };
+    if (!all_multi) {
+        for (u32 base = hi_p & ~(KE - 1); base < lim; base += 64 * KE) {
+            const u32 i0 = base + lane * KE;
+            const Keys K = ((const Keys *)V.pool)[i0 < lim ? i0 / KE : 0u];
+            u32 kw[KE], sz[KE], mine = 0;
+            bool in[KE];
+#pragma unroll
+            for (u32 e = 0; e < KE; e++) {
+                in[e] = i0 + e >= hi_p && i0 + e < lim;
+                kw[e] = V.bmp[in[e] ? V.kstart(K.k[e]) >> 5 : V.w_spare];
+            }
+#pragma unroll
+            for (u32 e = 0; e < KE; e++) {
+                in[e] = in[e] && !((kw[e] >> (V.kstart(K.k[e]) & 31)) & 1u);    // from here on: an inactive pBlock
+                sz[e] = in[e] ? V.ksize(K.k[e]) : 0u;
+                mine += sz[e];
+            }
+            u32 tot;
+            const u32 incl = wave_scan_add(mine, &tot);
+            if (sum + tot >= bsize) {
+                // the lane, then the key inside it, at which the request is covered
+                const u32 l = first_lane(ballot(mine && sum + incl >= bsize));
+                sum += from_lane(incl - mine, l);
+#pragma unroll
+                for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]) & ((1ull << l) - 1));
+#pragma unroll
+                for (u32 e = 0; e < KE; e++) {
+                    const u32 c = from_lane(sz[e], l);
+                    if (pos == NONE32 && c) {
+                        k++;
+                        sum += c;
+                        if (sum >= bsize) pos = base + l * KE + e;
+                    }
+                }
+                break;
+            }
+#pragma unroll
+            for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]));
+            sum += tot;
+        }
+    }
+    // single chunks, in chunk order: all free ones before word s_last, and the lowest s_take of that word
     u32 s_last = NONE32, s_take = 0, n_single = 0;
     if (pos == NONE32 && singles_ok) {
         const u32 want = bsize - sum;
-        for (u32 wb = 0; wb * 32 < V.n_chunks; wb += 64) {
-            const u32 m = singles_free(V, wb + lane);
-            const u32 pc = (u32)__builtin_popcount(m);
+        for (u32 qb = 0; qb < n_quads; qb += 64) {
+            const u32 q = qb + lane;
+            const Quad Q = quad_load(V, q < n_quads ? q : 0u);
+            u32 pc[4], mine = 0;
+#pragma unroll
+            for (u32 t = 0; t < 4; t++) {
+                pc[t] = q < n_quads ? (u32)__builtin_popcount(Q.single[t]) : 0u;
+                mine += pc[t];
+            }
             u32 tot;
-            const u32 incl = wave_scan_add(pc, &tot);
+            const u32 incl = wave_scan_add(mine, &tot);
             if (n_single + tot >= want) {
                 const u32 l = first_lane(ballot(n_single + incl >= want));
-                s_last = wb + l;
-                s_take = want - (n_single + from_lane(incl - pc, l));
+                // inside lane l: the word in which the count is reached
+                u32 before = n_single + from_lane(incl - mine, l), word = 4 * (qb + l);
+#pragma unroll
+                for (u32 t = 0; t < 3; t++) {
+                    const u32 c = from_lane(pc[t], l);
+                    const bool past = before + c < want && word == 4 * (qb + l) + t;
+                    before += past ? c : 0u;
+                    word += past ? 1u : 0u;
+                }
+                s_last = word;
+                s_take = want - before;
                 n_single = want;
                 break;
             }
@@ -593,32 +793,87 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, 
     // second pass: the candidates' chunks (and the new pBlock's) are collected in tmp[]
     u32 wmin = NONE32, wmax = 0;
     {
-        const u32 endi = pos != NONE32 ? pos + 1 : lim;
-        for (u32 base = hi_p; base < endi; base += 64) {
-            const u32 i = base + lane;
-            const pkey_t key = V.pool[i < endi ? i : 0u];
-            const u32 fc = V.kstart(key);
-            const u32 kw = V.bmp[i < endi ? fc >> 5 : V.w_spare];
-            const bool inact = i < endi && !((kw >> (fc & 31)) & 1u);
-            u32 len = V.ksize(key);
-            if (i == pos) len -= excess;
-            fine_mark(V, fc, inact ? len : 0u, wmin, wmax);
-        }
-        if (n_single) {
-            // (the last word's share: its lowest s_take free chunks)
-            for (u32 wb = 0; wb * 32 < V.n_chunks && (s_last == NONE32 || wb <= s_last); wb += 64) {
-                const u32 w = wb + lane;
-                u32 m = singles_free(V, w);
-                if (s_last != NONE32) {
-                    u32 rest = m;
-                    for (u32 t = 0; t < s_take; t++) rest &= rest - 1;      // m without its lowest s_take bits
-                    m = w < s_last ? m : (w == s_last ? m & ~rest : 0u);
+        if (all_multi) {
+            // every free multi-chunk pBlock, and the single chunks chosen above; four words per lane
+            for (u32 qb = 0; qb < n_quads; qb += 64) {
+                const u32 q = qb + lane;
+                const Quad Q = quad_load(V, q < n_quads ? q : 0u);
+                Blk16 out;
+#pragma unroll
+                for (u32 t = 0; t < 4; t++) {
+                    const u32 w = 4 * q + t;
+                    u32 sg = n_single ? Q.single[t] : 0u;
+                    if (s_last != NONE32) {
+                        u32 rest = sg;
+                        for (u32 i = 0; i < s_take; i++) rest &= rest - 1;      // sg without its lowest s_take bits
+                        sg = w < s_last ? sg : (w == s_last ? sg & ~rest : 0u);
+                    }
+                    const u32 m = q < n_quads ? Q.multi[t] | sg : 0u;
+                    out.w[t] = m;
+                    wmin = min(wmin, m ? w : NONE32);
+                    wmax = max(wmax, m ? w : 0u);
                 }
-                atomicOr(m ? &V.tmp[w] : &V.idle[lane], m);
-                wmin = min(wmin, m ? w : NONE32);
-                wmax = max(wmax, m ? w : 0u);
+                if (q < n_quads) ((Blk16 *)V.tmp)[q] = out;     // tmp[] is zero between uses
+            }
+        } else {
+            // The candidates' runs of chunks, whatever their lengths, in two steps: every candidate
+            // flips the bit of its first chunk and the bit behind its last one in tmp[]; a chunk then
+            // belongs to a candidate iff an odd number of flipped bits lies at or below it (runs do
+            // not overlap; where two touch, the two flips of the shared place cancel).
+            const u32 endi = pos != NONE32 ? pos + 1 : lim;
+            for (u32 base = hi_p & ~(KE - 1); base < endi; base += 64 * KE) {
+                const u32 i0 = base + lane * KE;
+                const Keys K = ((const Keys *)V.pool)[i0 < endi ? i0 / KE : 0u];
+                u32 kw[KE];
+                bool in[KE];
+#pragma unroll
+                for (u32 e = 0; e < KE; e++) {
+                    in[e] = i0 + e >= hi_p && i0 + e < endi;
+                    kw[e] = V.bmp[in[e] ? V.kstart(K.k[e]) >> 5 : V.w_spare];
+                }
+#pragma unroll
+                for (u32 e = 0; e < KE; e++) {
+                    const u32 fc = V.kstart(K.k[e]);
+                    in[e] = in[e] && !((kw[e] >> (fc & 31)) & 1u);
+                    const u32 end = fc + V.ksize(K.k[e]) - (i0 + e == pos ? excess : 0u);
+                    atomicXor(in[e] ? &V.tmp[fc >> 5] : &V.idle[lane], in[e] ? 1u << (fc & 31) : 0u);
+                    atomicXor(in[e] ? &V.tmp[end >> 5] : &V.idle[lane], in[e] ? 1u << (end & 31) : 0u);
+                }
+            }
+            wave_sync();
+            // flipped bits -> runs, four words per lane
+            u32 carry = 0;                                      // flipped bits below this step, mod 2
+            for (u32 qb = 0; qb * 128 <= V.n_chunks; qb += 64) {
+                const u32 q = qb + lane;
+                const bool mine = q * 128 <= V.n_chunks;
+                const Blk16 t = ((const Blk16 *)V.tmp)[mine ? q : 0u];
+                u32 pc = 0;
+#pragma unroll
+                for (u32 j = 0; j < 4; j++) pc += mine ? (u32)__builtin_popcount(t.w[j]) : 0u;
+                u32 tot;
+                const u32 incl = wave_scan_add(pc, &tot);
+                u32 odd = (carry + incl - pc) & 1u;             // flipped bits below the word at hand, mod 2
+                Blk16 out;
+#pragma unroll
+                for (u32 j = 0; j < 4; j++) {
+                    u32 x = mine ? t.w[j] : 0u;
+                    const u32 flips = (u32)__builtin_popcount(x) & 1u;
+                    x ^= x << 1;
+                    x ^= x << 2;
+                    x ^= x << 4;
+                    x ^= x << 8;
+                    x ^= x << 16;                               // bit i: flipped bits 0..i of this word, mod 2
+                    out.w[j] = odd ? ~x : x;
+                    odd ^= flips;
+                    const u32 w = 4 * q + j;
+                    wmin = min(wmin, out.w[j] ? w : NONE32);
+                    wmax = max(wmax, out.w[j] ? w : 0u);
+                }
+                if (mine) ((Blk16 *)V.tmp)[q] = out;
+                carry += tot;
             }
         }
+        wave_sync();
         if (!s3) fine_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
         wave_sync();
         wmin = wave_min_u32(wmin);
@@ -698,8 +953,8 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 reserved_units, 
 
 // The rare path of the replay loop (see vms_alloc_cold): its scalars wait in the LDS header.
 template <class IDX, class Slots>
-DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u32 bsize, u32 reserved_units, u32 ev,
-                        VmsRes &R)
+DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u32 bsize, u32 lo_p, u32 hi_p,
+                        u32 reserved_units, u32 ev, VmsRes &R)
 {
     u32 *sc = (u32 *)(lds + LDS_SCALARS);
     ColdState C;
@@ -711,7 +966,7 @@ DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u3
     AcctLds A;
     A.sc = sc;
     A.idle = V.idle;
-    fine_alloc_rest(V, S, bsize, reserved_units, P, A, ev, R);
+    fine_alloc_rest(V, S, bsize, lo_p, hi_p, reserved_units, P, A, ev, R);
     st_one(sc, (u32)SC_TOP, V.top);
     st_one(sc, (u32)SC_LIVE, V.live);
     st_one(sc, (u32)SC_NEXT_SID, V.next_sid);
@@ -867,7 +1122,10 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                     peak_active = max(peak_active, active);
                     EMIT(C_EXACT | B_SBLOCK | (1u << 8), ref)
                 }
-                if (bsize > 1 ? fine_s1_pblock(V, bsize, ref) : s1_single(V, ref)) {
+                // pool[lo_p, hi_p): the multi-chunk pBlocks of exactly bsize chunks
+                u32 lo_p, hi_p;
+                rank_desc2_k(V.pool, V.np, V.key(bsize, 0), (pkey_t)(((pkey_t)bsize << V.W) - 1), &lo_p, &hi_p);
+                if (bsize > 1 ? fine_s1_pblock(V, lo_p, hi_p, ref) : s1_single(V, ref)) {
                     bmp_fill(V.bmp, V.w_spare, ref, bsize, true);
                     S.bind(slot, size, ref, KIND_PBLOCK | (bsize << 2), 0u);
                     requested += size;
@@ -878,7 +1136,7 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                 }
                 // ---- no exact fit: states S2 to S5
                 VmsRes R;
-                const bool went = fine_alloc_cold(lds, V, S, P, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), base + j, R);
+                const bool went = fine_alloc_cold(lds, V, S, P, bsize, lo_p, hi_p, sp_reserved + (V.n_chunks << P.chunk_shift), base + j, R);
                 V.sp.refresh(V.ssz, V.ns);                  // the sBlock table may have changed
                 if (UNLIKELY(!went)) {                      // an engine table overflowed: the trace ends here
                     stop = true;

@@ -99,9 +99,10 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
 
 }  // namespace plan_detail
 
+// The plan for cfg with the variant it names (0: flat unless the tables are too large for it).
 // VMS_OK, VMS_EINVAL / VMS_ESTRUCT for a configuration that makes no sense, VMS_ETOOBIG for tables
 // that do not fit a compute unit's LDS.  Touches no device.
-inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
+inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
 {
     using namespace plan_detail;
     if (!cfg) return VMS_EINVAL;
@@ -125,10 +126,13 @@ inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
         return VMS_ETOOBIG;
 
     memset(&p, 0, sizeof p);
-    // tables beyond what flat sorted LDS arrays serve well (lists of more than 64 KB, thousands of
-    // blocks): the fine-grained variant with its lists in the workspace
-    p.fine = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
-    p.wide = c.max_chunks > 65000;
+    if (c.variant > VMS_VARIANT_FINE) return VMS_EINVAL;
+    // tables beyond what flat sorted LDS arrays serve (lists of more than 64 KB, thousands of blocks)
+    // need the fine-grained variant with its lists in the workspace
+    const bool big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
+    if (big && c.variant == VMS_VARIANT_FLAT) return VMS_ETOOBIG;
+    p.fine = big || c.variant == VMS_VARIANT_FINE;
+    p.wide = c.max_chunks > 63000;
     p.slot_regs = c.max_slots <= 64;
     p.fl_regs = c.max_free_blocks <= 192;
     uint32_t shift = 0;
@@ -159,10 +163,13 @@ inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
             k.cap_pblocks = c.max_multi_pblocks ? c.max_multi_pblocks : (c.max_pblocks < 4096 ? c.max_pblocks : 4096);
             if (k.cap_pblocks > 4096 || c.max_sblocks > 8000) return VMS_ETOOBIG;
             k.bmp_words = (uint32_t)align_up((uint64_t)c.max_chunks / 32 + 1, 64);
-            // list places are 16-bit granule numbers
+            // The arena holds 8-byte words: per sBlock two header words and at most one word per
+            // run, rounded up to whole granules of 2^gran_shift words.  List places are 16-bit
+            // granule numbers.
+            const uint64_t words = (uint64_t)c.max_runs + 5ull * c.max_sblocks;
             k.gran_shift = 2;
-            while (((uint64_t)c.max_runs >> k.gran_shift) > 65535) k.gran_shift++;
-            k.cap_grans = (uint32_t)((uint64_t)c.max_runs >> k.gran_shift);
+            while ((words >> k.gran_shift) > 65535) k.gran_shift++;
+            k.cap_grans = (uint32_t)(words >> k.gran_shift);
             if (k.cap_grans < 4) return VMS_EINVAL;
             // two halves (the lists, and where compaction copies them), each followed by 64 spare words
             k.ws_stride = align_up((((uint64_t)k.cap_grans << k.gran_shift) + 64) * 8, 256) * 2;
@@ -173,6 +180,28 @@ inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
         if ((c.policy_mask & (1u << pol)) && need > LDS_PER_CU) return VMS_ETOOBIG;
     }
     p.ws_bytes = (c.policy_mask & VMS_POLICY_VMS) ? (size_t)p.kp[1].ws_stride * c.n_traces : 0;
+    return VMS_OK;
+}
+
+// The plan for cfg.  With variant 0 the library chooses: a trace replays about twice as fast on the
+// flat variant (its lists are in LDS), but when the batch does not fit the compute units at once and
+// the fine-grained variant holds at least 2.5 times as many traces per compute unit, the latter
+// finishes the batch sooner.
+inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
+{
+    int rc = replay_plan_for(cfg, p);
+    if (rc != VMS_OK || !cfg || cfg->variant != VMS_VARIANT_AUTO || p.fine || !(cfg->policy_mask & VMS_POLICY_VMS)) return rc;
+    vms_config alt = *cfg;
+    alt.variant = VMS_VARIANT_FINE;
+    ReplayPlan q;
+    if (replay_plan_for(&alt, q) != VMS_OK) return rc;
+    const uint32_t CUS = 256, SIMD_WAVES = 32;              // compute units; wavefronts a compute unit can hold
+    auto per_cu = [&](const ReplayPlan &x) {
+        const uint64_t w = plan_detail::LDS_PER_CU / (x.kp[1].lds_bytes ? x.kp[1].lds_bytes : 1);
+        return (uint32_t)(w < SIMD_WAVES ? w : SIMD_WAVES);
+    };
+    const uint32_t flat = per_cu(p), fine = per_cu(q);
+    if ((uint64_t)cfg->n_traces > (uint64_t)CUS * flat && 2 * fine >= 5 * flat) p = q;
     return VMS_OK;
 }
 

@@ -10,6 +10,8 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
     __shared__ u32 in[64], out[64];
     __shared__ u64 arr[256];
     __shared__ u64 big[832];
+    __shared__ __attribute__((aligned(16))) uint16_t nar[2048];
+    __shared__ __attribute__((aligned(16))) u32 nar32[2048];
     const u32 lane = lane_id();
     u32 bad = 0;
     for (u32 round = 0; round < 8; round++) {
@@ -95,6 +97,41 @@ __global__ __launch_bounds__(64) void selftest_kernel(u32 *fail)
             if (big[i] != (u64)(5000 - 3 * i) << 32) bad |= 2048;
         for (u32 i = 701; i < 832; i++)
             if (big[i] != 0) bad |= 2048;
+    }
+    // arrays of narrow keys: block moves and the rank search with 128 probes in registers
+    for (u32 n = 5; n <= 1900; n = n < 40 ? n + 1 : n * 3 + 7) {
+        for (u32 pos = 0; pos < n; pos = pos < 18 ? pos + 1 : pos * 2 + 3) {
+            for (u32 i = lane; i < 2048; i += 64) nar[i] = nar32[i] = i < n ? 4000 - 2 * i : 0;
+            wave_sync();
+            blk_shift_up(nar, pos, n);
+            blk_shift_up(nar32, pos, n);
+            st_one(nar, pos, (uint16_t)7);
+            st_one(nar32, pos, 7u);
+            wave_sync();
+            for (u32 i = lane; i < 2048; i += 64) {
+                const u32 want = i < pos ? 4000 - 2 * i : (i == pos ? 7u : (i <= n ? 4000 - 2 * (i - 1) : 0u));
+                if (nar[i] != want || nar32[i] != want) bad |= 4096;
+            }
+            wave_sync();
+            blk_shift_down(nar, pos, n + 1);
+            blk_shift_down(nar32, pos, n + 1);
+            for (u32 i = lane; i < 2048; i += 64) {
+                const u32 want = i < n ? 4000 - 2 * i : 0u;
+                if (nar[i] != want || nar32[i] != want) bad |= 8192;
+            }
+            wave_sync();
+        }
+        Probe2<uint16_t> pr;
+        pr.refresh(nar, n);
+        for (u32 key = 150; key <= 4003; key += 7) {
+            u32 ref = 0;
+            for (u32 i = 0; i < n; i++) ref += nar[i] > key ? 1u : 0u;
+            if (pr.rank(nar, (uint16_t)key) != ref || rank_desc_k(nar, n, (uint16_t)key) != ref ||
+                rank_desc_k(nar32, n, key) != ref)
+                bad |= 16384;
+            const u32 b0 = pr.block((uint16_t)key);
+            if (b0 > ref || ref - b0 >= 64) bad |= 32768;
+        }
     }
     u64 any = ballot(bad != 0);
     if (lane == 0) *fail = any ? (bad | 0x80000000u) : 0;

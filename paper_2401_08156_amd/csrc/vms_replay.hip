@@ -106,7 +106,7 @@ static int selftest_run()
     if (e == hipSuccess) e = hipMemcpy(&h, d, sizeof h, hipMemcpyDeviceToHost);
     (void)hipFree(d);
     if (e != hipSuccess) return VMS_EHIP;
-    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFFF));
+    return h == 0 ? VMS_OK : -(int)(1000 + (h & 0xFFFF));
 }
 
 typedef void (*vms_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *, char *);

@@ -219,6 +219,27 @@ DI u32 rank_desc_k(const K *a, u32 n, K key)
     return b0 + popc64(ballot(a[b0 + lane] > key));
 }
 
+// the same for two keys (k1 >= k2, hence r1 <= r2) sharing the probe pass
+template <class K>
+DI void rank_desc2_k(const K *a, u32 n, K k1, K k2, u32 *r1, u32 *r2)
+{
+    const u32 lane = lane_id();
+    if (n <= 64) {
+        const K v = a[lane];
+        *r1 = popc64(ballot(v > k1));
+        *r2 = popc64(ballot(v > k2));
+        return;
+    }
+    const u32 stride = (n + 63) >> 6;
+    const u32 pi = lane * stride;
+    const K pv = a[pi < n ? pi : n];
+    const u32 c1 = popc64(ballot(pv > k1)), c2 = popc64(ballot(pv > k2));
+    const u32 b1 = dec_sat(c1) * stride, b2 = dec_sat(c2) * stride;
+    const K v1 = a[b1 + lane], v2 = a[b2 + lane];
+    *r1 = b1 + popc64(ballot(v1 > k1));
+    *r2 = b2 + popc64(ballot(v2 > k2));
+}
+
 // 128 probes held in registers: lane l holds a[l * stride] and a[(64 + l) * stride] (0 past the
 // end).  With stride < 64 (n <= 8064) the block of 64 keys from block() on holds every key greater
 // than `key` that lies behind its start, and the first key not greater than `key`.
@@ -246,63 +267,122 @@ struct Probe2 {
     }
 };
 
-// a[pos..n) -> a[pos+1..n+1) for an array of 2- or 4-byte elements, sixteen bytes per lane and
-// step (highest blocks first).  The array starts on a 16-byte boundary and is allocated up to the
-// end of the block that holds place n.  a[pos] keeps its old value (the caller overwrites it).
+// Moves of arrays of 2- or 4-byte elements, sixteen bytes (one block of E elements) per lane and
+// step.  The array starts on a 16-byte boundary, every place behind the n live ones is zero, and the
+// array is allocated two blocks beyond the one that holds place n.  A block is four 32-bit words;
+// moving it by one element is a funnel shift through the neighbouring block's edge element.
+struct Blk16 {
+    u32 w[4];
+};
+
+// the words of `moved` where the element index (block * E + j) is at least `from`, else of `old`
 template <class T>
-DI void blk_shift_up(T *a, u32 pos, u32 n)
+DI Blk16 blk_select(const Blk16 &old, const Blk16 &moved, u32 first_elem, u32 from)
+{
+    Blk16 out;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (u32 k = 0; k < 4; k++) {
+            const u32 m = (first_elem + 2 * k >= from ? 0x0000FFFFu : 0u) | (first_elem + 2 * k + 1 >= from ? 0xFFFF0000u : 0u);
+            out.w[k] = (moved.w[k] & m) | (old.w[k] & ~m);
+        }
+    } else {
+#pragma unroll
+        for (u32 k = 0; k < 4; k++) out.w[k] = first_elem + k >= from ? moved.w[k] : old.w[k];
+    }
+    return out;
+}
+
+// a[pos..n) -> a[pos+1..n+1) in each of the N arrays a[0..N) of equal element size (they hold the
+// fields of the same records), highest blocks first.  The loads of all arrays are on their way before
+// the first store: one LDS round trip per step, whatever N is.  a[pos] keeps its old value (the
+// caller overwrites it).
+template <class T, int N>
+DI void blk_shift_up(T *const (&a)[N], u32 pos, u32 n)
 {
     constexpr u32 E = 16 / sizeof(T);
-    struct alignas(16) Blk { T e[E]; };
-    Blk *b = (Blk *)a;
     const u32 bf = (pos + 1) / E, bl = n / E;       // first and last block that receive an element
     for (u32 hi = bl + 1; hi > bf;) {
         const u32 lo = hi - bf > 64 ? hi - 64 : bf;
         const u32 B = lo + lane_id();
         const bool mine = B < hi;
-        const Blk old = b[mine ? B : lo];
-        const T prev = a[(mine && B ? B : 1u) * E - 1];     // last element of the block below
-        wave_lockstep();
-        Blk out;
+        Blk16 old[N];
+        u32 prev[N];
 #pragma unroll
-        for (u32 j = 0; j < E; j++) {
-            const u32 at = B * E + j;
-            const T from = j ? old.e[j - 1] : prev;
-            out.e[j] = (at > pos && at <= n) ? from : old.e[j];
+        for (int f = 0; f < N; f++) {
+            old[f] = ((const Blk16 *)a[f])[mine ? B : lo];
+            prev[f] = a[f][(mine && B ? B : 1u) * E - 1];       // last element of the block below
         }
-        if (mine) b[B] = out;
+        wave_lockstep();
+#pragma unroll
+        for (int f = 0; f < N; f++) {
+            Blk16 mv;
+            if constexpr (sizeof(T) == 2) {
+                mv.w[0] = (old[f].w[0] << 16) | prev[f];
+#pragma unroll
+                for (u32 k = 1; k < 4; k++) mv.w[k] = (old[f].w[k] << 16) | (old[f].w[k - 1] >> 16);
+            } else {
+                mv.w[0] = prev[f];
+#pragma unroll
+                for (u32 k = 1; k < 4; k++) mv.w[k] = old[f].w[k - 1];
+            }
+            const Blk16 out = blk_select<T>(old[f], mv, B * E, pos + 1);
+            if (mine) ((Blk16 *)a[f])[B] = out;
+        }
         wave_lockstep();
         hi = lo;
     }
     wave_sync();
 }
 
-// a[pos+1..n) -> a[pos..n-1) and a[n-1] = 0, lowest blocks first; same layout as above, and the
-// block behind the one that holds place n-1 exists
-template <class T>
-DI void blk_shift_down(T *a, u32 pos, u32 n)
+// a[pos+1..n) -> a[pos..n-1) in each array, lowest blocks first; a[n-1] becomes 0 (the zero behind it moves in)
+template <class T, int N>
+DI void blk_shift_down(T *const (&a)[N], u32 pos, u32 n)
 {
     constexpr u32 E = 16 / sizeof(T);
-    struct alignas(16) Blk { T e[E]; };
-    Blk *b = (Blk *)a;
     const u32 bf = pos / E, bl = (n - 1) / E;
     for (u32 lo = bf; lo <= bl; lo += 64) {
         const u32 B = lo + lane_id();
         const bool mine = B <= bl;
-        const Blk old = b[mine ? B : bl];
-        const T next = a[(mine ? B : bl) * E + E];          // first element of the block above
-        wave_lockstep();
-        Blk out;
+        Blk16 old[N];
+        u32 next[N];
 #pragma unroll
-        for (u32 j = 0; j < E; j++) {
-            const u32 at = B * E + j;
-            const T from = j + 1 < E ? old.e[j + 1] : next;
-            out.e[j] = at >= pos && at + 1 < n ? from : (at + 1 == n ? (T)0 : old.e[j]);
+        for (int f = 0; f < N; f++) {
+            old[f] = ((const Blk16 *)a[f])[mine ? B : bl];
+            next[f] = a[f][(mine ? B : bl) * E + E];            // first element of the block above
         }
-        if (mine) b[B] = out;
+        wave_lockstep();
+#pragma unroll
+        for (int f = 0; f < N; f++) {
+            Blk16 mv;
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (u32 k = 0; k < 3; k++) mv.w[k] = (old[f].w[k] >> 16) | (old[f].w[k + 1] << 16);
+                mv.w[3] = (old[f].w[3] >> 16) | (next[f] << 16);
+            } else {
+#pragma unroll
+                for (u32 k = 0; k < 3; k++) mv.w[k] = old[f].w[k + 1];
+                mv.w[3] = next[f];
+            }
+            const Blk16 out = blk_select<T>(old[f], mv, B * E, pos);
+            if (mine) ((Blk16 *)a[f])[B] = out;
+        }
         wave_lockstep();
     }
     wave_sync();
+}
+
+template <class T>
+DI void blk_shift_up(T *a, u32 pos, u32 n)
+{
+    T *const one[1] = { a };
+    blk_shift_up<T, 1>(one, pos, n);
+}
+template <class T>
+DI void blk_shift_down(T *a, u32 pos, u32 n)
+{
+    T *const one[1] = { a };
+    blk_shift_down<T, 1>(one, pos, n);
 }
 
 #endif

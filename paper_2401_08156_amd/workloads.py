@@ -17,7 +17,7 @@ TABLES = {
     2: dict(max_free_blocks=192, max_pblocks=544, max_sblocks=576, max_runs=3840, max_chunks=4096),
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks (the fine-grained kernel
     # variant: single chunks in bitmaps, a table for the pBlocks of two or more chunks, lists in the workspace)
-    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=3072, max_sblocks=3584, max_runs=1 << 18, max_chunks=16384),
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2816, max_sblocks=2560, max_runs=1 << 18, max_chunks=10240),
     4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576),
     6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
 }
@@ -25,7 +25,7 @@ TABLES = {
 # events; replayed as three batches, one per kind, each with tables of its own
 TABLES_5 = {
     2: dict(max_free_blocks=192, max_pblocks=640, max_sblocks=640, max_runs=5120, max_chunks=4096),
-    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=3072, max_sblocks=4352, max_runs=1 << 18, max_chunks=16384),
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2944, max_sblocks=4352, max_runs=1 << 18, max_chunks=10240),
     4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576),
 }
 

@@ -119,6 +119,7 @@ DI u64 pin64(u64 x) { return x; }
 
 // LDS atomics: the lanes run one after another, so plain updates are atomic
 template <class T> DI T atomicOr(T *p, T v) { T o = *p; *p = o | v; return o; }
+template <class T> DI T atomicXor(T *p, T v) { T o = *p; *p = o ^ v; return o; }
 template <class T> DI T atomicAnd(T *p, T v) { T o = *p; *p = o & v; return o; }
 template <class T> DI T atomicAdd(T *p, T v) { T o = *p; *p = o + v; return o; }
 template <class T> DI T atomicMax(T *p, T v) { T o = *p; *p = max(o, v); return o; }
