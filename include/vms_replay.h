@@ -225,6 +225,7 @@ typedef struct vms_demo_report {
     /* one 2 GiB block built from chunk_bytes chunks, against hipMalloc(2 GiB): Table 1      */
     uint64_t table1_bytes;
     double   table1_hipmalloc_ms, table1_reserve_ms, table1_create_ms, table1_map_ms, table1_set_access_ms;
+    uint64_t peak_mapped_chunks; /* most chunk mappings alive at once, over all virtual ranges  */
 } vms_demo_report;
 
 /* Functional demonstration (Sec. 3.3.1, Sec. 2.5): execute the first n_events decisions of ONE
@@ -239,6 +240,14 @@ typedef struct vms_demo_report {
  * released before returning.  Synchronous; host code only, no kernel is launched.              */
 int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms, uint32_t n_events,
                  vms_demo_report *out);
+
+/* The same walk over the decisions with every driver call counted instead of made (host only, no
+ * device needed): out receives the call counts, chunks_created and peak_mapped_chunks that
+ * vms_demo_run would reach, so that a caller can pick a trace the device can hold (the driver
+ * refuses further mappings beyond some tens of thousands).  VMS_EINVAL (with failed_event) if the
+ * decisions contradict the books.                                                              */
+int vms_demo_plan(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms, uint32_t n_events,
+                  vms_demo_report *out);
 
 /* What vms_vmm_latency measured: host wall-clock milliseconds, the best of the rounds, summed over
  * the calls of one kind (n_chunks calls for create / map / set access / unmap / release).        */

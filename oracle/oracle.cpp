@@ -22,10 +22,13 @@
 // the stitching allocator's reserved bytes; per-event invariants checked by an
 // independent checker over the decision stream; exhaustive best-fit and
 // minimal-stitch enumeration on tiny pools; an independent naive Python
-// implementation on thousands of small random traces.
+// implementation on thousands of small random traces; hand-derived examples of
+// what StitchFree releases (Sec. 3.3.2: the least recently used sBlock, and only
+// an inactive one; a hand-out renews the use) and of the stitched block that
+// records a candidate cut in state S3 (Sec. 4.1, Fig. 9).
 // Parity unpinned (the paper fixes no order): which of several equal-sized
-// blocks is taken, the StitchFree eviction order, and the numeric ids reported
-// in the decision words.
+// blocks is taken, the StitchFree threshold's exact form, and the numeric ids
+// reported in the decision words.
 #include <algorithm>
 #include <atomic>
 #include <cstdint>

@@ -52,7 +52,8 @@ class vms_demo_report(ctypes.Structure):
                 ("ms_address_free", ctypes.c_double),
                 ("table1_bytes", ctypes.c_uint64), ("table1_hipmalloc_ms", ctypes.c_double),
                 ("table1_reserve_ms", ctypes.c_double), ("table1_create_ms", ctypes.c_double),
-                ("table1_map_ms", ctypes.c_double), ("table1_set_access_ms", ctypes.c_double)]
+                ("table1_map_ms", ctypes.c_double), ("table1_set_access_ms", ctypes.c_double),
+                ("peak_mapped_chunks", ctypes.c_uint64)]
 
 
 class vms_vmm_latency_report(ctypes.Structure):
@@ -104,7 +105,7 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
                         ("fragmentation", "<f8")])
 
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
-           "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms",
+           "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms", "vms_demo_plan",
            "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
            "vms_demo_run", "vms_vmm_latency", "vms_measure_peaks",
            "vms_live_config_default", "vms_live_create", "vms_live_malloc", "vms_live_free", "vms_live_run_trace",
@@ -152,6 +153,8 @@ def lib():
         L.vms_selftest.argtypes = []
         L.vms_demo_run.restype = ctypes.c_int
         L.vms_demo_run.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
+        L.vms_demo_plan.restype = ctypes.c_int
+        L.vms_demo_plan.argtypes = [ctypes.POINTER(vms_config), vp, vp, u32, ctypes.POINTER(vms_demo_report)]
         L.vms_vmm_latency.restype = ctypes.c_int
         L.vms_vmm_latency.argtypes = [u64, u64, u32, ctypes.POINTER(vms_vmm_latency_report)]
         L.vms_measure_peaks.restype = ctypes.c_int
@@ -212,6 +215,18 @@ def vms_demo_run(cfg, h_events, h_dec_vms, n_events=None):
     rep = vms_demo_report()
     rep.struct_size = ctypes.sizeof(vms_demo_report)
     rc = lib().vms_demo_run(ctypes.byref(cfg), ev.ctypes.data, dec.ctypes.data, n, ctypes.byref(rep))
+    return rc, rep
+
+
+def vms_demo_plan(cfg, h_events, h_dec_vms, n_events=None):
+    """The driver calls vms_demo_run would make for this trace, counted on the host.  Returns (rc, report)."""
+    ev = np.ascontiguousarray(h_events, dtype=np.uint64)
+    dec = np.ascontiguousarray(h_dec_vms, dtype=np.uint64)
+    assert ev.ndim == 1 and ev.shape == dec.shape
+    n = ev.shape[0] if n_events is None else min(int(n_events), ev.shape[0])
+    rep = vms_demo_report()
+    rep.struct_size = ctypes.sizeof(vms_demo_report)
+    rc = lib().vms_demo_plan(ctypes.byref(cfg), ev.ctypes.data, dec.ctypes.data, n, ctypes.byref(rep))
     return rc, rep
 
 

@@ -73,6 +73,8 @@ struct Demo {
     u32 next_sid = 0;
     u64 clock = 0;
     hipError_t err = hipSuccess;
+    bool dry = false;                        // books only: no driver call, mappings are counted
+    u64 mapped_now = 0;                      // chunks mapped at this moment, over all live ranges
 
     Demo(const vms_config &c, vms_demo_report &r) : cfg(c), rep(r), chunk_bytes(c.chunk_bytes), slots(c.max_slots) {}
 
@@ -95,6 +97,14 @@ struct Demo {
             covered += r.second;
         }
         if (covered != total_chunks) return nullptr;
+        mapped_now += total_chunks;
+        rep.peak_mapped_chunks = std::max<u64>(rep.peak_mapped_chunks, mapped_now);
+        if (dry) {
+            rep.n_reserve++;
+            rep.n_map += total_chunks;
+            rep.n_set_access += total_chunks;
+            return (char *)chunk_bytes;      // any non-null value: never dereferenced
+        }
         {
             Timer t(&rep.ms_reserve, &rep.n_reserve);
             if (!ok(hipMemAddressReserve(&va, (size_t)total_chunks * chunk_bytes, 0, nullptr, 0), 1)) return nullptr;
@@ -117,6 +127,12 @@ struct Demo {
     void unmap(char *va, u32 total_chunks)
     {
         if (!va) return;
+        mapped_now -= total_chunks;
+        if (dry) {
+            rep.n_unmap++;
+            rep.n_address_free++;
+            return;
+        }
         {
             Timer t(&rep.ms_unmap, &rep.n_unmap);
             ok(hipMemUnmap(va, (size_t)total_chunks * chunk_bytes), 5);
@@ -131,6 +147,12 @@ struct Demo {
         u32 start = (u32)chunks.size();
         for (u32 i = 0; i < len; i++) {
             hipMemGenericAllocationHandle_t h;
+            if (dry) {
+                memset(&h, 0, sizeof h);
+                chunks.push_back(h);
+                rep.n_create++;
+                continue;
+            }
             Timer t(&rep.ms_create, &rep.n_create);
             if (!ok(hipMemCreate(&h, chunk_bytes, &prop, 0), 2)) return false;
             chunks.push_back(h);
@@ -220,7 +242,7 @@ struct Demo {
     // range, read back through the sBlock's range.
     void check_alias(const SBlock &s)
     {
-        if (!s.va || rep.alias_checks >= 64) return;
+        if (dry || !s.va || rep.alias_checks >= 64) return;
         const PBlock &p = pblocks.at(s.runs[0].first);
         u64 pattern = 0xA5A5000000000000ull | ((u64)rep.alias_checks << 32) | s.runs[0].first, back = 0;
         if (!ok(hipMemcpy(p.va, &pattern, sizeof pattern, hipMemcpyHostToDevice), 8)) return;
@@ -337,6 +359,10 @@ struct Demo {
     {
         for (auto &s : sblocks) unmap(s.second.va, s.second.size);
         for (auto &p : pblocks) unmap(p.second.va, p.second.len);
+        if (dry) {
+            rep.n_release += chunks.size();
+            return;
+        }
         for (auto h : chunks) {
             Timer t(&rep.ms_release, &rep.n_release);
             ok(hipMemRelease(h), 6);
@@ -389,6 +415,31 @@ void table1(vms_demo_report &rep, const hipMemAllocationProp &prop, const hipMem
 }
 
 }  // namespace
+
+// What vms_demo_run would do, without touching the device: the same books, every driver call
+// counted instead of made.  Tells whether a trace fits the device before anything is mapped.
+extern "C" int vms_demo_plan(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms,
+                             uint32_t n_events, vms_demo_report *out)
+{
+    if (!cfg || !h_events || !h_dec_vms || !out) return VMS_EINVAL;
+    if (cfg->struct_size != sizeof(vms_config) || out->struct_size != sizeof(vms_demo_report)) return VMS_ESTRUCT;
+    memset((char *)out + sizeof(uint32_t), 0, sizeof *out - sizeof(uint32_t));
+    Demo d(*cfg, *out);
+    d.dry = true;
+    int rc = VMS_OK;
+    for (uint32_t i = 0; i < n_events; i++) {
+        if (!d.step(h_events[i], h_dec_vms[i])) {
+            out->failed_event = i;
+            rc = VMS_EINVAL;
+            break;
+        }
+        out->events_replayed = i + 1;
+    }
+    out->chunks_created = d.chunks.size();
+    out->sblocks_cached = (uint32_t)d.sblocks.size();
+    d.teardown();
+    return rc;
+}
 
 extern "C" int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, const uint64_t *h_dec_vms,
                             uint32_t n_events, vms_demo_report *out)

@@ -56,7 +56,11 @@ def test_worked_examples_on_gpu():
     for path in sorted(glob.glob(os.path.join(GOLDEN, "*.txt"))):
         fx = load_fixture(path)
         ev = fx["events"][None, :]
-        gpu_util.assert_parity(ev, gpu_util.make_cfg(1, ev.shape[1], 16), label=os.path.basename(path))
+        kw = dict(spool_threshold=int(fx["spool_threshold"])) if "spool_threshold" in fx else {}
+        gpu_util.assert_parity(ev, gpu_util.make_cfg(1, ev.shape[1], 16, **kw), label=os.path.basename(path))
+        # and through the fine-grained kernel variant
+        gpu_util.assert_parity(ev, gpu_util.make_cfg(1, ev.shape[1], 16, variant=binding.VMS_VARIANT_FINE, **kw),
+                               label=os.path.basename(path) + " (fine-grained variant)")
 
 
 def test_ragged_and_empty_traces():

@@ -37,7 +37,7 @@ FIXTURES = sorted(glob.glob(os.path.join(GOLDEN, "*.txt")))
 @pytest.mark.parametrize("path", FIXTURES, ids=[os.path.basename(p) for p in FIXTURES])
 def test_worked_example(path):
     fx = load_fixture(path)
-    P = oracle.make_params(max_slots=16)
+    P = oracle.make_params(max_slots=16, spool_threshold=int(fx.get("spool_threshold", 512)))
     for pol, name in ((oracle.SPLIT, "split"), (oracle.VMS, "vms")):
         if "codes_" + name not in fx:
             continue
@@ -53,6 +53,13 @@ def test_worked_example(path):
             is_alloc = (dec & np.uint64(15)) != 0
             got = ((dec >> np.uint64(5)) & np.uint64(1)) * is_alloc
             assert got.tolist() == [int(x) for x in fx["sblock_" + name].split()]
+        if "evicted_" + name in fx:
+            # bit 7 of an ALLOC decision: StitchFree released at least one sBlock
+            is_alloc = (dec & np.uint64(15)) != 0
+            got = ((dec >> np.uint64(7)) & np.uint64(1)) * is_alloc
+            assert got.tolist() == [int(x) for x in fx["evicted_" + name].split()]
+        if "n_evicted_" + name in fx:
+            assert st["n_sblock_evicted"][0] == int(fx["n_evicted_" + name])
         for key in ("peak_active", "peak_reserved"):
             if key + "_" + name in fx:
                 assert st[key][0] == int(fx[key + "_" + name]) * MiB
