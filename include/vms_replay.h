@@ -279,10 +279,13 @@ typedef struct vms_peaks_report {
     double   copy_ms, hbm_copy_gbs;
     uint64_t lds_bytes;          /* bytes read from LDS by the read loop per launch                */
     double   lds_ms, lds_read_gbs;
+    uint64_t read_bytes;         /* bytes read by the read-only kernel per launch                  */
+    double   read_ms, hbm_read_gbs;
 } vms_peaks_report;
 
 /* Two micro-benchmarks for the proportions of Sec. 5.1-style reports on the device at hand: a
- * plain 1 GiB device-to-device copy kernel (HBM bandwidth actually reachable, read + write) and a
+ * plain 1 GiB device-to-device copy kernel and the same kernel without its stores (HBM bandwidth
+ * actually reachable: read + write, and read alone; four 16-byte loads in flight per lane), and a
  * conflict-free 16-byte-per-lane LDS read loop on every compute unit (LDS bandwidth actually
  * reachable).  Allocates 2 GiB of device memory for the duration of the call; best of three timed
  * rounds each.  Synchronous, on the default stream.                                                */

@@ -69,7 +69,8 @@ class vms_peaks_report(ctypes.Structure):
     _fields_ = [("struct_size", ctypes.c_uint32), ("hip_error", ctypes.c_int32),
                 ("compute_units", ctypes.c_uint32), ("clock_mhz", ctypes.c_uint32),
                 ("copy_bytes", ctypes.c_uint64), ("copy_ms", ctypes.c_double), ("hbm_copy_gbs", ctypes.c_double),
-                ("lds_bytes", ctypes.c_uint64), ("lds_ms", ctypes.c_double), ("lds_read_gbs", ctypes.c_double)]
+                ("lds_bytes", ctypes.c_uint64), ("lds_ms", ctypes.c_double), ("lds_read_gbs", ctypes.c_double),
+                ("read_bytes", ctypes.c_uint64), ("read_ms", ctypes.c_double), ("hbm_read_gbs", ctypes.c_double)]
 
 
 class vms_live_config(ctypes.Structure):

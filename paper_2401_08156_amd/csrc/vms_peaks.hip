@@ -12,11 +12,38 @@ namespace {
 typedef uint32_t u32;
 typedef uint64_t u64;
 
-// grid-stride copy, 16 bytes per lane and trip
+// grid-stride copy: every lane has four 16-byte loads in flight before its first store (64 KB per
+// workgroup and trip); n16 is a multiple of 4 * 256
 __global__ __launch_bounds__(256) void peaks_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
 {
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+    const size_t stride = (size_t)gridDim.x * 1024;
+    for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) v[q] = __builtin_nontemporal_load(src + i + q * 256);
+#pragma unroll
+        for (int q = 0; q < 4; q++) __builtin_nontemporal_store(v[q], dst + i + q * 256);
+    }
+}
+
+// the same loads without the stores: what reading alone reaches; the xor of what was read is stored once
+__global__ __launch_bounds__(256) void peaks_read_kernel(const uint4 *__restrict__ src, u32 *out, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 1024;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
+        uint4 v[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) v[q] = __builtin_nontemporal_load(src + i + q * 256);
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            acc.x ^= v[q].x;
+            acc.y ^= v[q].y;
+            acc.z ^= v[q].z;
+            acc.w ^= v[q].w;
+        }
+    }
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
 }
 
 // every lane reads 16 bytes of the workgroup's 32 KB of LDS per trip, `iters` trips, conflict-free
@@ -66,16 +93,22 @@ extern "C" int vms_measure_peaks(vms_peaks_report *out)
     if (e == hipSuccess) e = hipMalloc(&b, bytes);
     if (e == hipSuccess) e = hipMalloc((void **)&o, (size_t)groups * 256 * sizeof(u32));
     if (e == hipSuccess) e = hipMemset(a, 1, bytes);
-    float best_copy = 1e30f, best_lds = 1e30f;
+    float best_copy = 1e30f, best_lds = 1e30f, best_read = 1e30f;
     for (int round = 0; round < 4 && e == hipSuccess; round++) {
         (void)hipEventRecord(e0, nullptr);
-        hipLaunchKernelGGL(peaks_copy_kernel, dim3((u32)prop.multiProcessorCount * 16), dim3(256), 0, nullptr,
+        hipLaunchKernelGGL(peaks_copy_kernel, dim3((u32)prop.multiProcessorCount * 8), dim3(256), 0, nullptr,
                            (const uint4 *)a, (uint4 *)b, bytes / 16);
         (void)hipEventRecord(e1, nullptr);
         e = hipEventSynchronize(e1);
         float ms = 0;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
         if (round && ms < best_copy) best_copy = ms;  // the first round warms up
+        (void)hipEventRecord(e0, nullptr);
+        hipLaunchKernelGGL(peaks_read_kernel, dim3(groups), dim3(256), 0, nullptr, (const uint4 *)a, o, bytes / 16);
+        (void)hipEventRecord(e1, nullptr);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (round && ms < best_read) best_read = ms;
         (void)hipEventRecord(e0, nullptr);
         hipLaunchKernelGGL(peaks_lds_kernel, dim3(groups), dim3(256), 0, nullptr, o, iters);
         (void)hipEventRecord(e1, nullptr);
@@ -96,6 +129,9 @@ extern "C" int vms_measure_peaks(vms_peaks_report *out)
     out->copy_bytes = 2 * (uint64_t)bytes;          // read + written
     out->copy_ms = best_copy;
     out->hbm_copy_gbs = (double)out->copy_bytes / (best_copy * 1e-3) / 1e9;
+    out->read_bytes = (uint64_t)bytes;
+    out->read_ms = best_read;
+    out->hbm_read_gbs = (double)out->read_bytes / (best_read * 1e-3) / 1e9;
     out->lds_bytes = (uint64_t)groups * 256 * 16 * 8 * iters;
     out->lds_ms = best_lds;
     out->lds_read_gbs = (double)out->lds_bytes / (best_lds * 1e-3) / 1e9;

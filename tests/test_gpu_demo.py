@@ -61,6 +61,33 @@ def test_demo_offload_trace_prefix():
     assert rep.chunks_created * cfg.chunk_bytes == st["final_reserved"][1, 0]    # no small requests here
 
 
+def test_demo_whole_config5_trace_chosen_by_plan():
+    # a whole trace of the 16,384 x 100,000 mixture with real mappings.  vms_demo_plan (host only)
+    # counts what a trace would map: the offloading trace would hold over a million chunk mappings at
+    # once (the driver refuses beyond some 60,000), the recomputation trace about 31,000.
+    chosen = None
+    for first, kind in ((1, 3), (0, 2)):
+        ev, ms = tg.generate(5, n_traces=1, n_events=100000, first_trace=first)
+        cfg = workloads.make_config(binding, 5, 1, 100000, ms, kind=kind)
+        _, dv, st = gpu_util.gpu_replay(ev, cfg)
+        rc, plan = binding.vms_demo_plan(cfg, ev[0], dv[0])
+        assert rc == 0 and plan.events_replayed == 100000
+        assert plan.n_stitches == st["n_sblock_created"][1, 0] and plan.n_sblocks_released == st["n_sblock_evicted"][1, 0]
+        if kind == 3:
+            assert plan.peak_mapped_chunks > 500000
+        else:
+            assert plan.peak_mapped_chunks < 48000
+            chosen = (cfg, ev[0], dv[0], st, plan)
+    cfg, ev, dv, st, plan = chosen
+    rc, rep = binding.vms_demo_run(cfg, ev, dv)
+    assert rc == 0, (rc, rep.failed_event, rep.hip_error, rep.failed_api, rep.chunks_created, rep.n_map)
+    assert rep.events_replayed == 100000 and rep.alias_failures == 0 and rep.alias_checks > 0
+    assert rep.chunks_created * cfg.chunk_bytes == st["final_reserved"][1, 0]
+    # the plan foresaw every call
+    for f in ("n_reserve", "n_create", "n_map", "n_set_access", "n_unmap", "n_release", "n_address_free", "peak_mapped_chunks"):
+        assert getattr(rep, f) == getattr(plan, f), f
+
+
 def test_demo_rejects_inconsistent_decisions():
     cfg, ev, dv, _ = replay_one(1, 600)
     bad = dv.copy()

@@ -88,7 +88,7 @@ def test_transformer_slices(cfg_id, nt, ne):
 
 
 def test_runs_in_global_memory_variant():
-    # more than 16384 run entries per trace moves the sBlock chunk runs from LDS to the workspace
+    # more than 16384 run entries per trace: the fine-grained variant, with its lists in the workspace
     ev, ms = tg.generate(1, n_traces=64, n_events=2000, seed=21)
     cfg = gpu_util.make_cfg(64, 2000, ms, max_runs=20000)
     gpu_util.assert_parity(ev, cfg, label="config 1, runs in HBM")
@@ -111,14 +111,14 @@ def test_config3_slice_with_large_tables():
     gpu_util.assert_parity(ev, cfg, label="config 3 slice")
 
 
-def test_stamps_in_workspace_when_tables_exceed_lds():
-    # tables this large do not fit 160 KB of LDS with the last-use stamps in it: the stamps move to
-    # the workspace; low thresholds keep StitchFree (their only reader) busy
+def test_largest_offloading_tables_with_low_thresholds():
+    # the table sizes of the largest offloading traces; low thresholds make StitchFree choose among many
+    # inactive sBlocks by their last-use stamps (read from the list headers in the workspace)
     for seed, threshold in ((5, 128), (6, 32)):
         ev, ms = tg.generate(3, n_traces=8, n_events=8000, seed=seed)
         cfg = gpu_util.make_cfg(8, 8000, ms, max_free_blocks=64, max_pblocks=8192, max_sblocks=4352,
                                 max_runs=1 << 18, max_chunks=16384, spool_threshold=threshold)
-        gpu_util.assert_parity(ev, cfg, label="config 3 slice, stamps in HBM, threshold %d" % threshold)
+        gpu_util.assert_parity(ev, cfg, label="config 3 slice, largest tables, threshold %d" % threshold)
 
 
 def test_table_overflow_is_reported_not_fatal():
@@ -232,3 +232,67 @@ def test_largest_requests_and_full_capacity():
         st = gpu_util.assert_parity(ev, cfg, label="largest requests, capacity %d" % cap)
         assert st["n_code"][:, 0, 5].min() >= 2                     # the 1 TiB request and the 2 MiB one fail under both policies
         assert (st["peak_reserved"] == 512 * GiB).all()
+
+
+def test_batch_summary_matches_the_oracle():
+    # Sec. 5.1 "Metric": sums of the peaks, mean and maximum fragmentation over the batch, and the
+    # memory reduction ratio (sum reserved splitting - sum reserved stitching) / sum reserved splitting,
+    # reduced on the device; here against the same reductions over the oracle's per-trace statistics
+    import torch
+    ev, ms = tg.generate(4, n_traces=70, n_events=3000, seed=9)
+    ev[3] = tg.make_events([("F", 0)] + [("A", 1, 2 * MiB)] * 2999)      # a trace with invalid events: flagged
+    for mask in (3, 1, 2):
+        cfg = gpu_util.make_cfg(70, 3000, ms, policy_mask=mask)
+        r = binding.Replay(cfg)
+        r.run(torch.from_numpy(ev.view(np.int64)).cuda())
+        got = r.summary()
+        gst = r.stats()
+        r.close()
+        P = gpu_util.oracle_params(cfg)
+        ost = [oracle.replay(ev, P, pol, want_decisions=False, threads=8)[1] if mask & (1 << pol) else None for pol in (0, 1)]
+        for pol in (0, 1):
+            if ost[pol] is None:
+                assert got.sum_peak_reserved[pol] == 0 and got.sum_peak_active[pol] == 0 and got.n_flagged[pol] == 0
+                assert got.max_fragmentation[pol] == 0.0 and got.mean_fragmentation[pol] == 0.0
+                continue
+            o = ost[pol]
+            assert got.sum_peak_reserved[pol] == int(o["peak_reserved"].sum(dtype=np.uint64))
+            assert got.sum_peak_active[pol] == int(o["peak_active"].sum(dtype=np.uint64))
+            assert got.n_flagged[pol] == int((o["status"] != 0).sum()) >= 1
+            assert got.max_fragmentation[pol] == float(o["fragmentation"].max())
+            mean = 0.0
+            for f in o["fragmentation"]:                 # summed in trace order, as the device does
+                mean += float(f)
+            assert got.mean_fragmentation[pol] == mean / 70
+            assert np.array_equal(gst[pol]["fragmentation"], o["fragmentation"])
+        if mask == 3:
+            a, b = int(ost[0]["peak_reserved"].sum(dtype=np.uint64)), int(ost[1]["peak_reserved"].sum(dtype=np.uint64))
+            assert got.mem_reduction_ratio == float(a - b) / float(a) and got.mem_reduction_ratio > 0
+        else:
+            assert got.mem_reduction_ratio == 0.0
+
+
+def test_kernel_variant_choice():
+    # the same traces through the flat and the fine-grained stitching kernels, chosen by hand; what the
+    # library chooses by itself; and 32-bit chunk numbers in the fine-grained one
+    ev, ms = tg.generate(2, n_traces=24, n_events=4000, seed=31)
+    for variant in (binding.VMS_VARIANT_FLAT, binding.VMS_VARIANT_FINE):
+        cfg = gpu_util.make_cfg(24, 4000, ms, variant=variant, max_chunks=4096)
+        r = binding.Replay(cfg)
+        lds = r.lds_bytes()[1]
+        r.close()
+        assert (lds < 20000) == (variant == binding.VMS_VARIANT_FINE)
+        gpu_util.assert_parity(ev, cfg, label="variant %d" % variant)
+    # few traces: the flat variant (lower latency per trace); a batch that does not fit the compute
+    # units at once, with tables that are small in the fine-grained layout: that one
+    few = binding.Replay(gpu_util.make_cfg(24, 4000, ms, max_chunks=4096))
+    many = binding.Replay(gpu_util.make_cfg(6000, 4000, ms, max_chunks=4096))
+    assert few.lds_bytes()[1] > 30000 > 20000 > many.lds_bytes()[1]
+    few.close()
+    many.close()
+    # tables too large for the flat variant cannot be forced into it
+    with pytest.raises(binding.VmsError):
+        binding.Replay(gpu_util.make_cfg(24, 4000, ms, variant=binding.VMS_VARIANT_FLAT, max_runs=1 << 18))
+    ev, ms = tg.generate(3, n_traces=6, n_events=5000, seed=32)
+    cfg = gpu_util.make_cfg(6, 5000, ms, max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=70000)
+    gpu_util.assert_parity(ev, cfg, label="fine-grained variant, 32-bit chunk numbers")

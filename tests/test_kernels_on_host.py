@@ -1,0 +1,89 @@
+"""The replay kernels compiled for the host (tests/emu: 64 lanes as cooperative fibers, guard bands
+around the LDS and every buffer) against the oracle: finds wrong indexing and wrong decisions
+without a GPU.  The lanes run one after another between wave-wide operations, so what this checks
+is the kernels' logic and memory accesses, not their timing; the GPU parity tests remain the
+proof for the device."""
+import glob
+import os
+
+import numpy as np
+import pytest
+
+import emu
+import gpu_util
+import oracle
+from paper_2401_08156_amd import binding
+from paper_2401_08156_amd import tracegen as tg
+from test_oracle_examples import GOLDEN, load_fixture
+
+MiB = 1 << 20
+
+
+def check(ev, cfg, n_events=None, label=""):
+    ds, dv, st = emu.replay(ev, cfg, binding.STATS_DTYPE, n_events)
+    P = gpu_util.oracle_params(cfg)
+    for pol, gdec in ((0, ds), (1, dv)):
+        if not (cfg.policy_mask & (1 << pol)):
+            continue
+        odec, ost = oracle.replay(ev, P, pol, n_events=n_events, threads=8)
+        gst = st[pol]
+        assert not (gst["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(), (label, pol, gst["status"], gst["overflow_event"])
+        valid = np.ones(ev.shape, dtype=bool) if n_events is None else np.arange(ev.shape[1])[None, :] < np.asarray(n_events)[:, None]
+        same = (gdec == odec) | ~valid
+        if not same.all():
+            t, i = np.argwhere(~same)[0]
+            raise AssertionError("%s policy %d trace %d event %d: kernel %#x oracle %#x" % (label, pol, t, i, int(gdec[t, i]), int(odec[t, i])))
+        assert np.all(gdec[~valid] == np.uint64(0xFFFFFFFFFFFFFFFF)), "wrote past the end of a trace"
+        for f in gpu_util.COMPARED_FIELDS:
+            assert np.array_equal(gst[f], ost[f]), (label, pol, f, gst[f], ost[f])
+    return st
+
+
+def test_wave_primitives_on_host_lanes():
+    assert emu.lib().emu_selftest() == 0
+
+
+def test_worked_examples_fine_grained_variant():
+    for path in sorted(glob.glob(os.path.join(GOLDEN, "*.txt"))):
+        fx = load_fixture(path)
+        ev = fx["events"][None, :]
+        kw = dict(spool_threshold=int(fx["spool_threshold"])) if "spool_threshold" in fx else {}
+        cfg = gpu_util.make_cfg(1, ev.shape[1], 16, variant=binding.VMS_VARIANT_FINE, policy_mask=2, **kw)
+        check(ev, cfg, label=os.path.basename(path))
+
+
+def test_splitting_kernels():
+    ev, ms = tg.generate(1, n_traces=2, n_events=1500)
+    check(ev, gpu_util.make_cfg(2, 1500, ms, policy_mask=1), label="pool in LDS")
+    check(ev, gpu_util.make_cfg(2, 1500, ms, policy_mask=1, max_free_blocks=150), label="pool in registers")
+    ev, ms = tg.generate(4, n_traces=1, n_events=2000)
+    check(ev, gpu_util.make_cfg(1, 2000, ms, policy_mask=1), label="slot table in LDS")
+
+
+@pytest.mark.parametrize("kind,nt,ne,tables", [
+    (1, 2, 2000, dict(max_runs=20000)),
+    (2, 2, 3000, dict(max_runs=20000)),
+    (3, 2, 4000, dict(max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=16384)),
+    (3, 2, 3000, dict(max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=16384, spool_threshold=32)),
+    (4, 1, 3000, dict(max_runs=20000, max_chunks=32768)),                       # slot table in LDS
+    (1, 1, 1500, dict(max_runs=20000, max_chunks=70000)),                       # 32-bit chunk numbers
+    (2, 1, 3000, dict(variant=2, max_runs=600, spool_threshold=40, max_sblocks=128)),   # small arena: lists are squeezed
+    (1, 2, 1200, dict(variant=2, frag_limit_bytes=8 * MiB, small_limit_bytes=512)),
+    (1, 2, 1200, dict(variant=2, capacity_bytes=256 * MiB)),
+])
+def test_fine_grained_variant(kind, nt, ne, tables):
+    ev, ms = tg.generate(kind, n_traces=nt, n_events=ne, seed=7 + kind)
+    cfg = gpu_util.make_cfg(nt, ne, ms, policy_mask=2, **tables)
+    check(ev, cfg, label="generator %d %s" % (kind, tables))
+
+
+def test_ragged_traces_and_nothing_written_past_the_end():
+    ev, ms = tg.generate(1, n_traces=3, n_events=700, seed=11)
+    check(ev, gpu_util.make_cfg(3, 700, ms, max_runs=20000), n_events=np.array([0, 333, 700], dtype=np.uint32), label="ragged")
+
+
+def test_table_overflow_is_flagged_not_fatal():
+    ev, ms = tg.generate(3, n_traces=1, n_events=2500, seed=5)
+    cfg = gpu_util.make_cfg(1, 2500, ms, policy_mask=2, variant=2, max_pblocks=64, max_sblocks=520, max_chunks=4096)
+    _, _, st = emu.replay(ev, cfg, binding.STATS_DTYPE)
+    assert st["status"][1, 0] & binding.VMS_ST_TABLE_OVERFLOW and st["overflow_event"][1, 0] < 2500

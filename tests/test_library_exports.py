@@ -32,7 +32,7 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding.vms_summary) == 88
     assert ctypes.sizeof(binding.vms_demo_report) == 232
     assert ctypes.sizeof(binding.vms_vmm_latency_report) == 104
-    assert ctypes.sizeof(binding.vms_peaks_report) == 64
+    assert ctypes.sizeof(binding.vms_peaks_report) == 88
     assert ctypes.sizeof(binding.vms_live_config) == 48
     assert ctypes.sizeof(binding.vms_live_api_report) == 152
 
