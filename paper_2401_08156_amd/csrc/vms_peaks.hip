@@ -11,14 +11,15 @@ namespace {
 
 typedef uint32_t u32;
 typedef uint64_t u64;
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));     // 16 bytes, a type the nontemporal builtins take
 
 // grid-stride copy: every lane has four 16-byte loads in flight before its first store (64 KB per
 // workgroup and trip); n16 is a multiple of 4 * 256
-__global__ __launch_bounds__(256) void peaks_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16)
+__global__ __launch_bounds__(256) void peaks_copy_kernel(const v4u *__restrict__ src, v4u *__restrict__ dst, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * 1024;
     for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
-        uint4 v[4];
+        v4u v[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) v[q] = __builtin_nontemporal_load(src + i + q * 256);
 #pragma unroll
@@ -27,21 +28,16 @@ __global__ __launch_bounds__(256) void peaks_copy_kernel(const uint4 *__restrict
 }
 
 // the same loads without the stores: what reading alone reaches; the xor of what was read is stored once
-__global__ __launch_bounds__(256) void peaks_read_kernel(const uint4 *__restrict__ src, u32 *out, size_t n16)
+__global__ __launch_bounds__(256) void peaks_read_kernel(const v4u *__restrict__ src, u32 *out, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * 1024;
-    uint4 acc = make_uint4(0, 0, 0, 0);
+    v4u acc = { 0, 0, 0, 0 };
     for (size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x; i < n16; i += stride) {
-        uint4 v[4];
+        v4u v[4];
 #pragma unroll
         for (int q = 0; q < 4; q++) v[q] = __builtin_nontemporal_load(src + i + q * 256);
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            acc.x ^= v[q].x;
-            acc.y ^= v[q].y;
-            acc.z ^= v[q].z;
-            acc.w ^= v[q].w;
-        }
+        for (int q = 0; q < 4; q++) acc ^= v[q];
     }
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
 }
@@ -97,14 +93,14 @@ extern "C" int vms_measure_peaks(vms_peaks_report *out)
     for (int round = 0; round < 4 && e == hipSuccess; round++) {
         (void)hipEventRecord(e0, nullptr);
         hipLaunchKernelGGL(peaks_copy_kernel, dim3((u32)prop.multiProcessorCount * 8), dim3(256), 0, nullptr,
-                           (const uint4 *)a, (uint4 *)b, bytes / 16);
+                           (const v4u *)a, (v4u *)b, bytes / 16);
         (void)hipEventRecord(e1, nullptr);
         e = hipEventSynchronize(e1);
         float ms = 0;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
         if (round && ms < best_copy) best_copy = ms;  // the first round warms up
         (void)hipEventRecord(e0, nullptr);
-        hipLaunchKernelGGL(peaks_read_kernel, dim3(groups), dim3(256), 0, nullptr, (const uint4 *)a, o, bytes / 16);
+        hipLaunchKernelGGL(peaks_read_kernel, dim3(groups), dim3(256), 0, nullptr, (const v4u *)a, o, bytes / 16);
         (void)hipEventRecord(e1, nullptr);
         if (e == hipSuccess) e = hipEventSynchronize(e1);
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
