@@ -188,6 +188,19 @@ int vms_replay_lds_bytes(const vms_replay *h, uint32_t out[2]);
 int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_events,
                    uint64_t *d_dec_split, uint64_t *d_dec_vms, void *d_workspace, void *hip_stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): vms_replay_run with the workspace taken from an array
+ * that is part of the library's device code (vms_replay_static_workspace_bytes() = 32 MiB per
+ * device, held from the first use on that device until the process ends) instead of from the
+ * caller.  Allocates nothing and calls no allocating routine.  VMS_EWORKSPACE if the handle needs
+ * more workspace than the array holds (vms_replay_workspace_bytes), VMS_EINVAL if the current
+ * device is not the one the handle was created on.  All calls on one device share the one array:
+ * runs that overlap on a device race (also across handles); the array keeps the last run's lists,
+ * which the next run overwrites before reading.  Everything else as vms_replay_run.            */
+int vms_replay_run_static(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_events,
+                          uint64_t *d_dec_split, uint64_t *d_dec_vms, void *hip_stream);
+size_t vms_replay_static_workspace_bytes(void);
+
 /* Wait for the last run and copy statistics to the host: h_out[p * n_traces + t]
  * with p = 0 splitting, 1 VMS; n must be 2 * n_traces.  Records of a policy
  * that did not run are zero.                                                  */

@@ -106,7 +106,7 @@ STATS_DTYPE = np.dtype([("peak_requested", "<u8"), ("peak_active", "<u8"), ("pea
                         ("fragmentation", "<f8")])
 
 EXPORTS = ["vms_config_default", "vms_replay_create", "vms_replay_workspace_bytes", "vms_replay_lds_bytes",
-           "vms_replay_run", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms", "vms_demo_plan",
+           "vms_replay_run", "vms_replay_run_static", "vms_replay_static_workspace_bytes", "vms_replay_stats", "vms_replay_summary", "vms_replay_last_kernel_ms", "vms_demo_plan",
            "vms_replay_destroy", "vms_replay_last_hip_error", "vms_strerror", "vms_selftest",
            "vms_demo_run", "vms_vmm_latency", "vms_measure_peaks",
            "vms_live_config_default", "vms_live_create", "vms_live_malloc", "vms_live_free", "vms_live_run_trace",
@@ -138,6 +138,10 @@ def lib():
         L.vms_replay_lds_bytes.argtypes = [vp, ctypes.POINTER(u32 * 2)]
         L.vms_replay_run.restype = ctypes.c_int
         L.vms_replay_run.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+        L.vms_replay_run_static.restype = ctypes.c_int
+        L.vms_replay_run_static.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.vms_replay_static_workspace_bytes.restype = sz
+        L.vms_replay_static_workspace_bytes.argtypes = []
         L.vms_replay_stats.restype = ctypes.c_int
         L.vms_replay_stats.argtypes = [vp, vp, sz]
         L.vms_replay_summary.restype = ctypes.c_int
@@ -290,6 +294,18 @@ class Replay:
                                   ctypes.c_void_p(ws_ptr) if ws_ptr else None, ctypes.c_void_p(s.cuda_stream))
         if rc != VMS_OK:
             raise VmsError(rc, "vms_replay_run (hip error %d)" % lib().vms_replay_last_hip_error(self._h))
+
+    def run_static(self, d_events, d_n_events=None, d_dec_split=None, d_dec_vms=None, stream=None):
+        """vms_replay_run_static: the same replay with the library's built-in workspace (nothing is allocated)."""
+        import torch
+        assert d_events.is_cuda and d_events.is_contiguous() and d_events.element_size() == 8
+        assert tuple(d_events.shape) == (self.cfg.n_traces, self.cfg.max_events)
+        s = torch.cuda.current_stream(d_events.device) if stream is None else stream
+        ptr = lambda t: None if t is None else ctypes.c_void_p(t.data_ptr())
+        rc = lib().vms_replay_run_static(self._h, ptr(d_events), ptr(d_n_events), ptr(d_dec_split), ptr(d_dec_vms),
+                                         ctypes.c_void_p(s.cuda_stream))
+        if rc != VMS_OK:
+            raise VmsError(rc, "vms_replay_run_static (hip error %d)" % lib().vms_replay_last_hip_error(self._h))
 
     def stats(self):
         """Statistics of the last run: numpy record array [2, n_traces] ([0] splitting, [1] VMS)."""

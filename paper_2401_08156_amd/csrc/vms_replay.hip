@@ -13,6 +13,14 @@ namespace {
 
 const uint32_t LDS_PER_CU = 160 * 1024;
 
+// Workspace for callers that cannot allocate (vms_replay_run_static): one array per device, part of
+// the loaded code object, held until the process ends.  In host code the name below is only a
+// handle for hipGetSymbolAddress; the device address it yields is what the kernels are given.
+const size_t STATIC_WS_BYTES = (size_t)32 << 20;
+const int STATIC_WS_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+void *g_scratch_ptr[STATIC_WS_DEVICES];     // per device: address of its copy of scratch[]
+
 }  // namespace
 
 struct vms_replay {
@@ -238,6 +246,29 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     h->last_stream = st;
     h->ran = true;
     return VMS_OK;
+}
+
+size_t vms_replay_static_workspace_bytes(void) { return STATIC_WS_BYTES; }
+
+int vms_replay_run_static(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_events, uint64_t *d_dec_split,
+                          uint64_t *d_dec_vms, void *hip_stream)
+{
+    if (!h || !d_events) return VMS_EINVAL;
+    if (h->ws_bytes > STATIC_WS_BYTES) return VMS_EWORKSPACE;   // this handle needs more than the built-in array holds
+    int dev = -1;
+    HIP_TRY(h, hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_WS_DEVICES || dev != h->device) return VMS_EINVAL;
+    if (!g_scratch_ptr[dev]) {
+        // once per device, with that device current: every device holds its own copy of the array
+        void *p = nullptr;
+        HIP_TRY(h, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255)) return VMS_EWORKSPACE;
+        g_scratch_ptr[dev] = p;
+    }
+    // Nothing in the array has to start at zero: the kernels write every word of a trace's slice
+    // before they read it.  Calls that overlap on one device share the array and race.
+    return vms_replay_run(h, d_events, d_n_events, d_dec_split, d_dec_vms, h->ws_bytes ? g_scratch_ptr[dev] : nullptr,
+                          hip_stream);
 }
 
 int vms_replay_stats(vms_replay *h, vms_trace_stats *h_out, size_t n)
