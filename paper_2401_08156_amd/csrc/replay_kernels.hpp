@@ -567,12 +567,8 @@ struct SplitRegs {
 //            Compacted through a global-memory buffer when full.
 //   pp, sp   first level of the rank searches in pool[] and skey[], held in registers.
 // ---------------------------------------------------------------------------
-// BIG: for traces whose sBlocks hold more entries than LDS can take, the arena lives in the
-// trace's slice of the global workspace (the other arrays stay in LDS) and smeta[] widens to
-// arena offset << 32 | entries.
-template <bool BIG>
 struct VmsT {
-    typedef typename std::conditional<BIG, u64, u32>::type meta_t;
+    typedef u32 meta_t;
     u64 *pool;
     u32 *bmp;
     u64 *skey;
@@ -583,14 +579,10 @@ struct VmsT {
     u32 np, ns, n_chunks, top, live_ent, next_sid, clock;
     u32 e_skip;                 // a list entry with an empty mask on the spare word behind the bitmap
     Probe pp, sp;
-    static DI meta_t pack(u32 off, u32 cnt) { return BIG ? (meta_t)(((u64)off << 32) | cnt) : (meta_t)((off << 16) | cnt); }
-    static DI u32 off(meta_t m) { return BIG ? (u32)((u64)m >> 32) : (u32)m >> 16; }
-    static DI u32 cnt(meta_t m) { return BIG ? (u32)m : (u32)m & 0xFFFFu; }
-    static DI meta_t pinm(meta_t m)             // pin() for a list place
-    {
-        if constexpr (BIG) return pin64(m);
-        else return pin(m);
-    }
+    static DI meta_t pack(u32 off, u32 cnt) { return (off << 16) | cnt; }
+    static DI u32 off(meta_t m) { return m >> 16; }
+    static DI u32 cnt(meta_t m) { return m & 0xFFFFu; }
+    static DI meta_t pinm(meta_t m) { return pin(m); }      // pin() for a list place
 };
 
 DI u32 from_lane_any(u32 v, u32 l) { return from_lane(v, l); }
@@ -611,8 +603,7 @@ DI u32 run_entry(u32 start, u32 len, u32 q)
 }
 
 // write the entries of one run (wave-uniform arguments) at arena[at..]; returns how many
-template <bool BIG>
-DI u32 arena_put(VmsT<BIG> &V, u32 at, u32 start, u32 len)
+DI u32 arena_put(VmsT &V, u32 at, u32 start, u32 len)
 {
     const u32 n = run_words(start, len);
     for (u32 qb = 0; qb < n; qb += 64) {
@@ -653,8 +644,7 @@ DI void bmp_fill(u32 *bmp, u32 spare, u32 start, u32 len, bool set)
 // One tile of list entries, one lane per entry (e, if live): their bits are set or cleared with LDS
 // atomics that return nothing, so entries that share a bitmap word need no ordering and the wave
 // does not wait for the result.  Lanes without an entry OR a zero into a spare word of their own.
-template <bool BIG>
-DI void entries_apply(const VmsT<BIG> &V, u32 e, bool live, bool set)
+DI void entries_apply(const VmsT &V, u32 e, bool live, bool set)
 {
     u32 *t = live ? &V.bmp[ENT_WORD(e)] : &V.idle[lane_id()];
     const u32 m = live ? emask(e) : 0u;
@@ -663,8 +653,7 @@ DI void entries_apply(const VmsT<BIG> &V, u32 e, bool live, bool set)
 }
 
 // all entries of one sBlock
-template <bool BIG>
-DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
+DI void bmp_fill_entries(const VmsT &V, u32 off, u32 cnt, bool set)
 {
     for (u32 rb = 0; rb < cnt; rb += 64) {
         const u32 r = rb + lane_id();
@@ -676,8 +665,7 @@ DI void bmp_fill_entries(const VmsT<BIG> &V, u32 off, u32 cnt, bool set)
 
 // A new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing;
 // wmin / wmax: per-lane range of the bitmap words touched so far) ...
-template <bool BIG>
-DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
+DI void list_mark(const VmsT &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 {
     const u32 end = start + len;
     const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
@@ -693,8 +681,7 @@ DI void list_mark(const VmsT<BIG> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
 
 // ... and read back as entries at arena[at..], one per range of consecutive chunks inside a word
 // (touching runs have merged), leaving tmp[] zero.  Returns the number of entries.
-template <bool BIG>
-DI u32 list_extract(const VmsT<BIG> &V, u32 wmin, u32 wmax, u32 at, u32 spare)
+DI u32 list_extract(const VmsT &V, u32 wmin, u32 wmax, u32 at, u32 spare)
 {
     u32 cnt = 0;
     for (u32 wb = wmin; wb <= wmax; wb += 64) {
@@ -726,8 +713,7 @@ DI u32 list_extract(const VmsT<BIG> &V, u32 wmin, u32 wmax, u32 at, u32 spare)
 
 // Is sBlock i inactive?  Evaluated by ONE lane for its own index i (lanes work on different
 // sBlocks side by side): the witness first, then the whole list.
-template <bool BIG>
-DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
+DI bool sblock_inactive_lane(const VmsT &V, u32 i)
 {
     const u32 wit = V.swit[i];
     if (V.bmp[ENT_WORD(wit)] & emask(wit)) return false;
@@ -744,8 +730,8 @@ DI bool sblock_inactive_lane(const VmsT<BIG> &V, u32 i)
     return true;
 }
 
-template <bool BIG, class AcctT>
-DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, AcctT &A)
+template <class AcctT>
+DI void pool_insert(VmsT &V, u32 size, u32 start, AcctT &A)
 {
     u64 key = ((u64)size << 32) | (u32)~start;
     u32 pos = rank_desc(V.pool, V.np, key);
@@ -759,8 +745,8 @@ DI void pool_insert(VmsT<BIG> &V, u32 size, u32 start, AcctT &A)
 // Split (Sec. 3.3.1): the pBlock at pool[idx] is replaced by its two pieces, both smaller and
 // therefore further down in pool order.  Only the keys between the old place and the new
 // places move: down by one up to the larger piece, up by one after the smaller piece.
-template <bool BIG, class AcctT>
-DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32 start_b, AcctT &A)
+template <class AcctT>
+DI void pool_cut(VmsT &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32 start_b, AcctT &A)
 {
     u64 k1 = ((u64)size_a << 32) | (u32)~start_a, k2 = ((u64)size_b << 32) | (u32)~start_b;
     if (k1 < k2) {
@@ -781,8 +767,7 @@ DI void pool_cut(VmsT<BIG> &V, u32 idx, u32 size_a, u32 start_a, u32 size_b, u32
 
 // skey[], smeta[], sstamp[] and swit[] move together: entries [pos, n) one place up (highest
 // tile first) or entries (pos, n) one place down (lowest tile first), one LDS round trip per tile
-template <bool BIG>
-DI void spool_shift_up(VmsT<BIG> &V, u32 pos, u32 n)
+DI void spool_shift_up(VmsT &V, u32 pos, u32 n)
 {
     for (u32 hi = n; hi > pos;) {
         const u32 lo = hi - pos > 64 ? hi - 64 : pos;
@@ -799,8 +784,7 @@ DI void spool_shift_up(VmsT<BIG> &V, u32 pos, u32 n)
     wave_sync();
 }
 
-template <bool BIG>
-DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
+DI void spool_shift_down(VmsT &V, u32 pos, u32 n)
 {
     for (u32 lo = pos + 1; lo < n; lo += 64) {
         const u32 i = lo + lane_id(), dst = i < n ? i - 1 : i;   // lanes past the end: see shift_down
@@ -817,13 +801,13 @@ DI void spool_shift_down(VmsT<BIG> &V, u32 pos, u32 n)
 
 // Stitch: the only creator of sBlocks (Sec. 3.3.1).  The entries are already in the arena.
 // Returns the position of the new sBlock in skey[].
-template <bool BIG, class AcctT>
-DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, AcctT &A, bool probe_valid)
+template <class AcctT>
+DI u32 spool_insert(VmsT &V, u32 size, u32 off, u32 cnt, AcctT &A, bool probe_valid)
 {
     u32 id = V.next_sid++;
     u64 key = ((u64)size << 32) | (u32)~id;
     // probe_valid: skey[] has not changed since its first search level was put into registers
-    u32 pos = probe_valid ? rank_fast<BIG>(V.sp, V.skey, V.ns, key) : rank_desc(V.skey, V.ns, key);
+    u32 pos = probe_valid ? rank_fast<false>(V.sp, V.skey, V.ns, key) : rank_desc(V.skey, V.ns, key);
     spool_shift_up(V, pos, V.ns);
     st_one(V.skey, pos, key);
     st_one(V.smeta, pos, V.pack(off, cnt));
@@ -838,8 +822,7 @@ DI u32 spool_insert(VmsT<BIG> &V, u32 size, u32 off, u32 cnt, AcctT &A, bool pro
     return pos;
 }
 
-template <bool BIG>
-DI void spool_remove(VmsT<BIG> &V, u32 idx)
+DI void spool_remove(VmsT &V, u32 idx)
 {
     V.live_ent -= V.cnt(ld_uni(V.smeta, idx));
     spool_shift_down(V, idx, V.ns);
@@ -850,8 +833,8 @@ DI void spool_remove(VmsT<BIG> &V, u32 idx)
 
 // Squeeze the entries of evicted sBlocks out of the arena: copy the live lists to the
 // global buffer in sPool order, then back.  Slots holding an sBlock learn its new place.
-template <bool BIG, class Slots>
-DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
+template <class Slots>
+DI void arena_compact(VmsT &V, Slots &S, const KParams &P)
 {
     u32 top = 0;
     for (u32 s = 0; s < V.ns; s++) {
@@ -862,27 +845,21 @@ DI void arena_compact(VmsT<BIG> &V, Slots &S, const KParams &P)
             V.bounce[top + r] = V.arena[off + r];
         }
         st_one(V.smeta, s, V.pack(top, cnt));
-        if (!BIG) S.moved((u32)meta, (u32)V.pack(top, cnt), P);
+        S.moved((u32)meta, (u32)V.pack(top, cnt), P);
         top += cnt;
     }
     __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");     // later reads are of other lanes' global writes
     wave_sync();
-    if (BIG) {
-        u32 *t = V.arena;       // both halves are global: the copy becomes the arena
-        V.arena = V.bounce;
-        V.bounce = t;
-    } else {
-        for (u32 rb = 0; rb < top; rb += 64) {
-            const u32 r = min(rb + lane_id(), top - 1);
-            V.arena[r] = V.bounce[r];
-        }
+    for (u32 rb = 0; rb < top; rb += 64) {
+        const u32 r = min(rb + lane_id(), top - 1);
+        V.arena[r] = V.bounce[r];
     }
     V.top = top;
     wave_sync();
 }
 
-template <bool BIG, class Slots, class AcctT>
-DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, AcctT &A, u32 ev)
+template <class Slots, class AcctT>
+DI bool arena_reserve(VmsT &V, Slots &S, u32 need, const KParams &P, AcctT &A, u32 ev)
 {
     if (UNLIKELY(V.top + need > P.cap_runs && V.live_ent < V.top)) arena_compact(V, S, P);
     if (UNLIKELY(V.top + need > P.cap_runs)) {
@@ -894,8 +871,7 @@ DI bool arena_reserve(VmsT<BIG> &V, Slots &S, u32 need, const KParams &P, AcctT 
 
 // Is any chunk of the list arena[off .. off + cnt) active?  All lanes work on the one list; if so,
 // *witness receives an entry that was seen active.
-template <bool BIG>
-DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
+DI bool list_busy(const VmsT &V, u32 off, u32 cnt, u32 *witness)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
         const u32 k = eb + lane_id();
@@ -918,8 +894,8 @@ DI bool list_busy(const VmsT<BIG> &V, u32 off, u32 cnt, u32 *witness)
 // least recently used of the sBlocks it saw.  The oldest of all is tested with all lanes on its
 // list; if it is active after all, its lane falls back on its second and the search goes on
 // without a new scan (a lane that runs out of its two forces one).
-template <bool BIG, class AcctT>
-DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
+template <class AcctT>
+DI bool stitch_free(VmsT &V, const KParams &P, AcctT &A)
 {
     const u32 lane = lane_id();
     bool any = false;
@@ -993,8 +969,7 @@ DI bool stitch_free(VmsT<BIG> &V, const KParams &P, AcctT &A)
 // round trips for the whole tile.  The others are tested in pool order with all lanes over the
 // entries of one list; the first inactive one is handed out (ref = creation number, list = where
 // its entries are).  This is the general route, from the tile that starts at `base`.
-template <bool BIG>
-DI bool s1_sblock_from(VmsT<BIG> &V, u32 bsize, u32 base, u32 &ref, u32 &list)
+DI bool s1_sblock_from(VmsT &V, u32 bsize, u32 base, u32 &ref, u32 &list)
 {
     const u32 lane = lane_id();
     for (;;) {
@@ -1056,14 +1031,13 @@ DI bool s1_sblock_from(VmsT<BIG> &V, u32 bsize, u32 base, u32 &ref, u32 &list)
 
 // ---- S1, primitive blocks: the first inactive pBlock of exactly bsize chunks in pool order.  As
 // above, the block of the rank search doubles as the first tile of candidates.
-template <bool BIG>
-DI bool s1_pblock(VmsT<BIG> &V, u32 bsize, u32 &start)
+DI bool s1_pblock(VmsT &V, u32 bsize, u32 &start)
 {
     const u32 lane = lane_id();
     const u64 q = ((u64)bsize << 32) | 0xFFFFFFFFu;
     u32 base;
     if (V.pp.stride >= 64) {
-        base = rank_fast<BIG>(V.pp, V.pool, V.np, q);
+        base = rank_fast<false>(V.pp, V.pool, V.np, q);
     } else {
         const u32 c = popc64(ballot(V.pp.v > q));
         base = dec_sat(c) * V.pp.stride;  // the first pBlock of bsize chunks lies inside this tile
@@ -1090,14 +1064,14 @@ struct VmsRes {
     u32 dec_lo;                 // low decision word (code C_OOM alone when the request failed)
     u32 ref;                    // pBlock first chunk / sBlock creation number (= high decision word)
     u32 kind, held;             // what the slot now holds, chunks held
-    u32 list;                   // sBlock: offset << 16 | entries of its list (not BIG)
+    u32 list;                   // sBlock: offset << 16 | entries of its list
 };
 
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of
 // its state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).  The rare path: a few per cent of
 // the requests of a converged trace.
-template <bool BIG, class Slots, class AcctT>
-DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, AcctT &A, u32 ev,
+template <class Slots, class AcctT>
+DI void vms_alloc_rest(VmsT &V, Slots &S, u32 bsize, u32 reserved_units, const KParams &P, AcctT &A, u32 ev,
                        VmsRes &R)
 {
     const u32 lane = lane_id();
@@ -1266,7 +1240,7 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     R.ref = V.next_sid;
     spool_insert(V, bsize, V.top, cnt, A, !(s3 && excess));
     bmp_fill_entries(V, V.top, cnt, true);
-    R.list = BIG ? 0u : (u32)V.pack(V.top, cnt);
+    R.list = (u32)V.pack(V.top, cnt);
     V.top += used;
     A.peak(SC_HW_MEMBERS, k + (s3 ? 0u : 1u));
     R.kind = KIND_SBLOCK;
@@ -1274,12 +1248,11 @@ DI void vms_alloc_rest(VmsT<BIG> &V, Slots &S, u32 bsize, u32 reserved_units, co
     if (stitch_free(V, P, A)) R.dec_lo |= B_7;
 }
 
-// Update (Sec. 3.3.2) of an sBlock that is looked up by its key (slot table in LDS, or lists in HBM)
-template <bool BIG>
-DI void vms_free_by_key(VmsT<BIG> &V, u32 ref, u32 held)
+// Update (Sec. 3.3.2) of an sBlock that is looked up by its key (slot table in LDS)
+DI void vms_free_by_key(VmsT &V, u32 ref, u32 held)
 {
     const u64 key = ((u64)held << 32) | (u32)~ref;
-    const u32 idx = rank_fast<BIG>(V.sp, V.skey, V.ns, key);
+    const u32 idx = rank_fast<false>(V.sp, V.skey, V.ns, key);
     const auto meta = ld_uni(V.smeta, idx);
     bmp_fill_entries(V, V.off(meta), V.cnt(meta), false);
 }
@@ -1307,21 +1280,19 @@ struct ColdState {
     DI u32 get(u32 k) const { return from_lane(v, k); }
 };
 
-template <bool BIG>
-DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool swapped)
+DI void vms_bind(VmsT &V, char *lds, char *ws_slice, const KParams &P)
 {
     V.pool = (u64 *)(lds + P.off_pool);
     V.bmp = (u32 *)(lds + P.off_bmp);
     V.skey = (u64 *)(lds + P.off_skey);
-    V.smeta = (typename VmsT<BIG>::meta_t *)(lds + P.off_smeta);
-    V.sstamp = BIG && P.ws_stamp_off ? (u32 *)(ws_slice + P.ws_stamp_off) : (u32 *)(lds + P.off_sstamp);
+    V.smeta = (VmsT::meta_t *)(lds + P.off_smeta);
+    V.sstamp = (u32 *)(lds + P.off_sstamp);
     V.swit = (u32 *)(lds + P.off_swit);
     V.tmp = (u32 *)(lds + P.off_tmp);
     V.idle = V.tmp + (P.cap_chunks + 31) / 32;
     V.e_skip = (((P.cap_chunks + 31) / 32) << 12) | WIT_NONE;
-    u32 *lo = (u32 *)ws_slice, *hi = lo + P.cap_runs + 64;
-    V.bounce = BIG && swapped ? hi : lo;
-    V.arena = BIG ? (swapped ? lo : hi) : (u32 *)(lds + P.off_arena);
+    V.bounce = (u32 *)ws_slice;                 // where arena_compact copies the lists
+    V.arena = (u32 *)(lds + P.off_arena);
 }
 
 // A request for bsize chunks that no cached block fits exactly (states S2 to S5): inlined into the
@@ -1329,8 +1300,7 @@ DI void vms_bind(VmsT<BIG> &V, char *lds, char *ws_slice, const KParams &P, bool
 // that come here can repay), working on the loop's own pool state; the three scalars that only
 // this path needs (arena top, live entries, next creation number) wait in LDS in between.
 // Returns false if an engine table overflowed (the trace ends).
-template <bool BIG>
-DI bool vms_alloc_cold(char *lds, VmsT<BIG> &V, const KParams &P, u32 bsize, u32 reserved_units, u32 ev, VmsRes &R,
+DI bool vms_alloc_cold(char *lds, VmsT &V, const KParams &P, u32 bsize, u32 reserved_units, u32 ev, VmsRes &R,
                        bool &compacted)
 {
     u32 *sc = (u32 *)(lds + LDS_SCALARS);
@@ -1442,7 +1412,7 @@ DI u64 tile_totals(const TileOut &T, u32 n_code[8])
 // the decisions with one coalesced write, count the decision codes and fold their event into
 // the digest, all 64 events side by side.
 // ---------------------------------------------------------------------------
-template <bool BIG, bool SLOT_REGS>
+template <bool SLOT_REGS>
 __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__restrict__ events,
                                                         const u32 *__restrict__ n_events,
                                                         u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
@@ -1451,14 +1421,14 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     WAVE_DYNAMIC_LDS(lds);
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
-    constexpr bool USE_LIST = SLOT_REGS && !BIG;
+    constexpr bool USE_LIST = SLOT_REGS;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
     ((u32 *)(lds + LDS_SCALARS))[lane] = lane == SC_FIRST_OOM || lane == SC_OVF_EVENT ? NONE32 : 0u;     // LDS header
-    VmsT<BIG> V;
-    vms_bind(V, lds, ws_slice, P, false);
+    VmsT V;
+    vms_bind(V, lds, ws_slice, P);
     V.np = V.ns = V.n_chunks = V.top = V.live_ent = V.next_sid = V.clock = 0;
     V.pp.v = V.sp.v = 0;
     V.pp.stride = V.sp.stride = 1;
@@ -1476,8 +1446,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
         V.swit[i] = WIT_NONE;
         V.smeta[i] = 0;
     }
-    if (!BIG)
-        for (u32 i = lane; i < P.cap_runs + 64; i += 64) V.arena[i] = WIT_NONE;
+    for (u32 i = lane; i < P.cap_runs + 64; i += 64) V.arena[i] = WIT_NONE;
     st_one(V.bmp, (P.cap_chunks + 31) / 32, 0u);                // the spare word
     wave_sync();
 
@@ -1609,7 +1578,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                     const u32 wit0 = V.swit[i];
                     const auto meta0 = V.smeta[i];
                     const u32 wit = pin(wit0);
-                    const auto meta = VmsT<BIG>::pinm(meta0);
+                    const auto meta = VmsT::pinm(meta0);
                     const u64 vm = ballot((u32)(key >> 32) == bsize);
                     if (UNLIKELY(!vm)) break;
                     const u32 wv = pin(V.bmp[ENT_WORD(wit)]);
@@ -1654,7 +1623,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 // tile (fast_limit keeps such a trace off the route above, at no cost to the others)
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 u32 ref, list = 0;
-                const u32 from = rank_fast<BIG>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
+                const u32 from = rank_fast<false>(V.sp, V.skey, V.ns, ((u64)bsize << 32) | 0xFFFFFFFFu);
                 if (s1_sblock_from(V, bsize, from, ref, list)) S1_SBLOCK_HIT
                 S1_PBLOCK_TRY
             }
@@ -1667,7 +1636,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
                 const u32 bsize = (size + chunk_units - 1) >> P.chunk_shift;
                 VmsRes R;
                 bool compacted;
-                const bool went = vms_alloc_cold<BIG>(lds, V, P, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), base + j,
+                const bool went = vms_alloc_cold(lds, V, P, bsize, sp_reserved + (V.n_chunks << P.chunk_shift), base + j,
                                                       R, compacted);
                 // the pools may have changed: renew the first search level of both
                 probe_refresh(V.sp, V.skey, V.ns);

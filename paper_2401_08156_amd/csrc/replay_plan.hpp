@@ -23,7 +23,6 @@ struct KParams {
         off_sstamp, off_swit, off_tmp, off_arena;
     uint32_t lds_bytes;
     uint32_t small_regs;             // stitching kernel: its pool for small requests is held in registers (cap_free <= 192)
-    uint32_t ws_stamp_off;           // unused by the current variants (kept zero)
     uint64_t ws_stride;              // workspace bytes per trace
     // fine-grained variant only (see replay_fine.hpp)
     uint32_t off_bnd, off_soff;      // block-start bitmap; list places of the sBlocks

@@ -128,7 +128,7 @@ vms_fn pick_vms(const ReplayPlan &p)
         if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32> : replay_vms_fine_kernel<false, u32>;
         return p.slot_regs ? replay_vms_fine_kernel<true, u16> : replay_vms_fine_kernel<false, u16>;
     }
-    return p.slot_regs ? replay_vms_kernel<false, true> : replay_vms_kernel<false, false>;
+    return p.slot_regs ? replay_vms_kernel<true> : replay_vms_kernel<false>;
 }
 // fl_regs: the splitting pool's inactive blocks fit three registers per lane (at most 192 blocks)
 split_fn pick_split(bool slot_regs, bool fl_regs)

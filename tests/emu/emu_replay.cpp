@@ -102,8 +102,8 @@ void body_vms(void *p)
 {
     Args &a = *(Args *)p;
     switch (a.variant) {
-    case 0: replay_vms_kernel<false, true>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 1: replay_vms_kernel<false, false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 0: replay_vms_kernel<true>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 1: replay_vms_kernel<false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
     case 2: replay_vms_fine_kernel<true, uint16_t>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
     case 3: replay_vms_fine_kernel<false, uint16_t>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
     case 4: replay_vms_fine_kernel<true, u32>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
