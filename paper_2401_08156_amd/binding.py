@@ -27,7 +27,8 @@ class vms_config(ctypes.Structure):
                 ("max_free_blocks", ctypes.c_uint32), ("max_pblocks", ctypes.c_uint32),
                 ("max_sblocks", ctypes.c_uint32), ("max_runs", ctypes.c_uint32),
                 ("max_chunks", ctypes.c_uint32), ("max_small_blocks", ctypes.c_uint32),
-                ("max_multi_pblocks", ctypes.c_uint32), ("variant", ctypes.c_uint32)]
+                ("max_multi_pblocks", ctypes.c_uint32), ("variant", ctypes.c_uint32),
+                ("retry_traces", ctypes.c_uint32), ("reserved0", ctypes.c_uint32)]
 
 
 class vms_summary(ctypes.Structure):

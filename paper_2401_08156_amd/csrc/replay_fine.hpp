@@ -114,6 +114,15 @@ DI Quad quad_load(const FineT<IDX> &V, u32 q)
     return r;
 }
 
+// bits of word w inside [start, end), 0 if the word lies outside
+DI u32 word_mask_or0(u32 w, u32 start, u32 end)
+{
+    const u32 lo = max(start, w * 32), hi = min(end, w * 32 + 32);
+    if (lo >= hi) return 0u;
+    const u32 n = hi - lo;
+    return (n == 32 ? 0xFFFFFFFFu : ((1u << n) - 1u)) << (lo & 31);
+}
+
 // S1 for a request of one chunk: the first inactive pBlock of one chunk
 template <class IDX>
 DI bool s1_single(const FineT<IDX> &V, u32 &start)
@@ -131,12 +140,15 @@ DI bool s1_single(const FineT<IDX> &V, u32 &start)
 }
 
 // ---- pool[] of multi-chunk pBlocks --------------------------------------------------------------
+// (4-byte keys move sixteen bytes per lane and step; the 8-byte keys of the variant with 32-bit chunk
+// numbers one key per lane)
 template <class IDX, class AcctT>
 DI void fine_pool_insert(FineT<IDX> &V, u32 size, u32 start, AcctT &A)
 {
     const auto k = V.key(size, start);
     const u32 pos = rank_desc_k(V.pool, V.np, k);
-    shift_up(V.pool, pos, V.np);
+    if constexpr (sizeof(IDX) == 2) blk_shift_up(V.pool, pos, V.np);
+    else shift_up(V.pool, pos, V.np);
     st_one(V.pool, pos, k);
     V.np++;
     A.peak(SC_HW_MULTI, V.np);
@@ -146,9 +158,14 @@ DI void fine_pool_insert(FineT<IDX> &V, u32 size, u32 start, AcctT &A)
 template <class IDX>
 DI void fine_pool_remove(FineT<IDX> &V, u32 idx)
 {
-    shift_down(V.pool, idx, V.np);
-    V.np--;
-    st_one(V.pool, V.np, (typename FineT<IDX>::pkey_t)0);
+    if constexpr (sizeof(IDX) == 2) {
+        blk_shift_down(V.pool, idx, V.np);                      // (leaves a zero key in the last place)
+        V.np--;
+    } else {
+        shift_down(V.pool, idx, V.np);
+        V.np--;
+        st_one(V.pool, V.np, (typename FineT<IDX>::pkey_t)0);
+    }
     wave_sync();
 }
 
@@ -570,21 +587,6 @@ DI void fine_free_sblock(const FineT<IDX> &V, u32 place)
     if (UNLIKELY(cnt > 62)) list_apply(V, list + 62, cnt - 62, false);
 }
 
-// a new list is collected in tmp[]: mark one run per lane (lanes with len == 0 mark nothing)
-template <class IDX>
-DI void fine_mark(const FineT<IDX> &V, u32 start, u32 len, u32 &wmin, u32 &wmax)
-{
-    const u32 end = start + len;
-    const u32 w0 = len ? start >> 5 : NONE32, w1 = len ? (end - 1) >> 5 : 0u;
-    for (u32 q = 0; ballot(len && w0 + q <= w1); q++) {
-        const bool in = len && w0 + q <= w1;
-        const u32 mw = word_mask(in ? w0 + q : 0u, start, end);
-        atomicOr(in ? &V.tmp[w0 + q] : &V.idle[lane_id()], in ? mw : 0u);
-    }
-    wmin = min(wmin, w0);
-    wmax = max(wmax, w1);
-}
-
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of its
 // state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).
 template <class IDX, class Slots, class AcctT>
@@ -675,14 +677,19 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
             k = t_hi;
         }
     }
-    // (the pool scans below take sixteen bytes of keys per lane and step: KE keys, all their bitmap
-    // words on their way before the first is looked at)
+    // The pool scan takes sixteen bytes of keys per lane and step (KE keys, all their bitmap words on
+    // their way before the first is looked at).  Each candidate it passes flips two bits in tmp[]: the
+    // bit of its first chunk and the bit behind its last one.  A chunk then belongs to a candidate iff
+    // an odd number of flipped bits lies at or below it (runs do not overlap; where two touch, the two
+    // flips of the shared place cancel): the list is read off tmp[] afterwards whatever the runs' lengths.
     constexpr u32 KE = 16 / sizeof(pkey_t);
     struct alignas(16) Keys {
         pkey_t k[KE];
     };
+    u64 qk = 0;                                                 // the key of a candidate that is cut
+    bool flipped = false;
     if (!all_multi) {
-        for (u32 base = hi_p & ~(KE - 1); base < lim; base += 64 * KE) {
+        for (u32 base = hi_p & ~(KE - 1); base < lim && pos == NONE32; base += 64 * KE) {
             const u32 i0 = base + lane * KE;
             const Keys K = ((const Keys *)V.pool)[i0 < lim ? i0 / KE : 0u];
             u32 kw[KE], sz[KE], mine = 0;
@@ -700,27 +707,43 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
             }
             u32 tot;
             const u32 incl = wave_scan_add(mine, &tot);
+            u32 l_end = 64, e_end = KE, cut_by = 0;             // the last candidate: key e_end of lane l_end (none: all of them)
             if (sum + tot >= bsize) {
                 // the lane, then the key inside it, at which the request is covered
-                const u32 l = first_lane(ballot(mine && sum + incl >= bsize));
-                sum += from_lane(incl - mine, l);
+                l_end = first_lane(ballot(mine && sum + incl >= bsize));
+                sum += from_lane(incl - mine, l_end);
 #pragma unroll
-                for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]) & ((1ull << l) - 1));
+                for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]) & ((1ull << l_end) - 1));
 #pragma unroll
                 for (u32 e = 0; e < KE; e++) {
-                    const u32 c = from_lane(sz[e], l);
+                    const u32 c = from_lane(sz[e], l_end);
                     if (pos == NONE32 && c) {
                         k++;
                         sum += c;
-                        if (sum >= bsize) pos = base + l * KE + e;
+                        if (sum >= bsize) {
+                            pos = base + l_end * KE + e;
+                            e_end = e;
+                        }
                     }
                 }
-                break;
+                cut_by = sum - bsize;
+                if (cut_by) qk = (u64)ld_uni(V.pool, pos);
+            } else {
+#pragma unroll
+                for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]));
+                sum += tot;
             }
 #pragma unroll
-            for (u32 e = 0; e < KE; e++) k += popc64(ballot(in[e]));
-            sum += tot;
+            for (u32 e = 0; e < KE; e++) {
+                const bool take = in[e] && (lane < l_end || (lane == l_end && e <= e_end));
+                const u32 fc = V.kstart(K.k[e]);
+                const u32 end = fc + V.ksize(K.k[e]) - (lane == l_end && e == e_end ? cut_by : 0u);
+                atomicXor(take ? &V.tmp[fc >> 5] : &V.idle[lane], take ? 1u << (fc & 31) : 0u);
+                atomicXor(take ? &V.tmp[end >> 5] : &V.idle[lane], take ? 1u << (end & 31) : 0u);
+            }
+            flipped = true;
         }
+        wave_sync();
     }
     // single chunks, in chunk order: all free ones before word s_last, and the lowest s_take of that word
     u32 s_last = NONE32, s_take = 0, n_single = 0;
@@ -760,13 +783,24 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
     }
     const bool s3 = sum >= bsize;
     const u32 excess = s3 ? sum - bsize : 0, deficit = s3 ? 0 : bsize - sum;
+    const u32 n_after = V.n_chunks + deficit;                   // chunks once the new pBlock exists
+    // giving up from here on: the flipped bits must not stay behind in tmp[]
+    auto wipe = [&]() {
+        if (flipped)
+            for (u32 i = lane; i < P.bmp_words; i += 64) V.tmp[i] = 0;
+        wave_sync();
+    };
+    u32 q_gr = 0;                                               // granules of the record of a cut candidate
+    if (excess) q_gr = V.grans(run_words(V.kstart((pkey_t)qk), V.ksize((pkey_t)qk)));
     if (!s3) {
         // S4 needs new physical chunks; S5 if the device cannot provide them
         if (UNLIKELY(reserved_units + (deficit << P.chunk_shift) > P.capacity_units)) {
+            wipe();
             R.dec_lo = C_OOM;
             return;
         }
-        if (UNLIKELY(V.n_chunks + deficit > P.cap_chunks)) {
+        if (UNLIKELY(n_after > P.cap_chunks)) {
+            wipe();
             A.overflow(ev, VMS_ST_OVF_CHUNKS);
             R.dec_lo = C_INVALID;
             return;
@@ -785,20 +819,32 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
         R.dec_lo = C_GROW;
         return;
     }
+    // room: two more pBlocks and sBlocks at most, a list of at most one word per bitmap word in use,
+    // and the record of a cut candidate
     if (UNLIKELY(V.np + 2 > P.cap_pblocks || V.ns + 2 > P.cap_sblocks)) {
         A.overflow(ev, (V.np + 2 > P.cap_pblocks ? VMS_ST_OVF_PBLOCKS : 0u) | (V.ns + 2 > P.cap_sblocks ? VMS_ST_OVF_SBLOCKS : 0u));
         R.dec_lo = C_INVALID;
         return;
     }
-    // second pass: the candidates' chunks (and the new pBlock's) are collected in tmp[]
-    u32 wmin = NONE32, wmax = 0;
+    if (UNLIKELY(!fine_reserve(V, S, V.grans((n_after + 31) >> 5) + q_gr, A, ev))) {
+        R.dec_lo = C_INVALID;
+        return;
+    }
+    // The list, four bitmap words per lane and step: the candidates' chunks (from the flipped bits, or,
+    // when every free multi-chunk pBlock is taken, straight from the bitmaps, with the chosen single
+    // chunks) and the new pBlock's; one list word per bitmap word touched; the chunks become active on
+    // the way and tmp[] is left zero.
+    const u32 place = V.top;
+    u32 cnt = 0, witness = NONE32;
     {
-        if (all_multi) {
-            // every free multi-chunk pBlock, and the single chunks chosen above; four words per lane
-            for (u32 qb = 0; qb < n_quads; qb += 64) {
-                const u32 q = qb + lane;
-                const Quad Q = quad_load(V, q < n_quads ? q : 0u);
-                Blk16 out;
+        u64 *l = V.list_at(place) + 2;
+        u32 carry = 0;                                          // flipped bits below this step, mod 2
+        for (u32 qb = 0; qb * 128 <= n_after; qb += 64) {
+            const u32 q = qb + lane;
+            const bool mine = q * 128 <= n_after;
+            u32 out[4];
+            if (all_multi) {
+                const Quad Q = quad_load(V, mine ? q : 0u);
 #pragma unroll
                 for (u32 t = 0; t < 4; t++) {
                     const u32 w = 4 * q + t;
@@ -808,110 +854,54 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
                         for (u32 i = 0; i < s_take; i++) rest &= rest - 1;      // sg without its lowest s_take bits
                         sg = w < s_last ? sg : (w == s_last ? sg & ~rest : 0u);
                     }
-                    const u32 m = q < n_quads ? Q.multi[t] | sg : 0u;
-                    out.w[t] = m;
-                    wmin = min(wmin, m ? w : NONE32);
-                    wmax = max(wmax, m ? w : 0u);
+                    out[t] = mine ? Q.multi[t] | sg : 0u;
                 }
-                if (q < n_quads) ((Blk16 *)V.tmp)[q] = out;     // tmp[] is zero between uses
-            }
-        } else {
-            // The candidates' runs of chunks, whatever their lengths, in two steps: every candidate
-            // flips the bit of its first chunk and the bit behind its last one in tmp[]; a chunk then
-            // belongs to a candidate iff an odd number of flipped bits lies at or below it (runs do
-            // not overlap; where two touch, the two flips of the shared place cancel).
-            const u32 endi = pos != NONE32 ? pos + 1 : lim;
-            for (u32 base = hi_p & ~(KE - 1); base < endi; base += 64 * KE) {
-                const u32 i0 = base + lane * KE;
-                const Keys K = ((const Keys *)V.pool)[i0 < endi ? i0 / KE : 0u];
-                u32 kw[KE];
-                bool in[KE];
-#pragma unroll
-                for (u32 e = 0; e < KE; e++) {
-                    in[e] = i0 + e >= hi_p && i0 + e < endi;
-                    kw[e] = V.bmp[in[e] ? V.kstart(K.k[e]) >> 5 : V.w_spare];
-                }
-#pragma unroll
-                for (u32 e = 0; e < KE; e++) {
-                    const u32 fc = V.kstart(K.k[e]);
-                    in[e] = in[e] && !((kw[e] >> (fc & 31)) & 1u);
-                    const u32 end = fc + V.ksize(K.k[e]) - (i0 + e == pos ? excess : 0u);
-                    atomicXor(in[e] ? &V.tmp[fc >> 5] : &V.idle[lane], in[e] ? 1u << (fc & 31) : 0u);
-                    atomicXor(in[e] ? &V.tmp[end >> 5] : &V.idle[lane], in[e] ? 1u << (end & 31) : 0u);
-                }
-            }
-            wave_sync();
-            // flipped bits -> runs, four words per lane
-            u32 carry = 0;                                      // flipped bits below this step, mod 2
-            for (u32 qb = 0; qb * 128 <= V.n_chunks; qb += 64) {
-                const u32 q = qb + lane;
-                const bool mine = q * 128 <= V.n_chunks;
-                const Blk16 t = ((const Blk16 *)V.tmp)[mine ? q : 0u];
+            } else {
+                const Blk16 t4 = ((const Blk16 *)V.tmp)[mine ? q : 0u];
                 u32 pc = 0;
 #pragma unroll
-                for (u32 j = 0; j < 4; j++) pc += mine ? (u32)__builtin_popcount(t.w[j]) : 0u;
+                for (u32 t = 0; t < 4; t++) pc += mine ? (u32)__builtin_popcount(t4.w[t]) : 0u;
                 u32 tot;
                 const u32 incl = wave_scan_add(pc, &tot);
                 u32 odd = (carry + incl - pc) & 1u;             // flipped bits below the word at hand, mod 2
-                Blk16 out;
 #pragma unroll
-                for (u32 j = 0; j < 4; j++) {
-                    u32 x = mine ? t.w[j] : 0u;
+                for (u32 t = 0; t < 4; t++) {
+                    u32 x = mine ? t4.w[t] : 0u;
                     const u32 flips = (u32)__builtin_popcount(x) & 1u;
                     x ^= x << 1;
                     x ^= x << 2;
                     x ^= x << 4;
                     x ^= x << 8;
                     x ^= x << 16;                               // bit i: flipped bits 0..i of this word, mod 2
-                    out.w[j] = odd ? ~x : x;
+                    out[t] = odd ? ~x : x;
                     odd ^= flips;
-                    const u32 w = 4 * q + j;
-                    wmin = min(wmin, out.w[j] ? w : NONE32);
-                    wmax = max(wmax, out.w[j] ? w : 0u);
                 }
-                if (mine) ((Blk16 *)V.tmp)[q] = out;
                 carry += tot;
+                wave_lockstep();
+                if (mine) ((Blk16 *)V.tmp)[q] = Blk16{ { 0, 0, 0, 0 } };
             }
-        }
-        wave_sync();
-        if (!s3) fine_mark(V, V.n_chunks, lane == 0 ? deficit : 0u, wmin, wmax);
-        wave_sync();
-        wmin = wave_min_u32(wmin);
-        wmax = wave_max_u32(wmax);
-    }
-    // room for the list (at most one word per bitmap word in range) and for the record of a cut candidate
-    u64 qk = 0;
-    u32 q_gr = 0;
-    if (excess) {
-        qk = (u64)ld_uni(V.pool, pos);
-        q_gr = V.grans(run_words(V.kstart((pkey_t)qk), V.ksize((pkey_t)qk)));
-    }
-    if (UNLIKELY(!fine_reserve(V, S, V.grans(wmax - wmin + 1) + q_gr, A, ev))) {
-        R.dec_lo = C_INVALID;
-        return;
-    }
-    // the list: one word per bitmap word touched; its chunks become active on the way
-    const u32 place = V.top;
-    u32 cnt = 0, witness = 0;
-    {
-        u64 *l = V.list_at(place) + 2;
-        u64 *spare = V.arena + ((size_t)V.cap_grans << V.gs);
-        for (u32 wb = wmin; wb <= wmax; wb += 64) {
-            const u32 w = min(wb + lane, wmax);
-            const u32 mw = V.tmp[w];
-            const u32 m = wb + lane <= wmax ? mw : 0u;
+            u32 words = 0;
+#pragma unroll
+            for (u32 t = 0; t < 4; t++) {
+                if (deficit) out[t] |= mine ? word_mask_or0(4 * q + t, V.n_chunks, n_after) : 0u;      // Alloc's chunks
+                words += out[t] ? 1u : 0u;
+                witness = min(witness, out[t] ? (4 * q + t) * 32 + (u32)__builtin_ctz(out[t]) : NONE32);
+            }
+            u32 tot;
+            const u32 incl = wave_scan_add(words, &tot);
+            u32 at = cnt + incl - words;
+            const Blk16 a4 = ((const Blk16 *)V.bmp)[mine ? q : 0u];
+            Blk16 act;
+#pragma unroll
+            for (u32 t = 0; t < 4; t++) {
+                if (out[t]) l[at++] = ((u64)(4 * q + t) << 32) | out[t];
+                act.w[t] = a4.w[t] | out[t];
+            }
             wave_lockstep();
-            const u64 has = ballot(m != 0);
-            if (!cnt && has) {
-                const u32 f = first_lane(has);
-                witness = (wb + f) * 32 + (u32)__builtin_ctz(from_lane(m, f));
-            }
-            // a lane without chunks writes into the spare words behind the arena
-            (m ? l + cnt + rank_in(has) : spare + lane)[0] = ((u64)w << 32) | m;
-            atomicOr(m ? &V.bmp[w] : &V.idle[lane], m);
-            if (wb + lane <= wmax) V.tmp[w] = 0;
-            cnt += popc64(has);
+            if (mine) ((Blk16 *)V.bmp)[q] = act;
+            cnt += tot;
         }
+        witness = wave_min_u32(witness);
         wave_sync();
     }
     u32 used = V.grans(cnt);
@@ -990,6 +980,19 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
+    u32 *taken = (u32 *)&stats[2 * (size_t)P.n_traces];     // traces the second pass has taken on
+    if (P.retry) {
+        // The second pass (larger tables): only the traces whose first replay ended in a table
+        // overflow, and as many of them as there is workspace for; the others stay flagged.
+        if (!(uni(stats[(size_t)P.n_traces + trace].status) & VMS_ST_TABLE_OVERFLOW)) return;
+        u32 mine = 0;
+        if (lane == 0) mine = atomicAdd(taken, 1u);
+        const u32 turn = from_lane(mine, 0);
+        if (turn >= P.retry_slots) return;
+        ws_slice = workspace + P.retry_ws_off + (size_t)turn * P.ws_stride;
+    } else if (P.retry_slots && trace == 0) {
+        *taken = 0;
+    }
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
@@ -1015,7 +1018,7 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
         for (u32 i = lane; i < P.cap_free + 128; i += 64) ((u64 *)(lds + P.off_fl))[i] = 0;
     SplitRegs<3> Q;                                         // the pool for small requests, if it fits registers
     Q.init(lds, P);
-    for (u32 i = lane; i < P.cap_pblocks + 64; i += 64) V.pool[i] = 0;
+    for (u32 i = lane; i < P.cap_pblocks + 80; i += 64) V.pool[i] = 0;
     for (u32 i = lane; i < P.cap_sblocks + 80; i += 64) {
         V.ssz[i] = 0;
         V.swit[i] = 0;

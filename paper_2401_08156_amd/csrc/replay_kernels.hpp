@@ -1423,6 +1423,8 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     const u32 trace = blockIdx.x;
     constexpr bool USE_LIST = SLOT_REGS;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
+    // a second pass follows for traces that outgrow these tables: it counts the traces it takes on
+    if (P.retry_slots && trace == 0) *(u32 *)&stats[2 * (size_t)P.n_traces] = 0;
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
@@ -1785,6 +1787,8 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
     WAVE_DYNAMIC_LDS(lds);
     const u32 lane = lane_id();
     const u32 trace = blockIdx.x;
+    // the second pass (larger tables): only the traces whose first replay ended in a table overflow
+    if (P.retry && !(uni(stats[trace].status) & VMS_ST_TABLE_OVERFLOW)) return;
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);

@@ -29,6 +29,10 @@ struct KParams {
     uint32_t bmp_words;              // words per bitmap that scans may read (a multiple of 64)
     uint32_t gran_shift;             // a list starts on a multiple of 2^gran_shift 8-byte words of the arena
     uint32_t cap_grans;              // granules per arena half
+    // second pass over the traces whose tables overflowed (see ReplayPlan::retry)
+    uint32_t retry;                  // this launch is that pass: traces without an overflow flag are left alone
+    uint32_t retry_slots;            // traces it has workspace for
+    uint64_t retry_ws_off;           // where that workspace starts (bytes from the start of the caller's workspace)
 };
 
 struct ReplayPlan {
@@ -38,6 +42,7 @@ struct ReplayPlan {
     bool slot_regs;                  // slot table in registers (at most 64 slots)
     bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 192)
     size_t ws_bytes;
+    bool has_retry;                  // a second pass with the plan below follows the first
 };
 
 namespace plan_detail {
@@ -74,7 +79,7 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
     k.off_fl = k.cap_free <= 192 ? 0 : take(((uint64_t)k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
     if (policy && p.fine) {
         const uint64_t idx = p.wide ? 4 : 2;                    // bytes of a chunk number
-        k.off_pool = take(((uint64_t)k.cap_pblocks + 64) * 2 * idx);
+        k.off_pool = take(((uint64_t)k.cap_pblocks + 80) * 2 * idx);      // 64 spare places, and moves of whole 16-byte blocks
         k.off_bmp = take(((uint64_t)k.bmp_words + 1) * 4);      // and one spare word
         k.off_bnd = take(((uint64_t)k.bmp_words + 1) * 4);      // scans read one word ahead
         k.off_tmp = take(((uint64_t)k.bmp_words + 64) * 4);     // and 64 spare words
@@ -201,6 +206,45 @@ inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
     };
     const uint32_t flat = per_cu(p), fine = per_cu(q);
     if ((uint64_t)cfg->n_traces > (uint64_t)CUS * flat && 2 * fine >= 5 * flat) p = q;
+    return VMS_OK;
+}
+
+// The plan of the second pass for cfg: every table doubled, as far as the fine-grained variant and a
+// compute unit's LDS allow.  VMS_OK and q.has_retry = false if no larger plan exists.
+inline int replay_plan_retry(const vms_config *cfg, const ReplayPlan &first, ReplayPlan &q)
+{
+    memset(&q, 0, sizeof q);
+    if (!cfg->retry_traces) return VMS_OK;
+    vms_config big = *cfg;
+    auto twice = [](uint32_t x, uint32_t cap) -> uint32_t { return (uint64_t)x * 2 > cap ? cap : x * 2; };
+    big.variant = VMS_VARIANT_FINE;
+    big.max_free_blocks = twice(cfg->max_free_blocks, 1u << 14);
+    big.max_small_blocks = 0;
+    big.max_pblocks = twice(cfg->max_pblocks, 1u << 20);
+    big.max_multi_pblocks = twice(first.fine ? first.kp[1].cap_pblocks : cfg->max_pblocks, 4096);
+    big.max_sblocks = twice(cfg->max_sblocks, 8000);
+    big.max_runs = twice(cfg->max_runs < (1u << 16) ? (1u << 16) : cfg->max_runs, plan_detail::TABLE_MAX);
+    big.max_chunks = twice(cfg->max_chunks, plan_detail::TABLE_MAX);
+    while ((uint64_t)big.max_chunks * big.chunk_bytes > plan_detail::ENGINE_MAX_BYTES) big.max_chunks /= 2;
+    // shrink towards the first pass's sizes until the tables fit
+    for (int tries = 0; tries < 8; tries++) {
+        const int rc = replay_plan_for(&big, q);
+        if (rc == VMS_OK) {
+            q.has_retry = true;
+            for (int pol = 0; pol < 2; pol++) {
+                q.kp[pol].retry = 1;
+                q.kp[pol].retry_slots = cfg->retry_traces;
+                q.kp[pol].retry_ws_off = first.ws_bytes;
+            }
+            q.ws_bytes = (cfg->policy_mask & VMS_POLICY_VMS) ? (size_t)q.kp[1].ws_stride * cfg->retry_traces : 0;
+            return VMS_OK;
+        }
+        if (rc != VMS_ETOOBIG) return rc;
+        big.max_chunks = big.max_chunks / 2 > cfg->max_chunks ? big.max_chunks / 2 : cfg->max_chunks;
+        big.max_sblocks = big.max_sblocks * 3 / 4 > cfg->max_sblocks ? big.max_sblocks * 3 / 4 : cfg->max_sblocks;
+        big.max_free_blocks = big.max_free_blocks / 2 > cfg->max_free_blocks ? big.max_free_blocks / 2 : cfg->max_free_blocks;
+    }
+    memset(&q, 0, sizeof q);
     return VMS_OK;
 }
 

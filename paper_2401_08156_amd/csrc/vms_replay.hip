@@ -26,6 +26,7 @@ void *g_scratch_ptr[STATIC_WS_DEVICES];     // per device: address of its copy o
 struct vms_replay {
     vms_config cfg;
     ReplayPlan plan;            // kernel variants, LDS layouts, workspace slice (replay_plan.hpp)
+    ReplayPlan retry;           // the same for the second pass over traces that outgrew the tables (has_retry)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
     hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
@@ -176,15 +177,23 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     memset(h, 0, sizeof *h);
     h->cfg = c;
     h->plan = plan;
-    h->ws_bytes = plan.ws_bytes;
+    const int rrc = replay_plan_retry(cfg, plan, h->retry);
+    if (rrc != VMS_OK) {
+        delete h;
+        return rrc;
+    }
+    if (h->retry.has_retry)
+        for (int pol = 0; pol < 2; pol++) h->plan.kp[pol].retry_slots = c.retry_traces;    // the first pass resets the count
+    h->ws_bytes = plan.ws_bytes + h->retry.ws_bytes;
 
     if (hipGetDevice(&h->device) != hipSuccess) {
         delete h;
         return VMS_EHIP;
     }
-    hipError_t e = hipMalloc((void **)&h->d_stats, sizeof(vms_trace_stats) * 2 * (size_t)c.n_traces);
+    // one record more than the traces need: its first word counts the traces the second pass takes on
+    hipError_t e = hipMalloc((void **)&h->d_stats, sizeof(vms_trace_stats) * (2 * (size_t)c.n_traces + 1));
     // records of a policy that never runs stay zero; a run rewrites every record of its policies
-    if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * 2 * (size_t)c.n_traces);
+    if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * (2 * (size_t)c.n_traces + 1));
     if (e == hipSuccess) e = hipMalloc((void **)&h->d_summary, sizeof(vms_summary));
     for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
@@ -194,6 +203,12 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
                                 (int)LDS_PER_CU);
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)pick_vms(h->plan), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)LDS_PER_CU);
+    if (e == hipSuccess && h->retry.has_retry)
+        e = hipFuncSetAttribute((const void *)pick_split(h->retry.slot_regs, h->retry.fl_regs),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_PER_CU);
+    if (e == hipSuccess && h->retry.has_retry)
+        e = hipFuncSetAttribute((const void *)pick_vms(h->retry), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e != hipSuccess) {
         int rc = e == hipErrorOutOfMemory ? VMS_ENOMEM : VMS_EHIP;
@@ -232,6 +247,12 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
         hipLaunchKernelGGL(pick_vms(h->plan), dim3(c.n_traces), dim3(64), h->plan.kp[1].lds_bytes, st, h->plan.kp[1],
                            d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
+        if (h->retry.has_retry) {
+            // second pass: traces whose tables overflowed, with larger tables (the others return at once)
+            hipLaunchKernelGGL(pick_vms(h->retry), dim3(c.n_traces), dim3(64), h->retry.kp[1].lds_bytes, st, h->retry.kp[1],
+                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+            HIP_TRY(h, hipGetLastError());
+        }
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
@@ -239,6 +260,11 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
         hipLaunchKernelGGL(pick_split(h->plan.slot_regs, h->plan.fl_regs), dim3(c.n_traces), dim3(64), h->plan.kp[0].lds_bytes, sst, h->plan.kp[0],
                            d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
+        if (h->retry.has_retry) {
+            hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(c.n_traces), dim3(64),
+                               h->retry.kp[0].lds_bytes, sst, h->retry.kp[0], d_events, d_n_events, d_dec_split, h->d_stats);
+            HIP_TRY(h, hipGetLastError());
+        }
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));
     if (both) HIP_TRY(h, hipStreamWaitEvent(st, h->ev[3], 0));

@@ -137,10 +137,15 @@ int emu_replay(const vms_config *cfg, const uint64_t *events, const uint32_t *n_
                uint64_t *dec_vms, vms_trace_stats *stats)
 {
     ReplayPlan plan;
-    const int rc = replay_plan_make(cfg, plan);
+    int rc = replay_plan_make(cfg, plan);
     if (rc != VMS_OK) return rc;
-    const size_t n = (size_t)cfg->n_traces * cfg->max_events;
-    Guarded g_dec(n * 8), g_stats(sizeof(vms_trace_stats) * 2 * cfg->n_traces), g_ws(plan.ws_bytes ? plan.ws_bytes : 256);
+    ReplayPlan again;
+    rc = replay_plan_retry(cfg, plan, again);
+    if (rc != VMS_OK) return rc;
+    if (again.has_retry)
+        for (int pol = 0; pol < 2; pol++) plan.kp[pol].retry_slots = cfg->retry_traces;
+    const size_t n = (size_t)cfg->n_traces * cfg->max_events, ws_bytes = plan.ws_bytes + again.ws_bytes;
+    Guarded g_dec(n * 8), g_stats(sizeof(vms_trace_stats) * (2 * cfg->n_traces + 1)), g_ws(ws_bytes ? ws_bytes : 256);
     memset(g_stats.ptr(), 0, g_stats.bytes);
     for (int pol = 0; pol < 2; pol++) {
         if (!(cfg->policy_mask & (1u << pol))) continue;
@@ -155,18 +160,24 @@ int emu_replay(const vms_config *cfg, const uint64_t *events, const uint32_t *n_
         if (pol) a.variant = plan.fine ? (plan.wide ? 4 : 2) + (plan.slot_regs ? 0 : 1) : (plan.slot_regs ? 0 : 1);
         else a.variant = (plan.fl_regs ? 0 : 2) + (plan.slot_regs ? 0 : 1);
         if (out) memset(g_dec.ptr(), 0xFF, n * 8);
-        for (u32 t = 0; t < cfg->n_traces; t++) {
-            memset(lds, CANARY, sizeof lds);
-            emu::launch(pol ? body_vms : body_split, &a, t);
-            for (size_t i = a.P.lds_bytes; i < sizeof lds; i++)
-                if ((unsigned char)lds[i] != CANARY) return -101;
+        for (int pass = 0; pass < (again.has_retry ? 2 : 1); pass++) {
+            const ReplayPlan &pl = pass ? again : plan;
+            a.P = pl.kp[pol];
+            if (pol) a.variant = pl.fine ? (pl.wide ? 4 : 2) + (pl.slot_regs ? 0 : 1) : (pl.slot_regs ? 0 : 1);
+            else a.variant = (pl.fl_regs ? 0 : 2) + (pl.slot_regs ? 0 : 1);
+            for (u32 t = 0; t < cfg->n_traces; t++) {
+                memset(lds, CANARY, sizeof lds);
+                emu::launch(pol ? body_vms : body_split, &a, t);
+                for (size_t i = a.P.lds_bytes; i < sizeof lds; i++)
+                    if ((unsigned char)lds[i] != CANARY) return -101;
+            }
         }
         if (!g_dec.intact()) return -102;
         if (!g_stats.intact()) return -103;
         if (!g_ws.intact()) return -104;
         if (out) memcpy(out, g_dec.ptr(), n * 8);
     }
-    memcpy(stats, g_stats.ptr(), g_stats.bytes);
+    memcpy(stats, g_stats.ptr(), sizeof(vms_trace_stats) * 2 * cfg->n_traces);
     return 0;
 }
 

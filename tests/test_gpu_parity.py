@@ -296,3 +296,29 @@ def test_kernel_variant_choice():
     ev, ms = tg.generate(3, n_traces=6, n_events=5000, seed=32)
     cfg = gpu_util.make_cfg(6, 5000, ms, max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=70000)
     gpu_util.assert_parity(ev, cfg, label="fine-grained variant, 32-bit chunk numbers")
+
+
+def test_second_pass_replays_traces_that_outgrow_the_tables():
+    # 40 transformer traces, three of them replaced by random traces whose many requests below one
+    # chunk outgrow the table of the stitching policy's small-request pool: without a second pass those
+    # three are flagged; with one they are replayed in full with doubled tables inside the same
+    # vms_replay_run, and everything matches the oracle
+    ev, ms = tg.generate(2, n_traces=40, n_events=2000, seed=17)
+    rnd, ms1 = tg.generate(1, n_traces=3, n_events=2000, seed=18)
+    slots = max(ms, ms1)
+    for i, t in enumerate((5, 22, 39)):
+        ev[t] = rnd[i]
+    for variant in (binding.VMS_VARIANT_FLAT, binding.VMS_VARIANT_FINE):
+        small = dict(variant=variant, max_free_blocks=128, max_small_blocks=32, max_pblocks=256, max_sblocks=560,
+                     max_runs=1200, max_chunks=4096)
+        _, _, st = gpu_util.gpu_replay(ev, gpu_util.make_cfg(40, 2000, slots, **small))
+        bad = np.flatnonzero((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=0))
+        assert bad.tolist() == [5, 22, 39] and not (st["status"][0] & binding.VMS_ST_TABLE_OVERFLOW).any()
+        gpu_util.assert_parity(ev, gpu_util.make_cfg(40, 2000, slots, retry_traces=4, **small), label="second pass, variant %d" % variant)
+        # room for two of the three only: one stays flagged, nothing else changes
+        _, _, st = gpu_util.gpu_replay(ev, gpu_util.make_cfg(40, 2000, slots, retry_traces=2, policy_mask=2, **small))
+        assert ((st["status"][1] & binding.VMS_ST_TABLE_OVERFLOW) != 0).sum() == 1
+    # the splitting policy's pool too small for most traces (in LDS, then in registers): all replayed again
+    for free in (100, 300):
+        cfg = gpu_util.make_cfg(40, 2000, slots, max_free_blocks=free // 3 if free == 300 else free, retry_traces=40, policy_mask=1)
+        gpu_util.assert_parity(ev, cfg, label="second pass, splitting pool of %d" % cfg.max_free_blocks)

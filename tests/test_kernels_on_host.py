@@ -82,6 +82,24 @@ def test_ragged_traces_and_nothing_written_past_the_end():
     check(ev, gpu_util.make_cfg(3, 700, ms, max_runs=20000), n_events=np.array([0, 333, 700], dtype=np.uint32), label="ragged")
 
 
+def test_second_pass_replays_traces_that_outgrow_the_tables():
+    # tables far too small for the first trace's pools (the other two fit): flagged without a second
+    # pass, replayed in full with doubled tables with one.  (The flat stitching kernel as first pass is
+    # covered on the GPU: its sources carry no lane-switch marks for this host build.)
+    ev, ms = tg.generate(1, n_traces=3, n_events=900, seed=13)
+    ev[1:, 60:] = ev[1:, :1] * 0 + tg.make_events([("A", 0, 2 * MiB), ("F", 0)] * 420)[None, :]
+    for variant in (binding.VMS_VARIANT_FINE,):
+        small = dict(variant=variant, max_free_blocks=24, max_pblocks=40, max_sblocks=560, max_runs=900, max_chunks=8192)
+        _, _, st = emu.replay(ev, gpu_util.make_cfg(3, 900, ms, **small), binding.STATS_DTYPE)
+        assert (st["status"][:, 0] & binding.VMS_ST_TABLE_OVERFLOW).all() and not (st["status"][:, 1:] & binding.VMS_ST_TABLE_OVERFLOW).any()
+        check(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=2, **small), label="second pass, first pass variant %d" % variant)
+    # more such traces than the second pass has room for: the rest stay flagged
+    ev, ms = tg.generate(1, n_traces=3, n_events=900, seed=13)
+    _, _, st = emu.replay(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=1, policy_mask=2, variant=2, max_pblocks=40, max_sblocks=560),
+                          binding.STATS_DTYPE)
+    assert ((st["status"][1] & binding.VMS_ST_TABLE_OVERFLOW) != 0).sum() == 2
+
+
 def test_table_overflow_is_flagged_not_fatal():
     ev, ms = tg.generate(3, n_traces=1, n_events=2500, seed=5)
     cfg = gpu_util.make_cfg(1, 2500, ms, policy_mask=2, variant=2, max_pblocks=64, max_sblocks=520, max_chunks=4096)

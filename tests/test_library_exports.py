@@ -27,7 +27,7 @@ def test_every_declared_symbol_is_exported_and_bound():
 
 
 def test_struct_layouts_match_the_header():
-    assert ctypes.sizeof(binding.vms_config) == 88
+    assert ctypes.sizeof(binding.vms_config) == 96
     assert binding.STATS_DTYPE.itemsize == 152
     assert ctypes.sizeof(binding.vms_summary) == 88
     assert ctypes.sizeof(binding.vms_demo_report) == 232
@@ -39,7 +39,7 @@ def test_struct_layouts_match_the_header():
 
 def test_config_default_and_argument_errors_need_no_gpu():
     cfg = binding.vms_config_default(7, 100, 9)
-    assert (cfg.struct_size, cfg.n_traces, cfg.max_events, cfg.max_slots) == (88, 7, 100, 9)
+    assert (cfg.struct_size, cfg.n_traces, cfg.max_events, cfg.max_slots) == (96, 7, 100, 9)
     assert cfg.chunk_bytes == 2 << 20 and cfg.policy_mask == 3 and cfg.spool_threshold == 512
     L = binding.lib()
     h = ctypes.c_void_p()
