@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, help="workload (default: config 5, the mixture of 16,384 x 100,000 events)")
     ap.add_argument("--traces", type=int, default=None)
     ap.add_argument("--events", type=int, default=None)
+    ap.add_argument("--launch", choices=("overlap", "serial"), default="overlap")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-demo", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=16, help="traces per batch the oracle is timed on")
@@ -169,19 +170,20 @@ def main():
         batches.append(dict(events=events, max_slots=max_slots, cfg=cfg, d_events=d_events,
                             d_split=torch.empty_like(d_events), d_vms=torch.empty_like(d_events),
                             rep=binding.Replay(cfg)))
-    # Every batch is launched on a stream of its own, the longest-running first: the wavefronts of
-    # the offloading batch fill three quarters of every compute unit's LDS for most of the step, and
-    # those of the other batches (a quarter of that footprint each) run beside them in what is left.
+    # Every batch is launched on a stream of its own (--launch overlap), the long-running offloading
+    # batch first, or all on one stream one after the other (--launch serial).
     main_stream = torch.cuda.current_stream(dev)
-    streams = [torch.cuda.Stream(device=dev) for _ in batches]
+    streams = [torch.cuda.Stream(device=dev) if args.launch == "overlap" else main_stream for _ in batches]
     order = sorted(range(len(batches)), key=lambda i: 0 if kinds[i] == 3 else 1)
 
     def step(acc=None):
         for i in order:
-            streams[i].wait_stream(main_stream)
+            if streams[i] is not main_stream:
+                streams[i].wait_stream(main_stream)
             batches[i]["rep"].run(batches[i]["d_events"], None, batches[i]["d_split"], batches[i]["d_vms"], streams[i])
         for i in order:
-            main_stream.wait_stream(streams[i])
+            if streams[i] is not main_stream:
+                main_stream.wait_stream(streams[i])
         if acc is not None:
             # HIP events recorded by the library on each batch's stream around its kernels; reading
             # them waits for the batch, which is also what serialises runs on one handle
