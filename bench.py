@@ -24,7 +24,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 BYTES_PER_EVENT_PER_KERNEL = 16       # 8 B event word read + 8 B decision word written
 KERNEL_SOURCES = ("replay_kernels.hpp", "replay_fine.hpp", "replay_plan.hpp", "vms_replay.hip", "wave_ops.hpp", "wave_hw.hpp")
-MAPPING_LIMIT = 48000                 # chunk mappings the demo may hold at once (the driver refuses beyond ~60,000)
+MAPPING_LIMIT = 40000                 # chunk mappings the demo may hold at once (hipMemSetAccess was refused at about 48,000)
 
 
 def source_hash():

@@ -107,19 +107,31 @@ struct Demo {
         }
         {
             Timer t(&rep.ms_reserve, &rep.n_reserve);
-            if (!ok(hipMemAddressReserve(&va, (size_t)total_chunks * chunk_bytes, 0, nullptr, 0), 1)) return nullptr;
+            if (!ok(hipMemAddressReserve(&va, (size_t)total_chunks * chunk_bytes, 0, nullptr, 0), 1)) {
+                mapped_now -= total_chunks;
+                return nullptr;
+            }
         }
-        size_t off = 0;
+        // a call that fails leaves nothing of this range behind: what was mapped so far is unmapped
+        // and the range returned (the first error is the one reported)
+        size_t off = 0, mapped = 0;
+        auto undo = [&]() -> char * {
+            for (size_t i = 0; i < mapped; i++) (void)hipMemUnmap((char *)va + i * chunk_bytes, chunk_bytes);
+            (void)hipMemAddressFree(va, (size_t)total_chunks * chunk_bytes);
+            mapped_now -= total_chunks;
+            return nullptr;
+        };
         for (auto &r : runs)
             for (u32 c = r.first; c < r.first + r.second; c++, off += chunk_bytes) {
                 Timer t(&rep.ms_map, &rep.n_map);
-                if (!ok(hipMemMap((char *)va + off, chunk_bytes, 0, chunks[c], 0), 3)) return nullptr;
+                if (!ok(hipMemMap((char *)va + off, chunk_bytes, 0, chunks[c], 0), 3)) return undo();
+                mapped++;
             }
         // the paper enables access chunk by chunk (Sec. 2.5); one call per mapped chunk here too
         off = 0;
         for (u32 i = 0; i < total_chunks; i++, off += chunk_bytes) {
             Timer t(&rep.ms_set_access, &rep.n_set_access);
-            if (!ok(hipMemSetAccess((char *)va + off, chunk_bytes, &access, 1), 4)) return nullptr;
+            if (!ok(hipMemSetAccess((char *)va + off, chunk_bytes, &access, 1), 4)) return undo();
         }
         return (char *)va;
     }
@@ -173,9 +185,13 @@ struct Demo {
         PBlock p = found->second;
         inactive.erase(PoolKey{ p.len, start });
         unmap(p.va, p.len);
+        pblocks.erase(found);                // its range is gone: no record may keep the address
         char *a = map_runs({ { start, keep } }, keep);
-        char *b = map_runs({ { start + keep, p.len - keep } }, p.len - keep);
-        if (!a || !b) return false;
+        char *b = a ? map_runs({ { start + keep, p.len - keep } }, p.len - keep) : nullptr;
+        if (!a || !b) {
+            unmap(a, keep);
+            return false;
+        }
         pblocks[start] = PBlock{ keep, false, a };
         pblocks[start + keep] = PBlock{ p.len - keep, false, b };
         inactive.insert(PoolKey{ keep, start });
@@ -479,6 +495,7 @@ extern "C" int vms_demo_run(const vms_config *cfg, const uint64_t *h_events, con
     d.teardown();
     if (rc == VMS_OK && d.err != hipSuccess) rc = VMS_EHIP;
     out->hip_error = (int)d.err;
+    if (d.err != hipSuccess) (void)hipGetLastError();   // reported here; not left for the caller's next HIP call to trip over
     if (rc == VMS_OK) table1(*out, d.prop, d.access, (size_t)2 << 30, cfg->chunk_bytes);
     return rc;
 }
@@ -560,6 +577,7 @@ extern "C" int vms_vmm_latency(uint64_t block_bytes, uint64_t chunk_bytes, uint3
         (void)hipMemAddressFree(va, bytes);
         if (e != hipSuccess) {
             out->hip_error = (int)e;
+            (void)hipGetLastError();
             return VMS_EHIP;
         }
         best[2] = std::min(best[2], ms(t0, t1));

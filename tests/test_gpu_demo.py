@@ -44,8 +44,8 @@ def test_demo_config1_trace():
 
 def test_demo_offload_trace_prefix():
     # an offloading trace of the config-5 mixture (kind 3): gigabyte-sized staging buffers.  Only a
-    # prefix: with one mapping per 2 MiB chunk the runtime refuses further hipMemSetAccess calls after
-    # some 60,000 mappings, which this trace reaches near event 650.
+    # prefix: with one mapping per 2 MiB chunk the runtime refuses further hipMemSetAccess calls once
+    # about 48,000 chunk mappings are live, which this trace reaches near event 650.
     # The trace: the lowest-index offloading trace whose stitched peak fits half of the free HBM.
     import torch
     free_bytes, _ = torch.cuda.mem_get_info()
@@ -64,7 +64,7 @@ def test_demo_offload_trace_prefix():
 def test_demo_whole_config5_trace_chosen_by_plan():
     # a whole trace of the 16,384 x 100,000 mixture with real mappings.  vms_demo_plan (host only)
     # counts what a trace would map: the offloading trace would hold over a million chunk mappings at
-    # once (the driver refuses beyond some 60,000), the recomputation trace about 31,000.
+    # once (hipMemSetAccess is refused at about 48,000 live mappings), the recomputation trace about 31,000.
     chosen = None
     for first, kind in ((1, 3), (0, 2)):
         ev, ms = tg.generate(5, n_traces=1, n_events=100000, first_trace=first)
@@ -76,7 +76,7 @@ def test_demo_whole_config5_trace_chosen_by_plan():
         if kind == 3:
             assert plan.peak_mapped_chunks > 500000
         else:
-            assert plan.peak_mapped_chunks < 48000
+            assert plan.peak_mapped_chunks < 40000
             chosen = (cfg, ev[0], dv[0], st, plan)
     cfg, ev, dv, st, plan = chosen
     rc, rep = binding.vms_demo_run(cfg, ev, dv)
@@ -86,6 +86,39 @@ def test_demo_whole_config5_trace_chosen_by_plan():
     # the plan foresaw every call
     for f in ("n_reserve", "n_create", "n_map", "n_set_access", "n_unmap", "n_release", "n_address_free", "peak_mapped_chunks"):
         assert getattr(rep, f) == getattr(plan, f), f
+
+
+def test_demo_reports_a_refused_mapping_and_leaves_nothing_behind():
+    # The prefix of an offloading trace that wants 150,000 chunk mappings at once.  Where the driver
+    # refuses a call on the way (seen: hipMemSetAccess -> hipErrorInvalidValue with about 48,000 live
+    # mappings), the demo must say which call and which error, give every range and chunk back, and
+    # leave no pending HIP error for the caller's next call; where it does not refuse, the prefix runs.
+    import torch
+    ev, ms = tg.generate(5, n_traces=1, n_events=100000, first_trace=1)
+    cfg = workloads.make_config(binding, 5, 1, 100000, ms, kind=3)
+    _, dv, st = gpu_util.gpu_replay(ev, cfg)
+    lo, hi = 1, 100000
+    while lo < hi:                                # the shortest prefix that reaches 150,000
+        mid = (lo + hi) // 2
+        _, plan = binding.vms_demo_plan(cfg, ev[0], dv[0], n_events=mid)
+        lo, hi = (lo, mid) if plan.peak_mapped_chunks >= 150000 else (mid + 1, hi)
+    rc, plan = binding.vms_demo_plan(cfg, ev[0], dv[0], n_events=lo)
+    free_before, _ = torch.cuda.mem_get_info()
+    assert rc == 0 and plan.chunks_created * cfg.chunk_bytes < free_before // 2
+    rc, rep = binding.vms_demo_run(cfg, ev[0], dv[0], n_events=lo)
+    if rc != 0:
+        assert rc == -5 and rep.hip_error != 0 and 1 <= rep.failed_api <= 8
+        assert rep.failed_event == rep.events_replayed < lo
+        assert rep.n_release == rep.n_create == rep.chunks_created
+        print("refused: api %d, hip error %d, at event %d with %d chunk mappings live (peak)"
+              % (rep.failed_api, rep.hip_error, rep.failed_event, rep.peak_mapped_chunks))
+    else:
+        assert rep.events_replayed == lo and rep.alias_failures == 0
+    x = torch.ones(1 << 20, device="cuda")        # the next HIP call of the process works
+    assert float(x.sum()) == float(1 << 20)
+    torch.cuda.synchronize()
+    free_after, _ = torch.cuda.mem_get_info()
+    assert abs(free_before - free_after) < (1 << 30)
 
 
 def test_demo_rejects_inconsistent_decisions():
