@@ -138,7 +138,7 @@ def main():
     ap.add_argument("--launch", choices=("overlap", "serial"), default="overlap")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-demo", action="store_true")
-    ap.add_argument("--cpu-sample", type=int, default=16, help="traces per batch the oracle is timed on")
+    ap.add_argument("--cpu-sample", type=int, default=64, help="traces per batch the oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the replay engine runs on one GPU only (traces are independent and would shard "

@@ -219,7 +219,8 @@ int vms_replay_summary(vms_replay *h, vms_summary *h_out);
 
 /* Milliseconds the kernels of the last run took on their stream (HIP events
  * recorded around them inside vms_replay_run); waits for the run.
- * out_ms[0] splitting kernel, [1] VMS kernel, [2] whole run.                  */
+ * out_ms[0] splitting kernel, [1] VMS kernel (both: the first pass alone),
+ * [2] whole run, second pass included.                                        */
 int vms_replay_last_kernel_ms(vms_replay *h, float out_ms[3]);
 
 void vms_replay_destroy(vms_replay *h);

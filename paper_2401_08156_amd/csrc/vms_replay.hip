@@ -29,7 +29,7 @@ struct vms_replay {
     ReplayPlan retry;           // the same for the second pass over traces that outgrew the tables (has_retry)
     vms_trace_stats *d_stats;
     vms_summary *d_summary;
-    hipEvent_t ev[5];           // run start, VMS kernel end, split kernel start / end, run end
+    hipEvent_t ev[6];           // run start, stitching kernel end, splitting kernel start / end, run end, side stream done
     hipStream_t side;           // the splitting kernel runs here, beside the stitching kernel
     hipStream_t last_stream;
     int device;
@@ -195,7 +195,7 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     // records of a policy that never runs stay zero; a run rewrites every record of its policies
     if (e == hipSuccess) e = hipMemset(h->d_stats, 0, sizeof(vms_trace_stats) * (2 * (size_t)c.n_traces + 1));
     if (e == hipSuccess) e = hipMalloc((void **)&h->d_summary, sizeof(vms_summary));
-    for (int i = 0; i < 5 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
+    for (int i = 0; i < 6 && e == hipSuccess; i++) e = hipEventCreate(&h->ev[i]);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
     if (e == hipSuccess)
@@ -247,27 +247,28 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
         hipLaunchKernelGGL(pick_vms(h->plan), dim3(c.n_traces), dim3(64), h->plan.kp[1].lds_bytes, st, h->plan.kp[1],
                            d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
-        if (h->retry.has_retry) {
-            // second pass: traces whose tables overflowed, with larger tables (the others return at once)
-            hipLaunchKernelGGL(pick_vms(h->retry), dim3(c.n_traces), dim3(64), h->retry.kp[1].lds_bytes, st, h->retry.kp[1],
-                               d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
-            HIP_TRY(h, hipGetLastError());
-        }
     }
-    HIP_TRY(h, hipEventRecord(h->ev[1], st));
+    HIP_TRY(h, hipEventRecord(h->ev[1], st));       // the kernel times are those of the first pass
+    if ((c.policy_mask & VMS_POLICY_VMS) && h->retry.has_retry) {
+        // second pass: traces whose tables overflowed, with larger tables (the others return at once)
+        hipLaunchKernelGGL(pick_vms(h->retry), dim3(c.n_traces), dim3(64), h->retry.kp[1].lds_bytes, st, h->retry.kp[1],
+                           d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
+        HIP_TRY(h, hipGetLastError());
+    }
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
         hipLaunchKernelGGL(pick_split(h->plan.slot_regs, h->plan.fl_regs), dim3(c.n_traces), dim3(64), h->plan.kp[0].lds_bytes, sst, h->plan.kp[0],
                            d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
-        if (h->retry.has_retry) {
-            hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(c.n_traces), dim3(64),
-                               h->retry.kp[0].lds_bytes, sst, h->retry.kp[0], d_events, d_n_events, d_dec_split, h->d_stats);
-            HIP_TRY(h, hipGetLastError());
-        }
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));
-    if (both) HIP_TRY(h, hipStreamWaitEvent(st, h->ev[3], 0));
+    if ((c.policy_mask & VMS_POLICY_SPLIT) && h->retry.has_retry) {
+        hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(c.n_traces), dim3(64),
+                           h->retry.kp[0].lds_bytes, sst, h->retry.kp[0], d_events, d_n_events, d_dec_split, h->d_stats);
+        HIP_TRY(h, hipGetLastError());
+    }
+    HIP_TRY(h, hipEventRecord(h->ev[5], sst));
+    if (both) HIP_TRY(h, hipStreamWaitEvent(st, h->ev[5], 0));
     HIP_TRY(h, hipEventRecord(h->ev[4], st));
     h->last_stream = st;
     h->ran = true;
@@ -334,7 +335,7 @@ void vms_replay_destroy(vms_replay *h)
     if (!h) return;
     if (h->d_stats) (void)hipFree(h->d_stats);
     if (h->d_summary) (void)hipFree(h->d_summary);
-    for (int i = 0; i < 5; i++)
+    for (int i = 0; i < 6; i++)
         if (h->ev[i]) (void)hipEventDestroy(h->ev[i]);
     if (h->side) (void)hipStreamDestroy(h->side);
     delete h;
