@@ -121,13 +121,14 @@ typedef struct vms_config {
                                     pBlocks / sBlocks), VMS_VARIANT_FINE = the fine-grained
                                     variant (a fraction of the LDS, lists in the workspace:
                                     more traces resident per compute unit)                   */
-    uint32_t retry_traces;       /* traces of one run that may be replayed a second time with
-                                    larger tables after one of the tables above proved too
-                                    small for them (0: none; such traces stay flagged
-                                    VMS_ST_TABLE_OVERFLOW).  The second pass doubles the
-                                    tables (as far as a compute unit's LDS goes) and runs
-                                    right behind the first inside vms_replay_run; it needs
-                                    workspace for retry_traces traces of that size          */
+    uint32_t retry_traces;       /* wavefronts of the second pass (0: no second pass; traces
+                                    that outgrow one of the tables above stay flagged
+                                    VMS_ST_TABLE_OVERFLOW).  The second pass runs right
+                                    behind the first inside vms_replay_run: retry_traces
+                                    wavefronts with every table doubled (as far as a compute
+                                    unit's LDS goes) share out the flagged traces and replay
+                                    each of them from its first event; it needs workspace
+                                    for retry_traces traces of that size                     */
     uint32_t reserved0;          /* 0                                                        */
 } vms_config;
 

@@ -978,20 +978,16 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     WAVE_DYNAMIC_LDS(lds);
     typedef typename FineT<IDX>::pkey_t pkey_t;
     const u32 lane = lane_id();
-    const u32 trace = blockIdx.x;
+    u32 trace = blockIdx.x;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
-    u32 *taken = (u32 *)&stats[2 * (size_t)P.n_traces];     // traces the second pass has taken on
+    u32 *taken = (u32 *)&stats[2 * (size_t)P.n_traces];     // [1]: trace numbers the second pass has handed out
+    if (!P.retry && P.retry_slots && trace == 0) taken[1] = 0;
+    SecondPass W;
+    do {        // once; the second pass: once per flagged trace this wavefront takes on
     if (P.retry) {
-        // The second pass (larger tables): only the traces whose first replay ended in a table
-        // overflow, and as many of them as there is workspace for; the others stay flagged.
-        if (!(uni(stats[(size_t)P.n_traces + trace].status) & VMS_ST_TABLE_OVERFLOW)) return;
-        u32 mine = 0;
-        if (lane == 0) mine = atomicAdd(taken, 1u);
-        const u32 turn = from_lane(mine, 0);
-        if (turn >= P.retry_slots) return;
-        ws_slice = workspace + P.retry_ws_off + (size_t)turn * P.ws_stride;
-    } else if (P.retry_slots && trace == 0) {
-        *taken = 0;
+        // larger tables, a workspace slice per wavefront of this launch behind those of the first pass
+        if (!W.next(P, stats + P.n_traces, &taken[1], trace)) return;
+        ws_slice = workspace + P.retry_ws_off + (size_t)blockIdx.x * P.ws_stride;
     }
 
     SlotsT<SLOT_REGS> S;
@@ -1250,6 +1246,8 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
         s.fragmentation = reserved ? 1.0 - (double)peak_active / (double)reserved : 0.0;
     }
+    wave_sync();
+    } while (P.retry);
 }
 
 #endif

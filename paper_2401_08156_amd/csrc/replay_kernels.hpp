@@ -1403,6 +1403,30 @@ DI u64 tile_totals(const TileOut &T, u32 n_code[8])
     return wave_sum_u64(T.dig);
 }
 
+// The second pass (vms_config.retry_traces): a launch of a few wavefronts with larger
+// tables that replays every trace whose first replay ended in a table overflow.  The wavefronts
+// share one counter over the trace numbers: each takes 64 numbers at a time, looks at their
+// status words side by side and replays the flagged ones among them one after the other.
+struct SecondPass {
+    u64 flagged = 0;
+    u32 first = 0;
+    // the next flagged trace for this wavefront, or false when all have been handed out
+    DI bool next(const KParams &P, const vms_trace_stats *__restrict__ st, u32 *counter, u32 &trace)
+    {
+        while (!flagged) {
+            u32 b = 0;
+            if (lane_id() == 0) b = atomicAdd(counter, 64u);
+            first = from_lane(b, 0);
+            if (first >= P.n_traces) return false;
+            const u32 t = first + lane_id();
+            flagged = ballot(t < P.n_traces && (st[t < P.n_traces ? t : 0u].status & VMS_ST_TABLE_OVERFLOW) != 0);
+        }
+        trace = first + first_lane(flagged);
+        flagged &= flagged - 1;
+        return true;
+    }
+};
+
 // ---------------------------------------------------------------------------
 // Replay under the stitching policy (Sec. 3, Sec. 4.1), one wavefront per trace.
 // SLOT_REGS: slot table in registers (max_slots <= 64).
@@ -1424,7 +1448,7 @@ __global__ __launch_bounds__(64) void replay_vms_kernel(KParams P, const u64 *__
     constexpr bool USE_LIST = SLOT_REGS;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
     // a second pass follows for traces that outgrow these tables: it counts the traces it takes on
-    if (P.retry_slots && trace == 0) *(u32 *)&stats[2 * (size_t)P.n_traces] = 0;
+    if (P.retry_slots && trace == 0) ((u32 *)&stats[2 * (size_t)P.n_traces])[1] = 0;     // the second pass counts from 0
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
@@ -1786,9 +1810,12 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
 {
     WAVE_DYNAMIC_LDS(lds);
     const u32 lane = lane_id();
-    const u32 trace = blockIdx.x;
-    // the second pass (larger tables): only the traces whose first replay ended in a table overflow
-    if (P.retry && !(uni(stats[trace].status) & VMS_ST_TABLE_OVERFLOW)) return;
+    u32 trace = blockIdx.x;
+    u32 *taken = (u32 *)&stats[2 * (size_t)P.n_traces];     // [0]: trace numbers the second pass has handed out
+    if (!P.retry && P.retry_slots && trace == 0) taken[0] = 0;
+    SecondPass W;
+    do {        // once; the second pass: once per flagged trace this wavefront takes on
+    if (P.retry && !W.next(P, stats, &taken[0], trace)) return;
 
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
@@ -1916,4 +1943,6 @@ __global__ __launch_bounds__(64) void replay_split_kernel(KParams P, const u64 *
         // Sec. 5.1: fragmentation = 1 - utilisation, utilisation = peak active / peak reserved
         s.fragmentation = reserved ? 1.0 - (double)peak_requested / (double)reserved : 0.0;
     }
+    wave_sync();
+    } while (P.retry);
 }

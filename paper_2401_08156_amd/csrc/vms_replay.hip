@@ -229,6 +229,8 @@ int vms_replay_lds_bytes(const vms_replay *h, uint32_t out[2])
     return VMS_OK;
 }
 
+static inline uint32_t second_pass_waves(const vms_config &c) { return c.retry_traces < c.n_traces ? c.retry_traces : c.n_traces; }
+
 int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_events, uint64_t *d_dec_split,
                    uint64_t *d_dec_vms, void *d_workspace, void *hip_stream)
 {
@@ -250,8 +252,8 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     }
     HIP_TRY(h, hipEventRecord(h->ev[1], st));       // the kernel times are those of the first pass
     if ((c.policy_mask & VMS_POLICY_VMS) && h->retry.has_retry) {
-        // second pass: traces whose tables overflowed, with larger tables (the others return at once)
-        hipLaunchKernelGGL(pick_vms(h->retry), dim3(c.n_traces), dim3(64), h->retry.kp[1].lds_bytes, st, h->retry.kp[1],
+        // second pass: retry_traces wavefronts with larger tables replay the traces whose tables overflowed
+        hipLaunchKernelGGL(pick_vms(h->retry), dim3(second_pass_waves(c)), dim3(64), h->retry.kp[1].lds_bytes, st, h->retry.kp[1],
                            d_events, d_n_events, d_dec_vms, h->d_stats, (char *)d_workspace);
         HIP_TRY(h, hipGetLastError());
     }
@@ -263,7 +265,7 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));
     if ((c.policy_mask & VMS_POLICY_SPLIT) && h->retry.has_retry) {
-        hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(c.n_traces), dim3(64),
+        hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(second_pass_waves(c)), dim3(64),
                            h->retry.kp[0].lds_bytes, sst, h->retry.kp[0], d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }

@@ -165,7 +165,9 @@ int emu_replay(const vms_config *cfg, const uint64_t *events, const uint32_t *n_
             a.P = pl.kp[pol];
             if (pol) a.variant = pl.fine ? (pl.wide ? 4 : 2) + (pl.slot_regs ? 0 : 1) : (pl.slot_regs ? 0 : 1);
             else a.variant = (pl.fl_regs ? 0 : 2) + (pl.slot_regs ? 0 : 1);
-            for (u32 t = 0; t < cfg->n_traces; t++) {
+            // the second pass is a launch of retry_traces wavefronts that share out the flagged traces
+            const u32 waves = pass ? std::min(cfg->retry_traces, cfg->n_traces) : cfg->n_traces;
+            for (u32 t = 0; t < waves; t++) {
                 memset(lds, CANARY, sizeof lds);
                 emu::launch(pol ? body_vms : body_split, &a, t);
                 for (size_t i = a.P.lds_bytes; i < sizeof lds; i++)

@@ -315,9 +315,10 @@ def test_second_pass_replays_traces_that_outgrow_the_tables():
         bad = np.flatnonzero((st["status"] & binding.VMS_ST_TABLE_OVERFLOW).any(axis=0))
         assert bad.tolist() == [5, 22, 39] and not (st["status"][0] & binding.VMS_ST_TABLE_OVERFLOW).any()
         gpu_util.assert_parity(ev, gpu_util.make_cfg(40, 2000, slots, retry_traces=4, **small), label="second pass, variant %d" % variant)
-        # room for two of the three only: one stays flagged, nothing else changes
-        _, _, st = gpu_util.gpu_replay(ev, gpu_util.make_cfg(40, 2000, slots, retry_traces=2, policy_mask=2, **small))
-        assert ((st["status"][1] & binding.VMS_ST_TABLE_OVERFLOW) != 0).sum() == 1
+        # fewer wavefronts in the second pass than flagged traces: they share the three out
+        for waves in (1, 2):
+            gpu_util.assert_parity(ev, gpu_util.make_cfg(40, 2000, slots, retry_traces=waves, **small),
+                                   label="second pass of %d wavefronts, variant %d" % (waves, variant))
     # the splitting policy's pool too small for most traces (in LDS, then in registers): all replayed again
     for free in (100, 300):
         cfg = gpu_util.make_cfg(40, 2000, slots, max_free_blocks=free // 3 if free == 300 else free, retry_traces=40, policy_mask=1)

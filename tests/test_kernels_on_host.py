@@ -93,11 +93,19 @@ def test_second_pass_replays_traces_that_outgrow_the_tables():
         _, _, st = emu.replay(ev, gpu_util.make_cfg(3, 900, ms, **small), binding.STATS_DTYPE)
         assert (st["status"][:, 0] & binding.VMS_ST_TABLE_OVERFLOW).all() and not (st["status"][:, 1:] & binding.VMS_ST_TABLE_OVERFLOW).any()
         check(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=2, **small), label="second pass, first pass variant %d" % variant)
-    # more such traces than the second pass has room for: the rest stay flagged
+    # more such traces than the second pass has wavefronts: one wavefront replays all three in turn
     ev, ms = tg.generate(1, n_traces=3, n_events=900, seed=13)
-    _, _, st = emu.replay(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=1, policy_mask=2, variant=2, max_pblocks=40, max_sblocks=560),
-                          binding.STATS_DTYPE)
-    assert ((st["status"][1] & binding.VMS_ST_TABLE_OVERFLOW) != 0).sum() == 2
+    cfg = gpu_util.make_cfg(3, 900, ms, policy_mask=2, variant=2, max_pblocks=40, max_sblocks=560)
+    _, _, st = emu.replay(ev, cfg, binding.STATS_DTYPE)
+    assert ((st["status"][1] & binding.VMS_ST_TABLE_OVERFLOW) != 0).sum() == 3
+    check(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=1, variant=2, max_pblocks=40, max_sblocks=560), label="second pass of one wavefront")
+    # 70 traces, every third flagged: the wavefronts take their trace numbers 64 at a time
+    ev, ms = tg.generate(1, n_traces=70, n_events=300, seed=21)
+    ev[np.arange(70) % 3 != 0, 10:] = tg.make_events([("A", 0, 2 * MiB), ("F", 0)] * 145)[None, :]
+    small = dict(variant=2, max_free_blocks=24, max_pblocks=24, max_sblocks=560, max_runs=900, max_chunks=8192)
+    _, _, st = emu.replay(ev, gpu_util.make_cfg(70, 300, ms, **small), binding.STATS_DTYPE)
+    assert 10 < (st["status"] & binding.VMS_ST_TABLE_OVERFLOW != 0).any(axis=0).sum() <= 24
+    check(ev, gpu_util.make_cfg(70, 300, ms, retry_traces=3, **small), label="second pass over 70 traces")
 
 
 def test_table_overflow_is_flagged_not_fatal():
