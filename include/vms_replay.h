@@ -70,6 +70,10 @@ extern "C" {
 #define VMS_VARIANT_FLAT 1u
 #define VMS_VARIANT_FINE 2u
 
+#define VMS_TABLES_AUTO      0u
+#define VMS_TABLES_LDS       1u
+#define VMS_TABLES_WORKSPACE 2u
+
 #define VMS_POLICY_SPLIT 1u
 #define VMS_POLICY_VMS   2u
 
@@ -129,7 +133,13 @@ typedef struct vms_config {
                                     unit's LDS goes) share out the flagged traces and replay
                                     each of them from its first event; it needs workspace
                                     for retry_traces traces of that size                     */
-    uint32_t reserved0;          /* 0                                                        */
+    uint32_t table_place;        /* fine-grained variant: where the witness and list-place
+                                    tables of the sBlocks live.  VMS_TABLES_LDS, or
+                                    VMS_TABLES_WORKSPACE (4 bytes per sBlock less LDS: more
+                                    wavefronts per compute unit, each a little slower; at
+                                    most 63000 chunks), or 0: the library takes the
+                                    workspace when that lets a quarter more wavefronts
+                                    share a compute unit and the batch needs them            */
 } vms_config;
 
 typedef struct vms_trace_stats {        /* one per (policy, trace) */

@@ -38,7 +38,7 @@
 
 typedef uint16_t u16;
 
-template <class IDX>
+template <class IDX, bool TH>
 struct FineT {
     typedef typename std::conditional<sizeof(IDX) == 2, u32, u64>::type pkey_t;
     static constexpr u32 W = sizeof(IDX) * 8;
@@ -59,6 +59,23 @@ struct FineT {
     static DI u32 ksize(pkey_t k) { return (u32)(k >> W); }
     static DI u32 kstart(pkey_t k) { return (u32)(IDX) ~(IDX)k; }
     DI u64 *list_at(u32 place) const { return arena + ((size_t)place << gs); }
+    // swit[] / soff[] live in LDS, or (TH) in the trace's workspace slice: then they are read with
+    // device-scope loads and moved by gblk_shift_*; IDX is 16 bits wide there
+    // before the first read of these tables after they were written (the stores must have arrived)
+    DI void tables_written() const
+    {
+        if constexpr (TH) tbl_fence();
+    }
+    DI u32 wit_at(u32 i) const
+    {
+        if constexpr (TH) return ld_tab((const u16 *)swit + i);
+        else return swit[i];
+    }
+    DI u32 off_at(u32 i) const
+    {
+        if constexpr (TH) return ld_tab(soff + i);
+        else return soff[i];
+    }
     DI u32 grans(u32 entries) const { return (entries + 2 + (1u << gs) - 1) >> gs; }
 };
 
@@ -71,8 +88,8 @@ DI K from_lane_k(K v, u32 l)
 
 // ---- single-chunk pBlocks --------------------------------------------------------------------
 // the chunks of bitmap word w that are inactive pBlocks of one chunk (one lane per word)
-template <class IDX>
-DI u32 singles_free(const FineT<IDX> &V, u32 w)
+template <class IDX, bool TH>
+DI u32 singles_free(const FineT<IDX, TH> &V, u32 w)
 {
     const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
     return b & ((b >> 1) | (bn << 31)) & ~a;
@@ -80,8 +97,8 @@ DI u32 singles_free(const FineT<IDX> &V, u32 w)
 
 // the chunks of bitmap word w that belong to inactive pBlocks of two or more chunks: the inactive
 // chunks that exist and are not single-chunk pBlocks (an inactive pBlock has none of its bits set)
-template <class IDX>
-DI u32 multi_free(const FineT<IDX> &V, u32 w)
+template <class IDX, bool TH>
+DI u32 multi_free(const FineT<IDX, TH> &V, u32 w)
 {
     const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
     const u32 single = b & ((b >> 1) | (bn << 31));
@@ -96,8 +113,8 @@ struct Quad {
     u32 single[4], multi[4], start[4];
 };
 
-template <class IDX>
-DI Quad quad_load(const FineT<IDX> &V, u32 q)
+template <class IDX, bool TH>
+DI Quad quad_load(const FineT<IDX, TH> &V, u32 q)
 {
     const Blk16 b = ((const Blk16 *)V.bnd)[q], a = ((const Blk16 *)V.bmp)[q];
     const u32 bn = V.bnd[4 * q + 4], n = V.n_chunks;
@@ -124,11 +141,13 @@ DI u32 word_mask_or0(u32 w, u32 start, u32 end)
 }
 
 // S1 for a request of one chunk: the first inactive pBlock of one chunk
-template <class IDX>
-DI bool s1_single(const FineT<IDX> &V, u32 &start)
+template <class IDX, bool TH>
+DI bool s1_single(const FineT<IDX, TH> &V, u32 &start)
 {
     for (u32 wb = 0; wb * 32 < V.n_chunks; wb += 64) {
-        const u32 m = singles_free(V, wb + lane_id());
+        const u32 w = wb + lane_id();
+        const bool in = w * 32 < V.n_chunks;                    // (the bitmaps end with the word of the last chunk)
+        const u32 m = in ? singles_free(V, in ? w : 0u) : 0u;
         const u64 bm = ballot(m != 0);
         if (bm) {
             const u32 l = first_lane(bm);
@@ -142,8 +161,8 @@ DI bool s1_single(const FineT<IDX> &V, u32 &start)
 // ---- pool[] of multi-chunk pBlocks --------------------------------------------------------------
 // (4-byte keys move sixteen bytes per lane and step; the 8-byte keys of the variant with 32-bit chunk
 // numbers one key per lane)
-template <class IDX, class AcctT>
-DI void fine_pool_insert(FineT<IDX> &V, u32 size, u32 start, AcctT &A)
+template <class IDX, bool TH, class AcctT>
+DI void fine_pool_insert(FineT<IDX, TH> &V, u32 size, u32 start, AcctT &A)
 {
     const auto k = V.key(size, start);
     const u32 pos = rank_desc_k(V.pool, V.np, k);
@@ -155,8 +174,8 @@ DI void fine_pool_insert(FineT<IDX> &V, u32 size, u32 start, AcctT &A)
     wave_sync();
 }
 
-template <class IDX>
-DI void fine_pool_remove(FineT<IDX> &V, u32 idx)
+template <class IDX, bool TH>
+DI void fine_pool_remove(FineT<IDX, TH> &V, u32 idx)
 {
     if constexpr (sizeof(IDX) == 2) {
         blk_shift_down(V.pool, idx, V.np);                      // (leaves a zero key in the last place)
@@ -164,15 +183,15 @@ DI void fine_pool_remove(FineT<IDX> &V, u32 idx)
     } else {
         shift_down(V.pool, idx, V.np);
         V.np--;
-        st_one(V.pool, V.np, (typename FineT<IDX>::pkey_t)0);
+        st_one(V.pool, V.np, (typename FineT<IDX, TH>::pkey_t)0);
     }
     wave_sync();
 }
 
 // Split (Sec. 3.3.1): the pBlock at pool[idx] = [start, start + size) becomes [start, start + keep)
 // and the rest.  A piece of one chunk leaves the array: its boundary bits say all there is to say.
-template <class IDX, class AcctT>
-DI void fine_cut(FineT<IDX> &V, u32 idx, u32 start, u32 size, u32 keep, AcctT &A)
+template <class IDX, bool TH, class AcctT>
+DI void fine_cut(FineT<IDX, TH> &V, u32 idx, u32 start, u32 size, u32 keep, AcctT &A)
 {
     fine_pool_remove(V, idx);
     const u32 cut = start + keep;
@@ -186,8 +205,8 @@ DI void fine_cut(FineT<IDX> &V, u32 idx, u32 start, u32 size, u32 keep, AcctT &A
 }
 
 // Alloc (Sec. 3.3.1): `len` new chunks behind the last one
-template <class IDX, class AcctT>
-DI u32 fine_grow(FineT<IDX> &V, u32 len, AcctT &A)
+template <class IDX, bool TH, class AcctT>
+DI u32 fine_grow(FineT<IDX, TH> &V, u32 len, AcctT &A)
 {
     const u32 start = V.n_chunks, end = start + len;
     atomicOr(lane_id() == 0 ? &V.bnd[end >> 5] : &V.idle[lane_id()], lane_id() == 0 ? 1u << (end & 31) : 0u);
@@ -201,8 +220,8 @@ DI u32 fine_grow(FineT<IDX> &V, u32 len, AcctT &A)
 
 // S1, primitive blocks of two or more chunks: the first inactive one among pool[lo_p, hi_p), the
 // pBlocks of exactly the requested number of chunks
-template <class IDX>
-DI bool fine_s1_pblock(const FineT<IDX> &V, u32 lo_p, u32 hi_p, u32 &start)
+template <class IDX, bool TH>
+DI bool fine_s1_pblock(const FineT<IDX, TH> &V, u32 lo_p, u32 hi_p, u32 &start)
 {
     const u32 lane = lane_id();
     for (u32 base = lo_p; base < hi_p; base += 64) {
@@ -222,16 +241,16 @@ DI bool fine_s1_pblock(const FineT<IDX> &V, u32 lo_p, u32 hi_p, u32 &start)
 // ---- lists ------------------------------------------------------------------------------------
 // One tile of list words (e, if live): their chunks are tested, set or cleared, one bitmap word per
 // lane.  Set and clear are LDS atomics without a result; idle lanes aim at a spare word of their own.
-template <class IDX>
-DI u64 tile_busy(const FineT<IDX> &V, u64 e, bool live, u32 &seen)
+template <class IDX, bool TH>
+DI u64 tile_busy(const FineT<IDX, TH> &V, u64 e, bool live, u32 &seen)
 {
     const u32 word = V.bmp[live ? (u32)(e >> 32) : V.w_spare];
     seen = live ? word & (u32)e : 0u;
     return ballot(seen != 0);
 }
 
-template <class IDX>
-DI void tile_apply(const FineT<IDX> &V, u64 e, bool live, bool set)
+template <class IDX, bool TH>
+DI void tile_apply(const FineT<IDX, TH> &V, u64 e, bool live, bool set)
 {
     u32 *t = live ? &V.bmp[(u32)(e >> 32)] : &V.idle[lane_id()];
     const u32 m = live ? (u32)e : 0u;
@@ -240,8 +259,8 @@ DI void tile_apply(const FineT<IDX> &V, u64 e, bool live, bool set)
 }
 
 // all chunks of the list at `list` (header word 0 already read: cnt entries)
-template <class IDX>
-DI void list_apply(const FineT<IDX> &V, const u64 *list, u32 cnt, bool set)
+template <class IDX, bool TH>
+DI void list_apply(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, bool set)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
         const u32 k = eb + lane_id();
@@ -252,8 +271,8 @@ DI void list_apply(const FineT<IDX> &V, const u64 *list, u32 cnt, bool set)
 }
 
 // Is any chunk of the list active?  If so *witness receives such a chunk.
-template <class IDX>
-DI bool list_busy(const FineT<IDX> &V, const u64 *list, u32 cnt, u32 &witness)
+template <class IDX, bool TH>
+DI bool list_busy(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, u32 &witness)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
         const u32 k = eb + lane_id();
@@ -271,10 +290,20 @@ DI bool list_busy(const FineT<IDX> &V, const u64 *list, u32 cnt, u32 &witness)
 
 // ---- sBlock table -------------------------------------------------------------------------------
 // the three fields of the records [pos, ns) move one place up / of (idx, ns) one place down
-template <class IDX>
-DI void fine_spool_shift(FineT<IDX> &V, u32 pos, bool up)
+template <class IDX, bool TH>
+DI void fine_spool_shift(FineT<IDX, TH> &V, u32 pos, bool up)
 {
-    if constexpr (sizeof(IDX) == 2) {
+    if constexpr (TH) {
+        static_assert(sizeof(IDX) == 2, "tables in the workspace: 16-bit chunk numbers only");
+        u16 *const g[2] = { (u16 *)V.swit, V.soff };
+        if (up) {
+            gblk_shift_up<2>(g, pos, V.ns);
+            blk_shift_up(V.ssz, pos, V.ns);
+        } else {
+            gblk_shift_down<2>(g, pos, V.ns);
+            blk_shift_down(V.ssz, pos, V.ns);
+        }
+    } else if constexpr (sizeof(IDX) == 2) {
         u16 *const f[3] = { V.ssz, V.swit, V.soff };
         if (up) blk_shift_up<u16, 3>(f, pos, V.ns);
         else blk_shift_down<u16, 3>(f, pos, V.ns);
@@ -291,8 +320,8 @@ DI void fine_spool_shift(FineT<IDX> &V, u32 pos, bool up)
 }
 
 // Stitch (Sec. 3.3.1): the new sBlock enters behind the cached ones of its size
-template <class IDX, class AcctT>
-DI void fine_spool_insert(FineT<IDX> &V, u32 size, u32 place, u32 witness, AcctT &A)
+template <class IDX, bool TH, class AcctT>
+DI void fine_spool_insert(FineT<IDX, TH> &V, u32 size, u32 place, u32 witness, AcctT &A)
 {
     V.sp.refresh(V.ssz, V.ns);
     const u32 pos = V.sp.rank(V.ssz, (IDX)(size - 1));          // sizes >= size come before it
@@ -305,16 +334,16 @@ DI void fine_spool_insert(FineT<IDX> &V, u32 size, u32 place, u32 witness, AcctT
     wave_sync();
 }
 
-template <class IDX>
-DI void fine_spool_remove(FineT<IDX> &V, u32 idx)
+template <class IDX, bool TH>
+DI void fine_spool_remove(FineT<IDX, TH> &V, u32 idx)
 {
     fine_spool_shift(V, idx, false);
     V.ns--;
 }
 
 // the two header words of a new list; its entries follow
-template <class IDX>
-DI void list_head(const FineT<IDX> &V, u32 place, u32 id, u32 cnt, u32 stamp)
+template <class IDX, bool TH>
+DI void list_head(const FineT<IDX, TH> &V, u32 place, u32 id, u32 cnt, u32 stamp)
 {
     u64 *l = V.list_at(place);
     const u32 lane = lane_id() & 1;                             // every lane stores one of the two words
@@ -322,8 +351,8 @@ DI void list_head(const FineT<IDX> &V, u32 place, u32 id, u32 cnt, u32 stamp)
 }
 
 // the list of one run of chunks [start, start + len) at `place`; returns its entries
-template <class IDX>
-DI u32 list_put_run(const FineT<IDX> &V, u32 place, u32 start, u32 len)
+template <class IDX, bool TH>
+DI u32 list_put_run(const FineT<IDX, TH> &V, u32 place, u32 start, u32 len)
 {
     const u32 n = run_words(start, len), w0 = start >> 5;
     u64 *l = V.list_at(place) + 2;
@@ -336,12 +365,13 @@ DI u32 list_put_run(const FineT<IDX> &V, u32 place, u32 start, u32 len)
 
 // Squeeze the lists of released sBlocks out: copy the live lists, in table order, to the other
 // half of the slice, which becomes the arena.  Slots that hold an sBlock learn its new place.
-template <class IDX, class Slots>
-DI void fine_compact(FineT<IDX> &V, Slots &S)
+template <class IDX, bool TH, class Slots>
+DI void fine_compact(FineT<IDX, TH> &V, Slots &S)
 {
     u32 top = 0;
+    V.tables_written();
     for (u32 s = 0; s < V.ns; s++) {
-        const u32 from = ld_uni(V.soff, s);
+        const u32 from = TH ? uni(V.off_at(s)) : ld_uni(V.soff, s);
         const u64 *src = V.list_at(from);
         const u32 cnt = (u32)(uni64(ld_list(src)) >> 32), words = cnt + 2;
         u64 *dst = V.bounce + ((size_t)top << V.gs);
@@ -362,8 +392,8 @@ DI void fine_compact(FineT<IDX> &V, Slots &S)
     V.top = V.live = top;
 }
 
-template <class IDX, class Slots, class AcctT>
-DI bool fine_reserve(FineT<IDX> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
+template <class IDX, bool TH, class Slots, class AcctT>
+DI bool fine_reserve(FineT<IDX, TH> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
 {
     if (UNLIKELY(V.top + need_grans > V.cap_grans && V.live < V.top)) fine_compact(V, S);
     if (UNLIKELY(V.top + need_grans > V.cap_grans)) {
@@ -380,8 +410,8 @@ DI bool fine_reserve(FineT<IDX> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
 // finds the inactive ones (witness first, whole list if the witness is idle), the 64 oldest of
 // them wait in registers (lane v: stamp, table index, granules), the ones that must go are
 // removed from the highest index down.  A call that leaves more than 64 to release goes round again.
-template <class IDX, class AcctT>
-DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
+template <class IDX, bool TH, class AcctT>
+DI bool fine_stitch_free(FineT<IDX, TH> &V, const KParams &P, AcctT &A)
 {
     constexpr u32 E = 16 / sizeof(IDX);                         // witnesses per lane and step
     const u32 lane = lane_id();
@@ -407,7 +437,8 @@ DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
         // four lists in flight at a time.
         auto test_noted = [&]() {
             const bool mine = lane < n_unk;
-            const u32 my_place = V.soff[mine ? u_idx : 0u];
+            V.tables_written();
+            const u32 my_place = V.off_at(mine ? u_idx : 0u);
             const u64 *ml = V.list_at(my_place);
             u64 h[6];
 #pragma unroll
@@ -459,10 +490,25 @@ DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
             n_unk = 0;
             wave_sync();
         };
+        // E witnesses per lane and step: sBlocks base + lane * E + j.  The block of the next step is on its
+        // way while this one is looked at (a step renews witnesses of its own and of earlier blocks only).
+        auto wit_block = [&](u32 base) {
+            const u32 wblk = min(base / E + lane, (V.ns - 1) / E);                  // (lanes past the table: its last block again)
+            if constexpr (TH) return gblk_load((const u16 *)V.swit, wblk);
+            else return ((const Blk16 *)V.swit)[wblk];
+        };
+        V.tables_written();
+        Blk16 wb_next;
+        if constexpr (TH) wb_next = wit_block(0);
         for (u32 base = 0; base < V.ns; base += 64 * E) {
-            // E witnesses per lane: sBlocks base + lane * E + j; all their bitmap words are on their way
-            // before the first is looked at
-            const Blk16 wb = ((const Blk16 *)V.swit)[min(base / E + lane, (V.ns - 1) / E)];    // (lanes past the table: its last block again)
+            // all the bitmap words of a step are on their way before the first is looked at
+            Blk16 wb;
+            if constexpr (TH) {
+                wb = wb_next;
+                if (base + 64 * E < V.ns) wb_next = wit_block(base + 64 * E);
+            } else {
+                wb = wit_block(base);
+            }
             u32 word[E], wit[E];
 #pragma unroll
             for (u32 j = 0; j < E; j++) {
@@ -512,8 +558,8 @@ DI bool fine_stitch_free(FineT<IDX> &V, const KParams &P, AcctT &A)
 // ---- S1 (Algorithm 1, first loop; Sec. 4.1 state S1) on stitched blocks, oldest first ------------
 // Is the sBlock whose list is at `place` active?  One read of the list (header and first 62 entries,
 // returned in e), more only for longer lists.  If active, *witness receives an active chunk.
-template <class IDX>
-DI bool sblock_busy(const FineT<IDX> &V, u32 place, u64 &e, u32 &cnt, u32 &witness)
+template <class IDX, bool TH>
+DI bool sblock_busy(const FineT<IDX, TH> &V, u32 place, u64 &e, u32 &cnt, u32 &witness)
 {
     const u32 lane = lane_id();
     const u64 *list = V.list_at(place);
@@ -531,8 +577,8 @@ DI bool sblock_busy(const FineT<IDX> &V, u32 place, u64 &e, u32 &cnt, u32 &witne
 }
 
 // hand out the (inactive) sBlock whose first list tile is e
-template <class IDX>
-DI void sblock_take(FineT<IDX> &V, u32 place, u64 e, u32 cnt)
+template <class IDX, bool TH>
+DI void sblock_take(FineT<IDX, TH> &V, u32 place, u64 e, u32 cnt)
 {
     const u32 lane = lane_id();
     u64 *list = V.list_at(place);
@@ -544,14 +590,16 @@ DI void sblock_take(FineT<IDX> &V, u32 place, u64 e, u32 cnt)
 // The block of 64 sizes that the rank search reads holds the first sBlock of bsize chunks, if there
 // is one: it doubles as the first tile of candidates.  One lane per candidate reads its witness;
 // the others are tested oldest first (table order) with all lanes over the words of one list.
-template <class IDX>
-DI bool fine_s1_sblock(FineT<IDX> &V, u32 bsize, u32 &ref, u32 &place_out)
+template <class IDX, bool TH>
+DI bool fine_s1_sblock(FineT<IDX, TH> &V, u32 bsize, u32 &ref, u32 &place_out)
 {
     const u32 lane = lane_id();
     u32 base = V.sp.block((IDX)bsize);
     for (;;) {
         const u32 i = base + lane;
-        const u32 sz = V.ssz[i], wit = V.swit[i], so = V.soff[i];   // zero sizes follow the table
+        V.tables_written();
+        const u32 wit = V.wit_at(i), so = V.off_at(i);              // (on their way while the sizes are compared)
+        const u32 sz = V.ssz[i];                                    // zero sizes follow the table
         const u64 vm = ballot(sz == bsize);
         if (!vm) return false;
         const u32 word = V.bmp[wit >> 5];
@@ -576,8 +624,8 @@ DI bool fine_s1_sblock(FineT<IDX> &V, u32 bsize, u32 &ref, u32 &place_out)
 }
 
 // Update (Sec. 3.3.2) of the sBlock whose list is at `place`
-template <class IDX>
-DI void fine_free_sblock(const FineT<IDX> &V, u32 place)
+template <class IDX, bool TH>
+DI void fine_free_sblock(const FineT<IDX, TH> &V, u32 place)
 {
     const u64 *list = V.list_at(place);
     const u32 lane = lane_id();
@@ -589,11 +637,11 @@ DI void fine_free_sblock(const FineT<IDX> &V, u32 place)
 
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of its
 // state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).
-template <class IDX, class Slots, class AcctT>
-DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, u32 reserved_units, const KParams &P,
+template <class IDX, bool TH, class Slots, class AcctT>
+DI void fine_alloc_rest(FineT<IDX, TH> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, u32 reserved_units, const KParams &P,
                         AcctT &A, u32 ev, VmsRes &R)
 {
-    typedef typename FineT<IDX>::pkey_t pkey_t;
+    typedef typename FineT<IDX, TH>::pkey_t pkey_t;
     const u32 lane = lane_id();
     R.kind = KIND_PBLOCK;
     R.held = bsize;
@@ -942,8 +990,8 @@ DI void fine_alloc_rest(FineT<IDX> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, 
 }
 
 // The rare path of the replay loop (see vms_alloc_cold): its scalars wait in the LDS header.
-template <class IDX, class Slots>
-DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u32 bsize, u32 lo_p, u32 hi_p,
+template <class IDX, bool TH, class Slots>
+DI bool fine_alloc_cold(char *lds, FineT<IDX, TH> &V, Slots &S, const KParams &P, u32 bsize, u32 lo_p, u32 hi_p,
                         u32 reserved_units, u32 ev, VmsRes &R)
 {
     u32 *sc = (u32 *)(lds + LDS_SCALARS);
@@ -969,14 +1017,14 @@ DI bool fine_alloc_cold(char *lds, FineT<IDX> &V, Slots &S, const KParams &P, u3
 // The kernel: same event loop, slot table, small-request pool and per-tile accounting as
 // replay_vms_kernel; the pools are the ones above.  IDX: the type of a chunk number.
 // ---------------------------------------------------------------------------
-template <bool SLOT_REGS, class IDX>
+template <bool SLOT_REGS, class IDX, bool TH>
 __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u64 *__restrict__ events,
                                                              const u32 *__restrict__ n_events,
                                                              u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
                                                              char *__restrict__ workspace)
 {
     WAVE_DYNAMIC_LDS(lds);
-    typedef typename FineT<IDX>::pkey_t pkey_t;
+    typedef typename FineT<IDX, TH>::pkey_t pkey_t;
     const u32 lane = lane_id();
     u32 trace = blockIdx.x;
     char *ws_slice = workspace + (size_t)trace * P.ws_stride;
@@ -993,19 +1041,24 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     SlotsT<SLOT_REGS> S;
     S.init(lds, P);
     ((u32 *)(lds + LDS_SCALARS))[lane] = lane == SC_FIRST_OOM || lane == SC_OVF_EVENT ? NONE32 : 0u;     // LDS header
-    FineT<IDX> V;
+    FineT<IDX, TH> V;
     V.pool = (pkey_t *)(lds + P.off_pool);
     V.bmp = (u32 *)(lds + P.off_bmp);
     V.bnd = (u32 *)(lds + P.off_bnd);
     V.tmp = (u32 *)(lds + P.off_tmp);
     V.idle = V.tmp + P.bmp_words;
     V.ssz = (IDX *)(lds + P.off_skey);
-    V.swit = (IDX *)(lds + P.off_swit);
-    V.soff = (u16 *)(lds + P.off_soff);
+    if constexpr (TH) {
+        V.swit = (IDX *)(ws_slice + 2 * P.ws_half);
+        V.soff = (u16 *)(ws_slice + 2 * P.ws_half + P.ws_tbl_bytes);
+    } else {
+        V.swit = (IDX *)(lds + P.off_swit);
+        V.soff = (u16 *)(lds + P.off_soff);
+    }
     V.gs = P.gran_shift;
     V.cap_grans = P.cap_grans;
     V.arena = (u64 *)ws_slice;
-    V.bounce = (u64 *)(ws_slice + P.ws_stride / 2);
+    V.bounce = (u64 *)(ws_slice + P.ws_half);
     V.w_spare = P.bmp_words;
     V.np = V.ns = V.n_chunks = V.np_all = V.top = V.live = V.next_sid = V.clock = 0;
     for (u32 i = lane; i < P.bmp_words + 1; i += 64) V.bmp[i] = V.bnd[i] = 0;
@@ -1017,8 +1070,10 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     for (u32 i = lane; i < P.cap_pblocks + 80; i += 64) V.pool[i] = 0;
     for (u32 i = lane; i < P.cap_sblocks + 80; i += 64) {
         V.ssz[i] = 0;
-        V.swit[i] = 0;
-        V.soff[i] = 0;
+        if constexpr (!TH) {        // (in the workspace nothing reads a place before it was written)
+            V.swit[i] = 0;
+            V.soff[i] = 0;
+        }
     }
     wave_sync();
     st_one(V.bnd, 0u, 1u);                                  // no chunk yet: the end of the last pBlock is chunk 0

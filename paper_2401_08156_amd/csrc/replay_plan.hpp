@@ -26,9 +26,12 @@ struct KParams {
     uint64_t ws_stride;              // workspace bytes per trace
     // fine-grained variant only (see replay_fine.hpp)
     uint32_t off_bnd, off_soff;      // block-start bitmap; list places of the sBlocks
-    uint32_t bmp_words;              // words per bitmap that scans may read (a multiple of 64)
+    uint32_t bmp_words;              // words per bitmap that scans may read (a multiple of 4: they are read 16 bytes at a time)
     uint32_t gran_shift;             // a list starts on a multiple of 2^gran_shift 8-byte words of the arena
     uint32_t cap_grans;              // granules per arena half
+    uint64_t ws_half;                // bytes of one arena half; the second starts there
+    uint32_t ws_tbl_bytes;           // tables in the workspace: bytes of each (witnesses, list places), behind the halves; else 0
+    uint32_t reserved_pad;
     // second pass over the traces whose tables overflowed (see ReplayPlan::retry)
     uint32_t retry;                  // this launch is that pass: traces without an overflow flag are left alone
     uint32_t retry_slots;            // traces it has workspace for
@@ -39,6 +42,7 @@ struct ReplayPlan {
     KParams kp[2];                   // [0] splitting kernel, [1] stitching kernel
     bool fine;                       // stitching kernel: the fine-grained variant (lists in the workspace)
     bool wide;                       // fine-grained variant with 32-bit chunk numbers (more than 65,000 chunks)
+    bool tbl_ws;                     // fine-grained variant: witness and list-place tables in the workspace, not in LDS
     bool slot_regs;                  // slot table in registers (at most 64 slots)
     bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 192)
     size_t ws_bytes;
@@ -84,8 +88,10 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
         k.off_bnd = take(((uint64_t)k.bmp_words + 1) * 4);      // scans read one word ahead
         k.off_tmp = take(((uint64_t)k.bmp_words + 64) * 4);     // and 64 spare words
         k.off_skey = take(((uint64_t)c.max_sblocks + 80) * idx);    // 64 spare places, and shifts move whole 16-byte blocks
-        k.off_swit = take(((uint64_t)c.max_sblocks + 80) * idx);
-        k.off_soff = take(((uint64_t)c.max_sblocks + 80) * 2);
+        if (!p.tbl_ws) {
+            k.off_swit = take(((uint64_t)c.max_sblocks + 80) * idx);
+            k.off_soff = take(((uint64_t)c.max_sblocks + 80) * 2);
+        }
     } else if (policy) {
         // 64 spare places behind each searched array: reads there need no bounds check
         k.off_pool = take(((uint64_t)c.max_pblocks + 64) * 8);
@@ -130,13 +136,15 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
         return VMS_ETOOBIG;
 
     memset(&p, 0, sizeof p);
-    if (c.variant > VMS_VARIANT_FINE) return VMS_EINVAL;
+    if (c.variant > VMS_VARIANT_FINE || c.table_place > VMS_TABLES_WORKSPACE) return VMS_EINVAL;
     // tables beyond what flat sorted LDS arrays serve (lists of more than 64 KB, thousands of blocks)
     // need the fine-grained variant with its lists in the workspace
     const bool big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
     if (big && c.variant == VMS_VARIANT_FLAT) return VMS_ETOOBIG;
     p.fine = big || c.variant == VMS_VARIANT_FINE;
     p.wide = c.max_chunks > 63000;
+    p.tbl_ws = p.fine && !p.wide && c.table_place == VMS_TABLES_WORKSPACE;
+    if (c.table_place == VMS_TABLES_WORKSPACE && p.fine && p.wide) return VMS_EINVAL;
     p.slot_regs = c.max_slots <= 64;
     p.fl_regs = c.max_free_blocks <= 192;
     uint32_t shift = 0;
@@ -166,7 +174,7 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
             // the one over the sBlocks 8064
             k.cap_pblocks = c.max_multi_pblocks ? c.max_multi_pblocks : (c.max_pblocks < 4096 ? c.max_pblocks : 4096);
             if (k.cap_pblocks > 4096 || c.max_sblocks > 8000) return VMS_ETOOBIG;
-            k.bmp_words = (uint32_t)align_up((uint64_t)c.max_chunks / 32 + 1, 64);
+            k.bmp_words = (uint32_t)align_up((uint64_t)c.max_chunks / 32 + 1, 4);
             // The arena holds 8-byte words: per sBlock two header words and at most one word per
             // run, rounded up to whole granules of 2^gran_shift words.  List places are 16-bit
             // granule numbers.
@@ -175,8 +183,11 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
             while ((words >> k.gran_shift) > 65535) k.gran_shift++;
             k.cap_grans = (uint32_t)(words >> k.gran_shift);
             if (k.cap_grans < 4) return VMS_EINVAL;
-            // two halves (the lists, and where compaction copies them), each followed by 64 spare words
-            k.ws_stride = align_up((((uint64_t)k.cap_grans << k.gran_shift) + 64) * 8, 256) * 2;
+            // two halves (the lists, and where compaction copies them), each followed by 64 spare words;
+            // behind them the two 16-bit tables, if they are kept here
+            k.ws_half = align_up((((uint64_t)k.cap_grans << k.gran_shift) + 64) * 8, 256);
+            k.ws_tbl_bytes = p.tbl_ws ? (uint32_t)align_up(((uint64_t)c.max_sblocks + 80) * 2, 256) : 0u;
+            k.ws_stride = 2 * k.ws_half + 2 * (uint64_t)k.ws_tbl_bytes;
         } else if (pol) {
             k.ws_stride = align_up(((uint64_t)c.max_runs + 64) * 4, 256);     // where compaction copies the lists
         }
@@ -187,25 +198,48 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
     return VMS_OK;
 }
 
+// Wavefronts of the stitching kernel that share a compute unit: LDS is handed out in granules of
+// 1,280 bytes, 128 of them per compute unit (measured: 31,680 B per wavefront gives five wavefronts
+// per compute unit, 32,576 B four).
+inline uint32_t plan_waves_per_cu(const ReplayPlan &x)
+{
+    const uint64_t granules = ((uint64_t)x.kp[1].lds_bytes + 1279) / 1280;
+    const uint64_t w = granules ? plan_detail::LDS_PER_CU / 1280 / granules : 32;
+    return (uint32_t)(w < 32 ? w : 32);                     // a compute unit holds 32 wavefronts at most
+}
+
 // The plan for cfg.  With variant 0 the library chooses: a trace replays about twice as fast on the
 // flat variant (its lists are in LDS), but when the batch does not fit the compute units at once and
 // the fine-grained variant holds at least 2.5 times as many traces per compute unit, the latter
-// finishes the batch sooner.
+// finishes the batch sooner.  With table_place 0 it chooses where the fine-grained variant keeps the
+// witnesses and list places of the sBlocks: throughput grows almost in proportion to the wavefronts
+// per compute unit (measured from 4 to 9), a wavefront with these tables in the workspace is about a
+// fifth slower, so the workspace it is when the LDS layout leaves fewer than two wavefronts per SIMD,
+// the workspace lets a quarter more in, and the batch has traces for them.
 inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
 {
     int rc = replay_plan_for(cfg, p);
-    if (rc != VMS_OK || !cfg || cfg->variant != VMS_VARIANT_AUTO || p.fine || !(cfg->policy_mask & VMS_POLICY_VMS)) return rc;
-    vms_config alt = *cfg;
-    alt.variant = VMS_VARIANT_FINE;
-    ReplayPlan q;
-    if (replay_plan_for(&alt, q) != VMS_OK) return rc;
-    const uint32_t CUS = 256, SIMD_WAVES = 32;              // compute units; wavefronts a compute unit can hold
-    auto per_cu = [&](const ReplayPlan &x) {
-        const uint64_t w = plan_detail::LDS_PER_CU / (x.kp[1].lds_bytes ? x.kp[1].lds_bytes : 1);
-        return (uint32_t)(w < SIMD_WAVES ? w : SIMD_WAVES);
-    };
-    const uint32_t flat = per_cu(p), fine = per_cu(q);
-    if ((uint64_t)cfg->n_traces > (uint64_t)CUS * flat && 2 * fine >= 5 * flat) p = q;
+    if (rc != VMS_OK || !cfg || !(cfg->policy_mask & VMS_POLICY_VMS)) return rc;
+    const uint32_t CUS = 256;
+    if (cfg->variant == VMS_VARIANT_AUTO && !p.fine) {
+        vms_config alt = *cfg;
+        alt.variant = VMS_VARIANT_FINE;
+        ReplayPlan q;
+        if (replay_plan_for(&alt, q) == VMS_OK) {
+            const uint32_t flat = plan_waves_per_cu(p), fine = plan_waves_per_cu(q);
+            if ((uint64_t)cfg->n_traces > (uint64_t)CUS * flat && 2 * fine >= 5 * flat) p = q;
+        }
+    }
+    if (p.fine && !p.wide && cfg->table_place == VMS_TABLES_AUTO) {
+        vms_config alt = *cfg;
+        alt.variant = VMS_VARIANT_FINE;
+        alt.table_place = VMS_TABLES_WORKSPACE;
+        ReplayPlan q;
+        if (replay_plan_for(&alt, q) == VMS_OK) {
+            const uint32_t lds = plan_waves_per_cu(p), ws = plan_waves_per_cu(q);
+            if ((uint64_t)cfg->n_traces > (uint64_t)CUS * lds && 4 * ws >= 5 * lds && lds < 8) p = q;
+        }
+    }
     return VMS_OK;
 }
 

@@ -122,12 +122,13 @@ typedef void (*vms_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats
 typedef void (*split_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_stats *);
 
 // the kernel variants: flat sorted tables in LDS or the fine-grained layout (16- or 32-bit chunk
-// numbers), slot table in LDS or registers
+// numbers; witness and list-place tables in LDS or in the workspace), slot table in LDS or registers
 vms_fn pick_vms(const ReplayPlan &p)
 {
     if (p.fine) {
-        if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32> : replay_vms_fine_kernel<false, u32>;
-        return p.slot_regs ? replay_vms_fine_kernel<true, u16> : replay_vms_fine_kernel<false, u16>;
+        if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32, false> : replay_vms_fine_kernel<false, u32, false>;
+        if (p.tbl_ws) return p.slot_regs ? replay_vms_fine_kernel<true, u16, true> : replay_vms_fine_kernel<false, u16, true>;
+        return p.slot_regs ? replay_vms_fine_kernel<true, u16, false> : replay_vms_fine_kernel<false, u16, false>;
     }
     return p.slot_regs ? replay_vms_kernel<true> : replay_vms_kernel<false>;
 }

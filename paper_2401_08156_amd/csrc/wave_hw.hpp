@@ -35,6 +35,8 @@ DI void wave_lockstep() {}
 // a 64-bit word of a list in global memory: read at device scope, past the compute unit's
 // vector cache (lists are written and read by the same wavefront, and read once)
 DI u64 ld_list(const u64 *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+// the same for one 16-bit element of a table kept in global memory
+DI u32 ld_tab(const uint16_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // c - 1, or 0 for 0, on a wave-uniform count: two scalar instructions (the conditional form is
 // compiled into a clamped vector subtract and a v_readfirstlane)

@@ -385,4 +385,101 @@ DI void blk_shift_down(T *a, u32 pos, u32 n)
     blk_shift_down<T, 1>(one, pos, n);
 }
 
+// The same moves for N arrays of 16-bit elements kept in GLOBAL memory (tables of the fine-grained
+// stitching kernel that do not fit the LDS budget).  Blocks are read with device-scope loads (other
+// lanes of this wavefront wrote them; tbl_fence() first, so that their stores have arrived), G steps of
+// 64 blocks are on their way before the first store.  A step never reads a block that an earlier step
+// of the same call has written.
+DI void tbl_fence() { __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup"); }
+DI Blk16 gblk_load(const uint16_t *a, u32 B)
+{
+    const u64 *p = (const u64 *)a + 2 * (size_t)B;
+    const u64 lo = ld_list(p), hi = ld_list(p + 1);
+    return Blk16{ { (u32)lo, (u32)(lo >> 32), (u32)hi, (u32)(hi >> 32) } };
+}
+DI void gblk_store(uint16_t *a, u32 B, const Blk16 &v)
+{
+    u64 *p = (u64 *)a + 2 * (size_t)B;
+    p[0] = v.w[0] | ((u64)v.w[1] << 32);
+    p[1] = v.w[2] | ((u64)v.w[3] << 32);
+}
+
+template <int N>
+DI void gblk_shift_up(uint16_t *const (&a)[N], u32 pos, u32 n)
+{
+    constexpr u32 E = 8, G = 4;
+    const u32 bf = (pos + 1) / E, bl = n / E;       // first and last block that receive an element
+    tbl_fence();
+    for (u32 hi = bl + 1; hi > bf;) {
+        Blk16 old[G][N];
+        u32 prev[G][N], B[G];
+        bool mine[G];
+        u32 h = hi;
+#pragma unroll
+        for (u32 g = 0; g < G; g++) {
+            const u32 lo = h - bf > 64 ? h - 64 : bf;
+            B[g] = lo + lane_id();
+            mine[g] = B[g] < h;                     // (a group past the first block: h == lo == bf, no lane takes part)
+#pragma unroll
+            for (int f = 0; f < N; f++) {
+                old[g][f] = gblk_load(a[f], mine[g] ? B[g] : bf);
+                prev[g][f] = ld_tab(a[f] + (size_t)(mine[g] && B[g] ? B[g] : 1u) * E - 1);    // last element of the block below
+            }
+            h = lo;
+        }
+        wave_lockstep();
+#pragma unroll
+        for (u32 g = 0; g < G; g++)
+#pragma unroll
+            for (int f = 0; f < N; f++) {
+                Blk16 mv;
+                mv.w[0] = (old[g][f].w[0] << 16) | prev[g][f];
+#pragma unroll
+                for (u32 k = 1; k < 4; k++) mv.w[k] = (old[g][f].w[k] << 16) | (old[g][f].w[k - 1] >> 16);
+                const Blk16 out = blk_select<uint16_t>(old[g][f], mv, B[g] * E, pos + 1);
+                if (mine[g]) gblk_store(a[f], B[g], out);
+            }
+        wave_lockstep();
+        hi = h;
+    }
+    wave_sync();
+}
+
+template <int N>
+DI void gblk_shift_down(uint16_t *const (&a)[N], u32 pos, u32 n)
+{
+    constexpr u32 E = 8, G = 4;
+    const u32 bf = pos / E, bl = (n - 1) / E;
+    tbl_fence();
+    for (u32 lo = bf; lo <= bl; lo += 64 * G) {
+        Blk16 old[G][N];
+        u32 next[G][N], B[G];
+        bool mine[G];
+#pragma unroll
+        for (u32 g = 0; g < G; g++) {
+            B[g] = lo + 64 * g + lane_id();
+            mine[g] = B[g] <= bl;
+#pragma unroll
+            for (int f = 0; f < N; f++) {
+                old[g][f] = gblk_load(a[f], mine[g] ? B[g] : bl);
+                next[g][f] = ld_tab(a[f] + (size_t)(mine[g] ? B[g] : bl) * E + E);            // first element of the block above
+            }
+        }
+        wave_lockstep();
+#pragma unroll
+        for (u32 g = 0; g < G; g++)
+#pragma unroll
+            for (int f = 0; f < N; f++) {
+                Blk16 mv;
+#pragma unroll
+                for (u32 k = 0; k < 3; k++) mv.w[k] = (old[g][f].w[k] >> 16) | (old[g][f].w[k + 1] << 16);
+                mv.w[3] = (old[g][f].w[3] >> 16) | (next[g][f] << 16);
+                const Blk16 out = blk_select<uint16_t>(old[g][f], mv, B[g] * E, pos);
+                if (mine[g]) gblk_store(a[f], B[g], out);
+            }
+        wave_lockstep();
+    }
+    wave_sync();
+}
+
 #endif

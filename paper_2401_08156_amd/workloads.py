@@ -18,7 +18,9 @@ TABLES = {
     2: dict(max_free_blocks=192, max_pblocks=544, max_sblocks=576, max_runs=3840, max_chunks=4096),
     # offloading grinds pBlocks down to single chunks: thousands of pBlocks and sBlocks (the fine-grained kernel
     # variant: single chunks in bitmaps, a table for the pBlocks of two or more chunks, lists in the workspace)
-    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2816, max_sblocks=2560, max_runs=1 << 18, max_chunks=10240),
+    # (31,680 B of LDS per wavefront: LDS is handed out in 1,280-byte granules, 128 per compute unit, so five
+    # wavefronts per compute unit need at most 32,000 B each; with 2,816 places for multi-chunk pBlocks it was four)
+    3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2592, max_sblocks=2560, max_runs=1 << 18, max_chunks=10240),
     4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576),
     6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
 }

@@ -66,6 +66,7 @@ DI void wave_lockstep() { emu::coll_of[emu::cur]++; emu::switch_lane(); }
 #define __builtin_amdgcn_fence(order, scope) wave_sync()
 
 DI u64 ld_list(const u64 *p) { return *p; }
+DI u32 ld_tab(const uint16_t *p) { return *p; }
 DI u32 dec_sat(u32 c) { return c - min(c, 1u); }
 
 DI u64 ballot(bool p)

@@ -298,6 +298,39 @@ def test_kernel_variant_choice():
     gpu_util.assert_parity(ev, cfg, label="fine-grained variant, 32-bit chunk numbers")
 
 
+def test_sblock_tables_in_the_workspace():
+    # the fine-grained kernel with the witnesses and list places of its sBlocks in the workspace instead
+    # of LDS: offloading traces with thousands of sBlocks, low thresholds (many releases: the tables move
+    # all the time), a tiny arena (compaction rewrites the list places), a slot table in LDS, ragged traces
+    W = dict(variant=binding.VMS_VARIANT_FINE, table_place=binding.VMS_TABLES_WORKSPACE)
+    ev, ms = tg.generate(3, n_traces=12, n_events=8000)
+    big = dict(max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=16384)
+    lds = []
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
+        r = binding.Replay(gpu_util.make_cfg(12, 8000, ms, variant=binding.VMS_VARIANT_FINE, table_place=place, **big))
+        lds.append(r.lds_bytes()[1])
+        r.close()
+    assert lds[0] - lds[1] == 2 * (2048 + 80) * 2
+    gpu_util.assert_parity(ev, gpu_util.make_cfg(12, 8000, ms, **dict(W, **big)), label="config 3 slice, tables in the workspace")
+    for seed, threshold in ((5, 128), (6, 32)):
+        ev, ms = tg.generate(3, n_traces=8, n_events=8000, seed=seed)
+        cfg = gpu_util.make_cfg(8, 8000, ms, max_free_blocks=64, max_pblocks=8192, max_sblocks=4352, max_runs=1 << 18,
+                                max_chunks=16384, spool_threshold=threshold, **W)
+        gpu_util.assert_parity(ev, cfg, label="largest tables in the workspace, threshold %d" % threshold)
+    ev, ms = tg.generate(2, n_traces=16, n_events=5000)
+    gpu_util.assert_parity(ev, gpu_util.make_cfg(16, 5000, ms, max_runs=600, spool_threshold=40, max_sblocks=128, **W),
+                           label="tables in the workspace, small arena")
+    ev, ms = tg.generate(4, n_traces=6, n_events=4000)
+    gpu_util.assert_parity(ev, gpu_util.make_cfg(6, 4000, ms, max_runs=20000, max_chunks=32768, **W),
+                           label="tables in the workspace, slot table in LDS")
+    ev, ms = tg.generate(1, n_traces=5, n_events=900, seed=44)
+    gpu_util.assert_parity(ev, gpu_util.make_cfg(5, 900, ms, **W), n_events=np.array([0, 1, 63, 500, 900], dtype=np.uint32),
+                           label="tables in the workspace, ragged")
+    # 32-bit chunk numbers keep their tables in LDS: asking for the workspace is refused
+    with pytest.raises(binding.VmsError):
+        binding.Replay(gpu_util.make_cfg(5, 900, ms, max_chunks=70000, **W))
+
+
 def test_second_pass_replays_traces_that_outgrow_the_tables():
     # 40 transformer traces, three of them replaced by random traces whose many requests below one
     # chunk outgrow the table of the stitching policy's small-request pool: without a second pass those

@@ -48,8 +48,9 @@ def test_worked_examples_fine_grained_variant():
         fx = load_fixture(path)
         ev = fx["events"][None, :]
         kw = dict(spool_threshold=int(fx["spool_threshold"])) if "spool_threshold" in fx else {}
-        cfg = gpu_util.make_cfg(1, ev.shape[1], 16, variant=binding.VMS_VARIANT_FINE, policy_mask=2, **kw)
-        check(ev, cfg, label=os.path.basename(path))
+        for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
+            cfg = gpu_util.make_cfg(1, ev.shape[1], 16, variant=binding.VMS_VARIANT_FINE, table_place=place, policy_mask=2, **kw)
+            check(ev, cfg, label=os.path.basename(path))
 
 
 def test_splitting_kernels():
@@ -72,9 +73,13 @@ def test_splitting_kernels():
     (1, 2, 1200, dict(variant=2, capacity_bytes=256 * MiB)),
 ])
 def test_fine_grained_variant(kind, nt, ne, tables):
+    # the witness and list-place tables of the sBlocks in LDS, then in the workspace (16-bit chunk numbers only)
     ev, ms = tg.generate(kind, n_traces=nt, n_events=ne, seed=7 + kind)
-    cfg = gpu_util.make_cfg(nt, ne, ms, policy_mask=2, **tables)
-    check(ev, cfg, label="generator %d %s" % (kind, tables))
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
+        if place == binding.VMS_TABLES_WORKSPACE and tables.get("max_chunks", 0) > 63000:
+            continue
+        cfg = gpu_util.make_cfg(nt, ne, ms, policy_mask=2, **dict(dict(variant=2), table_place=place, **tables))
+        check(ev, cfg, label="generator %d %s tables %d" % (kind, tables, place))
 
 
 def test_ragged_traces_and_nothing_written_past_the_end():
