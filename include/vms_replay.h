@@ -72,7 +72,8 @@ extern "C" {
 
 #define VMS_TABLES_AUTO      0u
 #define VMS_TABLES_LDS       1u
-#define VMS_TABLES_WORKSPACE 2u
+#define VMS_TABLES_WORKSPACE 2u       /* witnesses and list places */
+#define VMS_TABLES_WORKSPACE_ALL 3u   /* and the sizes */
 
 #define VMS_POLICY_SPLIT 1u
 #define VMS_POLICY_VMS   2u
@@ -133,13 +134,13 @@ typedef struct vms_config {
                                     unit's LDS goes) share out the flagged traces and replay
                                     each of them from its first event; it needs workspace
                                     for retry_traces traces of that size                     */
-    uint32_t table_place;        /* fine-grained variant: where the witness and list-place
-                                    tables of the sBlocks live.  VMS_TABLES_LDS, or
-                                    VMS_TABLES_WORKSPACE (4 bytes per sBlock less LDS: more
-                                    wavefronts per compute unit, each a little slower; at
-                                    most 63000 chunks), or 0: the library takes the
-                                    workspace when that lets a quarter more wavefronts
-                                    share a compute unit and the batch needs them            */
+    uint32_t table_place;        /* fine-grained variant: where the tables of the sBlocks
+                                    live.  VMS_TABLES_LDS; VMS_TABLES_WORKSPACE (witnesses
+                                    and list places in the workspace: 4 bytes of LDS less
+                                    per sBlock) or VMS_TABLES_WORKSPACE_ALL (sizes too: 6
+                                    bytes less): more wavefronts per compute unit, each of
+                                    them slower; at most 63000 chunks.  0: the library
+                                    chooses by the rounds of wavefronts the batch takes      */
 } vms_config;
 
 typedef struct vms_trace_stats {        /* one per (policy, trace) */

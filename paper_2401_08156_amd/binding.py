@@ -14,7 +14,7 @@ from . import build as _build
 VMS_OK = 0
 VMS_POLICY_SPLIT, VMS_POLICY_VMS = 1, 2
 VMS_VARIANT_AUTO, VMS_VARIANT_FLAT, VMS_VARIANT_FINE = 0, 1, 2
-VMS_TABLES_AUTO, VMS_TABLES_LDS, VMS_TABLES_WORKSPACE = 0, 1, 2
+VMS_TABLES_AUTO, VMS_TABLES_LDS, VMS_TABLES_WORKSPACE, VMS_TABLES_WORKSPACE_ALL = 0, 1, 2, 3
 VMS_ST_INVALID_EVENT, VMS_ST_TABLE_OVERFLOW = 1, 2
 VMS_ST_OVF_FREE_BLOCKS, VMS_ST_OVF_PBLOCKS, VMS_ST_OVF_SBLOCKS, VMS_ST_OVF_RUNS, VMS_ST_OVF_CHUNKS = 4, 8, 16, 32, 64
 

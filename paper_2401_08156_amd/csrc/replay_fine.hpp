@@ -38,7 +38,7 @@
 
 typedef uint16_t u16;
 
-template <class IDX, bool TH>
+template <class IDX, int TH>
 struct FineT {
     typedef typename std::conditional<sizeof(IDX) == 2, u32, u64>::type pkey_t;
     static constexpr u32 W = sizeof(IDX) * 8;
@@ -59,12 +59,18 @@ struct FineT {
     static DI u32 ksize(pkey_t k) { return (u32)(k >> W); }
     static DI u32 kstart(pkey_t k) { return (u32)(IDX) ~(IDX)k; }
     DI u64 *list_at(u32 place) const { return arena + ((size_t)place << gs); }
-    // swit[] / soff[] live in LDS, or (TH) in the trace's workspace slice: then they are read with
-    // device-scope loads and moved by gblk_shift_*; IDX is 16 bits wide there
+    // TH 0: ssz[] / swit[] / soff[] live in LDS.  TH 2: swit[] and soff[], TH 3: all three live in the
+    // trace's workspace slice: then they are read with device-scope loads and moved by gblk_shift_*;
+    // IDX is 16 bits wide there
     // before the first read of these tables after they were written (the stores must have arrived)
     DI void tables_written() const
     {
         if constexpr (TH) tbl_fence();
+    }
+    DI u32 sz_at(u32 i) const
+    {
+        if constexpr (TH == 3) return ld_tab((const u16 *)ssz + i);
+        else return ssz[i];
     }
     DI u32 wit_at(u32 i) const
     {
@@ -88,7 +94,7 @@ DI K from_lane_k(K v, u32 l)
 
 // ---- single-chunk pBlocks --------------------------------------------------------------------
 // the chunks of bitmap word w that are inactive pBlocks of one chunk (one lane per word)
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI u32 singles_free(const FineT<IDX, TH> &V, u32 w)
 {
     const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
@@ -97,7 +103,7 @@ DI u32 singles_free(const FineT<IDX, TH> &V, u32 w)
 
 // the chunks of bitmap word w that belong to inactive pBlocks of two or more chunks: the inactive
 // chunks that exist and are not single-chunk pBlocks (an inactive pBlock has none of its bits set)
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI u32 multi_free(const FineT<IDX, TH> &V, u32 w)
 {
     const u32 b = V.bnd[w], bn = V.bnd[w + 1], a = V.bmp[w];
@@ -113,7 +119,7 @@ struct Quad {
     u32 single[4], multi[4], start[4];
 };
 
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI Quad quad_load(const FineT<IDX, TH> &V, u32 q)
 {
     const Blk16 b = ((const Blk16 *)V.bnd)[q], a = ((const Blk16 *)V.bmp)[q];
@@ -141,7 +147,7 @@ DI u32 word_mask_or0(u32 w, u32 start, u32 end)
 }
 
 // S1 for a request of one chunk: the first inactive pBlock of one chunk
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI bool s1_single(const FineT<IDX, TH> &V, u32 &start)
 {
     for (u32 wb = 0; wb * 32 < V.n_chunks; wb += 64) {
@@ -161,7 +167,7 @@ DI bool s1_single(const FineT<IDX, TH> &V, u32 &start)
 // ---- pool[] of multi-chunk pBlocks --------------------------------------------------------------
 // (4-byte keys move sixteen bytes per lane and step; the 8-byte keys of the variant with 32-bit chunk
 // numbers one key per lane)
-template <class IDX, bool TH, class AcctT>
+template <class IDX, int TH, class AcctT>
 DI void fine_pool_insert(FineT<IDX, TH> &V, u32 size, u32 start, AcctT &A)
 {
     const auto k = V.key(size, start);
@@ -174,7 +180,7 @@ DI void fine_pool_insert(FineT<IDX, TH> &V, u32 size, u32 start, AcctT &A)
     wave_sync();
 }
 
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void fine_pool_remove(FineT<IDX, TH> &V, u32 idx)
 {
     if constexpr (sizeof(IDX) == 2) {
@@ -190,7 +196,7 @@ DI void fine_pool_remove(FineT<IDX, TH> &V, u32 idx)
 
 // Split (Sec. 3.3.1): the pBlock at pool[idx] = [start, start + size) becomes [start, start + keep)
 // and the rest.  A piece of one chunk leaves the array: its boundary bits say all there is to say.
-template <class IDX, bool TH, class AcctT>
+template <class IDX, int TH, class AcctT>
 DI void fine_cut(FineT<IDX, TH> &V, u32 idx, u32 start, u32 size, u32 keep, AcctT &A)
 {
     fine_pool_remove(V, idx);
@@ -205,7 +211,7 @@ DI void fine_cut(FineT<IDX, TH> &V, u32 idx, u32 start, u32 size, u32 keep, Acct
 }
 
 // Alloc (Sec. 3.3.1): `len` new chunks behind the last one
-template <class IDX, bool TH, class AcctT>
+template <class IDX, int TH, class AcctT>
 DI u32 fine_grow(FineT<IDX, TH> &V, u32 len, AcctT &A)
 {
     const u32 start = V.n_chunks, end = start + len;
@@ -220,7 +226,7 @@ DI u32 fine_grow(FineT<IDX, TH> &V, u32 len, AcctT &A)
 
 // S1, primitive blocks of two or more chunks: the first inactive one among pool[lo_p, hi_p), the
 // pBlocks of exactly the requested number of chunks
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI bool fine_s1_pblock(const FineT<IDX, TH> &V, u32 lo_p, u32 hi_p, u32 &start)
 {
     const u32 lane = lane_id();
@@ -241,7 +247,7 @@ DI bool fine_s1_pblock(const FineT<IDX, TH> &V, u32 lo_p, u32 hi_p, u32 &start)
 // ---- lists ------------------------------------------------------------------------------------
 // One tile of list words (e, if live): their chunks are tested, set or cleared, one bitmap word per
 // lane.  Set and clear are LDS atomics without a result; idle lanes aim at a spare word of their own.
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI u64 tile_busy(const FineT<IDX, TH> &V, u64 e, bool live, u32 &seen)
 {
     const u32 word = V.bmp[live ? (u32)(e >> 32) : V.w_spare];
@@ -249,7 +255,7 @@ DI u64 tile_busy(const FineT<IDX, TH> &V, u64 e, bool live, u32 &seen)
     return ballot(seen != 0);
 }
 
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void tile_apply(const FineT<IDX, TH> &V, u64 e, bool live, bool set)
 {
     u32 *t = live ? &V.bmp[(u32)(e >> 32)] : &V.idle[lane_id()];
@@ -259,7 +265,7 @@ DI void tile_apply(const FineT<IDX, TH> &V, u64 e, bool live, bool set)
 }
 
 // all chunks of the list at `list` (header word 0 already read: cnt entries)
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void list_apply(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, bool set)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
@@ -271,7 +277,7 @@ DI void list_apply(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, bool set)
 }
 
 // Is any chunk of the list active?  If so *witness receives such a chunk.
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI bool list_busy(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, u32 &witness)
 {
     for (u32 eb = 0; eb < cnt; eb += 64) {
@@ -290,18 +296,24 @@ DI bool list_busy(const FineT<IDX, TH> &V, const u64 *list, u32 cnt, u32 &witnes
 
 // ---- sBlock table -------------------------------------------------------------------------------
 // the three fields of the records [pos, ns) move one place up / of (idx, ns) one place down
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void fine_spool_shift(FineT<IDX, TH> &V, u32 pos, bool up)
 {
     if constexpr (TH) {
         static_assert(sizeof(IDX) == 2, "tables in the workspace: 16-bit chunk numbers only");
-        u16 *const g[2] = { (u16 *)V.swit, V.soff };
-        if (up) {
-            gblk_shift_up<2>(g, pos, V.ns);
-            blk_shift_up(V.ssz, pos, V.ns);
+        if constexpr (TH == 3) {
+            u16 *const g[3] = { (u16 *)V.ssz, (u16 *)V.swit, V.soff };
+            if (up) gblk_shift_up<3>(g, pos, V.ns);
+            else gblk_shift_down<3>(g, pos, V.ns);
         } else {
-            gblk_shift_down<2>(g, pos, V.ns);
-            blk_shift_down(V.ssz, pos, V.ns);
+            u16 *const g[2] = { (u16 *)V.swit, V.soff };
+            if (up) {
+                gblk_shift_up<2>(g, pos, V.ns);
+                blk_shift_up(V.ssz, pos, V.ns);
+            } else {
+                gblk_shift_down<2>(g, pos, V.ns);
+                blk_shift_down(V.ssz, pos, V.ns);
+            }
         }
     } else if constexpr (sizeof(IDX) == 2) {
         u16 *const f[3] = { V.ssz, V.swit, V.soff };
@@ -320,11 +332,12 @@ DI void fine_spool_shift(FineT<IDX, TH> &V, u32 pos, bool up)
 }
 
 // Stitch (Sec. 3.3.1): the new sBlock enters behind the cached ones of its size
-template <class IDX, bool TH, class AcctT>
+template <class IDX, int TH, class AcctT>
 DI void fine_spool_insert(FineT<IDX, TH> &V, u32 size, u32 place, u32 witness, AcctT &A)
 {
-    V.sp.refresh(V.ssz, V.ns);
-    const u32 pos = V.sp.rank(V.ssz, (IDX)(size - 1));          // sizes >= size come before it
+    V.tables_written();
+    V.sp.template refresh<TH == 3>(V.ssz, V.ns);
+    const u32 pos = V.sp.template rank<TH == 3>(V.ssz, (IDX)(size - 1));    // sizes >= size come before it
     fine_spool_shift(V, pos, true);
     st_one(V.ssz, pos, (IDX)size);
     st_one(V.swit, pos, (IDX)witness);
@@ -334,7 +347,7 @@ DI void fine_spool_insert(FineT<IDX, TH> &V, u32 size, u32 place, u32 witness, A
     wave_sync();
 }
 
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void fine_spool_remove(FineT<IDX, TH> &V, u32 idx)
 {
     fine_spool_shift(V, idx, false);
@@ -342,7 +355,7 @@ DI void fine_spool_remove(FineT<IDX, TH> &V, u32 idx)
 }
 
 // the two header words of a new list; its entries follow
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void list_head(const FineT<IDX, TH> &V, u32 place, u32 id, u32 cnt, u32 stamp)
 {
     u64 *l = V.list_at(place);
@@ -351,7 +364,7 @@ DI void list_head(const FineT<IDX, TH> &V, u32 place, u32 id, u32 cnt, u32 stamp
 }
 
 // the list of one run of chunks [start, start + len) at `place`; returns its entries
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI u32 list_put_run(const FineT<IDX, TH> &V, u32 place, u32 start, u32 len)
 {
     const u32 n = run_words(start, len), w0 = start >> 5;
@@ -365,7 +378,7 @@ DI u32 list_put_run(const FineT<IDX, TH> &V, u32 place, u32 start, u32 len)
 
 // Squeeze the lists of released sBlocks out: copy the live lists, in table order, to the other
 // half of the slice, which becomes the arena.  Slots that hold an sBlock learn its new place.
-template <class IDX, bool TH, class Slots>
+template <class IDX, int TH, class Slots>
 DI void fine_compact(FineT<IDX, TH> &V, Slots &S)
 {
     u32 top = 0;
@@ -392,7 +405,7 @@ DI void fine_compact(FineT<IDX, TH> &V, Slots &S)
     V.top = V.live = top;
 }
 
-template <class IDX, bool TH, class Slots, class AcctT>
+template <class IDX, int TH, class Slots, class AcctT>
 DI bool fine_reserve(FineT<IDX, TH> &V, Slots &S, u32 need_grans, AcctT &A, u32 ev)
 {
     if (UNLIKELY(V.top + need_grans > V.cap_grans && V.live < V.top)) fine_compact(V, S);
@@ -410,7 +423,7 @@ DI bool fine_reserve(FineT<IDX, TH> &V, Slots &S, u32 need_grans, AcctT &A, u32 
 // finds the inactive ones (witness first, whole list if the witness is idle), the 64 oldest of
 // them wait in registers (lane v: stamp, table index, granules), the ones that must go are
 // removed from the highest index down.  A call that leaves more than 64 to release goes round again.
-template <class IDX, bool TH, class AcctT>
+template <class IDX, int TH, class AcctT>
 DI bool fine_stitch_free(FineT<IDX, TH> &V, const KParams &P, AcctT &A)
 {
     constexpr u32 E = 16 / sizeof(IDX);                         // witnesses per lane and step
@@ -558,7 +571,7 @@ DI bool fine_stitch_free(FineT<IDX, TH> &V, const KParams &P, AcctT &A)
 // ---- S1 (Algorithm 1, first loop; Sec. 4.1 state S1) on stitched blocks, oldest first ------------
 // Is the sBlock whose list is at `place` active?  One read of the list (header and first 62 entries,
 // returned in e), more only for longer lists.  If active, *witness receives an active chunk.
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI bool sblock_busy(const FineT<IDX, TH> &V, u32 place, u64 &e, u32 &cnt, u32 &witness)
 {
     const u32 lane = lane_id();
@@ -577,7 +590,7 @@ DI bool sblock_busy(const FineT<IDX, TH> &V, u32 place, u64 &e, u32 &cnt, u32 &w
 }
 
 // hand out the (inactive) sBlock whose first list tile is e
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void sblock_take(FineT<IDX, TH> &V, u32 place, u64 e, u32 cnt)
 {
     const u32 lane = lane_id();
@@ -590,7 +603,7 @@ DI void sblock_take(FineT<IDX, TH> &V, u32 place, u64 e, u32 cnt)
 // The block of 64 sizes that the rank search reads holds the first sBlock of bsize chunks, if there
 // is one: it doubles as the first tile of candidates.  One lane per candidate reads its witness;
 // the others are tested oldest first (table order) with all lanes over the words of one list.
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI bool fine_s1_sblock(FineT<IDX, TH> &V, u32 bsize, u32 &ref, u32 &place_out)
 {
     const u32 lane = lane_id();
@@ -599,7 +612,7 @@ DI bool fine_s1_sblock(FineT<IDX, TH> &V, u32 bsize, u32 &ref, u32 &place_out)
         const u32 i = base + lane;
         V.tables_written();
         const u32 wit = V.wit_at(i), so = V.off_at(i);              // (on their way while the sizes are compared)
-        const u32 sz = V.ssz[i];                                    // zero sizes follow the table
+        const u32 sz = V.sz_at(i);                                  // zero sizes follow the table
         const u64 vm = ballot(sz == bsize);
         if (!vm) return false;
         const u32 word = V.bmp[wit >> 5];
@@ -624,7 +637,7 @@ DI bool fine_s1_sblock(FineT<IDX, TH> &V, u32 bsize, u32 &ref, u32 &place_out)
 }
 
 // Update (Sec. 3.3.2) of the sBlock whose list is at `place`
-template <class IDX, bool TH>
+template <class IDX, int TH>
 DI void fine_free_sblock(const FineT<IDX, TH> &V, u32 place)
 {
     const u64 *list = V.list_at(place);
@@ -637,7 +650,7 @@ DI void fine_free_sblock(const FineT<IDX, TH> &V, u32 place)
 
 // No block of exactly bsize chunks is free: BestFit's second loop and the post-processing of its
 // state (Algorithm 1; Sec. 4.1, Fig. 9, states S2 to S5).
-template <class IDX, bool TH, class Slots, class AcctT>
+template <class IDX, int TH, class Slots, class AcctT>
 DI void fine_alloc_rest(FineT<IDX, TH> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi_p, u32 reserved_units, const KParams &P,
                         AcctT &A, u32 ev, VmsRes &R)
 {
@@ -990,7 +1003,7 @@ DI void fine_alloc_rest(FineT<IDX, TH> &V, Slots &S, u32 bsize, u32 lo_p, u32 hi
 }
 
 // The rare path of the replay loop (see vms_alloc_cold): its scalars wait in the LDS header.
-template <class IDX, bool TH, class Slots>
+template <class IDX, int TH, class Slots>
 DI bool fine_alloc_cold(char *lds, FineT<IDX, TH> &V, Slots &S, const KParams &P, u32 bsize, u32 lo_p, u32 hi_p,
                         u32 reserved_units, u32 ev, VmsRes &R)
 {
@@ -1017,7 +1030,7 @@ DI bool fine_alloc_cold(char *lds, FineT<IDX, TH> &V, Slots &S, const KParams &P
 // The kernel: same event loop, slot table, small-request pool and per-tile accounting as
 // replay_vms_kernel; the pools are the ones above.  IDX: the type of a chunk number.
 // ---------------------------------------------------------------------------
-template <bool SLOT_REGS, class IDX, bool TH>
+template <bool SLOT_REGS, class IDX, int TH>
 __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u64 *__restrict__ events,
                                                              const u32 *__restrict__ n_events,
                                                              u64 *__restrict__ decisions, vms_trace_stats *__restrict__ stats,
@@ -1047,7 +1060,7 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     V.bnd = (u32 *)(lds + P.off_bnd);
     V.tmp = (u32 *)(lds + P.off_tmp);
     V.idle = V.tmp + P.bmp_words;
-    V.ssz = (IDX *)(lds + P.off_skey);
+    V.ssz = TH == 3 ? (IDX *)(ws_slice + 2 * P.ws_half + 2 * (size_t)P.ws_tbl_bytes) : (IDX *)(lds + P.off_skey);
     if constexpr (TH) {
         V.swit = (IDX *)(ws_slice + 2 * P.ws_half);
         V.soff = (u16 *)(ws_slice + 2 * P.ws_half + P.ws_tbl_bytes);
@@ -1077,7 +1090,8 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
     }
     wave_sync();
     st_one(V.bnd, 0u, 1u);                                  // no chunk yet: the end of the last pBlock is chunk 0
-    V.sp.refresh(V.ssz, 0u);
+    V.tables_written();
+    V.sp.template refresh<TH == 3>(V.ssz, 0u);
     wave_sync();
 
     u32 requested = 0, active = 0, peak_requested = 0, peak_active = 0;
@@ -1191,7 +1205,8 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                 // ---- no exact fit: states S2 to S5
                 VmsRes R;
                 const bool went = fine_alloc_cold(lds, V, S, P, bsize, lo_p, hi_p, sp_reserved + (V.n_chunks << P.chunk_shift), base + j, R);
-                V.sp.refresh(V.ssz, V.ns);                  // the sBlock table may have changed
+                V.tables_written();
+                V.sp.template refresh<TH == 3>(V.ssz, V.ns);        // the sBlock table may have changed
                 if (UNLIKELY(!went)) {                      // an engine table overflowed: the trace ends here
                     stop = true;
                     done = j;

@@ -42,7 +42,7 @@ struct ReplayPlan {
     KParams kp[2];                   // [0] splitting kernel, [1] stitching kernel
     bool fine;                       // stitching kernel: the fine-grained variant (lists in the workspace)
     bool wide;                       // fine-grained variant with 32-bit chunk numbers (more than 65,000 chunks)
-    bool tbl_ws;                     // fine-grained variant: witness and list-place tables in the workspace, not in LDS
+    int tbl_ws;                      // fine-grained variant: 0 the sBlock tables in LDS; 2 witnesses and list places in the workspace; 3 sizes too
     bool slot_regs;                  // slot table in registers (at most 64 slots)
     bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 192)
     size_t ws_bytes;
@@ -87,7 +87,7 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
         k.off_bmp = take(((uint64_t)k.bmp_words + 1) * 4);      // and one spare word
         k.off_bnd = take(((uint64_t)k.bmp_words + 1) * 4);      // scans read one word ahead
         k.off_tmp = take(((uint64_t)k.bmp_words + 64) * 4);     // and 64 spare words
-        k.off_skey = take(((uint64_t)c.max_sblocks + 80) * idx);    // 64 spare places, and shifts move whole 16-byte blocks
+        if (p.tbl_ws != 3) k.off_skey = take(((uint64_t)c.max_sblocks + 80) * idx);    // 64 spare places, and shifts move whole 16-byte blocks
         if (!p.tbl_ws) {
             k.off_swit = take(((uint64_t)c.max_sblocks + 80) * idx);
             k.off_soff = take(((uint64_t)c.max_sblocks + 80) * 2);
@@ -136,15 +136,15 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
         return VMS_ETOOBIG;
 
     memset(&p, 0, sizeof p);
-    if (c.variant > VMS_VARIANT_FINE || c.table_place > VMS_TABLES_WORKSPACE) return VMS_EINVAL;
+    if (c.variant > VMS_VARIANT_FINE || c.table_place > VMS_TABLES_WORKSPACE_ALL) return VMS_EINVAL;
     // tables beyond what flat sorted LDS arrays serve (lists of more than 64 KB, thousands of blocks)
     // need the fine-grained variant with its lists in the workspace
     const bool big = c.max_runs > 16384 || c.max_pblocks > 4096 || c.max_sblocks > 4096;
     if (big && c.variant == VMS_VARIANT_FLAT) return VMS_ETOOBIG;
     p.fine = big || c.variant == VMS_VARIANT_FINE;
     p.wide = c.max_chunks > 63000;
-    p.tbl_ws = p.fine && !p.wide && c.table_place == VMS_TABLES_WORKSPACE;
-    if (c.table_place == VMS_TABLES_WORKSPACE && p.fine && p.wide) return VMS_EINVAL;
+    p.tbl_ws = p.fine && !p.wide && c.table_place >= VMS_TABLES_WORKSPACE ? (int)c.table_place : 0;
+    if (c.table_place >= VMS_TABLES_WORKSPACE && p.fine && p.wide) return VMS_EINVAL;
     p.slot_regs = c.max_slots <= 64;
     p.fl_regs = c.max_free_blocks <= 192;
     uint32_t shift = 0;
@@ -187,7 +187,7 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
             // behind them the two 16-bit tables, if they are kept here
             k.ws_half = align_up((((uint64_t)k.cap_grans << k.gran_shift) + 64) * 8, 256);
             k.ws_tbl_bytes = p.tbl_ws ? (uint32_t)align_up(((uint64_t)c.max_sblocks + 80) * 2, 256) : 0u;
-            k.ws_stride = 2 * k.ws_half + 2 * (uint64_t)k.ws_tbl_bytes;
+            k.ws_stride = 2 * k.ws_half + (uint64_t)p.tbl_ws * k.ws_tbl_bytes;          // (2 or 3 tables)
         } else if (pol) {
             k.ws_stride = align_up(((uint64_t)c.max_runs + 64) * 4, 256);     // where compaction copies the lists
         }
@@ -212,10 +212,10 @@ inline uint32_t plan_waves_per_cu(const ReplayPlan &x)
 // flat variant (its lists are in LDS), but when the batch does not fit the compute units at once and
 // the fine-grained variant holds at least 2.5 times as many traces per compute unit, the latter
 // finishes the batch sooner.  With table_place 0 it chooses where the fine-grained variant keeps the
-// witnesses and list places of the sBlocks: throughput grows almost in proportion to the wavefronts
-// per compute unit (measured from 4 to 9), a wavefront with these tables in the workspace is about a
-// fifth slower, so the workspace it is when the LDS layout leaves fewer than two wavefronts per SIMD,
-// the workspace lets a quarter more in, and the batch has traces for them.
+// tables of the sBlocks: throughput grows almost in proportion to the wavefronts per compute unit
+// (measured from 4 to 9) while a wavefront with tables in the workspace is slower, so the workspace it
+// is when the LDS layout leaves fewer than two wavefronts per SIMD and the batch then takes fewer
+// rounds of wavefronts by more than the wavefronts lose.
 inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
 {
     int rc = replay_plan_for(cfg, p);
@@ -231,14 +231,26 @@ inline int replay_plan_make(const vms_config *cfg, ReplayPlan &p)
         }
     }
     if (p.fine && !p.wide && cfg->table_place == VMS_TABLES_AUTO) {
-        vms_config alt = *cfg;
-        alt.variant = VMS_VARIANT_FINE;
-        alt.table_place = VMS_TABLES_WORKSPACE;
-        ReplayPlan q;
-        if (replay_plan_for(&alt, q) == VMS_OK) {
-            const uint32_t lds = plan_waves_per_cu(p), ws = plan_waves_per_cu(q);
-            if ((uint64_t)cfg->n_traces > (uint64_t)CUS * lds && 4 * ws >= 5 * lds && lds < 8) p = q;
-        }
+        // rounds of wavefronts the batch takes, times what a wavefront pays for tables in the workspace
+        // (measured on offloading traces: 1.2 with two tables there, 1.45 with all three)
+        auto cost = [&](const ReplayPlan &x, uint32_t tenths) {
+            const uint64_t slots = (uint64_t)CUS * plan_waves_per_cu(x);
+            return ((cfg->n_traces + slots - 1) / slots) * tenths;
+        };
+        uint64_t best = cost(p, 100);
+        if (plan_waves_per_cu(p) < 8)
+            for (uint32_t place = VMS_TABLES_WORKSPACE; place <= VMS_TABLES_WORKSPACE_ALL; place++) {
+                vms_config alt = *cfg;
+                alt.variant = VMS_VARIANT_FINE;
+                alt.table_place = place;
+                ReplayPlan q;
+                if (replay_plan_for(&alt, q) != VMS_OK) continue;
+                const uint64_t c = cost(q, place == VMS_TABLES_WORKSPACE ? 120 : 145);
+                if (c < best) {
+                    best = c;
+                    p = q;
+                }
+            }
     }
     return VMS_OK;
 }

@@ -126,9 +126,10 @@ typedef void (*split_fn)(KParams, const u64 *, const u32 *, u64 *, vms_trace_sta
 vms_fn pick_vms(const ReplayPlan &p)
 {
     if (p.fine) {
-        if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32, false> : replay_vms_fine_kernel<false, u32, false>;
-        if (p.tbl_ws) return p.slot_regs ? replay_vms_fine_kernel<true, u16, true> : replay_vms_fine_kernel<false, u16, true>;
-        return p.slot_regs ? replay_vms_fine_kernel<true, u16, false> : replay_vms_fine_kernel<false, u16, false>;
+        if (p.wide) return p.slot_regs ? replay_vms_fine_kernel<true, u32, 0> : replay_vms_fine_kernel<false, u32, 0>;
+        if (p.tbl_ws == 3) return p.slot_regs ? replay_vms_fine_kernel<true, u16, 3> : replay_vms_fine_kernel<false, u16, 3>;
+        if (p.tbl_ws) return p.slot_regs ? replay_vms_fine_kernel<true, u16, 2> : replay_vms_fine_kernel<false, u16, 2>;
+        return p.slot_regs ? replay_vms_fine_kernel<true, u16, 0> : replay_vms_fine_kernel<false, u16, 0>;
     }
     return p.slot_regs ? replay_vms_kernel<true> : replay_vms_kernel<false>;
 }

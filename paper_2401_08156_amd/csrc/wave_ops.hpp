@@ -247,11 +247,19 @@ template <class K>
 struct Probe2 {
     K v0, v1;       // per lane
     u32 stride;     // wave-uniform
+    // G: the array is a table in global memory (16-bit keys, read past the vector cache)
+    template <bool G = false>
+    DI K at(const K *a, u32 i) const
+    {
+        if constexpr (G) return (K)ld_tab(a + i);
+        else return a[i];
+    }
+    template <bool G = false>
     DI void refresh(const K *a, u32 n)
     {
         stride = n > 128 ? (n + 127) >> 7 : 1;
         const u32 p0 = lane_id() * stride, p1 = (64 + lane_id()) * stride;
-        const K x0 = a[p0 < n ? p0 : n], x1 = a[p1 < n ? p1 : n];   // a[n] is a spare zero key
+        const K x0 = at<G>(a, p0 < n ? p0 : n), x1 = at<G>(a, p1 < n ? p1 : n);     // a[n] is a spare zero key
         v0 = x0;
         v1 = x1;
     }
@@ -260,10 +268,11 @@ struct Probe2 {
         const u32 c = popc64(ballot(v0 > key)) + popc64(ballot(v1 > key));
         return dec_sat(c) * stride;
     }
+    template <bool G = false>
     DI u32 rank(const K *a, K key) const
     {
         const u32 b0 = block(key);
-        return b0 + popc64(ballot(a[b0 + lane_id()] > key));
+        return b0 + popc64(ballot(at<G>(a, b0 + lane_id()) > key));
     }
 };
 

@@ -104,12 +104,14 @@ void body_vms(void *p)
     switch (a.variant) {
     case 0: replay_vms_kernel<true>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
     case 1: replay_vms_kernel<false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 2: replay_vms_fine_kernel<true, uint16_t, false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 3: replay_vms_fine_kernel<false, uint16_t, false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 4: replay_vms_fine_kernel<true, u32, false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 5: replay_vms_fine_kernel<false, u32, false>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 6: replay_vms_fine_kernel<true, uint16_t, true>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
-    case 7: replay_vms_fine_kernel<false, uint16_t, true>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 2: replay_vms_fine_kernel<true, uint16_t, 0>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 3: replay_vms_fine_kernel<false, uint16_t, 0>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 4: replay_vms_fine_kernel<true, u32, 0>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 5: replay_vms_fine_kernel<false, u32, 0>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 6: replay_vms_fine_kernel<true, uint16_t, 2>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 7: replay_vms_fine_kernel<false, uint16_t, 2>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 8: replay_vms_fine_kernel<true, uint16_t, 3>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
+    case 9: replay_vms_fine_kernel<false, uint16_t, 3>(a.P, a.events, a.n_events, a.dec, a.stats, a.ws); break;
     }
 }
 
@@ -159,13 +161,13 @@ int emu_replay(const vms_config *cfg, const uint64_t *events, const uint32_t *n_
         a.dec = out ? (u64 *)g_dec.ptr() : nullptr;
         a.stats = (vms_trace_stats *)g_stats.ptr();
         a.ws = g_ws.ptr();
-        if (pol) a.variant = plan.fine ? (plan.wide ? 4 : plan.tbl_ws ? 6 : 2) + (plan.slot_regs ? 0 : 1) : (plan.slot_regs ? 0 : 1);
+        if (pol) a.variant = plan.fine ? (plan.wide ? 4 : plan.tbl_ws == 3 ? 8 : plan.tbl_ws ? 6 : 2) + (plan.slot_regs ? 0 : 1) : (plan.slot_regs ? 0 : 1);
         else a.variant = (plan.fl_regs ? 0 : 2) + (plan.slot_regs ? 0 : 1);
         if (out) memset(g_dec.ptr(), 0xFF, n * 8);
         for (int pass = 0; pass < (again.has_retry ? 2 : 1); pass++) {
             const ReplayPlan &pl = pass ? again : plan;
             a.P = pl.kp[pol];
-            if (pol) a.variant = pl.fine ? (pl.wide ? 4 : pl.tbl_ws ? 6 : 2) + (pl.slot_regs ? 0 : 1) : (pl.slot_regs ? 0 : 1);
+            if (pol) a.variant = pl.fine ? (pl.wide ? 4 : pl.tbl_ws == 3 ? 8 : pl.tbl_ws ? 6 : 2) + (pl.slot_regs ? 0 : 1) : (pl.slot_regs ? 0 : 1);
             else a.variant = (pl.fl_regs ? 0 : 2) + (pl.slot_regs ? 0 : 1);
             // the second pass is a launch of retry_traces wavefronts that share out the flagged traces
             const u32 waves = pass ? std::min(cfg->retry_traces, cfg->n_traces) : cfg->n_traces;

@@ -298,19 +298,21 @@ def test_kernel_variant_choice():
     gpu_util.assert_parity(ev, cfg, label="fine-grained variant, 32-bit chunk numbers")
 
 
-def test_sblock_tables_in_the_workspace():
-    # the fine-grained kernel with the witnesses and list places of its sBlocks in the workspace instead
-    # of LDS: offloading traces with thousands of sBlocks, low thresholds (many releases: the tables move
-    # all the time), a tiny arena (compaction rewrites the list places), a slot table in LDS, ragged traces
-    W = dict(variant=binding.VMS_VARIANT_FINE, table_place=binding.VMS_TABLES_WORKSPACE)
+@pytest.mark.parametrize("place", [binding.VMS_TABLES_WORKSPACE, binding.VMS_TABLES_WORKSPACE_ALL])
+def test_sblock_tables_in_the_workspace(place):
+    # the fine-grained kernel with the witnesses and list places of its sBlocks (and, second case, their sizes
+    # too) in the workspace instead of LDS: offloading traces with thousands of sBlocks, low thresholds (many
+    # releases: the tables move all the time), a tiny arena (compaction rewrites the list places), a slot
+    # table in LDS, ragged traces
+    W = dict(variant=binding.VMS_VARIANT_FINE, table_place=place)
     ev, ms = tg.generate(3, n_traces=12, n_events=8000)
     big = dict(max_pblocks=4096, max_sblocks=2048, max_runs=1 << 18, max_chunks=16384)
     lds = []
-    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
-        r = binding.Replay(gpu_util.make_cfg(12, 8000, ms, variant=binding.VMS_VARIANT_FINE, table_place=place, **big))
+    for pl in (binding.VMS_TABLES_LDS, place):
+        r = binding.Replay(gpu_util.make_cfg(12, 8000, ms, variant=binding.VMS_VARIANT_FINE, table_place=pl, **big))
         lds.append(r.lds_bytes()[1])
         r.close()
-    assert lds[0] - lds[1] == 2 * (2048 + 80) * 2
+    assert lds[0] - lds[1] == place * (2048 + 80) * 2
     gpu_util.assert_parity(ev, gpu_util.make_cfg(12, 8000, ms, **dict(W, **big)), label="config 3 slice, tables in the workspace")
     for seed, threshold in ((5, 128), (6, 32)):
         ev, ms = tg.generate(3, n_traces=8, n_events=8000, seed=seed)

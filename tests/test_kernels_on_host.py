@@ -48,7 +48,7 @@ def test_worked_examples_fine_grained_variant():
         fx = load_fixture(path)
         ev = fx["events"][None, :]
         kw = dict(spool_threshold=int(fx["spool_threshold"])) if "spool_threshold" in fx else {}
-        for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
+        for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE, binding.VMS_TABLES_WORKSPACE_ALL):
             cfg = gpu_util.make_cfg(1, ev.shape[1], 16, variant=binding.VMS_VARIANT_FINE, table_place=place, policy_mask=2, **kw)
             check(ev, cfg, label=os.path.basename(path))
 
@@ -75,8 +75,8 @@ def test_splitting_kernels():
 def test_fine_grained_variant(kind, nt, ne, tables):
     # the witness and list-place tables of the sBlocks in LDS, then in the workspace (16-bit chunk numbers only)
     ev, ms = tg.generate(kind, n_traces=nt, n_events=ne, seed=7 + kind)
-    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE):
-        if place == binding.VMS_TABLES_WORKSPACE and tables.get("max_chunks", 0) > 63000:
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE, binding.VMS_TABLES_WORKSPACE_ALL):
+        if place != binding.VMS_TABLES_LDS and tables.get("max_chunks", 0) > 63000:
             continue
         cfg = gpu_util.make_cfg(nt, ne, ms, policy_mask=2, **dict(dict(variant=2), table_place=place, **tables))
         check(ev, cfg, label="generator %d %s tables %d" % (kind, tables, place))
