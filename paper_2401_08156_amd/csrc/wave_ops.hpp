@@ -416,7 +416,7 @@ DI void gblk_store(uint16_t *a, u32 B, const Blk16 &v)
 template <int N>
 DI void gblk_shift_up(uint16_t *const (&a)[N], u32 pos, u32 n)
 {
-    constexpr u32 E = 8, G = 4;
+    constexpr u32 E = 8, G = 2;
     const u32 bf = (pos + 1) / E, bl = n / E;       // first and last block that receive an element
     tbl_fence();
     for (u32 hi = bl + 1; hi > bf;) {
@@ -457,7 +457,7 @@ DI void gblk_shift_up(uint16_t *const (&a)[N], u32 pos, u32 n)
 template <int N>
 DI void gblk_shift_down(uint16_t *const (&a)[N], u32 pos, u32 n)
 {
-    constexpr u32 E = 8, G = 4;
+    constexpr u32 E = 8, G = 2;
     const u32 bf = pos / E, bl = (n - 1) / E;
     tbl_fence();
     for (u32 lo = bf; lo <= bl; lo += 64 * G) {
