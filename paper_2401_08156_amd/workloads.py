@@ -28,10 +28,15 @@ TABLES = {
 # events; replayed as three batches, one per kind, each with tables of its own
 TABLES_5 = {
     2: dict(max_free_blocks=192, max_pblocks=640, max_sblocks=640, max_runs=5120, max_chunks=4096),
-    # (40,832 B of LDS per wavefront: four wavefronts per compute unit; the margins over the high-water marks
-    # are one to two per cent, and a trace that outgrows a table is replayed again by the second pass)
+    # (the margins over the high-water marks are one to two per cent; a trace that outgrows a table is replayed
+    # again by the second pass.  40,208 B of LDS per wavefront with every table in LDS, four wavefronts per compute
+    # unit; the library moves the sBlock tables to the workspace: 14,960 B, ten)
     3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2720, max_sblocks=4128, max_runs=1 << 18, max_chunks=8480),
-    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576),
+    # (beside the other two batches the fine-grained kernel with its sBlock tables in the workspace, 23.5 KB of LDS
+    # per wavefront, finishes the step sooner than the flat one with 50.8 KB: 1,405 against 1,456 ms; alone they
+    # take the same 340 ms)
+    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576,
+            variant=2, table_place=3),
 }
 
 

@@ -98,6 +98,9 @@ def test_second_pass_replays_traces_that_outgrow_the_tables():
         _, _, st = emu.replay(ev, gpu_util.make_cfg(3, 900, ms, **small), binding.STATS_DTYPE)
         assert (st["status"][:, 0] & binding.VMS_ST_TABLE_OVERFLOW).all() and not (st["status"][:, 1:] & binding.VMS_ST_TABLE_OVERFLOW).any()
         check(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=2, **small), label="second pass, first pass variant %d" % variant)
+        # both passes with the sBlock tables in the workspace
+        check(ev, gpu_util.make_cfg(3, 900, ms, retry_traces=2, table_place=binding.VMS_TABLES_WORKSPACE_ALL, **small),
+              label="second pass, tables in the workspace")
     # more such traces than the second pass has wavefronts: one wavefront replays all three in turn
     ev, ms = tg.generate(1, n_traces=3, n_events=900, seed=13)
     cfg = gpu_util.make_cfg(3, 900, ms, policy_mask=2, variant=2, max_pblocks=40, max_sblocks=560)
