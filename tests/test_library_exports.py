@@ -85,6 +85,27 @@ def test_tables_that_exceed_the_lds_are_refused_before_any_device_call():
     assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -6
 
 
+def test_table_place_is_validated_without_a_device():
+    L = binding.lib()
+    h = ctypes.c_void_p()
+    cfg = binding.vms_config_default(4, 100, 9)
+    cfg.variant, cfg.table_place = binding.VMS_VARIANT_FINE, 4                 # no such place
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -1
+    cfg.table_place, cfg.max_chunks = binding.VMS_TABLES_WORKSPACE_ALL, 70000   # 32-bit chunk numbers keep their tables in LDS
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) == -1
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE, binding.VMS_TABLES_WORKSPACE_ALL):
+        cfg = binding.vms_config_default(4, 100, 9)
+        cfg.variant, cfg.table_place = binding.VMS_VARIANT_FINE, place
+        rc = L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h))
+        assert rc in (0, -5)                    # -5: no device here; the plan itself was accepted
+        if rc == 0:
+            L.vms_replay_destroy(h)
+    # the flat variant has no such tables: the field is ignored there
+    cfg = binding.vms_config_default(4, 100, 9)
+    cfg.variant, cfg.table_place = binding.VMS_VARIANT_FLAT, binding.VMS_TABLES_WORKSPACE_ALL
+    assert L.vms_replay_create(ctypes.byref(cfg), ctypes.byref(h)) in (0, -5)
+
+
 def test_table_sizes_that_would_wrap_a_32_bit_layout_are_refused():
     # the LDS layout is computed in 64 bits and every table size is bounded: a huge value must end as
     # "too big" (or invalid), never as a small layout that a kernel would then overrun
