@@ -56,6 +56,27 @@ def recorded_counters(config):
         return {}
 
 
+VALU_PEAK_GIPS = 256 * 4 * 2.4 / 4        # G wave64 VALU instructions per second: 614.4
+
+
+def alu_view(c, ms):
+    if "valu_instructions" not in c or not ms:
+        return None
+    a = c["valu_instructions"] / (ms * 1e-3) / 1e9
+    return {"achieved": a, "peak": VALU_PEAK_GIPS, "unit": "G wave64 VALU instructions/s", "frac": a / VALU_PEAK_GIPS,
+            "all_instructions_per_simd_cycle": c["instructions"] / (ms * 1e-3 * 2.4e9 * 1024)}
+
+
+def step_alu_view(counters, ms):
+    if not counters or not all("valu_instructions" in c for c in counters.values()):
+        return None
+    valu = sum(c["valu_instructions"] for c in counters.values())
+    every = sum(c["instructions"] for c in counters.values())
+    a = valu / (ms * 1e-3) / 1e9
+    return {"achieved": a, "peak": VALU_PEAK_GIPS, "unit": "G wave64 VALU instructions/s", "frac": a / VALU_PEAK_GIPS,
+            "all_instructions_per_simd_cycle": every / (ms * 1e-3 * 2.4e9 * 1024)}
+
+
 def cpu_baseline(batches, per_kind, max_seconds=40.0):
     """The oracle, as it stands, on a bounded sample of the same workload (the first traces of every
     batch), all host cores, both policies, decisions written."""
@@ -279,7 +300,14 @@ def main():
                      # from the committed counter summary of this workload (null once the kernels have changed)
                      "issue_rate": dom_counters.get("issue_rate"),           # wave instructions per SIMD cycle
                      "lds": dom_counters.get("lds"),                         # bytes, GB/s and fraction of the measured peak
-                     "waves_per_cu_observed": dom_counters.get("waves_per_cu")},
+                     "waves_per_cu_observed": dom_counters.get("waves_per_cu"),
+                     # What bounds the path is the rate at which the SIMDs issue: the launch's vector ALU
+                     # instructions (counted by the profiler; the same for every run of the same kernel on
+                     # the same input) over its duration in this run, against one wave64 instruction per
+                     # 4 cycles on each of 256 x 4 SIMDs at 2.4 GHz.
+                     "alu": alu_view(dom_counters, per_batch[dom_b][dom_p])},
+        # the same over the whole step: all launches' instructions over the step time
+        "step_alu": step_alu_view(counters, ms_per_step),
         "kernels": counters or None,
         "table_high_water": {k: int(st[k].max()) for k in ("max_free_blocks", "max_pblocks", "max_multi_pblocks", "max_sblocks",
                                                             "max_runs", "max_members")},
