@@ -1150,20 +1150,28 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                     active -= (b >> 2) << P.chunk_shift;
                     EMIT((u32)C_FREE, a)
                 }
-                bool ml = false, mr = false;
                 if (LIKELY(P.small_regs)) {
+                    // (each outcome parks its results and goes on from where it is found: handed back
+                    // through a record they would meet in flags that are tested again)
                     AcctLds A;
                     A.sc = (u32 *)(lds + LDS_SCALARS);
                     A.idle = V.idle;
                     Q.release(a >> 2, req, a & 3, A, base + j,
-                              [&](bool l, bool r) {
-                                  ml = l;
-                                  mr = r;
+                              [&](bool ml, bool mr) {
+                                  active -= req;
+                                  write_lane4(v_dlo, v_dhi, v_act, v_res, C_FREE | B_SMALL | (ml ? B_6 : 0u) | (mr ? B_7 : 0u),
+                                              a >> 2, active, sp_reserved + (V.n_chunks << P.chunk_shift), j);
+                                  wave_sync();
                               },
-                              [&]() {});
-                } else {
-                    small_free(lds, P, V.idle, a >> 2, req, a & 3, base + j, &ml, &mr);
+                              [&]() {
+                                  stop = true;
+                                  done = j;
+                                  todo = 0;
+                              });
+                    continue;
                 }
+                bool ml = false, mr = false;
+                small_free(lds, P, V.idle, a >> 2, req, a & 3, base + j, &ml, &mr);
                 if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
                     stop = true;
                     done = j;
@@ -1225,26 +1233,44 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                 // ---- a request below one chunk: the policy's own splitting pool (Sec. 3.1)
                 const u32 seg = ((size + chunk_units - 1) >> P.chunk_shift) << P.chunk_shift;
                 const u32 reserved = sp_reserved + (V.n_chunks << P.chunk_shift);
-                SplitRes r;
-                r.code = C_OOM;
-                r.addr = r.flags = 0;
-                r.split = false;
                 if (LIKELY(P.small_regs)) {
                     AcctLds A;
                     A.sc = (u32 *)(lds + LDS_SCALARS);
                     A.idle = V.idle;
                     Q.alloc(size, seg, reserved + seg <= P.capacity_units, A, base + j,
                             [&](u32 code, u32 addr, u32 flags, bool split) {
-                                r.code = code;
-                                r.addr = addr;
-                                r.flags = flags;
-                                r.split = split;
+                                sp_reserved = Q.reserved();
+                                u32 d_lo = C_OOM, d_hi = 0;
+                                if (code == C_OOM) {
+                                    S.set_req(slot, (u32)SLOT_OOM);
+                                    ColdState C;            // rare: note the first failed request
+                                    C.load(lds);
+                                    if (C.get(SC_FIRST_OOM) == NONE32)
+                                        st_one((u32 *)(lds + LDS_SCALARS), (u32)SC_FIRST_OOM, base + j);
+                                } else {
+                                    S.set_a(slot, (addr << 2) | flags);
+                                    S.set_b(slot, (u32)KIND_SMALL);
+                                    S.set_req(slot, size);
+                                    requested += size;
+                                    active += size;
+                                    peak_requested = max(peak_requested, requested);
+                                    peak_active = max(peak_active, active);
+                                    d_lo = code | B_SMALL | (split ? B_6 : 0u) | ((code == C_GROW ? 0u : 1u) << 8);
+                                    d_hi = addr;
+                                }
+                                write_lane4(v_dlo, v_dhi, v_act, v_res, d_lo, d_hi, active,
+                                            sp_reserved + (V.n_chunks << P.chunk_shift), j);
+                                wave_sync();
                             },
-                            [&]() {});
-                    sp_reserved = Q.reserved();
-                } else {
-                    small_alloc(lds, P, V.idle, size, seg, reserved + seg <= P.capacity_units, base + j, r, sp_reserved);
+                            [&]() {
+                                stop = true;
+                                done = j;
+                                todo = 0;
+                            });
+                    continue;
                 }
+                SplitRes r;
+                small_alloc(lds, P, V.idle, size, seg, reserved + seg <= P.capacity_units, base + j, r, sp_reserved);
                 if (UNLIKELY(ld_uni((u32 *)(lds + LDS_SCALARS), (u32)SC_STOP) != 0)) {
                     stop = true;
                     done = j;
