@@ -137,13 +137,14 @@ struct SlotsT<true> {
 
 template <>
 struct SlotsT<false> {
-    u32 *req, *a, *b, *c;
+    u32 *req, *a, *b;
+    uint16_t *c;                // fine-grained variant only: a list place (a 15-bit granule number) and the mark of relocate()
     DI void init(char *lds, const KParams &P)
     {
         req = (u32 *)(lds + P.off_slot_req);
         a = (u32 *)(lds + P.off_slot_a);
         b = (u32 *)(lds + P.off_slot_b);
-        c = (u32 *)(lds + P.off_slot_c);
+        c = (uint16_t *)(lds + P.off_slot_c);
         n_slots = P.max_slots;
         for (u32 i = lane_id(); i < P.max_slots; i += 64) req[i] = SLOT_UNBOUND;
     }
@@ -154,7 +155,7 @@ struct SlotsT<false> {
     DI void set_req(u32 s, u32 v) { st_one(req, s, v); }
     DI void set_a(u32 s, u32 v) { st_one(a, s, v); }
     DI void set_b(u32 s, u32 v) { st_one(b, s, v); }
-    DI void set_c(u32 s, u32 v) { st_one(c, s, v); }
+    DI void set_c(u32 s, u32 v) { st_one(c, s, (uint16_t)v); }
     DI void bind(u32 s, u32 vreq, u32 va, u32 vb, u32)
     {
         st_one(req, s, vreq);
@@ -168,13 +169,13 @@ struct SlotsT<false> {
     {
         for (u32 i = lane_id(); i < n_slots; i += 64) {
             const bool hit = req[i] + 1u > 1u && (b[i] & 3) == KIND_SBLOCK && c[i] == from;
-            if (hit) c[i] = to | 0x80000000u;
+            if (hit) c[i] = (uint16_t)(to | 0x8000u);
         }
         wave_sync();
     }
     DI void relocate_done()
     {
-        for (u32 i = lane_id(); i < n_slots; i += 64) c[i] &= 0x7FFFFFFFu;
+        for (u32 i = lane_id(); i < n_slots; i += 64) c[i] &= 0x7FFFu;
         wave_sync();
     }
 };

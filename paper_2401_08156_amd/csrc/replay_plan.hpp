@@ -77,7 +77,7 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
         k.off_slot_req = take((uint64_t)c.max_slots * 4);
         k.off_slot_a = take((uint64_t)c.max_slots * 4);
         k.off_slot_b = policy ? take((uint64_t)c.max_slots * 4) : 0;
-        k.off_slot_c = policy && p.fine ? take((uint64_t)c.max_slots * 4) : 0;
+        k.off_slot_c = policy && p.fine ? take((uint64_t)c.max_slots * 2) : 0;   // 16-bit list places
     }
     // the splitting policy keeps small pools in registers: no LDS array then
     k.off_fl = k.cap_free <= 192 ? 0 : take(((uint64_t)k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
@@ -177,10 +177,10 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
             k.bmp_words = (uint32_t)align_up((uint64_t)c.max_chunks / 32 + 1, 4);
             // The arena holds 8-byte words: per sBlock two header words and at most one word per
             // run, rounded up to whole granules of 2^gran_shift words.  List places are 16-bit
-            // granule numbers.
+            // granule numbers; a slot table in LDS keeps them in 15 bits beside a mark.
             const uint64_t words = (uint64_t)c.max_runs + 5ull * c.max_sblocks;
             k.gran_shift = 2;
-            while ((words >> k.gran_shift) > 65535) k.gran_shift++;
+            while ((words >> k.gran_shift) > (p.slot_regs ? 65535u : 32767u)) k.gran_shift++;
             k.cap_grans = (uint32_t)(words >> k.gran_shift);
             if (k.cap_grans < 4) return VMS_EINVAL;
             // two halves (the lists, and where compaction copies them), each followed by 64 spare words;

@@ -23,7 +23,7 @@ TABLES = {
     3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2592, max_sblocks=2560, max_runs=1 << 18, max_chunks=10240),
     # (the fine-grained kernel with its sBlock tables in the workspace: six wavefronts per compute unit instead of
     # the flat kernel's three, 175 against 179 ms per step)
-    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=24576,
+    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=18432,
             variant=2, table_place=3),
     6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
 }
@@ -38,7 +38,7 @@ TABLES_5 = {
     # (beside the other two batches the fine-grained kernel with its sBlock tables in the workspace, 23.5 KB of LDS
     # per wavefront, finishes the step sooner than the flat one with 50.8 KB: 1,405 against 1,456 ms; alone they
     # take the same 340 ms)
-    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=24576,
+    4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=18432,
             variant=2, table_place=3),
 }
 
