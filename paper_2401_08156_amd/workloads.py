@@ -21,11 +21,14 @@ TABLES = {
     # (31,680 B of LDS per wavefront: LDS is handed out in 1,280-byte granules, 128 per compute unit, so five
     # wavefronts per compute unit need at most 32,000 B each; with 2,816 places for multi-chunk pBlocks it was four)
     3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2592, max_sblocks=2560, max_runs=1 << 18, max_chunks=10240),
-    # (the fine-grained kernel with its sBlock tables in the workspace: six wavefronts per compute unit instead of
-    # the flat kernel's three, 175 against 179 ms per step)
+    # (the fine-grained kernel with its sBlock tables in the workspace, chunk tables for the 17,699 chunks the
+    # largest trace reserves: 19.5 KB of LDS per wavefront, eight per compute unit instead of the flat kernel's
+    # three, 153 against 179 ms per step)
     4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=640, max_sblocks=576, max_runs=3840, max_chunks=18432,
             variant=2, table_place=3),
-    6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=16384),
+    # (the same for the 1,280 traces of the scale-out regime, 9,408 chunks at most: 22.9 KB, all traces resident
+    # at once, 20.0 against 25.8 ms)
+    6: dict(max_free_blocks=192, max_pblocks=512, max_sblocks=576, max_runs=3072, max_chunks=9728, variant=2, table_place=3),
 }
 # config 5 mixes the generators of configs 2, 3 and 4 (trace i uses kind 2 + i mod 3) with twice the
 # events; replayed as three batches, one per kind, each with tables of its own
@@ -35,9 +38,9 @@ TABLES_5 = {
     # again by the second pass.  40,208 B of LDS per wavefront with every table in LDS, four wavefronts per compute
     # unit; the library moves the sBlock tables to the workspace: 14,960 B, ten)
     3: dict(max_free_blocks=64, max_pblocks=8192, max_multi_pblocks=2720, max_sblocks=4128, max_runs=1 << 18, max_chunks=8480),
-    # (beside the other two batches the fine-grained kernel with its sBlock tables in the workspace, 23.5 KB of LDS
-    # per wavefront, finishes the step sooner than the flat one with 50.8 KB: 1,405 against 1,456 ms; alone they
-    # take the same 340 ms)
+    # (beside the other two batches the fine-grained kernel with its sBlock tables in the workspace, 19.9 KB of LDS
+    # per wavefront, finishes the step sooner than the flat one with 50.8 KB: 1,339 against 1,456 ms; 18,055
+    # chunks is the most a trace of this kind reserves)
     4: dict(max_free_blocks=320, max_small_blocks=192, max_pblocks=736, max_sblocks=576, max_runs=4224, max_chunks=18432,
             variant=2, table_place=3),
 }
