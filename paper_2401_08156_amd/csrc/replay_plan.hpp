@@ -44,7 +44,8 @@ struct ReplayPlan {
     bool wide;                       // fine-grained variant with 32-bit chunk numbers (more than 65,000 chunks)
     int tbl_ws;                      // fine-grained variant: 0 the sBlock tables in LDS; 2 witnesses and list places in the workspace; 3 sizes too
     bool slot_regs;                  // slot table in registers (at most 64 slots)
-    bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 192)
+    bool fl_regs;                    // splitting policy: inactive blocks in registers (at most 320)
+    uint32_t fl_tiles;               // ... in that many registers per lane: 3 (at most 192 blocks) or 5; 0: in LDS
     size_t ws_bytes;
     bool has_retry;                  // a second pass with the plan below follows the first
 };
@@ -80,7 +81,8 @@ inline uint64_t layout(KParams &k, int policy, const vms_config &c, const Replay
         k.off_slot_c = policy && p.fine ? take((uint64_t)c.max_slots * 2) : 0;   // 16-bit list places
     }
     // the splitting policy keeps small pools in registers: no LDS array then
-    k.off_fl = k.cap_free <= 192 ? 0 : take(((uint64_t)k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
+    // (up to 320 blocks; the stitching policy's pool for small requests: up to 192)
+    k.off_fl = k.cap_free <= (policy ? 192u : 320u) ? 0 : take(((uint64_t)k.cap_free + 128) * 8);   // 128 spare places: scans read whole tiles
     if (policy && p.fine) {
         const uint64_t idx = p.wide ? 4 : 2;                    // bytes of a chunk number
         k.off_pool = take(((uint64_t)k.cap_pblocks + 80) * 2 * idx);      // 64 spare places, and moves of whole 16-byte blocks
@@ -146,7 +148,8 @@ inline int replay_plan_for(const vms_config *cfg, ReplayPlan &p)
     p.tbl_ws = p.fine && !p.wide && c.table_place >= VMS_TABLES_WORKSPACE ? (int)c.table_place : 0;
     if (c.table_place >= VMS_TABLES_WORKSPACE && p.fine && p.wide) return VMS_EINVAL;
     p.slot_regs = c.max_slots <= 64;
-    p.fl_regs = c.max_free_blocks <= 192;
+    p.fl_tiles = c.max_free_blocks <= 192 ? 3u : c.max_free_blocks <= 320 ? 5u : 0u;
+    p.fl_regs = p.fl_tiles != 0;
     uint32_t shift = 0;
     while ((UNIT << shift) < c.chunk_bytes) shift++;
     const uint64_t cap = c.capacity_bytes ? (c.capacity_bytes < ENGINE_MAX_BYTES ? c.capacity_bytes : ENGINE_MAX_BYTES)

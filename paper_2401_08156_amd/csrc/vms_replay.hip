@@ -133,10 +133,11 @@ vms_fn pick_vms(const ReplayPlan &p)
     }
     return p.slot_regs ? replay_vms_kernel<true> : replay_vms_kernel<false>;
 }
-// fl_regs: the splitting pool's inactive blocks fit three registers per lane (at most 192 blocks)
-split_fn pick_split(bool slot_regs, bool fl_regs)
+// fl_tiles: the splitting pool's inactive blocks fit three or five registers per lane (at most 192 / 320 blocks)
+split_fn pick_split(bool slot_regs, uint32_t fl_tiles)
 {
-    if (fl_regs) return slot_regs ? replay_split_kernel<true, 3> : replay_split_kernel<false, 3>;
+    if (fl_tiles == 3) return slot_regs ? replay_split_kernel<true, 3> : replay_split_kernel<false, 3>;
+    if (fl_tiles == 5) return slot_regs ? replay_split_kernel<true, 5> : replay_split_kernel<false, 5>;
     return slot_regs ? replay_split_kernel<true, 0> : replay_split_kernel<false, 0>;
 }
 
@@ -201,13 +202,13 @@ int vms_replay_create(const vms_config *cfg, vms_replay **out)
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking);
     // LDS above 64 KB per workgroup has to be requested explicitly
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)pick_split(h->plan.slot_regs, h->plan.fl_regs), hipFuncAttributeMaxDynamicSharedMemorySize,
+        e = hipFuncSetAttribute((const void *)pick_split(h->plan.slot_regs, h->plan.fl_tiles), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)pick_vms(h->plan), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)LDS_PER_CU);
     if (e == hipSuccess && h->retry.has_retry)
-        e = hipFuncSetAttribute((const void *)pick_split(h->retry.slot_regs, h->retry.fl_regs),
+        e = hipFuncSetAttribute((const void *)pick_split(h->retry.slot_regs, h->retry.fl_tiles),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)LDS_PER_CU);
     if (e == hipSuccess && h->retry.has_retry)
         e = hipFuncSetAttribute((const void *)pick_vms(h->retry), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -261,13 +262,13 @@ int vms_replay_run(vms_replay *h, const uint64_t *d_events, const uint32_t *d_n_
     }
     HIP_TRY(h, hipEventRecord(h->ev[2], sst));
     if (c.policy_mask & VMS_POLICY_SPLIT) {
-        hipLaunchKernelGGL(pick_split(h->plan.slot_regs, h->plan.fl_regs), dim3(c.n_traces), dim3(64), h->plan.kp[0].lds_bytes, sst, h->plan.kp[0],
+        hipLaunchKernelGGL(pick_split(h->plan.slot_regs, h->plan.fl_tiles), dim3(c.n_traces), dim3(64), h->plan.kp[0].lds_bytes, sst, h->plan.kp[0],
                            d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }
     HIP_TRY(h, hipEventRecord(h->ev[3], sst));
     if ((c.policy_mask & VMS_POLICY_SPLIT) && h->retry.has_retry) {
-        hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_regs), dim3(second_pass_waves(c)), dim3(64),
+        hipLaunchKernelGGL(pick_split(h->retry.slot_regs, h->retry.fl_tiles), dim3(second_pass_waves(c)), dim3(64),
                            h->retry.kp[0].lds_bytes, sst, h->retry.kp[0], d_events, d_n_events, d_dec_split, h->d_stats);
         HIP_TRY(h, hipGetLastError());
     }

@@ -123,6 +123,8 @@ void body_split(void *p)
     case 1: replay_split_kernel<false, 3>(a.P, a.events, a.n_events, a.dec, a.stats); break;
     case 2: replay_split_kernel<true, 0>(a.P, a.events, a.n_events, a.dec, a.stats); break;
     case 3: replay_split_kernel<false, 0>(a.P, a.events, a.n_events, a.dec, a.stats); break;
+    case 4: replay_split_kernel<true, 5>(a.P, a.events, a.n_events, a.dec, a.stats); break;
+    case 5: replay_split_kernel<false, 5>(a.P, a.events, a.n_events, a.dec, a.stats); break;
     }
 }
 
@@ -162,13 +164,13 @@ int emu_replay(const vms_config *cfg, const uint64_t *events, const uint32_t *n_
         a.stats = (vms_trace_stats *)g_stats.ptr();
         a.ws = g_ws.ptr();
         if (pol) a.variant = plan.fine ? (plan.wide ? 4 : plan.tbl_ws == 3 ? 8 : plan.tbl_ws ? 6 : 2) + (plan.slot_regs ? 0 : 1) : (plan.slot_regs ? 0 : 1);
-        else a.variant = (plan.fl_regs ? 0 : 2) + (plan.slot_regs ? 0 : 1);
+        else a.variant = (plan.fl_tiles == 3 ? 0 : plan.fl_tiles == 5 ? 4 : 2) + (plan.slot_regs ? 0 : 1);
         if (out) memset(g_dec.ptr(), 0xFF, n * 8);
         for (int pass = 0; pass < (again.has_retry ? 2 : 1); pass++) {
             const ReplayPlan &pl = pass ? again : plan;
             a.P = pl.kp[pol];
             if (pol) a.variant = pl.fine ? (pl.wide ? 4 : pl.tbl_ws == 3 ? 8 : pl.tbl_ws ? 6 : 2) + (pl.slot_regs ? 0 : 1) : (pl.slot_regs ? 0 : 1);
-            else a.variant = (pl.fl_regs ? 0 : 2) + (pl.slot_regs ? 0 : 1);
+            else a.variant = (pl.fl_tiles == 3 ? 0 : pl.fl_tiles == 5 ? 4 : 2) + (pl.slot_regs ? 0 : 1);
             // the second pass is a launch of retry_traces wavefronts that share out the flagged traces
             const u32 waves = pass ? std::min(cfg->retry_traces, cfg->n_traces) : cfg->n_traces;
             for (u32 t = 0; t < waves; t++) {

@@ -37,6 +37,16 @@ def test_splitting_pool_in_registers():
     cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=192)
     st = gpu_util.assert_parity(ev, cfg, label="config 1, register pool")
     assert st["n_merge"][0].min() > 0 and st["max_free_blocks"][0].max() <= 192
+    # up to 320: five registers per lane (slot table in registers, then in LDS)
+    cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=320)
+    gpu_util.assert_parity(ev, cfg, label="config 1, register pool of 320")
+    ev4, ms4 = tg.generate(4, n_traces=48, n_events=6000, seed=5)
+    st = gpu_util.assert_parity(ev4, gpu_util.make_cfg(48, 6000, ms4, max_free_blocks=320), label="LoRA traces, register pool of 320")
+    assert ms4 > 64 and st["max_free_blocks"][0].max() > 64
+    ev3, ms3 = tg.generate(3, n_traces=48, n_events=6000, seed=5)
+    assert ms3 <= 64
+    gpu_util.assert_parity(ev3, gpu_util.make_cfg(48, 6000, ms3, max_free_blocks=320, policy_mask=1),
+                           label="offloading traces, slot table and pool of 320 in registers")
     cfg = gpu_util.make_cfg(64, 1500, ms, max_free_blocks=6)
     _, _, st = gpu_util.gpu_replay(ev, cfg)
     assert (st["status"][0] & binding.VMS_ST_TABLE_OVERFLOW).all()

@@ -57,8 +57,13 @@ def test_splitting_kernels():
     ev, ms = tg.generate(1, n_traces=2, n_events=1500)
     check(ev, gpu_util.make_cfg(2, 1500, ms, policy_mask=1), label="pool in LDS")
     check(ev, gpu_util.make_cfg(2, 1500, ms, policy_mask=1, max_free_blocks=150), label="pool in registers")
+    check(ev, gpu_util.make_cfg(2, 1500, ms, policy_mask=1, max_free_blocks=300), label="pool in five registers per lane")
     ev, ms = tg.generate(4, n_traces=1, n_events=2000)
     check(ev, gpu_util.make_cfg(1, 2000, ms, policy_mask=1), label="slot table in LDS")
+    check(ev, gpu_util.make_cfg(1, 2000, ms, policy_mask=1, max_free_blocks=320), label="slot table in LDS, pool in five registers per lane")
+    ev, ms = tg.generate(3, n_traces=1, n_events=2000)
+    assert ms <= 64
+    check(ev, gpu_util.make_cfg(1, 2000, ms, policy_mask=1, max_free_blocks=320), label="slot table and pool (five per lane) in registers")
 
 
 @pytest.mark.parametrize("kind,nt,ne,tables", [
