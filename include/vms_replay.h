@@ -108,7 +108,7 @@ typedef struct vms_config {
                                     while more than this many are cached (Sec. 4.2.3)        */
     uint32_t max_slots;          /* slots are 0 .. max_slots-1                               */
     /* engine table sizes per trace; a trace that needs more gets VMS_ST_TABLE_OVERFLOW     */
-    uint32_t max_free_blocks;    /* inactive blocks of a splitting pool                      */
+    uint32_t max_free_blocks;    /* inactive blocks of a splitting pool (up to 320: registers) */
     uint32_t max_pblocks;        /* pBlocks (active and inactive)                            */
     uint32_t max_sblocks;        /* cached sBlocks; must exceed spool_threshold + 2          */
     uint32_t max_runs;           /* chunk runs summed over all cached sBlocks                */
