@@ -343,6 +343,20 @@ def test_sblock_tables_in_the_workspace(place):
         binding.Replay(gpu_util.make_cfg(5, 900, ms, max_chunks=70000, **W))
 
 
+def test_lists_are_compacted_under_a_slot_table_in_lds():
+    # LoRA-type traces (650 slots: the slot table lives in LDS and keeps list places in halfwords), a
+    # StitchFree threshold of 16 and a small arena: each trace stitches 220 to 550 sBlocks, more granules
+    # one after the other than the arena has, so the lists are squeezed together several times and the
+    # slots learn the new places; a trace that outgrows the arena all the same goes to the second pass
+    ev, ms = tg.generate(4, n_traces=24, n_events=14000, seed=3)
+    assert ms > 64
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE_ALL):
+        cfg = gpu_util.make_cfg(24, 14000, ms, policy_mask=2, variant=binding.VMS_VARIANT_FINE, table_place=place, spool_threshold=16,
+                                max_pblocks=1024, max_sblocks=128, max_runs=700, max_chunks=20480, retry_traces=24)
+        st = gpu_util.assert_parity(ev, cfg, label="compaction, slot table in LDS, tables %d" % place)
+        assert st["n_sblock_created"][1].min() > 200 and st["n_sblock_evicted"][1].min() > 100
+
+
 def test_second_pass_replays_traces_that_outgrow_the_tables():
     # 40 transformer traces, three of them replaced by random traces whose many requests below one
     # chunk outgrow the table of the stitching policy's small-request pool: without a second pass those

@@ -121,6 +121,20 @@ def test_second_pass_replays_traces_that_outgrow_the_tables():
     check(ev, gpu_util.make_cfg(70, 300, ms, retry_traces=3, **small), label="second pass over 70 traces")
 
 
+def test_lists_are_compacted_under_a_slot_table_in_lds():
+    # 650 slots (in LDS: list places are halfwords there), a StitchFree threshold of 16 and an arena
+    # of 290 granules: the 408 sBlocks this trace stitches take more granules than that one after the
+    # other, so their lists are squeezed together several times and the slots that hold one learn
+    # its new place; every later FREE of such a slot must still find the right list
+    ev, ms = tg.generate(4, n_traces=1, n_events=14000, seed=3)
+    assert ms > 64
+    for place in (binding.VMS_TABLES_LDS, binding.VMS_TABLES_WORKSPACE_ALL):
+        cfg = gpu_util.make_cfg(1, 14000, ms, policy_mask=2, variant=binding.VMS_VARIANT_FINE, table_place=place, spool_threshold=16,
+                                max_pblocks=1024, max_sblocks=92, max_runs=700, max_chunks=20480)
+        st = check(ev, cfg, label="compaction, slot table in LDS, tables %d" % place)
+        assert st["n_sblock_created"][1, 0] > 400 and st["n_sblock_evicted"][1, 0] > 300
+
+
 def test_table_overflow_is_flagged_not_fatal():
     ev, ms = tg.generate(3, n_traces=1, n_events=2500, seed=5)
     cfg = gpu_util.make_cfg(1, 2500, ms, policy_mask=2, variant=2, max_pblocks=64, max_sblocks=520, max_chunks=4096)
