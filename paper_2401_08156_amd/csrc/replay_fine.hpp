@@ -1037,6 +1037,7 @@ __global__ __launch_bounds__(64) void replay_vms_fine_kernel(KParams P, const u6
                                                              char *__restrict__ workspace)
 {
     WAVE_DYNAMIC_LDS(lds);
+    wave_priority<2>();
     typedef typename FineT<IDX, TH>::pkey_t pkey_t;
     const u32 lane = lane_id();
     u32 trace = blockIdx.x;

@@ -38,6 +38,12 @@ DI u64 ld_list(const u64 *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __H
 // the same for one 16-bit element of a table kept in global memory
 DI u32 ld_tab(const uint16_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
+// The wavefront's priority at instruction issue (0, the default, to 3) from here on.  The stitching
+// kernels hold LDS for as long as they run and the splitting kernels beside them hold none, so the
+// former go first where both wait at one SIMD.
+template <int PRIO>
+DI void wave_priority() { __builtin_amdgcn_s_setprio(PRIO); }
+
 // c - 1, or 0 for 0, on a wave-uniform count: two scalar instructions (the conditional form is
 // compiled into a clamped vector subtract and a v_readfirstlane)
 DI u32 dec_sat(u32 c) { return c - min(c, 1u); }

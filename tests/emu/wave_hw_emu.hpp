@@ -67,6 +67,8 @@ DI void wave_lockstep() { emu::coll_of[emu::cur]++; emu::switch_lane(); }
 
 DI u64 ld_list(const u64 *p) { return *p; }
 DI u32 ld_tab(const uint16_t *p) { return *p; }
+template <int PRIO>
+DI void wave_priority() {}
 DI u32 dec_sat(u32 c) { return c - min(c, 1u); }
 
 DI u64 ballot(bool p)
